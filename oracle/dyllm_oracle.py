@@ -1,0 +1,352 @@
+"""CPU oracle for DyLLM's per-denoising-step sparse layer update.
+
+TEST INFRASTRUCTURE ONLY.  This is a plain, slow numpy implementation in
+float64 of what the GPU library computes.  It is written from the paper alone
+and shares no code with the HIP path; only tests, the smoke check and the
+bench's CPU-baseline leg may import it.  Library matmuls serve as steps; there
+is no blocking, fusion or reordering beyond what the algorithm states.
+
+What each function follows:
+  cosine_rows, salient_mask ....... Sec. 3.1 (temporal cosine similarity) and
+                                    Sec. 3.2 (salient set A = {i : s < tau})
+  attention_rows .................. Sec. 3.3, salient path: exact attention rows
+                                    for salient queries against all keys/values
+  layer_step ...................... App. C.3, Alg. 3 (SparseStep), the body of
+                                    its layer loop restricted to the salient
+                                    (row-sparse) path
+  full_step ....................... App. C.2, Alg. 2 (FullStep), one layer
+  compact ......................... the where(...) of Alg. 3
+  rmsnorm ......................... App. E, proof of Prop. 1 (RMSNorm definition)
+
+Readings taken where the paper is silent (also listed in the design notes):
+pre-norm residual block (h = x + Wo C, y = h + FFN(RMSNorm(h))); the "FFN
+output cache" holds the layer's output hidden state; one cosine per token over
+the concatenated per-head context, before Wo; strict '<' against tau; each norm
+in the cosine clamped below at 1e-8; rotary embedding on q and k in the
+half-split pairing (j, j + dh/2), keys cached after rotation; softmax scale
+1/sqrt(dh), no mask; query head h reads KV head h // g; SwiGLU FFN
+down(silu(gate) * up).
+
+Parity pins: every function here is pinned by tests/test_oracle_pins.py
+(closed forms, brute-force loops on tiny inputs, the paper's propositions and
+the dense == all-salient equivalence).  The approximation quality of the method
+against the dense model is "parity unpinned": the paper shows it only through
+benchmark accuracy with trained weights.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+
+F64 = np.float64
+COS_NORM_FLOOR = 1e-8
+
+
+@dataclass(frozen=True)
+class LayerCfg:
+    hidden: int
+    n_heads: int
+    n_kv_heads: int
+    head_dim: int
+    ffn: int
+    rms_eps: float = 1e-5
+    rope_theta: float = 10000.0
+
+
+def _f64(a):
+    return None if a is None else np.asarray(a, dtype=F64)
+
+
+# --------------------------------------------------------------------------
+# elementary pieces
+# --------------------------------------------------------------------------
+
+def rmsnorm(x: np.ndarray, gain: np.ndarray, eps: float) -> np.ndarray:
+    """RMSNorm(y) = y / RMS(y) * g with RMS(y) = sqrt(mean(y^2) (+ eps)).  [App. E, Prop. 1 proof]"""
+    x = _f64(x)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * _f64(gain)
+
+
+def silu(z: np.ndarray) -> np.ndarray:
+    z = _f64(z)
+    return z / (1.0 + np.exp(-z))
+
+
+def rope(x: np.ndarray, pos: np.ndarray, theta: float) -> np.ndarray:
+    """Rotary embedding, half-split pairing.
+
+    x: [n, heads, dh]; pos: [n] positions inside the sequence.  Pair j couples
+    elements j and j + dh/2 and is rotated by the angle pos * theta^(-2j/dh).
+    """
+    x = _f64(x)
+    n, _, dh = x.shape
+    half = dh // 2
+    j = np.arange(half, dtype=F64)
+    inv_freq = theta ** (-2.0 * j / dh)
+    ang = _f64(pos)[:, None] * inv_freq[None, :]  # [n, half]
+    cos, sin = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+    x1, x2 = x[..., :half], x[..., half:]
+    out = np.empty_like(x)
+    out[..., :half] = x1 * cos - x2 * sin
+    out[..., half:] = x2 * cos + x1 * sin
+    return out
+
+
+def swiglu_ffn(f: np.ndarray, w: Dict[str, np.ndarray]) -> np.ndarray:
+    """down( silu(gate f) * (up f) ) for rows f [m, hidden]."""
+    gate = f @ _f64(w["w_gate"]).T
+    up = f @ _f64(w["w_up"]).T
+    return (silu(gate) * up) @ _f64(w["w_down"]).T
+
+
+def project_qkv(n_rows: np.ndarray, pos: np.ndarray, w: Dict[str, np.ndarray], cfg: LayerCfg):
+    """q, k, v for normalised rows n_rows [m, hidden] at sequence positions pos [m]."""
+    q = n_rows @ _f64(w["wq"]).T
+    k = n_rows @ _f64(w["wk"]).T
+    v = n_rows @ _f64(w["wv"]).T
+    if w.get("bq") is not None:
+        q = q + _f64(w["bq"])
+    if w.get("bk") is not None:
+        k = k + _f64(w["bk"])
+    if w.get("bv") is not None:
+        v = v + _f64(w["bv"])
+    m = n_rows.shape[0]
+    q = rope(q.reshape(m, cfg.n_heads, cfg.head_dim), pos, cfg.rope_theta)
+    k = rope(k.reshape(m, cfg.n_kv_heads, cfg.head_dim), pos, cfg.rope_theta)
+    v = v.reshape(m, cfg.n_kv_heads, cfg.head_dim)
+    return q, k, v
+
+
+def attention_rows(q: np.ndarray, k: np.ndarray, v: np.ndarray) -> np.ndarray:
+    """Exact attention rows of one sequence.  [Sec. 3.3 salient path; Alg. 3 C_sal]
+
+    q: [m, H, dh] queries of the selected rows; k, v: [L, Hkv, dh] all keys and
+    values of the sequence.  Every query attends to all L keys (no mask).
+    Returns [m, H*dh].
+    """
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    m, H, dh = q.shape
+    Hkv = k.shape[1]
+    g = H // Hkv
+    out = np.empty((m, H, dh), dtype=F64)
+    for h in range(H):
+        kh, vh = k[:, h // g, :], v[:, h // g, :]
+        z = (q[:, h, :] @ kh.T) / np.sqrt(dh)  # [m, L]
+        z = z - z.max(axis=1, keepdims=True)
+        p = np.exp(z)
+        p = p / p.sum(axis=1, keepdims=True)
+        out[:, h, :] = p @ vh
+    return out.reshape(m, H * dh)
+
+
+def cosine_rows(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """s = <a,b> / (max(|a|, floor) * max(|b|, floor)) per row.  [Sec. 3.1]"""
+    a, b = _f64(a), _f64(b)
+    dot = np.sum(a * b, axis=-1)
+    na = np.maximum(np.sqrt(np.sum(a * a, axis=-1)), COS_NORM_FLOOR)
+    nb = np.maximum(np.sqrt(np.sum(b * b, axis=-1)), COS_NORM_FLOOR)
+    return dot / (na * nb)
+
+
+def salient_mask(s: np.ndarray, tau: float) -> np.ndarray:
+    """A = {i : s_i < tau}, strict.  [Sec. 3.2]"""
+    return np.asarray(s) < tau
+
+
+def compact(flag: np.ndarray, rows: Optional[np.ndarray], B: int, L: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Ascending list of flagged token ids and per-sequence offsets [B+1].
+
+    flag[j] belongs to token rows[j] (rows ascending flat ids b*L+i), or to
+    token j when rows is None.
+    """
+    flag = np.asarray(flag).astype(bool)
+    ids = np.arange(flag.size, dtype=np.int64) if rows is None else np.asarray(rows, dtype=np.int64)
+    out = ids[flag]
+    offsets = np.zeros(B + 1, dtype=np.int32)
+    for b in range(B):
+        offsets[b + 1] = offsets[b] + int(np.sum((out >= b * L) & (out < (b + 1) * L)))
+    return out.astype(np.int32), offsets
+
+
+# --------------------------------------------------------------------------
+# stand-alone forms of the boundary calls
+# --------------------------------------------------------------------------
+
+def saliency(c_new: np.ndarray, c_cache: np.ndarray, rows: Optional[np.ndarray], tau: float,
+             commit: bool = False) -> Tuple[np.ndarray, np.ndarray]:
+    """Cosine and salient flag per candidate.  [Sec. 3.1-3.2; Alg. 3 cosine line]
+
+    rows given: c_new is [M, D] (one row per candidate), c_cache is [T, D] and
+    candidate j is compared with c_cache[rows[j]].  rows None: both are [T, D].
+    With commit the old cache row is read first and then overwritten by the new
+    context (cache commit of Alg. 3); c_cache must then be a float64 array.
+    """
+    cn = _f64(c_new)
+    if rows is None:
+        old = _f64(c_cache)
+    else:
+        old = _f64(c_cache)[np.asarray(rows, dtype=np.int64)]
+    s = cosine_rows(cn, old)
+    flag = salient_mask(s, tau)
+    if commit:
+        if rows is None:
+            c_cache[...] = cn
+        else:
+            c_cache[np.asarray(rows, dtype=np.int64)] = cn
+    return s, flag
+
+
+def partial_attention(q_sal: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,
+                      rows: np.ndarray, B: int, L: int) -> np.ndarray:
+    """C rows for the tokens in rows (flat ids), each against its own sequence's K/V.
+
+    q_sal: [M, H, dh]; k_cache, v_cache: [B, L, Hkv, dh].  Returns [M, H*dh].
+    """
+    rows = np.asarray(rows, dtype=np.int64)
+    M, H, dh = q_sal.shape
+    out = np.empty((M, H * dh), dtype=F64)
+    for b in range(B):
+        sel = np.nonzero((rows >= b * L) & (rows < (b + 1) * L))[0]
+        if sel.size:
+            out[sel] = attention_rows(q_sal[sel], k_cache[b], v_cache[b])
+    return out
+
+
+def salient_ffn(x: np.ndarray, c: np.ndarray, rows_out: np.ndarray, w: Dict[str, np.ndarray],
+                cfg: LayerCfg, out_cache: np.ndarray) -> None:
+    """Output projection, residual, norm, FFN, residual for rows_out; commit into out_cache.
+
+    x: [T, hidden] layer input; c: [T, H*dh] merged attention context;
+    out_cache: [T, hidden] float64, updated in place at rows_out only.
+    [Alg. 3: the out_proj / FFN / cache lines]
+    """
+    r = np.asarray(rows_out, dtype=np.int64)
+    if r.size == 0:
+        return
+    h = _f64(x)[r] + _f64(c)[r] @ _f64(w["wo"]).T
+    f = rmsnorm(h, w["g_ffn"], cfg.rms_eps)
+    out_cache[r] = h + swiglu_ffn(f, w)
+
+
+# --------------------------------------------------------------------------
+# the two steps
+# --------------------------------------------------------------------------
+
+def new_caches(B: int, L: int, cfg: LayerCfg) -> Dict[str, np.ndarray]:
+    """K, V, C and layer-output caches (zero-filled).  [Alg. 1 initialisation]"""
+    return {
+        "k": np.zeros((B, L, cfg.n_kv_heads, cfg.head_dim), dtype=F64),
+        "v": np.zeros((B, L, cfg.n_kv_heads, cfg.head_dim), dtype=F64),
+        "c": np.zeros((B, L, cfg.n_heads * cfg.head_dim), dtype=F64),
+        "out": np.zeros((B, L, cfg.hidden), dtype=F64),
+    }
+
+
+def full_step(x: np.ndarray, w: Dict[str, np.ndarray], cfg: LayerCfg,
+              caches: Dict[str, np.ndarray]) -> None:
+    """Dense pass of one layer over all rows; fills all four caches.  [Alg. 2]
+
+    Written on its own (matrix form, rotary embedding through complex
+    multiplication) and not through layer_step's helpers, so that the
+    "all rows salient == dense" pin compares two separate derivations.
+    """
+    x = _f64(x)
+    B, L, d = x.shape
+    H, Hkv, dh = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
+    g = H // Hkv
+    wq, wk, wv, wo = (_f64(w[n]) for n in ("wq", "wk", "wv", "wo"))
+    wg, wu, wd = (_f64(w[n]) for n in ("w_gate", "w_up", "w_down"))
+    ga, gf = _f64(w["g_attn"]), _f64(w["g_ffn"])
+    half = dh // 2
+    # rotation factors e^{i * pos * theta^(-2j/dh)}
+    phase = np.exp(1j * np.outer(np.arange(L, dtype=F64),
+                                 cfg.rope_theta ** (-2.0 * np.arange(half, dtype=F64) / dh)))
+
+    def rot(t):  # t: [L, heads, dh]
+        z = (t[..., :half] + 1j * t[..., half:]) * phase[:, None, :]
+        return np.concatenate([z.real, z.imag], axis=-1)
+
+    for b in range(B):
+        xb = x[b]
+        n = xb * (1.0 / np.sqrt((xb ** 2).mean(axis=1, keepdims=True) + cfg.rms_eps)) * ga
+        Q, K, V = n @ wq.T, n @ wk.T, n @ wv.T
+        if w.get("bq") is not None:
+            Q = Q + _f64(w["bq"])
+        if w.get("bk") is not None:
+            K = K + _f64(w["bk"])
+        if w.get("bv") is not None:
+            V = V + _f64(w["bv"])
+        Q = rot(Q.reshape(L, H, dh))
+        K = rot(K.reshape(L, Hkv, dh))
+        V = V.reshape(L, Hkv, dh)
+        C = np.empty((L, H, dh), dtype=F64)
+        for h in range(H):
+            S = Q[:, h] @ K[:, h // g].T / np.sqrt(dh)
+            E = np.exp(S - S.max(axis=1, keepdims=True))
+            C[:, h] = (E / E.sum(axis=1, keepdims=True)) @ V[:, h // g]
+        C = C.reshape(L, H * dh)
+        hcur = xb + C @ wo.T
+        f = hcur / np.sqrt((hcur ** 2).mean(axis=1, keepdims=True) + cfg.rms_eps) * gf
+        gate = f @ wg.T
+        y = hcur + ((gate / (1.0 + np.exp(-gate))) * (f @ wu.T)) @ wd.T
+        caches["k"][b], caches["v"][b], caches["c"][b], caches["out"][b] = K, V, C, y
+
+
+def layer_step(x: np.ndarray, idx_in: np.ndarray, w: Dict[str, np.ndarray], cfg: LayerCfg,
+               caches: Dict[str, np.ndarray], tau: float):
+    """One layer of SparseStep on the salient path.  [Alg. 3 layer body; Sec. 3.2-3.3]
+
+    x: [B, L, hidden] layer input; idx_in: ascending flat token ids b*L+i (the
+    salient set handed over by the previous layer / step); caches are updated
+    in place.  Returns (idx_out, offsets_out, cos) where cos[j] belongs to
+    idx_in[j] and idx_out lists the tokens with cos < tau.
+
+    Order, as in Alg. 3: (1) norm, q/k/v projection and rotation of the
+    idx_in rows; (2) their K and V rows replace the cached ones, for all of
+    idx_in, before any attention row is evaluated; (3) exact attention rows
+    against the merged K/V; (4) cosine against the old cached context, then the
+    '<' test; (5) commit the new contexts; (6) out-projection + residual, norm,
+    FFN + residual for the newly selected rows only, committed to the output
+    cache.  Rows outside idx_in keep all four cache rows; rows of idx_in that
+    fail the test keep their cached output row.
+    """
+    x = _f64(x)
+    B, L, d = x.shape
+    idx_in = np.asarray(idx_in, dtype=np.int64)
+    xf = x.reshape(B * L, d)
+    kc = caches["k"].reshape(B * L, cfg.n_kv_heads, cfg.head_dim)
+    vc = caches["v"].reshape(B * L, cfg.n_kv_heads, cfg.head_dim)
+    cc = caches["c"].reshape(B * L, cfg.n_heads * cfg.head_dim)
+    oc = caches["out"].reshape(B * L, d)
+    if idx_in.size == 0:
+        return np.zeros(0, np.int32), np.zeros(B + 1, np.int32), np.zeros(0, F64)
+
+    # (1) projections of the salient rows
+    n_rows = rmsnorm(xf[idx_in], w["g_attn"], cfg.rms_eps)
+    q, k, v = project_qkv(n_rows, idx_in % L, w, cfg)
+    # (2) K/V merge
+    kc[idx_in] = k
+    vc[idx_in] = v
+    # (3) exact rows
+    c_new = partial_attention(q, caches["k"], caches["v"], idx_in, B, L)
+    # (4) cosine against the cached context, selection
+    cos = cosine_rows(c_new, cc[idx_in])
+    flag = salient_mask(cos, tau)
+    # (5) context commit
+    cc[idx_in] = c_new
+    idx_out, offsets_out = compact(flag, idx_in, B, L)
+    # (6) out-projection and FFN for the newly selected rows
+    salient_ffn(xf, cc, idx_out, w, cfg, oc)
+    return idx_out, offsets_out, cos
+
+
+def kv_only_bytes_per_token(cfg: LayerCfg, elem: int) -> int:
+    return 2 * cfg.n_kv_heads * cfg.head_dim * elem
+
+
+def cache_bytes_per_token(cfg: LayerCfg, elem: int) -> int:
+    """K + V + C + layer output per token.  [Sec. 5 memory discussion]"""
+    return (2 * cfg.n_kv_heads * cfg.head_dim + cfg.n_heads * cfg.head_dim + cfg.hidden) * elem

@@ -1,0 +1,434 @@
+"""Pins for the CPU oracle: closed forms, brute force on tiny inputs, the paper's
+propositions and structural equivalences.  None of these re-uses the oracle's
+own formulas: brute-force checks are scalar Python loops written here, library
+checks call torch routines the oracle does not use.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dyllm_oracle as O
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+def _weights(cfg, rng, std=0.3, bias=False):
+    d, dq, dkv, f = cfg.hidden, cfg.n_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim, cfg.ffn
+    w = {
+        "wq": rng.normal(0, std, (dq, d)), "wk": rng.normal(0, std, (dkv, d)),
+        "wv": rng.normal(0, std, (dkv, d)), "wo": rng.normal(0, std, (d, dq)),
+        "w_gate": rng.normal(0, std, (f, d)), "w_up": rng.normal(0, std, (f, d)),
+        "w_down": rng.normal(0, std, (d, f)),
+        "g_attn": 1 + 0.2 * rng.normal(size=d), "g_ffn": 1 + 0.2 * rng.normal(size=d),
+    }
+    if bias:
+        w["bq"], w["bk"], w["bv"] = rng.normal(size=dq), rng.normal(size=dkv), rng.normal(size=dkv)
+    return w
+
+
+# ---------------------------------------------------------------- cosine / selection
+
+def test_cosine_hand_cases_from_fixture():
+    with open(os.path.join(GOLD, "cosine_cases.txt")) as fh:
+        for line in fh:
+            if line.startswith("#") or not line.strip():
+                continue
+            a, b, s = line.split(";")
+            a = np.array([float(t) for t in a.split()])[None]
+            b = np.array([float(t) for t in b.split()])[None]
+            assert O.cosine_rows(a, b)[0] == pytest.approx(float(s), abs=1e-15)
+
+
+def test_cosine_identical_scaled_and_zero_rows():
+    r = _rng(0)
+    a = r.normal(size=(7, 33))
+    assert np.all(O.cosine_rows(a, a) >= 1 - 1e-12)
+    assert np.allclose(O.cosine_rows(3.7 * a, a), 1.0, atol=1e-12)
+    assert np.allclose(O.cosine_rows(-a, a), -1.0, atol=1e-12)
+    z = np.zeros_like(a)
+    assert np.all(O.cosine_rows(a, z) == 0.0)  # zero cache row: s = 0, never NaN
+    assert np.all(O.cosine_rows(z, z) == 0.0)
+
+
+def test_cosine_matches_torch_library():
+    r = _rng(1)
+    a, b = r.normal(size=(11, 64)), r.normal(size=(11, 64))
+    ref = torch.nn.functional.cosine_similarity(torch.from_numpy(a), torch.from_numpy(b), dim=-1, eps=1e-8)
+    assert np.allclose(O.cosine_rows(a, b), ref.numpy(), atol=1e-14)
+
+
+def test_selection_rule_is_strict_and_bruteforce():
+    s = np.array([0.5, 0.99, 0.98999, 0.99001, 1.0, -1.0])
+    assert O.salient_mask(s, 0.99).tolist() == [True, False, True, False, False, True]
+    assert O.salient_mask(s, 1.5).all()
+    assert not O.salient_mask(s, -1.0).any()
+    r = _rng(2)
+    s = r.uniform(-1, 1, 64)
+    want = [i for i in range(64) if s[i] < 0.3]
+    got, off = O.compact(O.salient_mask(s, 0.3), None, 4, 16)
+    assert got.tolist() == want
+    assert off.tolist() == [sum(1 for i in want if i < 16 * b) for b in range(5)]
+
+
+def test_compact_with_candidate_rows_and_empty_sequences():
+    rows = np.array([3, 9, 17, 18, 40, 47])  # L = 16: seq 0,0,1,1,2,2 ; seq 3 empty
+    flag = np.array([1, 0, 0, 1, 1, 1], dtype=np.uint8)
+    idx, off = O.compact(flag, rows, 4, 16)
+    assert idx.tolist() == [3, 18, 40, 47]
+    assert off.tolist() == [0, 1, 2, 4, 4]
+    idx, off = O.compact(np.zeros(6, np.uint8), rows, 4, 16)
+    assert idx.size == 0 and off.tolist() == [0] * 5
+
+
+# ---------------------------------------------------------------- rmsnorm / silu / rope
+
+def test_rmsnorm_closed_forms():
+    g = np.array([1.0, 2.0, 3.0, 4.0])
+    assert np.allclose(O.rmsnorm(np.full((1, 4), 5.0), g, 0.0), g)
+    y = O.rmsnorm(np.array([[3.0, -4.0, 0.0, 0.0]]), np.ones(4), 0.0)
+    assert np.allclose(y, np.array([[3, -4, 0, 0]]) / math.sqrt(25 / 4))
+    # eps sits inside the square root, added to the mean square
+    y = O.rmsnorm(np.array([[2.0, 2.0]]), np.ones(2), 5.0)
+    assert np.allclose(y, 2.0 / 3.0)
+    r = _rng(3)
+    x = r.normal(size=(5, 16))
+    ref = torch.nn.functional.rms_norm(torch.from_numpy(x), (16,), torch.from_numpy(np.ones(16)), 1e-5)
+    assert np.allclose(O.rmsnorm(x, np.ones(16), 1e-5), ref.numpy(), atol=1e-13)
+
+
+def test_silu_closed_forms():
+    z = np.linspace(-6, 6, 25)
+    s = O.silu(z)
+    assert s[12] == 0.0
+    assert np.allclose(s - O.silu(-z), z, atol=1e-13)  # silu(z) - silu(-z) = z
+    assert O.silu(np.array([1.0]))[0] == pytest.approx(1 / (1 + math.exp(-1)), abs=1e-15)
+    assert np.allclose(s, torch.nn.functional.silu(torch.from_numpy(z)).numpy(), atol=1e-14)
+
+
+def test_rope_closed_forms():
+    # head_dim 2: one pair, plain rotation by the angle pos (theta^0 = 1)
+    x = np.array([[[1.0, 0.0]], [[0.0, 1.0]], [[2.0, 3.0]]])
+    y = O.rope(x, np.array([0.5, 0.5, 0.0]), 10000.0)
+    assert np.allclose(y[0, 0], [math.cos(0.5), math.sin(0.5)])
+    assert np.allclose(y[1, 0], [-math.sin(0.5), math.cos(0.5)])
+    assert np.allclose(y[2, 0], [2.0, 3.0])  # position 0 is the identity
+    # head_dim 4, theta 100: pair (0,2) turns by pos, pair (1,3) by pos / 10
+    x = np.array([[[1.0, 1.0, 0.0, 0.0]]])
+    y = O.rope(x, np.array([2.0]), 100.0)
+    assert np.allclose(y[0, 0], [math.cos(2.0), math.cos(0.2), math.sin(2.0), math.sin(0.2)])
+
+
+def test_rope_preserves_norm_and_is_relative():
+    r = _rng(4)
+    q, k = r.normal(size=(1, 3, 16)), r.normal(size=(1, 3, 16))
+    for m, n in [(5, 2), (105, 102), (40, 37)]:
+        qm, kn = O.rope(q, np.array([m]), 10000.0), O.rope(k, np.array([n]), 10000.0)
+        assert np.allclose(np.linalg.norm(qm, axis=-1), np.linalg.norm(q, axis=-1))
+        dots = np.sum(qm * kn, axis=-1)
+        if m == 5:
+            first = dots
+        assert np.allclose(dots, first, atol=1e-10)  # depends on m - n only
+
+
+# ---------------------------------------------------------------- attention
+
+def _attn_bruteforce(q, k, v):
+    m, H, dh = q.shape
+    L, Hkv, _ = k.shape
+    g = H // Hkv
+    out = np.zeros((m, H * dh))
+    for i in range(m):
+        for h in range(H):
+            z = [sum(q[i, h, e] * k[j, h // g, e] for e in range(dh)) / math.sqrt(dh) for j in range(L)]
+            zmax = max(z)
+            p = [math.exp(t - zmax) for t in z]
+            tot = sum(p)
+            for e in range(dh):
+                out[i, h * dh + e] = sum(p[j] * v[j, h // g, e] for j in range(L)) / tot
+    return out
+
+
+@pytest.mark.parametrize("H,Hkv", [(2, 2), (4, 2), (6, 1)])
+def test_attention_rows_vs_bruteforce(H, Hkv):
+    r = _rng(5)
+    q, k, v = r.normal(size=(3, H, 4)), r.normal(size=(7, Hkv, 4)), r.normal(size=(7, Hkv, 4))
+    assert np.allclose(O.attention_rows(q, k, v), _attn_bruteforce(q, k, v), atol=1e-13)
+
+
+def test_attention_special_cases():
+    r = _rng(6)
+    q = r.normal(size=(4, 2, 8))
+    k1, v1 = r.normal(size=(1, 2, 8)), r.normal(size=(1, 2, 8))
+    assert np.allclose(O.attention_rows(q, k1, v1), np.tile(v1.reshape(1, 16), (4, 1)))  # one key
+    k = np.tile(r.normal(size=(1, 2, 8)), (9, 1, 1))  # all keys equal -> uniform weights
+    v = r.normal(size=(9, 2, 8))
+    assert np.allclose(O.attention_rows(q, k, v), np.tile(v.mean(axis=0).reshape(1, 16), (4, 1)))
+    # grouped-query layout with repeated KV heads equals multi-head attention
+    kk, vv = r.normal(size=(9, 1, 8)), r.normal(size=(9, 1, 8))
+    assert np.allclose(O.attention_rows(q, kk, vv),
+                       O.attention_rows(q, np.repeat(kk, 2, 1), np.repeat(vv, 2, 1)))
+
+
+def test_attention_vs_torch_sdpa():
+    r = _rng(7)
+    H, Hkv, dh, L, m = 4, 2, 16, 33, 5
+    q, k, v = r.normal(size=(m, H, dh)), r.normal(size=(L, Hkv, dh)), r.normal(size=(L, Hkv, dh))
+    tq = torch.from_numpy(q).permute(1, 0, 2)[None]
+    tk = torch.from_numpy(np.repeat(k, H // Hkv, 1)).permute(1, 0, 2)[None]
+    tv = torch.from_numpy(np.repeat(v, H // Hkv, 1)).permute(1, 0, 2)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv)[0].permute(1, 0, 2).reshape(m, H * dh)
+    assert np.allclose(O.attention_rows(q, k, v), ref.numpy(), atol=1e-12)
+
+
+def test_partial_attention_uses_each_rows_own_sequence():
+    r = _rng(8)
+    B, L, H, dh = 3, 6, 2, 4
+    kc, vc = r.normal(size=(B, L, H, dh)), r.normal(size=(B, L, H, dh))
+    rows = np.array([1, 4, 13, 17])  # seq 0, 0, 2, 2 ; seq 1 empty
+    q = r.normal(size=(4, H, dh))
+    got = O.partial_attention(q, kc, vc, rows, B, L)
+    assert np.allclose(got[:2], _attn_bruteforce(q[:2], kc[0], vc[0]))
+    assert np.allclose(got[2:], _attn_bruteforce(q[2:], kc[2], vc[2]))
+
+
+# ---------------------------------------------------------------- propositions
+
+def test_prop1_scale_invariance():
+    r = _rng(9)
+    d = 24
+    wo, c, g = r.normal(size=(d, d)), r.normal(size=(5, d)), 1 + 0.3 * r.normal(size=d)
+    base = O.rmsnorm(c @ wo.T, g, 0.0)
+    for alpha in (1e-3, 0.5, 7.0, 1e4):
+        assert np.allclose(O.rmsnorm((alpha * c) @ wo.T, g, 0.0), base, rtol=1e-10, atol=1e-12)
+
+
+def test_prop2_error_bound_unit_normalised_form():
+    # the proof normalises to unit vectors: |f(u) - f(v)| <= kappa(Wo) * sqrt(2 (1 - s))
+    r = _rng(10)
+    d = 16
+    for trial in range(20):
+        wo = np.eye(d) + 0.2 * r.normal(size=(d, d))
+        kappa = np.linalg.cond(wo)
+        a = r.normal(size=(1, d))
+        b = a + (10.0 ** r.uniform(-4, 0)) * r.normal(size=(1, d))
+        s = O.cosine_rows(a, b)[0]
+        ya, yb = a @ wo.T, b @ wo.T
+        # RMSNorm with unit gain is the unit vector times sqrt(d)
+        delta = np.linalg.norm(O.rmsnorm(ya, np.ones(d), 0.0) - O.rmsnorm(yb, np.ones(d), 0.0)) / math.sqrt(d)
+        assert delta <= kappa * math.sqrt(max(0.0, 2 * (1 - s))) + 1e-9
+
+
+def test_memory_factor_matches_paper_formula():
+    with open(os.path.join(GOLD, "memory_factor.txt")) as fh:
+        for line in fh:
+            if line.startswith("#") or not line.strip():
+                continue
+            name, d, H, Hkv, dh, factor = line.split()
+            cfg = O.LayerCfg(int(d), int(H), int(Hkv), int(dh), 4 * int(d))
+            g = int(H) // int(Hkv)
+            assert O.cache_bytes_per_token(cfg, 2) / O.kv_only_bytes_per_token(cfg, 2) == int(factor)
+            assert (2 * int(d) / g + 2 * int(d)) / (2 * int(d) / g) == int(factor)
+
+
+# ---------------------------------------------------------------- GEMM-level pieces
+
+def test_ffn_and_projection_vs_scalar_loops():
+    r = _rng(11)
+    cfg = O.LayerCfg(hidden=6, n_heads=2, n_kv_heads=1, head_dim=4, ffn=5)
+    w = _weights(cfg, r, bias=True)
+    f = r.normal(size=(2, 6))
+    got = O.swiglu_ffn(f, w)
+    for i in range(2):
+        act = []
+        for n in range(5):
+            gate = sum(w["w_gate"][n, k] * f[i, k] for k in range(6))
+            up = sum(w["w_up"][n, k] * f[i, k] for k in range(6))
+            act.append(gate / (1 + math.exp(-gate)) * up)
+        for o in range(6):
+            assert got[i, o] == pytest.approx(sum(w["w_down"][o, n] * act[n] for n in range(5)), abs=1e-12)
+    # projection + bias at position 0 (rotation = identity): [out, in] weights, y = W n + b
+    q, k, v = O.project_qkv(f, np.zeros(2), w, cfg)
+    for i in range(2):
+        for o in range(8):
+            want = sum(w["wq"][o, kk] * f[i, kk] for kk in range(6)) + w["bq"][o]
+            assert q.reshape(2, 8)[i, o] == pytest.approx(want, abs=1e-12)
+        for o in range(4):
+            assert k.reshape(2, 4)[i, o] == pytest.approx(
+                sum(w["wk"][o, kk] * f[i, kk] for kk in range(6)) + w["bk"][o], abs=1e-12)
+            assert v.reshape(2, 4)[i, o] == pytest.approx(
+                sum(w["wv"][o, kk] * f[i, kk] for kk in range(6)) + w["bv"][o], abs=1e-12)
+
+
+def _dense_layer_torch(x, w, cfg):
+    """Third opinion for a whole dense layer built from torch library routines."""
+    t = {k: torch.from_numpy(np.asarray(v, dtype=np.float64)) for k, v in w.items()}
+    X = torch.from_numpy(x)
+    B, L, d = X.shape
+    H, Hkv, dh = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
+    n = torch.nn.functional.rms_norm(X, (d,), t["g_attn"], cfg.rms_eps)
+    q = torch.nn.functional.linear(n, t["wq"], t.get("bq")).view(B, L, H, dh)
+    k = torch.nn.functional.linear(n, t["wk"], t.get("bk")).view(B, L, Hkv, dh)
+    v = torch.nn.functional.linear(n, t["wv"], t.get("bv")).view(B, L, Hkv, dh)
+    inv = cfg.rope_theta ** (-torch.arange(0, dh, 2, dtype=torch.float64) / dh)
+    ang = torch.arange(L, dtype=torch.float64)[:, None] * inv[None]
+    cos, sin = torch.cat([ang.cos(), ang.cos()], -1)[None, :, None], torch.cat([ang.sin(), ang.sin()], -1)[None, :, None]
+
+    def rot_half(u):
+        return torch.cat([-u[..., dh // 2:], u[..., :dh // 2]], -1)
+
+    q, k = q * cos + rot_half(q) * sin, k * cos + rot_half(k) * sin
+    kk, vv = k.repeat_interleave(H // Hkv, 2), v.repeat_interleave(H // Hkv, 2)
+    c = torch.nn.functional.scaled_dot_product_attention(
+        q.transpose(1, 2), kk.transpose(1, 2), vv.transpose(1, 2)).transpose(1, 2).reshape(B, L, H * dh)
+    h = X + torch.nn.functional.linear(c, t["wo"])
+    f = torch.nn.functional.rms_norm(h, (d,), t["g_ffn"], cfg.rms_eps)
+    y = h + torch.nn.functional.linear(
+        torch.nn.functional.silu(torch.nn.functional.linear(f, t["w_gate"])) * torch.nn.functional.linear(f, t["w_up"]),
+        t["w_down"])
+    return k.numpy(), v.numpy(), c.numpy(), y.numpy()
+
+
+@pytest.mark.parametrize("H,Hkv,bias", [(4, 4, False), (4, 2, True)])
+def test_full_step_vs_torch_library_layer(H, Hkv, bias):
+    r = _rng(12)
+    cfg = O.LayerCfg(hidden=32, n_heads=H, n_kv_heads=Hkv, head_dim=8, ffn=48, rope_theta=100.0)
+    w = _weights(cfg, r, std=0.2, bias=bias)
+    x = r.normal(size=(2, 9, 32))
+    caches = O.new_caches(2, 9, cfg)
+    O.full_step(x, w, cfg, caches)
+    k, v, c, y = _dense_layer_torch(x, w, cfg)
+    for name, ref in (("k", k), ("v", v), ("c", c), ("out", y)):
+        assert np.allclose(caches[name], ref, atol=1e-11), name
+
+
+# ---------------------------------------------------------------- whole step
+
+def _setup(seed=13, B=2, L=10, H=4, Hkv=2, bias=False):
+    r = _rng(seed)
+    cfg = O.LayerCfg(hidden=16, n_heads=H, n_kv_heads=Hkv, head_dim=4, ffn=24, rope_theta=50.0)
+    w = _weights(cfg, r, std=0.3, bias=bias)
+    x0 = r.normal(size=(B, L, 16))
+    caches = O.new_caches(B, L, cfg)
+    O.full_step(x0, w, cfg, caches)
+    return r, cfg, w, x0, caches
+
+
+def _copy(c):
+    return {k: v.copy() for k, v in c.items()}
+
+
+def test_step_with_empty_input_set_is_a_noop():
+    r, cfg, w, x0, caches = _setup()
+    before = _copy(caches)
+    idx_out, off, cos = O.layer_step(r.normal(size=x0.shape), np.zeros(0, np.int64), w, cfg, caches, 0.99)
+    assert idx_out.size == 0 and cos.size == 0 and off.tolist() == [0, 0, 0]
+    for k in caches:
+        assert np.array_equal(caches[k], before[k])
+
+
+@pytest.mark.parametrize("bias", [False, True])
+def test_all_rows_salient_equals_dense_step(bias):
+    r, cfg, w, x0, caches = _setup(bias=bias)
+    x1 = r.normal(size=x0.shape)
+    dense = O.new_caches(*x0.shape[:2], cfg)
+    O.full_step(x1, w, cfg, dense)
+    idx_out, off, cos = O.layer_step(x1, np.arange(x0.shape[0] * x0.shape[1]), w, cfg, caches, 1.5)
+    assert idx_out.tolist() == list(range(20)) and off.tolist() == [0, 10, 20]
+    for k in caches:
+        assert np.allclose(caches[k], dense[k], rtol=1e-11, atol=1e-12), k
+
+
+def test_repeating_a_step_with_unchanged_input_selects_nothing():
+    r, cfg, w, x0, caches = _setup()
+    x1 = x0.copy()
+    idx = np.array([1, 4, 7, 12, 19])
+    x1.reshape(20, -1)[idx] = r.normal(size=(5, 16))
+    out1, _, cos1 = O.layer_step(x1, idx, w, cfg, caches, 0.99)
+    snap = _copy(caches)
+    out2, off2, cos2 = O.layer_step(x1, idx, w, cfg, caches, 0.99)
+    assert np.all(cos2 >= 1 - 1e-12) and out2.size == 0 and off2.tolist() == [0, 0, 0]
+    for k in ("k", "v", "out"):
+        assert np.array_equal(caches[k], snap[k])
+    assert np.allclose(caches["c"], snap["c"], atol=1e-14)
+
+
+def test_sparse_step_touches_only_its_rows_and_matches_dense_rows():
+    r, cfg, w, x0, caches = _setup()
+    B, L = x0.shape[:2]
+    before = _copy(caches)
+    x1 = x0.copy()
+    idx = np.array([0, 3, 8, 11, 15])
+    x1.reshape(B * L, -1)[idx] = r.normal(size=(5, 16))
+    idx_out, off, cos = O.layer_step(x1, idx, w, cfg, caches, 0.999999)
+    others = np.setdiff1d(np.arange(B * L), idx)
+    for k in caches:
+        flat_new = caches[k].reshape(B * L, -1)
+        flat_old = before[k].reshape(B * L, -1)
+        assert np.array_equal(flat_new[others], flat_old[others]), k
+    # K and V rows of idx equal a dense projection of x1 (dense K/V depend on their own row only)
+    dense = O.new_caches(B, L, cfg)
+    O.full_step(x1, w, cfg, dense)
+    for k in ("k", "v"):
+        assert np.allclose(caches[k].reshape(B * L, -1)[idx], dense[k].reshape(B * L, -1)[idx], atol=1e-12)
+    # x1 differs from x0 only on idx, so merged K/V == dense K/V and the recomputed rows are exact
+    assert np.allclose(caches["c"].reshape(B * L, -1)[idx], dense["c"].reshape(B * L, -1)[idx], atol=1e-12)
+    assert np.allclose(caches["out"].reshape(B * L, -1)[idx_out], dense["out"].reshape(B * L, -1)[idx_out], atol=1e-11)
+    assert set(idx_out.tolist()) <= set(idx.tolist())
+    assert off[-1] == idx_out.size
+
+
+def test_rows_failing_the_test_keep_their_cached_output():
+    r, cfg, w, x0, caches = _setup()
+    B, L = x0.shape[:2]
+    x1 = x0.copy()
+    idx = np.array([2, 5, 13, 17])
+    flat = x1.reshape(B * L, -1)
+    flat[[2, 13]] += 1e-7 * r.normal(size=(2, 16))  # tiny change: cosine ~ 1
+    # rows 5 and 17: input unchanged, but their cached context is stale (negated): cosine = -1
+    caches["c"].reshape(B * L, -1)[[5, 17]] *= -1.0
+    before = _copy(caches)
+    idx_out, off, cos = O.layer_step(x1, idx, w, cfg, caches, 0.9999)
+    assert cos[0] > 0.9999 and cos[2] > 0.9999
+    assert cos[1] < -0.9999 and cos[3] < -0.9999
+    assert idx_out.tolist() == [5, 17] and off.tolist() == [0, 1, 2]
+    out_new, out_old = caches["out"].reshape(B * L, -1), before["out"].reshape(B * L, -1)
+    assert np.array_equal(out_new[[2, 13]], out_old[[2, 13]])  # output row reused
+    assert not np.array_equal(caches["k"].reshape(B * L, -1)[2], before["k"].reshape(B * L, -1)[2])  # K refreshed
+    assert not np.array_equal(caches["c"].reshape(B * L, -1)[2], before["c"].reshape(B * L, -1)[2])  # C committed
+
+
+def test_saliency_reads_old_cache_before_commit():
+    r = _rng(14)
+    cache = r.normal(size=(6, 8))
+    old = cache.copy()
+    rows = np.array([1, 4])
+    new = r.normal(size=(2, 8))
+    s, flag = O.saliency(new, cache, rows, 0.5, commit=True)
+    for j, row in enumerate(rows):
+        want = float(new[j] @ old[row] / (np.linalg.norm(new[j]) * np.linalg.norm(old[row])))
+        assert s[j] == pytest.approx(want, abs=1e-14)
+    assert np.array_equal(cache[rows], new)
+    assert np.array_equal(cache[[0, 2, 3, 5]], old[[0, 2, 3, 5]])
+    s_all, _ = O.saliency(cache, old, None, 0.5)
+    assert s_all[0] == pytest.approx(1.0) and s_all[1] == pytest.approx(s[0])
+
+
+def test_context_delta_decomposition_identity():
+    # Eq. 3: dC = S_t dV + dS V_{t-1}; with unchanged scores (dS = 0) the update S dV is exact
+    r = _rng(15)
+    L, dh = 7, 4
+    q, k = r.normal(size=(L, 1, dh)), r.normal(size=(L, 1, dh))
+    v0 = r.normal(size=(L, 1, dh))
+    v1 = v0.copy()
+    v1[[2, 5]] = r.normal(size=(2, 1, dh))
+    c0, c1 = O.attention_rows(q, k, v0), O.attention_rows(q, k, v1)
+    S = np.exp(q[:, 0] @ k[:, 0].T / math.sqrt(dh))
+    S /= S.sum(axis=1, keepdims=True)
+    assert np.allclose(c1 - c0, S[:, [2, 5]] @ (v1 - v0)[[2, 5], 0], atol=1e-13)
