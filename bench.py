@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse layer step on one MI355X.
+
+A "step" is one dyllm_layer_step (the whole hot path: gather+norm, q/k/v GEMM, rotation and K/V
+merge, partial attention, cosine saliency + commit, compaction, out-projection, FFN, scatter-back)
+over one batch of synthetic input that is already resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2|c3|c4] [--frac 0.10]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+FP32_VALU_PEAK_TFLOPS = 157.3
+RIDGE = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)  # flop per byte
+
+
+def stage_work(shape, B, L, M_in, M_out, esz):
+    """Algorithmic flops and HBM bytes of each stage for one step (M_in candidates, M_out salient)."""
+    d, dq, dkv, F = shape.hidden, shape.dq, shape.dkv, shape.ffn
+    nq = dq + 2 * dkv
+    w = {}
+    w["gather_rmsnorm"] = (4.0 * M_in * d, M_in * d * esz * 2 + d * esz)
+    w["gemm_qkv"] = (2.0 * M_in * d * nq, nq * d * esz + M_in * d * esz + M_in * nq * 4)
+    w["rope_scatter"] = (6.0 * M_in * nq, M_in * nq * 4 + M_in * nq * esz)
+    w["partial_attention"] = (4.0 * M_in * L * dq, 2 * B * L * dkv * esz + 2 * M_in * dq * esz)
+    w["saliency"] = (6.0 * M_in * dq, 3 * M_in * dq * esz)
+    w["compact"] = (0.0, M_in + 4 * M_out)
+    w["gemm_oproj"] = (2.0 * M_out * dq * d, d * dq * esz + M_out * dq * esz + M_out * d * (esz + 4))
+    w["rmsnorm_ffn"] = (4.0 * M_out * d, M_out * d * (4 + esz))
+    w["gemm_swiglu"] = (4.0 * M_out * d * F, 2 * F * d * esz + M_out * d * esz + M_out * F * esz)
+    w["gemm_down"] = (2.0 * M_out * F * d, d * F * esz + M_out * F * esz + M_out * d * (4 + esz))
+    return w
+
+
+def cpu_baseline(wl, budget_s=20.0):
+    """Times the CPU oracle as it stands on a bounded sample of the same workload."""
+    import numpy as np
+    from dataclasses import replace
+    from oracle import dyllm_oracle as O
+    from synth import workload as W
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    nb = min(wl.batch, 2)
+    sub = replace(wl, batch=nb, t_full=1)
+    s = sub.shape
+    cfg = O.LayerCfg(s.hidden, s.n_heads, s.n_kv_heads, s.head_dim, s.ffn, s.rms_eps, s.rope_theta)
+    w = W.make_weights(s)
+    caches = O.new_caches(nb, sub.seq, cfg)
+    times = []
+    t_begin = time.time()
+    for st in W.step_stream(sub, 12):
+        if st.dense:
+            O.full_step(st.x, w, cfg, caches)
+            continue
+        t0 = time.time()
+        O.layer_step(st.x, st.idx, w, cfg, caches, sub.tau)
+        times.append(time.time() - t0)
+        if time.time() - t_begin > budget_s and len(times) >= 2:
+            break
+    t = float(np.median(times))
+    return {
+        "value": nb * sub.seq / t, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+        "sample": "%d sparse layer steps of %s on the first %d of %d sequences after one dense warm-up step "
+                  "(numpy float64 oracle, median %.3f s per step)" % (len(times), wl.name, nb, wl.batch, t),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--frac", type=float, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dense-iters", type=int, default=3)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on exactly one GPU (the path shards along the batch with no "
+                         "exchange; see DESIGN.md); --gpus %d is not supported\n" % args.gpus)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2603_08026_amd.layer import Layer
+    from synth import workload as W
+
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py: no GPU visible\n")
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    wl = W.CONFIGS[args.config]
+    if args.frac is not None:
+        wl = W.with_frac(wl, args.frac)
+    s = wl.shape
+    esz = 4 if s.dtype == "f32" else 2
+    K, Wu = args.steps, args.warmup
+
+    lay = Layer.from_shape(s, wl.batch, wl.seq)
+    lay.set_weights(W.make_weights(s))
+    dense_x, steps = [], []
+    for st in W.step_stream(wl, wl.t_full + Wu + K):
+        xd = lay.upload(st.x)
+        if st.dense:
+            dense_x.append(xd)
+        else:
+            steps.append((xd, lay.make_list(st.idx, st.offsets), int(st.idx.size)))
+    # cache warm-up: T_full dense steps (Sec. 3.2)
+    for xd in dense_x:
+        lay.full_step(xd)
+    torch.cuda.synchronize()
+
+    def run(range_):
+        for i in range_:
+            xd, il, _ = steps[i]
+            lay.layer_step(xd, il, wl.tau, want_cos=False)
+
+    run(range(Wu))
+    torch.cuda.synchronize()
+    snap = {k: getattr(lay, k).clone() for k in ("k", "v", "c", "out")}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(range(Wu, Wu + K))
+    torch.cuda.synchronize()
+    t_step = (time.perf_counter() - t0) / K
+    m_out_last = int(lay.idx_out.offsets[-1].item())
+
+    # the same K steps again, from the same cache state, with one HIP event after every stage
+    # (recorded on the stream of the launches)
+    for k_, v_ in snap.items():
+        getattr(lay, k_).copy_(v_)
+    torch.cuda.synchronize()
+    lay.ctx.profile_begin(K)
+    t0 = time.perf_counter()
+    run(range(Wu, Wu + K))
+    torch.cuda.synchronize()
+    t_step_instr = (time.perf_counter() - t0) / K
+    stage_ms, calls = lay.ctx.profile_end()
+    del snap
+
+    # dense step of the same shape on the same GPU
+    xd = dense_x[-1] if dense_x else steps[0][0]
+    lay.full_step(xd)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.dense_iters):
+        lay.full_step(xd)
+    torch.cuda.synchronize()
+    t_dense = (time.perf_counter() - t0) / args.dense_iters
+
+    m_in = float(np.mean([m for _, _, m in steps[Wu:Wu + K]]))
+    work = stage_work(s, wl.batch, wl.seq, m_in, m_in, esz)  # every candidate passes the test here
+    stages = {}
+    for name, ms in stage_ms.items():
+        fl, by = work[name]
+        stages[name] = {"ms": round(ms, 5), "gbps": round(by / (ms * 1e-3) / 1e9, 1) if ms > 0 else None,
+                        "tflops": round(fl / (ms * 1e-3) / 1e12, 2) if ms > 0 else None}
+    dom = max(stage_ms, key=lambda n: stage_ms[n])
+    fl, by = work[dom]
+    ms = stage_ms[dom]
+    is_gemm_or_attn = dom.startswith("gemm") or dom == "partial_attention"
+    if s.dtype == "bf16" and is_gemm_or_attn and fl / by >= RIDGE:
+        roof = {"bound": "mfma", "achieved": fl / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    elif s.dtype == "f32" and is_gemm_or_attn and fl / by >= FP32_VALU_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS:
+        roof = {"bound": "alu", "achieved": fl / (ms * 1e-3) / 1e12, "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "hbm", "achieved": by / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["kernel"] = dom
+    roof["launch_ms"] = ms
+    roof["traffic"] = None
+    tr = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.config)
+    if os.path.exists(tr):
+        try:
+            roof["traffic"] = json.load(open(tr)).get(dom)
+        except Exception:
+            roof["traffic"] = None
+
+    out = {
+        "metric": "denoised tokens/s per layer-step at 8B shape; speedup vs dense step",
+        "value": wl.tokens / t_step, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wu,
+        "ms_per_step": t_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": s.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "batch": wl.batch, "seq_len": wl.seq, "salient_frac": wl.frac,
+                   "salient_rows_mean": m_in, "salient_rows_out_last": m_out_last, "tau": wl.tau,
+                   "hidden": s.hidden, "n_heads": s.n_heads, "n_kv_heads": s.n_kv_heads, "ffn": s.ffn},
+        "dense_ms_per_step": t_dense * 1e3, "speedup_vs_dense": t_dense / t_step,
+        "salient_rows_per_s": m_in / t_step,
+        "ms_per_step_with_stage_events": t_step_instr * 1e3, "stage_calls": calls, "stages": stages,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    lay.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

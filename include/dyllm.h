@@ -1,0 +1,196 @@
+/*
+ * dyllm.h - C ABI of the MI355X (gfx950) library for DyLLM's per-denoising-step
+ * sparse layer update.
+ *
+ * One call = one transformer layer, one denoising step.  The salient tokens of
+ * the step get their K/V rows refreshed, their exact attention rows recomputed
+ * against all keys, a cosine test against the cached previous context, and --
+ * for those that pass the test -- output projection and FFN; every other token
+ * reuses its cached K, V, context and layer output.
+ * [App. C.3, Alg. 3 (SparseStep), layer body; Sec. 3.1-3.3]
+ *
+ * Conventions (all entry points)
+ *  - Every tensor pointer is DEVICE memory owned by the caller (allocated and
+ *    freed by the caller); the library owns only the scratch workspace of its
+ *    context.  Pointers named host_* are host memory.
+ *  - Tensors are dense row-major.  A "token id" is b*L + i for position i of
+ *    sequence b; T = B*L.  Element type is the context's dtype (fp32 or bf16)
+ *    unless a parameter says otherwise.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue work on it: no device synchronisation, no device-to-host
+ *    copy.  Row counts stay on the device (offsets[B]).
+ *  - Return value: 0 on success, a negative DYLLM_ERR_* code otherwise.
+ *    Argument and shape errors are found on the host before anything is
+ *    launched.  Nothing throws, aborts or prints.  dyllm_last_error gives a
+ *    message for the last failing call on a context.
+ *  - A context is not thread-safe; calls that share a context must be ordered
+ *    on one stream.
+ */
+#ifndef DYLLM_H
+#define DYLLM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DYLLM_OK 0
+#define DYLLM_ERR_INVALID_ARG (-1) /* NULL pointer, negative size, bad enum */
+#define DYLLM_ERR_BAD_SHAPE (-2)   /* sizes inconsistent with the context's configuration */
+#define DYLLM_ERR_UNSUPPORTED (-3) /* shape the kernels are not written for */
+#define DYLLM_ERR_NO_MEM (-4)      /* workspace allocation failed */
+#define DYLLM_ERR_HIP (-5)         /* a HIP runtime call failed */
+#define DYLLM_ERR_CAPACITY (-6)    /* an index list did not fit its capacity (see dyllm_poll_status) */
+
+typedef struct dyllm_ctx dyllm_ctx; /* opaque; owns only scratch workspace */
+
+typedef enum { DYLLM_F32 = 0, DYLLM_BF16 = 1 } dyllm_dtype;
+
+/* Layer configuration.  hidden must equal n_heads*head_dim is NOT required;
+ * n_heads must be a multiple of n_kv_heads (query head h reads KV head
+ * h / (n_heads/n_kv_heads)).  Kernel limits: head_dim 64 or 128; hidden,
+ * n_heads*head_dim and ffn_dim multiples of 64 (bf16: of 128). */
+typedef struct {
+  int32_t hidden;     /* d */
+  int32_t n_heads;    /* H */
+  int32_t n_kv_heads; /* Hkv */
+  int32_t head_dim;   /* dh */
+  int32_t ffn_dim;    /* F */
+  int32_t max_batch;  /* largest B of any call */
+  int32_t max_seq;    /* largest L of any call */
+  int32_t max_rows;   /* largest number of rows one call recomputes (capacity of its index
+                         lists); 0 means max_batch*max_seq, which dyllm_full_step needs */
+  int32_t dtype;      /* dyllm_dtype: storage type of weights, activations and caches */
+  float rms_eps;      /* added to the mean square inside RMSNorm's square root */
+  float rope_theta;   /* rotary base */
+} dyllm_layer_cfg;
+
+/* Weights of one layer, [out, in] row-major: y = W x (+ b). */
+typedef struct {
+  const void *wq;     /* [H*dh, d] */
+  const void *wk;     /* [Hkv*dh, d] */
+  const void *wv;     /* [Hkv*dh, d] */
+  const void *wo;     /* [d, H*dh] */
+  const void *w_gate; /* [F, d] */
+  const void *w_up;   /* [F, d] */
+  const void *w_down; /* [d, F] */
+  const void *bq;     /* [H*dh] or NULL */
+  const void *bk;     /* [Hkv*dh] or NULL */
+  const void *bv;     /* [Hkv*dh] or NULL */
+  const void *g_attn; /* [d] RMSNorm gain before attention */
+  const void *g_ffn;  /* [d] RMSNorm gain before the FFN */
+} dyllm_layer_weights;
+
+/* The four per-layer caches [Alg. 1 initialisation; Alg. 2 / Alg. 3 cache lines].
+ * Updated in place. */
+typedef struct {
+  void *k;   /* [B, L, Hkv, dh]  keys, stored AFTER the rotary embedding */
+  void *v;   /* [B, L, Hkv, dh] */
+  void *c;   /* [B, L, H*dh]     attention context, before the output projection */
+  void *out; /* [B, L, d]        layer output hidden state ("FFN output cache") */
+} dyllm_layer_cache;
+
+/* A set of tokens: ascending, unique token ids, grouped by sequence. */
+typedef struct {
+  int32_t *idx;     /* [cap] token ids b*L+i; entries beyond the count are undefined */
+  int32_t *offsets; /* [B+1] offsets[b]..offsets[b+1] = entries of sequence b; offsets[B] = count */
+  int32_t cap;      /* capacity of idx (host value); the count on the device must not exceed it */
+} dyllm_index_list;
+
+/* Bytes of device scratch a context with this configuration allocates. */
+int dyllm_workspace_bytes(const dyllm_layer_cfg *cfg, size_t *host_bytes);
+
+/* Creates a context on the current HIP device (allocates its workspace once).
+ * Errors: INVALID_ARG, UNSUPPORTED (kernel limits above), NO_MEM. */
+int dyllm_create(const dyllm_layer_cfg *cfg, dyllm_ctx **host_ctx_out);
+/* Frees the workspace.  The caller must have synchronised the streams it used. */
+int dyllm_destroy(dyllm_ctx *ctx);
+
+const char *dyllm_strerror(int code);
+const char *dyllm_last_error(const dyllm_ctx *ctx);
+
+/* Copies the context's device status word (0, or DYLLM_ERR_CAPACITY if some kernel since the
+ * last poll found more rows than a list's capacity and dropped the excess) to *host_status.
+ * This is the one call that synchronises `stream`. */
+int dyllm_poll_status(dyllm_ctx *ctx, int32_t *host_status, void *stream);
+
+/* Temporal cosine similarity and the salient test.  [Sec. 3.1; Sec. 3.2: A = {i : s_i < tau}]
+ *   rows != NULL: c_new is [count, D] (row j belongs to token rows->idx[j]) and is compared with
+ *                 c_cache[rows->idx[j]]; cos_out / flag_out are [rows->cap] (count entries written).
+ *   rows == NULL: c_new and c_cache are both [B*L, D]; cos_out / flag_out are [B*L].
+ * D = n_heads*head_dim.  s = <a,b> / (max(|a|,1e-8) * max(|b|,1e-8)), accumulated in fp32 over the
+ * stored values; flag = (s < tau), strict.  With commit != 0 the old cache row is read first and
+ * then overwritten with the new row [Alg. 3 cache commit]; commit requires rows != NULL or
+ * c_new != c_cache.  cos_out may be NULL. */
+int dyllm_saliency(dyllm_ctx *ctx, const void *c_new, void *c_cache, const dyllm_index_list *rows,
+                   int32_t B, int32_t L, float tau, float *cos_out, uint8_t *flag_out, int commit,
+                   void *stream);
+
+/* Stable compaction of the flagged tokens into an ascending index list.  [Alg. 3: where(...)]
+ * flag[j] != 0 selects token rows->idx[j] (rows != NULL, j < count) or token j (rows == NULL,
+ * j < B*L).  Writes out->idx, out->offsets[0..B].  If more than out->cap tokens are flagged the
+ * excess is dropped and the status word is set (dyllm_poll_status). */
+int dyllm_compact(dyllm_ctx *ctx, const uint8_t *flag, const dyllm_index_list *rows, int32_t B,
+                  int32_t L, dyllm_index_list *out, void *stream);
+
+/* K/V refresh of the salient rows.  [Alg. 3: norm, q_proj, k_proj / v_proj merge lines]
+ * For every token r in rows: n = RMSNorm(x[r]; g_attn); q, k, v = W n (+ b); q and k rotated by the
+ * rotary embedding at position r mod L; cache->k[r] = k, cache->v[r] = v (other rows untouched);
+ * q_sal_out[j] = q for the j-th entry of rows, layout [rows->cap, H, dh]. */
+int dyllm_qkv_refresh(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x,
+                      const dyllm_index_list *rows, int32_t B, int32_t L, dyllm_layer_cache *cache,
+                      void *q_sal_out, void *stream);
+
+/* Exact attention rows for the salient queries against ALL keys and values of their own sequence,
+ * bidirectional (no mask), softmax scale 1/sqrt(dh).  [Sec. 3.3 salient path; Alg. 3: C_sal]
+ * q_sal: [rows->cap, H, dh] (count rows used); k_cache, v_cache: [B, L, Hkv, dh];
+ * c_sal_out: [rows->cap, H*dh]. */
+int dyllm_partial_attention(dyllm_ctx *ctx, const void *q_sal, const void *k_cache,
+                            const void *v_cache, const dyllm_index_list *rows, int32_t B, int32_t L,
+                            void *c_sal_out, void *stream);
+
+/* Output projection + residual, RMSNorm, SwiGLU FFN + residual for the tokens in rows_out, written
+ * into out_cache at those rows only.  [Alg. 3: out_proj / FFN / cache lines; Sec. 3.2]
+ *   h = x[r] + Wo c[r];  y = h + Wdown( silu(Wgate f) * (Wup f) ), f = RMSNorm(h; g_ffn);
+ *   out_cache[r] = y.
+ * x: [B*L, d] layer input; c: [B*L, H*dh] merged attention context (the context cache after its
+ * commit); out_cache: [B*L, d]. */
+int dyllm_salient_ffn(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x, const void *c,
+                      const dyllm_index_list *rows_out, int32_t B, int32_t L, void *out_cache,
+                      void *stream);
+
+/* One layer of SparseStep on the salient path.  [Alg. 3 layer body; Sec. 3.2-3.3]
+ * = dyllm_qkv_refresh(idx_in) -> dyllm_partial_attention -> dyllm_saliency(commit) ->
+ *   dyllm_compact -> dyllm_salient_ffn(idx_out), all enqueued on `stream`.
+ * x: [B, L, d] layer input (must not alias cache->out).  idx_in: tokens to recompute (the salient
+ * set handed over by the previous layer or step).  idx_out: receives the tokens whose cosine fell
+ * below tau (a subset of idx_in); it is the next layer's idx_in.  cos_out: [idx_in->cap] or NULL.
+ * The layer's output is cache->out (all rows).  An empty idx_in changes no cache byte and yields
+ * an empty idx_out. */
+int dyllm_layer_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
+                     const void *x, const dyllm_index_list *idx_in, int32_t B, int32_t L, float tau,
+                     dyllm_index_list *idx_out, float *cos_out, void *stream);
+
+/* Dense pass of one layer over all B*L rows; fills all four caches.  [App. C.2, Alg. 2]
+ * Needs a context with max_rows covering B*L. */
+int dyllm_full_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
+                    const void *x, int32_t B, int32_t L, void *stream);
+
+/* Per-stage timing of dyllm_layer_step / dyllm_full_step for measurement.  After
+ * dyllm_profile_begin the next max_calls (<= 4096) step calls on this context record a HIP event on
+ * their stream after every stage (gather+norm, q/k/v GEMM, rotation+merge, attention, saliency,
+ * compaction, out-projection GEMM, FFN norm, gate/up GEMM, down GEMM).  dyllm_profile_end waits for
+ * those events, writes the mean milliseconds per stage into host_stage_ms[dyllm_stage_count()] and
+ * the number of recorded calls into *host_calls, and switches profiling off.  A stage's time runs
+ * from the end of the previous stage to its own end on the stream. */
+int dyllm_profile_begin(dyllm_ctx *ctx, int32_t max_calls);
+int dyllm_profile_end(dyllm_ctx *ctx, float *host_stage_ms, int32_t *host_calls);
+int dyllm_stage_count(void);
+const char *dyllm_stage_name(int stage);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DYLLM_H */

@@ -1,0 +1,483 @@
+// C ABI of the library: context, argument checks on the host, and the composition of the
+// kernels into the boundary calls.  Everything is enqueued on the caller's stream; row counts stay
+// on the device.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "../../include/dyllm.h"
+#include "kernels.h"
+
+using namespace dy;
+
+struct dyllm_ctx {
+  dyllm_layer_cfg cfg;
+  int rows_cap;  // max rows of one call
+  int dq, dkv;
+  size_t esz;
+  char *ws;  // one device allocation, carved below
+  size_t ws_bytes;
+  // carved buffers
+  void *ns;        // [R, d]        normalised salient rows
+  float *qkv;      // [R, dq+2dkv]  fp32 projections before rotation
+  void *qs;        // [R, dq]       rotated queries
+  float *part_o;   // attention split partials
+  float *part_ml;
+  size_t part_elems;
+  void *cs;        // [R, dq]       new contexts of the candidate rows
+  float *cosb;     // [R]
+  uint8_t *flag;   // [R]
+  float *hs;       // [R, d]        x + Wo c (fp32)
+  void *fs;        // [R, d]        RMSNorm(h)
+  void *act;       // [R, F]        silu(gate)*up
+  int32_t *status; // device status word
+  float *rope;     // [max_seq, dh/2, 2]
+  // optional per-stage timing (dyllm_profile_begin / _end)
+  std::vector<hipEvent_t> *prof_events;
+  int prof_max_calls, prof_calls;
+  hipEvent_t *prof_cur;
+  char err[256];
+};
+
+namespace {
+
+struct Layout {
+  size_t ns, qkv, qs, part_o, part_ml, cs, cosb, flag, hs, fs, act, status, rope, total;
+  size_t part_elems;
+};
+
+size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+Layout make_layout(const dyllm_layer_cfg &c) {
+  Layout l;
+  const size_t R = c.max_rows > 0 ? (size_t)c.max_rows : (size_t)c.max_batch * c.max_seq;
+  const size_t e = c.dtype == DYLLM_F32 ? 4 : 2;
+  const size_t d = c.hidden, dq = (size_t)c.n_heads * c.head_dim, dkv = (size_t)c.n_kv_heads * c.head_dim;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  l.ns = take(R * d * e);
+  l.qkv = take(R * (dq + 2 * dkv) * 4);
+  l.qs = take(R * dq * e);
+  // split partials: room for 16 splits of up to 2048 rows, or one set of R rows
+  const size_t prow = R < 2048 ? R : 2048;
+  l.part_elems = (16 * prow > R ? 16 * prow : R) * dq;
+  l.part_o = take(l.part_elems * 4);
+  l.part_ml = take(l.part_elems / c.head_dim * 2 * 4);
+  l.cs = take(R * dq * e);
+  l.cosb = take(R * 4);
+  l.flag = take(R);
+  l.hs = take(R * d * 4);
+  l.fs = take(R * d * e);
+  l.act = take(R * (size_t)c.ffn_dim * e);
+  l.status = take(256);
+  l.rope = take((size_t)c.max_seq * (c.head_dim / 2) * 2 * 4);
+  l.total = off;
+  return l;
+}
+
+int check_cfg(const dyllm_layer_cfg *c) {
+  if (!c) return DYLLM_ERR_INVALID_ARG;
+  if (c->dtype != DYLLM_F32 && c->dtype != DYLLM_BF16) return DYLLM_ERR_INVALID_ARG;
+  if (c->hidden <= 0 || c->n_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 || c->ffn_dim <= 0 ||
+      c->max_batch <= 0 || c->max_seq <= 0 || c->max_rows < 0)
+    return DYLLM_ERR_INVALID_ARG;
+  if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return DYLLM_ERR_INVALID_ARG;
+  if (c->n_heads % c->n_kv_heads) return DYLLM_ERR_BAD_SHAPE;
+  if ((long)c->max_batch * c->max_seq > (1l << 30)) return DYLLM_ERR_UNSUPPORTED;
+  if (c->max_rows > 0 && (long)c->max_rows > (long)c->max_batch * c->max_seq) return DYLLM_ERR_BAD_SHAPE;
+  if (c->head_dim != 64 && c->head_dim != 128) return DYLLM_ERR_UNSUPPORTED;
+  const int q = c->dtype == DYLLM_BF16 ? 128 : 64;
+  if (c->hidden % q || c->ffn_dim % q || (c->n_heads * c->head_dim) % q) return DYLLM_ERR_UNSUPPORTED;
+  return DYLLM_OK;
+}
+
+int fail(dyllm_ctx *ctx, int code, const char *what) {
+  if (ctx) snprintf(ctx->err, sizeof(ctx->err), "%s: %s", dyllm_strerror(code), what);
+  return code;
+}
+
+int hip_fail(dyllm_ctx *ctx, hipError_t e, const char *where) {
+  if (ctx) ctx->prof_cur = nullptr;
+  if (ctx) snprintf(ctx->err, sizeof(ctx->err), "HIP error at %s: %s", where, hipGetErrorString(e));
+  return DYLLM_ERR_HIP;
+}
+
+int check_launch(dyllm_ctx *ctx, const char *where) {
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? DYLLM_OK : hip_fail(ctx, e, where);
+}
+
+int check_bl(dyllm_ctx *ctx, int B, int L) {
+  if (B <= 0 || L <= 0) return fail(ctx, DYLLM_ERR_INVALID_ARG, "B and L must be positive");
+  if (B > ctx->cfg.max_batch || L > ctx->cfg.max_seq)
+    return fail(ctx, DYLLM_ERR_BAD_SHAPE, "B or L exceeds the context's max_batch / max_seq");
+  return DYLLM_OK;
+}
+
+int check_list(dyllm_ctx *ctx, const dyllm_index_list *l, const char *name) {
+  if (!l || !l->idx || !l->offsets) return fail(ctx, DYLLM_ERR_INVALID_ARG, name);
+  if (l->cap < 0) return fail(ctx, DYLLM_ERR_INVALID_ARG, "negative list capacity");
+  if (l->cap > ctx->rows_cap) return fail(ctx, DYLLM_ERR_CAPACITY, "list capacity exceeds the context's max_rows");
+  return DYLLM_OK;
+}
+
+Rows rows_of(const dyllm_index_list *l, int B) { return Rows{l->idx, l->offsets + B, l->cap}; }
+
+DType dt(const dyllm_ctx *c) { return c->cfg.dtype == DYLLM_F32 ? F32 : BF16; }
+
+// Stages of a step in execution order; with profiling on, an event is recorded after each.
+enum Stage {
+  ST_GATHER_NORM = 0, ST_GEMM_QKV, ST_ROPE_SCATTER, ST_ATTENTION, ST_SALIENCY, ST_COMPACT, ST_GEMM_OPROJ,
+  ST_NORM_FFN, ST_GEMM_SWIGLU, ST_GEMM_DOWN, N_STAGES
+};
+const char *const kStageNames[N_STAGES] = {
+    "gather_rmsnorm", "gemm_qkv", "rope_scatter", "partial_attention", "saliency", "compact",
+    "gemm_oproj", "rmsnorm_ffn", "gemm_swiglu", "gemm_down"};
+
+void prof_begin_call(dyllm_ctx *ctx, hipStream_t s) {
+  ctx->prof_cur = nullptr;
+  if (!ctx->prof_events || ctx->prof_calls >= ctx->prof_max_calls) return;
+  ctx->prof_cur = ctx->prof_events->data() + (size_t)ctx->prof_calls * (N_STAGES + 1);
+  ++ctx->prof_calls;
+  (void)hipEventRecord(ctx->prof_cur[0], s);
+}
+void prof_mark(dyllm_ctx *ctx, int stage, hipStream_t s) {
+  if (ctx->prof_cur) (void)hipEventRecord(ctx->prof_cur[stage + 1], s);
+}
+
+// a-1..a-3: gather + norm, q/k/v projection, rotation, K/V merge
+int enqueue_qkv(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x, Rows rows, int L,
+                dyllm_layer_cache *cache, void *q_out, hipStream_t s) {
+  const dyllm_layer_cfg &c = ctx->cfg;
+  launch_gather_rmsnorm(dt(ctx), x, w->g_attn, rows, c.hidden, c.rms_eps, ctx->ns, s);
+  prof_mark(ctx, ST_GATHER_NORM, s);
+  launch_gemm_qkv(dt(ctx), GemmA{ctx->ns, nullptr, c.hidden}, rows, c.hidden, w->wq, w->wk, w->wv,
+                  ctx->dq, ctx->dkv, ctx->qkv, s);
+  prof_mark(ctx, ST_GEMM_QKV, s);
+  launch_rope_scatter(dt(ctx), ctx->qkv, ctx->rope, rows, L, c.n_heads, c.n_kv_heads, c.head_dim,
+                      w->bq, w->bk, w->bv, q_out, cache->k, cache->v, s);
+  prof_mark(ctx, ST_ROPE_SCATTER, s);
+  return check_launch(ctx, "qkv refresh");
+}
+
+int enqueue_attention(dyllm_ctx *ctx, const void *q, const void *k, const void *v, Rows rows,
+                      const int32_t *offsets, int B, int L, void *out, hipStream_t s) {
+  const dyllm_layer_cfg &c = ctx->cfg;
+  AttnArgs a;
+  a.q = q; a.k = k; a.v = v; a.rows = rows; a.offsets = offsets;
+  a.B = B; a.L = L; a.H = c.n_heads; a.Hkv = c.n_kv_heads; a.dh = c.head_dim;
+  attention_plan(dt(ctx), B, L, c.n_heads, c.head_dim, rows.cap, ctx->part_elems, &a.splits, &a.chunk);
+  a.part_o = ctx->part_o; a.part_ml = ctx->part_ml; a.out = out;
+  launch_attention(dt(ctx), a, s);
+  prof_mark(ctx, ST_ATTENTION, s);
+  return check_launch(ctx, "partial attention");
+}
+
+// a-7..a-9: out-projection + residual, norm, SwiGLU FFN + residual, scatter into the output cache
+int enqueue_ffn(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x, const void *c_all,
+                Rows rows, void *out_cache, hipStream_t s) {
+  const dyllm_layer_cfg &c = ctx->cfg;
+  launch_gemm_oproj(dt(ctx), GemmA{c_all, rows.idx, ctx->dq}, rows, ctx->dq, c.hidden, w->wo, x,
+                    ctx->hs, s);
+  prof_mark(ctx, ST_GEMM_OPROJ, s);
+  launch_rmsnorm_f32in(dt(ctx), ctx->hs, w->g_ffn, rows, c.hidden, c.rms_eps, ctx->fs, s);
+  prof_mark(ctx, ST_NORM_FFN, s);
+  launch_gemm_swiglu(dt(ctx), GemmA{ctx->fs, nullptr, c.hidden}, rows, c.hidden, c.ffn_dim, w->w_gate,
+                     w->w_up, ctx->act, s);
+  prof_mark(ctx, ST_GEMM_SWIGLU, s);
+  launch_gemm_down(dt(ctx), GemmA{ctx->act, nullptr, c.ffn_dim}, rows, c.ffn_dim, c.hidden, w->w_down,
+                   ctx->hs, out_cache, s);
+  prof_mark(ctx, ST_GEMM_DOWN, s);
+  return check_launch(ctx, "salient ffn");
+}
+
+int check_weights(dyllm_ctx *ctx, const dyllm_layer_weights *w, bool attn, bool ffn) {
+  if (!w) return fail(ctx, DYLLM_ERR_INVALID_ARG, "weights is NULL");
+  if (attn && (!w->wq || !w->wk || !w->wv || !w->g_attn))
+    return fail(ctx, DYLLM_ERR_INVALID_ARG, "wq / wk / wv / g_attn is NULL");
+  if (ffn && (!w->wo || !w->w_gate || !w->w_up || !w->w_down || !w->g_ffn))
+    return fail(ctx, DYLLM_ERR_INVALID_ARG, "wo / w_gate / w_up / w_down / g_ffn is NULL");
+  return DYLLM_OK;
+}
+
+int check_cache(dyllm_ctx *ctx, const dyllm_layer_cache *c) {
+  if (!c || !c->k || !c->v || !c->c || !c->out) return fail(ctx, DYLLM_ERR_INVALID_ARG, "cache pointer is NULL");
+  return DYLLM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *dyllm_strerror(int code) {
+  switch (code) {
+    case DYLLM_OK: return "ok";
+    case DYLLM_ERR_INVALID_ARG: return "invalid argument";
+    case DYLLM_ERR_BAD_SHAPE: return "bad shape";
+    case DYLLM_ERR_UNSUPPORTED: return "unsupported configuration";
+    case DYLLM_ERR_NO_MEM: return "out of device memory";
+    case DYLLM_ERR_HIP: return "HIP runtime error";
+    case DYLLM_ERR_CAPACITY: return "index list capacity exceeded";
+    default: return "unknown error";
+  }
+}
+
+const char *dyllm_last_error(const dyllm_ctx *ctx) { return ctx ? ctx->err : "no context"; }
+
+int dyllm_workspace_bytes(const dyllm_layer_cfg *cfg, size_t *host_bytes) {
+  if (!host_bytes) return DYLLM_ERR_INVALID_ARG;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  *host_bytes = make_layout(*cfg).total;
+  return DYLLM_OK;
+}
+
+int dyllm_create(const dyllm_layer_cfg *cfg, dyllm_ctx **out) {
+  if (!out) return DYLLM_ERR_INVALID_ARG;
+  *out = nullptr;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  dyllm_ctx *ctx = new (std::nothrow) dyllm_ctx;
+  if (!ctx) return DYLLM_ERR_NO_MEM;
+  memset(ctx, 0, sizeof(*ctx));
+  ctx->cfg = *cfg;
+  ctx->rows_cap = cfg->max_rows > 0 ? cfg->max_rows : cfg->max_batch * cfg->max_seq;
+  ctx->dq = cfg->n_heads * cfg->head_dim;
+  ctx->dkv = cfg->n_kv_heads * cfg->head_dim;
+  ctx->esz = cfg->dtype == DYLLM_F32 ? 4 : 2;
+  const Layout l = make_layout(*cfg);
+  ctx->ws_bytes = l.total;
+  if (hipMalloc((void **)&ctx->ws, l.total) != hipSuccess) {
+    (void)hipGetLastError();
+    delete ctx;
+    return DYLLM_ERR_NO_MEM;
+  }
+  char *b = ctx->ws;
+  ctx->ns = b + l.ns; ctx->qkv = (float *)(b + l.qkv); ctx->qs = b + l.qs;
+  ctx->part_o = (float *)(b + l.part_o); ctx->part_ml = (float *)(b + l.part_ml);
+  ctx->part_elems = l.part_elems;
+  ctx->cs = b + l.cs; ctx->cosb = (float *)(b + l.cosb); ctx->flag = (uint8_t *)(b + l.flag);
+  ctx->hs = (float *)(b + l.hs); ctx->fs = b + l.fs; ctx->act = b + l.act;
+  ctx->status = (int32_t *)(b + l.status); ctx->rope = (float *)(b + l.rope);
+
+  // rotary table in double precision on the host, cleared status word
+  const int half = cfg->head_dim / 2;
+  std::vector<float> tab((size_t)cfg->max_seq * half * 2);
+  for (int p = 0; p < cfg->max_seq; ++p)
+    for (int j = 0; j < half; ++j) {
+      const double ang = (double)p * pow((double)cfg->rope_theta, -2.0 * j / cfg->head_dim);
+      tab[((size_t)p * half + j) * 2] = (float)cos(ang);
+      tab[((size_t)p * half + j) * 2 + 1] = (float)sin(ang);
+    }
+  hipError_t e = hipMemcpy(ctx->rope, tab.data(), tab.size() * 4, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemset(ctx->status, 0, 256);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    (void)hipFree(ctx->ws);
+    delete ctx;
+    return DYLLM_ERR_HIP;
+  }
+  *out = ctx;
+  return DYLLM_OK;
+}
+
+int dyllm_profile_begin(dyllm_ctx *ctx, int32_t max_calls) {
+  if (!ctx || max_calls <= 0 || max_calls > 4096) return DYLLM_ERR_INVALID_ARG;
+  if (ctx->prof_events) return fail(ctx, DYLLM_ERR_INVALID_ARG, "profiling already on");
+  auto *ev = new (std::nothrow) std::vector<hipEvent_t>((size_t)max_calls * (N_STAGES + 1));
+  if (!ev) return DYLLM_ERR_NO_MEM;
+  for (size_t i = 0; i < ev->size(); ++i)
+    if (hipEventCreate(&(*ev)[i]) != hipSuccess) {
+      for (size_t k = 0; k < i; ++k) (void)hipEventDestroy((*ev)[k]);
+      delete ev;
+      return hip_fail(ctx, hipGetLastError(), "hipEventCreate");
+    }
+  ctx->prof_events = ev;
+  ctx->prof_max_calls = max_calls;
+  ctx->prof_calls = 0;
+  ctx->prof_cur = nullptr;
+  return DYLLM_OK;
+}
+
+int dyllm_profile_end(dyllm_ctx *ctx, float *host_stage_ms, int32_t *host_calls) {
+  if (!ctx || !host_stage_ms || !host_calls) return DYLLM_ERR_INVALID_ARG;
+  if (!ctx->prof_events) return fail(ctx, DYLLM_ERR_INVALID_ARG, "profiling is not on");
+  std::vector<hipEvent_t> &ev = *ctx->prof_events;
+  int rc = DYLLM_OK;
+  for (int i = 0; i < N_STAGES; ++i) host_stage_ms[i] = 0.f;
+  for (int c = 0; c < ctx->prof_calls && rc == DYLLM_OK; ++c) {
+    hipEvent_t *e = ev.data() + (size_t)c * (N_STAGES + 1);
+    if (hipEventSynchronize(e[N_STAGES]) != hipSuccess) rc = hip_fail(ctx, hipGetLastError(), "event sync");
+    for (int i = 0; i < N_STAGES && rc == DYLLM_OK; ++i) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, e[i], e[i + 1]) != hipSuccess) rc = hip_fail(ctx, hipGetLastError(), "event elapsed");
+      host_stage_ms[i] += ms;
+    }
+  }
+  *host_calls = ctx->prof_calls;
+  if (rc == DYLLM_OK && ctx->prof_calls > 0)
+    for (int i = 0; i < N_STAGES; ++i) host_stage_ms[i] /= (float)ctx->prof_calls;
+  for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+  delete ctx->prof_events;
+  ctx->prof_events = nullptr;
+  ctx->prof_cur = nullptr;
+  return rc;
+}
+
+int dyllm_stage_count(void) { return N_STAGES; }
+const char *dyllm_stage_name(int stage) { return (stage >= 0 && stage < N_STAGES) ? kStageNames[stage] : ""; }
+
+int dyllm_destroy(dyllm_ctx *ctx) {
+  if (!ctx) return DYLLM_ERR_INVALID_ARG;
+  if (ctx->prof_events) {
+    for (hipEvent_t e : *ctx->prof_events) (void)hipEventDestroy(e);
+    delete ctx->prof_events;
+  }
+  hipError_t e = hipFree(ctx->ws);
+  delete ctx;
+  return e == hipSuccess ? DYLLM_OK : DYLLM_ERR_HIP;
+}
+
+int dyllm_poll_status(dyllm_ctx *ctx, int32_t *host_status, void *stream) {
+  if (!ctx || !host_status) return DYLLM_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t e = hipMemcpyAsync(host_status, ctx->status, 4, hipMemcpyDeviceToHost, s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "poll_status copy");
+  launch_fill_i32(ctx->status, 0, 1, s);
+  e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "poll_status sync");
+  return DYLLM_OK;
+}
+
+int dyllm_saliency(dyllm_ctx *ctx, const void *c_new, void *c_cache, const dyllm_index_list *rows,
+                   int32_t B, int32_t L, float tau, float *cos_out, uint8_t *flag_out, int commit,
+                   void *stream) {
+  if (!ctx) return DYLLM_ERR_INVALID_ARG;
+  if (!c_new || !c_cache || !flag_out) return fail(ctx, DYLLM_ERR_INVALID_ARG, "NULL tensor");
+  int rc = check_bl(ctx, B, L);
+  if (rc) return rc;
+  Rows r;
+  if (rows) {
+    if ((rc = check_list(ctx, rows, "rows"))) return rc;
+    r = rows_of(rows, B);
+  } else {
+    if (commit && c_new == c_cache) return fail(ctx, DYLLM_ERR_INVALID_ARG, "commit onto itself");
+    r = Rows{nullptr, nullptr, B * L};
+  }
+  launch_saliency(dt(ctx), c_new, c_cache, r, ctx->dq, tau, cos_out, flag_out, commit, (hipStream_t)stream);
+  return check_launch(ctx, "saliency");
+}
+
+int dyllm_compact(dyllm_ctx *ctx, const uint8_t *flag, const dyllm_index_list *rows, int32_t B,
+                  int32_t L, dyllm_index_list *out, void *stream) {
+  if (!ctx) return DYLLM_ERR_INVALID_ARG;
+  if (!flag || !out || !out->idx || !out->offsets || out->cap < 0)
+    return fail(ctx, DYLLM_ERR_INVALID_ARG, "NULL flag or output list");
+  int rc = check_bl(ctx, B, L);
+  if (rc) return rc;
+  Rows r;
+  if (rows) {
+    if ((rc = check_list(ctx, rows, "rows"))) return rc;
+    r = rows_of(rows, B);
+  } else {
+    r = Rows{nullptr, nullptr, B * L};
+  }
+  launch_compact(flag, r, B, L, out->idx, out->offsets, out->cap, ctx->status, (hipStream_t)stream);
+  return check_launch(ctx, "compact");
+}
+
+int dyllm_qkv_refresh(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x,
+                      const dyllm_index_list *rows, int32_t B, int32_t L, dyllm_layer_cache *cache,
+                      void *q_sal_out, void *stream) {
+  if (!ctx) return DYLLM_ERR_INVALID_ARG;
+  int rc;
+  if ((rc = check_weights(ctx, w, true, false))) return rc;
+  if (!x || !q_sal_out || !cache || !cache->k || !cache->v) return fail(ctx, DYLLM_ERR_INVALID_ARG, "NULL tensor");
+  if ((rc = check_bl(ctx, B, L))) return rc;
+  if ((rc = check_list(ctx, rows, "rows"))) return rc;
+  return enqueue_qkv(ctx, w, x, rows_of(rows, B), L, cache, q_sal_out, (hipStream_t)stream);
+}
+
+int dyllm_partial_attention(dyllm_ctx *ctx, const void *q_sal, const void *k_cache,
+                            const void *v_cache, const dyllm_index_list *rows, int32_t B, int32_t L,
+                            void *c_sal_out, void *stream) {
+  if (!ctx) return DYLLM_ERR_INVALID_ARG;
+  if (!q_sal || !k_cache || !v_cache || !c_sal_out) return fail(ctx, DYLLM_ERR_INVALID_ARG, "NULL tensor");
+  int rc;
+  if ((rc = check_bl(ctx, B, L))) return rc;
+  if ((rc = check_list(ctx, rows, "rows"))) return rc;
+  return enqueue_attention(ctx, q_sal, k_cache, v_cache, rows_of(rows, B), rows->offsets, B, L,
+                           c_sal_out, (hipStream_t)stream);
+}
+
+int dyllm_salient_ffn(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x, const void *c,
+                      const dyllm_index_list *rows_out, int32_t B, int32_t L, void *out_cache,
+                      void *stream) {
+  if (!ctx) return DYLLM_ERR_INVALID_ARG;
+  int rc;
+  if ((rc = check_weights(ctx, w, false, true))) return rc;
+  if (!x || !c || !out_cache) return fail(ctx, DYLLM_ERR_INVALID_ARG, "NULL tensor");
+  if (x == out_cache) return fail(ctx, DYLLM_ERR_INVALID_ARG, "x aliases out_cache");
+  if ((rc = check_bl(ctx, B, L))) return rc;
+  if ((rc = check_list(ctx, rows_out, "rows_out"))) return rc;
+  return enqueue_ffn(ctx, w, x, c, rows_of(rows_out, B), out_cache, (hipStream_t)stream);
+}
+
+int dyllm_layer_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
+                     const void *x, const dyllm_index_list *idx_in, int32_t B, int32_t L, float tau,
+                     dyllm_index_list *idx_out, float *cos_out, void *stream) {
+  if (!ctx) return DYLLM_ERR_INVALID_ARG;
+  int rc;
+  if ((rc = check_weights(ctx, w, true, true))) return rc;
+  if ((rc = check_cache(ctx, cache))) return rc;
+  if (!x) return fail(ctx, DYLLM_ERR_INVALID_ARG, "x is NULL");
+  if (x == cache->out) return fail(ctx, DYLLM_ERR_INVALID_ARG, "x aliases cache->out");
+  if ((rc = check_bl(ctx, B, L))) return rc;
+  if ((rc = check_list(ctx, idx_in, "idx_in"))) return rc;
+  if ((rc = check_list(ctx, idx_out, "idx_out"))) return rc;
+  if (idx_out->idx == idx_in->idx || idx_out->offsets == idx_in->offsets)
+    return fail(ctx, DYLLM_ERR_INVALID_ARG, "idx_out aliases idx_in");
+  hipStream_t s = (hipStream_t)stream;
+  const Rows rin = rows_of(idx_in, B);
+  prof_begin_call(ctx, s);
+  if ((rc = enqueue_qkv(ctx, w, x, rin, L, cache, ctx->qs, s))) return rc;
+  if ((rc = enqueue_attention(ctx, ctx->qs, cache->k, cache->v, rin, idx_in->offsets, B, L, ctx->cs, s)))
+    return rc;
+  launch_saliency(dt(ctx), ctx->cs, cache->c, rin, ctx->dq, tau, cos_out ? cos_out : ctx->cosb,
+                  ctx->flag, 1, s);
+  prof_mark(ctx, ST_SALIENCY, s);
+  launch_compact(ctx->flag, rin, B, L, idx_out->idx, idx_out->offsets, idx_out->cap, ctx->status, s);
+  prof_mark(ctx, ST_COMPACT, s);
+  if ((rc = check_launch(ctx, "saliency / compact"))) return rc;
+  rc = enqueue_ffn(ctx, w, x, cache->c, rows_of(idx_out, B), cache->out, s);
+  ctx->prof_cur = nullptr;
+  return rc;
+}
+
+int dyllm_full_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
+                    const void *x, int32_t B, int32_t L, void *stream) {
+  if (!ctx) return DYLLM_ERR_INVALID_ARG;
+  int rc;
+  if ((rc = check_weights(ctx, w, true, true))) return rc;
+  if ((rc = check_cache(ctx, cache))) return rc;
+  if (!x) return fail(ctx, DYLLM_ERR_INVALID_ARG, "x is NULL");
+  if (x == cache->out) return fail(ctx, DYLLM_ERR_INVALID_ARG, "x aliases cache->out");
+  if ((rc = check_bl(ctx, B, L))) return rc;
+  if ((long)B * L > ctx->rows_cap) return fail(ctx, DYLLM_ERR_CAPACITY, "B*L exceeds the context's max_rows");
+  hipStream_t s = (hipStream_t)stream;
+  const Rows all{nullptr, nullptr, B * L};
+  prof_begin_call(ctx, s);
+  if ((rc = enqueue_qkv(ctx, w, x, all, L, cache, ctx->qs, s))) return rc;
+  // every row is a query: the context cache is written directly
+  if ((rc = enqueue_attention(ctx, ctx->qs, cache->k, cache->v, all, nullptr, B, L, cache->c, s))) return rc;
+  prof_mark(ctx, ST_SALIENCY, s);
+  prof_mark(ctx, ST_COMPACT, s);
+  rc = enqueue_ffn(ctx, w, x, cache->c, all, cache->out, s);
+  ctx->prof_cur = nullptr;
+  return rc;
+}
+
+}  // extern "C"

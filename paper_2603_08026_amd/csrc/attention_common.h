@@ -1,0 +1,58 @@
+// Pieces shared by the partial-attention kernels: the mapping from a workgroup's tile number to
+// (sequence, first query row, row count) over ragged per-sequence row lists, and the key-range
+// split arithmetic.
+#pragma once
+#include "common.h"
+#include "kernels.h"
+
+namespace dy {
+
+// Upper bound (host) of the number of query tiles: sum_b ceil(n_b / BQ) <= cap/BQ + B.
+inline int max_q_tiles(const AttnArgs &a, int BQ) {
+  if (!a.offsets) return a.B * ((a.L + BQ - 1) / BQ);
+  int t = (a.rows.cap + BQ - 1) / BQ + a.B;
+  return t < 1 ? 1 : t;
+}
+
+// Keys per split, a multiple of the key tile BK.
+__host__ __device__ inline int split_chunk(int L, int splits, int BK) {
+  int c = (L + splits - 1) / splits;
+  return ((c + BK - 1) / BK) * BK;
+}
+
+// Tile number -> info[0] = sequence (or -1 if the tile does not exist), info[1] = index of its
+// first query row in the row list, info[2] = rows in the tile.  Called by one thread.
+__device__ inline void find_tile(const AttnArgs &a, int BQ, int tile, int *info) {
+  info[0] = -1;
+  info[1] = 0;
+  info[2] = 0;
+  if (!a.offsets) {
+    const int per = (a.L + BQ - 1) / BQ;
+    const int b = tile / per, t = tile % per;
+    if (b < a.B) {
+      info[0] = b;
+      info[1] = b * a.L + t * BQ;
+      info[2] = min(BQ, a.L - t * BQ);
+    }
+    return;
+  }
+  const int total = min(a.offsets[a.B], a.rows.cap);
+  int t = tile;
+  for (int b = 0; b < a.B; ++b) {
+    const int lo = min(a.offsets[b], total), hi = min(a.offsets[b + 1], total);
+    const int nt = (hi - lo + BQ - 1) / BQ;
+    if (t < nt) {
+      info[0] = b;
+      info[1] = lo + t * BQ;
+      info[2] = min(BQ, hi - lo - t * BQ);
+      return;
+    }
+    t -= nt;
+  }
+}
+
+void launch_attention_f32(DType t, const AttnArgs &a, hipStream_t s);
+void launch_attention_bf16(const AttnArgs &a, hipStream_t s);
+void launch_attn_combine(DType t, const AttnArgs &a, hipStream_t s);
+
+}  // namespace dy

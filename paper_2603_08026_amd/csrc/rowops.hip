@@ -1,0 +1,273 @@
+// Row-wise kernels of the sparse layer step: gather + RMSNorm, rotary embedding + K/V merge,
+// cosine saliency (+ context commit), stream compaction.  All are HBM-bound: one workgroup walks
+// one token row with 16-byte loads, reductions in fp32.
+#include "common.h"
+#include "kernels.h"
+
+namespace dy {
+
+namespace {
+
+constexpr int RB = 256;  // threads per row workgroup
+
+__device__ __forceinline__ int row_count(const Rows &rows) {
+  return rows.count ? min(*rows.count, rows.cap) : rows.cap;
+}
+
+// ---- gather + RMSNorm  [Alg. 3: layernorm(x) restricted to the salient rows] -------------------
+template <typename T>
+__global__ __launch_bounds__(RB) void k_gather_rmsnorm(const T *__restrict__ x,
+                                                        const T *__restrict__ gain, Rows rows, int d,
+                                                        float eps, T *__restrict__ out) {
+  __shared__ float red[RB / WAVE];
+  constexpr int N = Vec16<T>::N;
+  const int n = row_count(rows), nv = d / N;
+  for (int j = blockIdx.x; j < n; j += gridDim.x) {
+    const int r = rows.idx ? rows.idx[j] : j;
+    const T *xr = x + (size_t)r * d;
+    float ss = 0.f;
+    for (int v = threadIdx.x; v < nv; v += RB) {
+      Vec16<T> a = ld16(xr + v * N);
+#pragma unroll
+      for (int i = 0; i < N; ++i) ss += a.get(i) * a.get(i);
+    }
+    ss = block_sum<RB>(ss, red);
+    const float sc = 1.0f / sqrtf(ss / (float)d + eps);
+    T *orow = out + (size_t)j * d;
+    for (int v = threadIdx.x; v < nv; v += RB) {
+      Vec16<T> a = ld16(xr + v * N), g = ld16(gain + v * N), o;
+#pragma unroll
+      for (int i = 0; i < N; ++i) o.set(i, a.get(i) * sc * g.get(i));
+      st16(orow + v * N, o);
+    }
+  }
+}
+
+// ---- RMSNorm of fp32 rows (input of the FFN) ---------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(RB) void k_rmsnorm_f32in(const float *__restrict__ h,
+                                                       const T *__restrict__ gain, Rows rows, int d,
+                                                       float eps, T *__restrict__ out) {
+  __shared__ float red[RB / WAVE];
+  const int n = row_count(rows), nv = d / 4;
+  for (int j = blockIdx.x; j < n; j += gridDim.x) {
+    const float *hr = h + (size_t)j * d;
+    float ss = 0.f;
+    for (int v = threadIdx.x; v < nv; v += RB) {
+      float4 a = *reinterpret_cast<const float4 *>(hr + v * 4);
+      ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+    }
+    ss = block_sum<RB>(ss, red);
+    const float sc = 1.0f / sqrtf(ss / (float)d + eps);
+    T *orow = out + (size_t)j * d;
+    for (int v = threadIdx.x; v < nv; v += RB) {
+      float4 a = *reinterpret_cast<const float4 *>(hr + v * 4);
+      const T *g = gain + v * 4;
+      orow[v * 4 + 0] = from_f<T>(a.x * sc * to_f<T>(g[0]));
+      orow[v * 4 + 1] = from_f<T>(a.y * sc * to_f<T>(g[1]));
+      orow[v * 4 + 2] = from_f<T>(a.z * sc * to_f<T>(g[2]));
+      orow[v * 4 + 3] = from_f<T>(a.w * sc * to_f<T>(g[3]));
+    }
+  }
+}
+
+// ---- bias + rotary embedding + K/V merge  [Alg. 3: K[idx] <- k_proj(x[idx]), same for V] -------
+// Half-split pairing: element p of a head couples with element p + dh/2, rotated by the angle
+// pos * theta^(-2p/dh); the table holds (cos, sin) per (pos, p).
+template <typename T>
+__global__ __launch_bounds__(RB) void k_rope_scatter(const float *__restrict__ qkv,
+                                                      const float *__restrict__ tab, Rows rows, int L,
+                                                      int H, int Hkv, int dh, const T *__restrict__ bq,
+                                                      const T *__restrict__ bk,
+                                                      const T *__restrict__ bv, T *__restrict__ q_out,
+                                                      T *__restrict__ kc, T *__restrict__ vc) {
+  const int n = row_count(rows);
+  const int half = dh / 2, dq = H * dh, dkv = Hkv * dh, ld = dq + 2 * dkv;
+  const int qpairs = H * half, kpairs = Hkv * half;
+  for (int j = blockIdx.x; j < n; j += gridDim.x) {
+    const int r = rows.idx ? rows.idx[j] : j;
+    const int pos = r % L;
+    const float *src = qkv + (size_t)j * ld;
+    const float *t = tab + (size_t)pos * half * 2;
+    for (int e = threadIdx.x; e < qpairs + kpairs; e += RB) {
+      const bool isq = e < qpairs;
+      const int ee = isq ? e : e - qpairs;
+      const int head = ee / half, p = ee % half;
+      const int c0 = head * dh + p, c1 = c0 + half;
+      const float *s = isq ? src : src + dq;
+      const T *b = isq ? bq : bk;
+      float x1 = s[c0], x2 = s[c1];
+      if (b) {
+        x1 += to_f<T>(b[c0]);
+        x2 += to_f<T>(b[c1]);
+      }
+      const float cs = t[2 * p], sn = t[2 * p + 1];
+      const float y1 = x1 * cs - x2 * sn, y2 = x2 * cs + x1 * sn;
+      T *dst = isq ? q_out + (size_t)j * dq : kc + (size_t)r * dkv;
+      dst[c0] = from_f<T>(y1);
+      dst[c1] = from_f<T>(y2);
+    }
+    const float *sv = src + dq + dkv;
+    T *dv = vc + (size_t)r * dkv;
+    for (int e = threadIdx.x; e < dkv; e += RB) {
+      float v = sv[e];
+      if (bv) v += to_f<T>(bv[e]);
+      dv[e] = from_f<T>(v);
+    }
+  }
+}
+
+// ---- temporal cosine similarity + salient test (+ commit)  [Sec. 3.1, Sec. 3.2] ----------------
+// s = <a,b> / (max(|a|,1e-8) max(|b|,1e-8)), flag = s < tau.  The old cache row b is read before
+// the same thread overwrites the same elements with a.
+template <typename T>
+__global__ __launch_bounds__(RB) void k_saliency(const T *__restrict__ c_new, T *c_cache, Rows rows,
+                                                  int D, float tau, float *__restrict__ cos_out,
+                                                  uint8_t *__restrict__ flag_out, int commit) {
+  __shared__ float red[RB / WAVE];
+  constexpr int N = Vec16<T>::N;
+  const int n = row_count(rows), nv = D / N;
+  for (int j = blockIdx.x; j < n; j += gridDim.x) {
+    const int r = rows.idx ? rows.idx[j] : j;
+    const T *a = c_new + (size_t)j * D;
+    T *b = c_cache + (size_t)r * D;
+    float dot = 0.f, na = 0.f, nb = 0.f;
+    for (int v = threadIdx.x; v < nv; v += RB) {
+      Vec16<T> va = ld16(a + v * N), vb = ld16(b + v * N);
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        const float fa = va.get(i), fb = vb.get(i);
+        dot += fa * fb;
+        na += fa * fa;
+        nb += fb * fb;
+      }
+      if (commit) st16(b + v * N, va);
+    }
+    dot = block_sum<RB>(dot, red);
+    na = block_sum<RB>(na, red);
+    nb = block_sum<RB>(nb, red);
+    if (threadIdx.x == 0) {
+      const float s = dot / (fmaxf(sqrtf(na), 1e-8f) * fmaxf(sqrtf(nb), 1e-8f));
+      if (cos_out) cos_out[j] = s;
+      flag_out[j] = (s < tau) ? 1 : 0;
+    }
+  }
+}
+
+// ---- stream compaction  [Alg. 3: idx_sal <- where(cos < tau)] ----------------------------------
+// One workgroup of 1024 threads sweeps the flags in chunks of 1024: wave64 ballot + popcount give
+// each flagged lane its rank inside the wave, 16 per-wave totals are combined through LDS.  The
+// output keeps the input order, so it is ascending.  Per-sequence offsets are found afterwards by
+// binary search for b*L in the list just written.
+constexpr int CB = 1024;
+
+__global__ __launch_bounds__(CB) void k_compact(const uint8_t *__restrict__ flag, Rows rows, int B,
+                                                 int L, int32_t *out_idx, int32_t *out_off,
+                                                 int out_cap, int32_t *status, int overflow_code) {
+  __shared__ int wave_cnt[CB / WAVE];
+  const int n = row_count(rows);
+  const int tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
+  int base = 0;
+  for (int start = 0; start < n; start += CB) {
+    const int j = start + tid;
+    const bool f = (j < n) && (flag[j] != 0);
+    const unsigned long long bal = __ballot(f);
+    const int before = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) wave_cnt[w] = __popcll(bal);
+    __syncthreads();
+    int woff = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < CB / WAVE; ++i) {
+      const int c = wave_cnt[i];
+      woff += (i < w) ? c : 0;
+      tot += c;
+    }
+    if (f) {
+      const int p = base + woff + before;
+      if (p < out_cap) out_idx[p] = rows.idx ? rows.idx[j] : j;
+    }
+    base += tot;
+    __syncthreads();
+  }
+  const int m = min(base, out_cap);
+  if (base > out_cap && tid == 0) *status = overflow_code;
+  __threadfence_block();
+  __syncthreads();
+  for (int b = tid; b <= B; b += CB) {
+    const int key = b * L;
+    int lo = 0, hi = m;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (out_idx[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    out_off[b] = lo;
+  }
+}
+
+__global__ void k_fill_i32(int32_t *p, int32_t v, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+inline int row_grid(int cap) { return cap < 1 ? 1 : (cap > 8192 ? 8192 : cap); }
+
+}  // namespace
+
+void launch_gather_rmsnorm(DType t, const void *x, const void *gain, Rows rows, int d, float eps,
+                           void *out, hipStream_t s) {
+  if (rows.cap <= 0) return;
+  if (t == F32)
+    k_gather_rmsnorm<float><<<row_grid(rows.cap), RB, 0, s>>>((const float *)x, (const float *)gain,
+                                                              rows, d, eps, (float *)out);
+  else
+    k_gather_rmsnorm<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>((const bf16_t *)x, (const bf16_t *)gain,
+                                                               rows, d, eps, (bf16_t *)out);
+}
+
+void launch_rmsnorm_f32in(DType t, const float *h, const void *gain, Rows rows, int d, float eps,
+                          void *out, hipStream_t s) {
+  if (rows.cap <= 0) return;
+  if (t == F32)
+    k_rmsnorm_f32in<float><<<row_grid(rows.cap), RB, 0, s>>>(h, (const float *)gain, rows, d, eps,
+                                                             (float *)out);
+  else
+    k_rmsnorm_f32in<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>(h, (const bf16_t *)gain, rows, d, eps,
+                                                              (bf16_t *)out);
+}
+
+void launch_rope_scatter(DType t, const float *qkv, const float *rope_tab, Rows rows, int L, int H,
+                         int Hkv, int dh, const void *bq, const void *bk, const void *bv,
+                         void *q_out, void *k_cache, void *v_cache, hipStream_t s) {
+  if (rows.cap <= 0) return;
+  if (t == F32)
+    k_rope_scatter<float><<<row_grid(rows.cap), RB, 0, s>>>(
+        qkv, rope_tab, rows, L, H, Hkv, dh, (const float *)bq, (const float *)bk, (const float *)bv,
+        (float *)q_out, (float *)k_cache, (float *)v_cache);
+  else
+    k_rope_scatter<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>(
+        qkv, rope_tab, rows, L, H, Hkv, dh, (const bf16_t *)bq, (const bf16_t *)bk,
+        (const bf16_t *)bv, (bf16_t *)q_out, (bf16_t *)k_cache, (bf16_t *)v_cache);
+}
+
+void launch_saliency(DType t, const void *c_new, void *c_cache, Rows rows, int D, float tau,
+                     float *cos_out, uint8_t *flag_out, int commit, hipStream_t s) {
+  if (rows.cap <= 0) return;
+  if (t == F32)
+    k_saliency<float><<<row_grid(rows.cap), RB, 0, s>>>((const float *)c_new, (float *)c_cache, rows,
+                                                        D, tau, cos_out, flag_out, commit);
+  else
+    k_saliency<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>((const bf16_t *)c_new, (bf16_t *)c_cache,
+                                                         rows, D, tau, cos_out, flag_out, commit);
+}
+
+void launch_compact(const uint8_t *flag, Rows rows, int B, int L, int32_t *out_idx,
+                    int32_t *out_offsets, int out_cap, int32_t *status, hipStream_t s) {
+  k_compact<<<1, CB, 0, s>>>(flag, rows, B, L, out_idx, out_offsets, out_cap, status, -6);
+}
+
+void launch_fill_i32(int32_t *p, int32_t v, int n, hipStream_t s) {
+  if (n <= 0) return;
+  k_fill_i32<<<(n + 255) / 256, 256, 0, s>>>(p, v, n);
+}
+
+}  // namespace dy

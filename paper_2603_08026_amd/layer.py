@@ -1,0 +1,99 @@
+"""Device-side holder of one layer's weights, caches and index buffers.
+
+Convenience over the raw binding for tests and the bench: it allocates torch
+tensors, uploads numpy inputs and calls the library.  No step of the method is
+computed here.
+"""
+from __future__ import annotations
+
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+import torch
+
+from . import binding as B_
+
+
+def torch_dtype(dtype: str):
+    return torch.float32 if dtype == "f32" else torch.bfloat16
+
+
+def to_device(a: np.ndarray, dtype: str) -> torch.Tensor:
+    """fp32 numpy values (already representable in dtype) -> device tensor of the storage type."""
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t if dtype == "f32" else t.to(torch.bfloat16)
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+class Layer:
+    def __init__(self, hidden, n_heads, n_kv_heads, head_dim, ffn, dtype: str, batch: int, seq: int,
+                 max_rows: int = 0, rms_eps: float = 1e-5, rope_theta: float = 10000.0):
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU: the dyllm library only runs on a HIP device")
+        self.dtype = dtype
+        self.B, self.L = batch, seq
+        self.hidden, self.H, self.Hkv, self.dh, self.F = hidden, n_heads, n_kv_heads, head_dim, ffn
+        self.dq, self.dkv = n_heads * head_dim, n_kv_heads * head_dim
+        self.cfg = B_.LayerCfg(hidden, n_heads, n_kv_heads, head_dim, ffn, batch, seq, max_rows,
+                               B_.F32 if dtype == "f32" else B_.BF16, rms_eps, rope_theta)
+        self.ctx = B_.Context(self.cfg)
+        td = torch_dtype(dtype)
+        T = batch * seq
+        self.k = torch.zeros(batch, seq, n_kv_heads, head_dim, dtype=td, device="cuda")
+        self.v = torch.zeros_like(self.k)
+        self.c = torch.zeros(batch, seq, self.dq, dtype=td, device="cuda")
+        self.out = torch.zeros(batch, seq, hidden, dtype=td, device="cuda")
+        self.cache = B_.make_cache(self.k, self.v, self.c, self.out)
+        self.rows_cap = max_rows if max_rows > 0 else T
+        self.idx_out = B_.IndexList.empty(self.rows_cap, batch)
+        self.cos = torch.zeros(self.rows_cap, dtype=torch.float32, device="cuda")
+        self.wt: Dict[str, torch.Tensor] = {}
+        self.w = None
+
+    @classmethod
+    def from_shape(cls, shape, batch, seq, max_rows=0):
+        return cls(shape.hidden, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.ffn, shape.dtype,
+                   batch, seq, max_rows, shape.rms_eps, shape.rope_theta)
+
+    def set_weights(self, w: Dict[str, np.ndarray]):
+        self.wt = {k: to_device(v, self.dtype) for k, v in w.items() if v is not None}
+        self.w = B_.make_weights(self.wt)
+
+    def set_caches(self, caches: Dict[str, np.ndarray]):
+        for name in ("k", "v", "c", "out"):
+            getattr(self, name).copy_(to_device(caches[name].astype(np.float32), self.dtype))
+
+    def get_caches(self) -> Dict[str, np.ndarray]:
+        return {n: to_host(getattr(self, n)) for n in ("k", "v", "c", "out")}
+
+    def make_list(self, idx: np.ndarray, offsets: np.ndarray, cap: Optional[int] = None) -> B_.IndexList:
+        cap = int(idx.size if cap is None else cap)
+        buf = np.zeros(max(cap, 1), dtype=np.int32)
+        buf[:idx.size] = idx
+        il = B_.IndexList(torch.from_numpy(buf).cuda()[:cap],
+                          torch.from_numpy(np.ascontiguousarray(offsets, dtype=np.int32)).cuda())
+        return il
+
+    def upload(self, x: np.ndarray) -> torch.Tensor:
+        return to_device(x, self.dtype)
+
+    def full_step(self, x_dev: torch.Tensor):
+        self.ctx.full_step(self.w, self.cache, x_dev, self.B, self.L)
+
+    def layer_step(self, x_dev: torch.Tensor, idx_in: B_.IndexList, tau: float,
+                   idx_out: Optional[B_.IndexList] = None, want_cos: bool = True):
+        out = self.idx_out if idx_out is None else idx_out
+        self.ctx.layer_step(self.w, self.cache, x_dev, idx_in, self.B, self.L, tau, out,
+                            self.cos if want_cos else None)
+        return out
+
+    def read_list(self, il: B_.IndexList) -> Tuple[np.ndarray, np.ndarray]:
+        off = il.offsets.cpu().numpy()
+        n = int(off[-1])
+        return il.idx[:n].cpu().numpy(), off
+
+    def close(self):
+        self.ctx.close()

@@ -1,0 +1,284 @@
+"""GPU-vs-oracle parity of each boundary call, through the C ABI, on seeded inputs that span
+several tiles with ragged tails, empty sequences and the degenerate cases."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dyllm_oracle as O
+from paper_2603_08026_amd import binding as Bd
+from paper_2603_08026_amd.layer import Layer, to_device, to_host
+from synth import workload as W
+from tests.helpers import (TOL, assert_close, assert_index_sets_match, oracle_cfg, rand_rows, rand_weights,
+                           small_shape)
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print("[case]", *a, flush=True)
+
+
+def _vals(seed, shape, dtype, scale=1.0, *key):
+    x = W.philox(seed, "vals", *key).standard_normal(shape, dtype=np.float32) * np.float32(scale)
+    return W.round_bf16(x) if dtype == "bf16" else x
+
+
+# ------------------------------------------------------------------ saliency
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_saliency_candidates_and_commit(dtype):
+    _say("saliency candidates", dtype)
+    s = small_shape(dtype)
+    B, L = 3, 50
+    lay = Layer.from_shape(s, B, L)
+    D = s.dq
+    cache = _vals(1, (B * L, D), dtype)
+    idx, off = rand_rows(2, B, L, [17, 0, 33])
+    M = idx.size
+    # candidates: some identical to the cache, some scaled, some slightly / strongly perturbed, one zero row
+    sig = 10.0 ** W.philox(3, "sig").uniform(-4, 0, M)
+    new = W.perturbed_rows(cache[idx], sig, 4)
+    new[0] = cache[idx[0]]
+    new[1] = 2.0 * cache[idx[1]]
+    new[2] = 0.0
+    cache[idx[3]] = 0.0
+    new = W.round_bf16(new) if dtype == "bf16" else new
+    tau = 0.99
+    ref_cache = cache.astype(np.float64)
+    cos_ref, flag_ref = O.saliency(new, ref_cache, idx, tau, commit=True)
+
+    d_cache = to_device(cache, dtype)
+    d_new = to_device(new, dtype)
+    rows = lay.make_list(idx, off, cap=M + 5)
+    cos = torch.full((M + 5,), 7.0, device="cuda")
+    flag = torch.full((M + 5,), 9, dtype=torch.uint8, device="cuda")
+    lay.ctx.saliency(d_new, d_cache, rows, B, L, tau, cos, flag, commit=True)
+    torch.cuda.synchronize()
+    cos_g, flag_g = cos.cpu().numpy(), flag.cpu().numpy()
+    assert np.max(np.abs(cos_g[:M] - cos_ref)) < 2e-6
+    assert cos_g[0] >= 1 - 1e-6 and flag_g[0] == 0  # unchanged context is never salient
+    assert abs(cos_g[1] - 1) < 1e-6  # scale invariance of the metric
+    assert cos_g[2] == 0.0 and flag_g[2] == 1 and cos_g[3] == 0.0  # zero rows: s = 0, no NaN
+    firm = np.abs(cos_ref - tau) > 1e-3
+    assert np.array_equal(flag_g[:M][firm], flag_ref[firm].astype(np.uint8))
+    assert np.all(cos_g[M:] == 7.0) and np.all(flag_g[M:] == 9)  # nothing written past the count
+    assert np.array_equal(to_host(d_cache), ref_cache)  # commit: rows replaced, others untouched
+    lay.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_saliency_all_rows_form(dtype):
+    _say("saliency all rows", dtype)
+    s = small_shape(dtype)
+    B, L = 2, 37
+    lay = Layer.from_shape(s, B, L)
+    a = _vals(5, (B * L, s.dq), dtype)
+    sig = 10.0 ** W.philox(6, "sig").uniform(-4, 0, B * L)
+    b = W.perturbed_rows(a, sig, 7)
+    b = W.round_bf16(b) if dtype == "bf16" else b
+    cos_ref, flag_ref = O.saliency(b, a, None, 0.995)
+    cos = torch.zeros(B * L, device="cuda")
+    flag = torch.zeros(B * L, dtype=torch.uint8, device="cuda")
+    d_a = to_device(a, dtype)
+    lay.ctx.saliency(to_device(b, dtype), d_a, None, B, L, 0.995, cos, flag, commit=False)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(cos.cpu().numpy() - cos_ref)) < 2e-6
+    firm = np.abs(cos_ref - 0.995) > 1e-3
+    assert np.array_equal(flag.cpu().numpy()[firm], flag_ref[firm].astype(np.uint8))
+    assert np.array_equal(to_host(d_a), a.astype(np.float64))
+    lay.close()
+
+
+# ------------------------------------------------------------------ compaction
+
+@pytest.mark.parametrize("case", ["candidates", "identity", "empty", "all", "big"])
+def test_compact_bit_exact(case):
+    _say("compact", case)
+    s = small_shape("f32")
+    B, L = (4, 300) if case != "big" else (16, 2048)
+    lay = Layer.from_shape(s, B, L)
+    g = W.philox(8, "compact", case)
+    if case == "identity" or case == "big":
+        rows_np, off_np, rows = None, None, None
+        n = B * L
+    else:
+        counts = [123, 0, 300, 1]
+        rows_np, off_np = rand_rows(9, B, L, counts)
+        n = rows_np.size
+        rows = lay.make_list(rows_np, off_np, cap=n + 3)
+    p = {"empty": 0.0, "all": 1.0}.get(case, 0.3)
+    flag_np = (g.uniform(size=n) < p).astype(np.uint8)
+    if case == "big":
+        flag_np[: 3 * L] = 0  # three leading sequences without any salient token
+    idx_ref, off_ref = O.compact(flag_np, rows_np, B, L)
+    out = Bd.IndexList.empty(n, B)
+    out.idx.fill_(-1)
+    flag = torch.from_numpy(np.concatenate([flag_np, np.ones(3, np.uint8)])).cuda()
+    lay.ctx.compact(flag, rows, B, L, out)
+    idx_g, off_g = lay.read_list(out)
+    assert np.array_equal(off_g, off_ref)
+    assert np.array_equal(idx_g, idx_ref)
+    assert lay.ctx.poll_status() == 0
+    lay.close()
+
+
+def test_compact_capacity_overflow_is_reported():
+    _say("compact overflow")
+    s = small_shape("f32")
+    B, L = 2, 100
+    lay = Layer.from_shape(s, B, L)
+    flag_np = np.ones(B * L, np.uint8)
+    out = Bd.IndexList.empty(50, B)
+    guard = torch.full((60,), -7, dtype=torch.int32, device="cuda")
+    out = Bd.IndexList(guard[:50], out.offsets)
+    lay.ctx.compact(torch.from_numpy(flag_np).cuda(), None, B, L, out)
+    assert lay.ctx.poll_status() == Bd.ERR_CAPACITY
+    assert lay.ctx.poll_status() == 0  # cleared by the poll
+    idx_g, off_g = lay.read_list(out)
+    assert np.array_equal(idx_g, np.arange(50)) and off_g.tolist() == [0, 50, 50]
+    assert np.all(guard[50:].cpu().numpy() == -7)
+    lay.close()
+
+
+# ------------------------------------------------------------------ q/k/v refresh
+
+@pytest.mark.parametrize("dtype,gqa,dh,bias", [("f32", False, 64, False), ("f32", True, 128, True),
+                                              ("bf16", False, 128, False), ("bf16", True, 64, True)])
+def test_qkv_refresh(dtype, gqa, dh, bias):
+    _say("qkv_refresh", dtype, gqa, dh, bias)
+    s = small_shape(dtype, gqa, dh)
+    cfg = oracle_cfg(s)
+    B, L = 3, 90
+    lay = Layer.from_shape(s, B, L)
+    w = rand_weights(s, 11, bias=bias)
+    lay.set_weights(w)
+    x = _vals(12, (B, L, s.hidden), dtype)
+    idx, off = rand_rows(13, B, L, [70, 0, 5])
+    k0, v0 = _vals(14, (B * L, s.dkv), dtype), _vals(15, (B * L, s.dkv), dtype)
+    lay.k.copy_(to_device(k0, dtype).view_as(lay.k))
+    lay.v.copy_(to_device(v0, dtype).view_as(lay.v))
+    rows = lay.make_list(idx, off, cap=idx.size + 2)
+    q_out = torch.zeros(idx.size + 2, s.dq, dtype=lay.k.dtype, device="cuda")
+    lay.ctx.qkv_refresh(lay.w, lay.upload(x), rows, B, L, lay.cache, q_out)
+    torch.cuda.synchronize()
+    n = O.rmsnorm(x.reshape(B * L, -1)[idx], w["g_attn"], cfg.rms_eps)
+    q, k, v = O.project_qkv(n, idx % L, w, cfg)
+    tol = TOL[dtype]
+    assert_close(to_host(q_out)[:idx.size], q.reshape(idx.size, -1), tol, "q")
+    kg, vg = to_host(lay.k).reshape(B * L, -1), to_host(lay.v).reshape(B * L, -1)
+    assert_close(kg[idx], k.reshape(idx.size, -1), tol, "k rows")
+    assert_close(vg[idx], v.reshape(idx.size, -1), tol, "v rows")
+    others = np.setdiff1d(np.arange(B * L), idx)
+    assert np.array_equal(kg[others], k0[others].astype(np.float64))  # K/V merge leaves the rest alone
+    assert np.array_equal(vg[others], v0[others].astype(np.float64))
+    assert np.all(to_host(q_out)[idx.size:] == 0)
+    lay.close()
+
+
+# ------------------------------------------------------------------ partial attention
+
+@pytest.mark.parametrize("dtype,gqa,dh,B,L,counts", [
+    ("f32", False, 64, 3, 70, [33, 0, 70]),
+    ("f32", True, 128, 2, 45, [1, 20]),
+    ("bf16", False, 128, 3, 200, [100, 0, 7]),
+    ("bf16", True, 64, 2, 333, [65, 129]),
+    ("bf16", False, 128, 1, 1024, [106]),
+    ("bf16", True, 128, 1, 77, [77]),
+])
+def test_partial_attention(dtype, gqa, dh, B, L, counts):
+    _say("partial_attention", dtype, gqa, dh, B, L, counts)
+    s = small_shape(dtype, gqa, dh)
+    lay = Layer.from_shape(s, B, L)
+    idx, off = rand_rows(21, B, L, counts)
+    M = idx.size
+    q = _vals(22, (M, s.n_heads, dh), dtype, 1.5)
+    k = _vals(23, (B, L, s.n_kv_heads, dh), dtype, 1.5)
+    v = _vals(24, (B, L, s.n_kv_heads, dh), dtype)
+    ref = O.partial_attention(q, k, v, idx, B, L)
+    rows = lay.make_list(idx, off, cap=M + 3)
+    out = torch.zeros(M + 3, s.dq, dtype=lay.k.dtype, device="cuda")
+    qd = torch.zeros(M + 3, s.n_heads, dh, dtype=lay.k.dtype, device="cuda")
+    qd[:M] = to_device(q, dtype)
+    lay.ctx.partial_attention(qd, to_device(k, dtype), to_device(v, dtype), rows, B, L, out)
+    torch.cuda.synchronize()
+    assert_close(to_host(out)[:M], ref, TOL[dtype], "context rows")
+    assert np.all(to_host(out)[M:] == 0)
+    lay.close()
+
+
+def test_partial_attention_special_cases():
+    _say("partial_attention special cases")
+    s = small_shape("f32")
+    B, L = 1, 40
+    lay = Layer.from_shape(s, B, L)
+    idx, off = np.arange(0, 40, 3, dtype=np.int32), np.array([0, 14], np.int32)
+    q = _vals(25, (14, s.n_heads, 64), "f32")
+    krow = _vals(26, (1, 1, s.n_kv_heads, 64), "f32")
+    k = np.tile(krow, (1, L, 1, 1))  # all keys equal: uniform weights, context = mean of V
+    v = _vals(27, (B, L, s.n_kv_heads, 64), "f32")
+    out = torch.zeros(14, s.dq, device="cuda")
+    lay.ctx.partial_attention(to_device(q, "f32"), to_device(k, "f32"), to_device(v, "f32"),
+                              lay.make_list(idx, off), B, L, out)
+    want = np.tile(v[0].mean(axis=0).reshape(1, -1), (14, 1))
+    assert_close(to_host(out), want, 1e-5, "uniform attention")
+    lay.close()
+    # a single key: the context is that value row
+    lay = Layer.from_shape(s, 2, 1)
+    v1 = _vals(28, (2, 1, s.n_kv_heads, 64), "f32")
+    out = torch.zeros(2, s.dq, device="cuda")
+    lay.ctx.partial_attention(to_device(q[:2], "f32"), to_device(_vals(29, (2, 1, s.n_kv_heads, 64), "f32"), "f32"),
+                              to_device(v1, "f32"), lay.make_list(np.array([0, 1], np.int32), np.array([0, 1, 2], np.int32)),
+                              2, 1, out)
+    assert_close(to_host(out), v1.reshape(2, -1), 1e-6, "single key")
+    lay.close()
+
+
+# ------------------------------------------------------------------ salient FFN
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_salient_ffn(dtype):
+    _say("salient_ffn", dtype)
+    s = small_shape(dtype)
+    cfg = oracle_cfg(s)
+    B, L = 2, 150
+    lay = Layer.from_shape(s, B, L)
+    w = rand_weights(s, 31)
+    lay.set_weights(w)
+    x = _vals(32, (B * L, s.hidden), dtype)
+    c = _vals(33, (B * L, s.dq), dtype)
+    out0 = _vals(34, (B * L, s.hidden), dtype)
+    idx, off = rand_rows(35, B, L, [101, 9])
+    ref = out0.astype(np.float64)
+    O.salient_ffn(x, c, idx, w, cfg, ref)
+    d_out = to_device(out0, dtype)
+    lay.ctx.salient_ffn(lay.w, to_device(x, dtype), to_device(c, dtype), lay.make_list(idx, off, cap=idx.size + 1),
+                        B, L, d_out)
+    torch.cuda.synchronize()
+    got = to_host(d_out)
+    assert_close(got[idx], ref[idx], TOL[dtype], "ffn rows")
+    others = np.setdiff1d(np.arange(B * L), idx)
+    assert np.array_equal(got[others], out0[others].astype(np.float64))
+    lay.close()
+
+
+def test_error_paths_do_not_launch():
+    _say("error paths")
+    s = small_shape("f32")
+    lay = Layer.from_shape(s, 2, 32, max_rows=16)
+    lay.set_weights(rand_weights(s, 36))
+    x = lay.upload(_vals(37, (2, 32, s.hidden), "f32"))
+    big = Bd.IndexList.empty(17, 2)
+    with pytest.raises(Bd.DyllmError) as e:
+        lay.layer_step(x, big, 0.99)
+    assert e.value.code == Bd.ERR_CAPACITY
+    with pytest.raises(Bd.DyllmError) as e:
+        lay.full_step(x)  # needs max_rows >= B*L
+    assert e.value.code == Bd.ERR_CAPACITY
+    with pytest.raises(Bd.DyllmError) as e:
+        lay.ctx.layer_step(lay.w, lay.cache, lay.out, Bd.IndexList.empty(4, 2), 2, 32, 0.99, lay.idx_out, None)
+    assert e.value.code == -1  # x aliases the output cache
+    with pytest.raises(Bd.DyllmError) as e:
+        lay.ctx.full_step(lay.w, lay.cache, x, 3, 32)
+    assert e.value.code == -2
+    torch.cuda.synchronize()
+    lay.close()
