@@ -94,7 +94,8 @@ typedef struct {
 
 /* A set of tokens: ascending, unique token ids, grouped by sequence. */
 typedef struct {
-  int32_t *idx;     /* [cap] token ids b*L+i; entries beyond the count are undefined */
+  int32_t *idx;     /* [cap] token ids b*L+i; entries beyond the count are undefined; may be NULL
+                       if cap is 0 */
   int32_t *offsets; /* [B+1] offsets[b]..offsets[b+1] = entries of sequence b; offsets[B] = count */
   int32_t cap;      /* capacity of idx (host value); the count on the device must not exceed it */
 } dyllm_index_list;

@@ -118,8 +118,9 @@ int check_bl(dyllm_ctx *ctx, int B, int L) {
 }
 
 int check_list(dyllm_ctx *ctx, const dyllm_index_list *l, const char *name) {
-  if (!l || !l->idx || !l->offsets) return fail(ctx, DYLLM_ERR_INVALID_ARG, name);
+  if (!l || !l->offsets) return fail(ctx, DYLLM_ERR_INVALID_ARG, name);
   if (l->cap < 0) return fail(ctx, DYLLM_ERR_INVALID_ARG, "negative list capacity");
+  if (!l->idx && l->cap > 0) return fail(ctx, DYLLM_ERR_INVALID_ARG, name);  // idx may be NULL only for cap 0
   if (l->cap > ctx->rows_cap) return fail(ctx, DYLLM_ERR_CAPACITY, "list capacity exceeds the context's max_rows");
   return DYLLM_OK;
 }
@@ -374,7 +375,7 @@ int dyllm_saliency(dyllm_ctx *ctx, const void *c_new, void *c_cache, const dyllm
 int dyllm_compact(dyllm_ctx *ctx, const uint8_t *flag, const dyllm_index_list *rows, int32_t B,
                   int32_t L, dyllm_index_list *out, void *stream) {
   if (!ctx) return DYLLM_ERR_INVALID_ARG;
-  if (!flag || !out || !out->idx || !out->offsets || out->cap < 0)
+  if (!flag || !out || !out->offsets || out->cap < 0 || (!out->idx && out->cap > 0))
     return fail(ctx, DYLLM_ERR_INVALID_ARG, "NULL flag or output list");
   int rc = check_bl(ctx, B, L);
   if (rc) return rc;
@@ -438,7 +439,7 @@ int dyllm_layer_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_c
   if ((rc = check_bl(ctx, B, L))) return rc;
   if ((rc = check_list(ctx, idx_in, "idx_in"))) return rc;
   if ((rc = check_list(ctx, idx_out, "idx_out"))) return rc;
-  if (idx_out->idx == idx_in->idx || idx_out->offsets == idx_in->offsets)
+  if ((idx_out->idx && idx_out->idx == idx_in->idx) || idx_out->offsets == idx_in->offsets)
     return fail(ctx, DYLLM_ERR_INVALID_ARG, "idx_out aliases idx_in");
   hipStream_t s = (hipStream_t)stream;
   const Rows rin = rows_of(idx_in, B);
