@@ -156,7 +156,7 @@ int enqueue_qkv(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x, Row
   launch_gather_rmsnorm(dt(ctx), x, w->g_attn, rows, c.hidden, c.rms_eps, ctx->ns, s);
   prof_mark(ctx, ST_GATHER_NORM, s);
   launch_gemm_qkv(dt(ctx), GemmA{ctx->ns, nullptr, c.hidden}, rows, c.hidden, w->wq, w->wk, w->wv,
-                  ctx->dq, ctx->dkv, ctx->qkv, s);
+                  ctx->dq, ctx->dkv, ctx->qkv, ctx->part_o, ctx->part_elems, s);
   prof_mark(ctx, ST_GEMM_QKV, s);
   launch_rope_scatter(dt(ctx), ctx->qkv, ctx->rope, rows, L, c.n_heads, c.n_kv_heads, c.head_dim,
                       w->bq, w->bk, w->bv, q_out, cache->k, cache->v, s);
@@ -182,15 +182,15 @@ int enqueue_ffn(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x, con
                 Rows rows, void *out_cache, hipStream_t s) {
   const dyllm_layer_cfg &c = ctx->cfg;
   launch_gemm_oproj(dt(ctx), GemmA{c_all, rows.idx, ctx->dq}, rows, ctx->dq, c.hidden, w->wo, x,
-                    ctx->hs, s);
+                    ctx->hs, ctx->part_o, ctx->part_elems, s);
   prof_mark(ctx, ST_GEMM_OPROJ, s);
   launch_rmsnorm_f32in(dt(ctx), ctx->hs, w->g_ffn, rows, c.hidden, c.rms_eps, ctx->fs, s);
   prof_mark(ctx, ST_NORM_FFN, s);
   launch_gemm_swiglu(dt(ctx), GemmA{ctx->fs, nullptr, c.hidden}, rows, c.hidden, c.ffn_dim, w->w_gate,
-                     w->w_up, ctx->act, s);
+                     w->w_up, ctx->act, ctx->part_o, ctx->part_elems, s);
   prof_mark(ctx, ST_GEMM_SWIGLU, s);
   launch_gemm_down(dt(ctx), GemmA{ctx->act, nullptr, c.ffn_dim}, rows, c.ffn_dim, c.hidden, w->w_down,
-                   ctx->hs, out_cache, s);
+                   ctx->hs, out_cache, ctx->part_o, ctx->part_elems, s);
   prof_mark(ctx, ST_GEMM_DOWN, s);
   return check_launch(ctx, "salient ffn");
 }
@@ -453,7 +453,10 @@ int dyllm_layer_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_c
   launch_compact(ctx->flag, rin, B, L, idx_out->idx, idx_out->offsets, idx_out->cap, ctx->status, s);
   prof_mark(ctx, ST_COMPACT, s);
   if ((rc = check_launch(ctx, "saliency / compact"))) return rc;
-  rc = enqueue_ffn(ctx, w, x, cache->c, rows_of(idx_out, B), cache->out, s);
+  // idx_out is a subset of idx_in: its count never exceeds idx_in's capacity, which sizes the grids
+  Rows rout = rows_of(idx_out, B);
+  if (rout.cap > idx_in->cap) rout.cap = idx_in->cap;
+  rc = enqueue_ffn(ctx, w, x, cache->c, rout, cache->out, s);
   ctx->prof_cur = nullptr;
   return rc;
 }

@@ -1,28 +1,95 @@
-// bf16 salient-row GEMMs (placeholder: routes through the FMA kernels until the MFMA kernels land).
-#include "kernels.h"
+// bf16 salient-row GEMMs: tile-shape choice per regime and the four fused launchers.
+#include "gemm_bf16_kernel.h"
 
 namespace dy {
 
-void gemm_f32_qkv(DType, GemmA, Rows, int, const void *, const void *, const void *, int, int, float *, hipStream_t);
-void gemm_f32_oproj(DType, GemmA, Rows, int, int, const void *, const void *, float *, hipStream_t);
-void gemm_f32_swiglu(DType, GemmA, Rows, int, int, const void *, const void *, void *, hipStream_t);
-void gemm_f32_down(DType, GemmA, Rows, int, int, const void *, const float *, void *, hipStream_t);
+using namespace mm;
+
+namespace {
+
+// Large regime: 128 x 128 tile (128 x (64 + 64) when gate and up are fused), waves 2 x 2.
+typedef Shape<128, 128, 2, 2, false> LargeS;
+typedef Shape<128, 64, 2, 2, true> LargeD;
+// Skinny regime (weight streaming): every row in one 128-row tile; 64-column tiles and a K split so
+// that about two workgroups per CU are in flight (fused gate/up: 32 + 32 columns, no split).
+typedef Shape<128, 64, 2, 2, false> SkinnyS;
+typedef Shape<128, 32, 4, 1, true> SkinnyD;
+
+constexpr int SKINNY_MAX_ROWS = 128;
+
+template <typename SH, typename Epi>
+void run_tiles(GemmA A, Rows rows, int K, int N, WSeg seg, const void *w2, Epi epi, int splitk,
+               float *part, hipStream_t s) {
+  set_lds_once<SH, Epi>();
+  const int tiles = ((rows.cap + SH::BM - 1) / SH::BM) * (N / SH::BN);
+  int gx = tiles < 1 ? 1 : tiles;
+  if (gx > 2048) gx = 2048;
+  gx = (gx + N_XCD - 1) / N_XCD * N_XCD;  // multiple of the XCD count: p % 8 is then the XCD of p
+  SplitStore sp{splitk > 1 ? part : nullptr, (size_t)rows.cap * N, N};
+  dim3 grid(gx, splitk);
+  k_gemm_bf16<SH, Epi><<<grid, NT, SH::LDS_BYTES, s>>>(
+      (const bf16_t *)A.a, A.gather, A.lda, rows, N, seg, (const bf16_t *)w2, K, K / splitk,
+      /*group_m=*/4, epi, sp);
+  if (splitk > 1) {
+    size_t total = (size_t)rows.cap * N;
+    int gr = (int)((total + NT - 1) / NT);
+    if (gr > 4096) gr = 4096;
+    k_split_reduce<Epi><<<gr, NT, 0, s>>>(sp, splitk, rows, epi);
+  }
+}
+
+// K split for the skinny regime when the column tiles alone cannot fill the chip.
+inline int pick_splitk(int N, int K, int bn, size_t part_elems, int cap) {
+  const int tiles = N / bn;
+  int s = 1;
+  while (tiles * s < 384 && s < 8 && (K / (s * 2)) % BK == 0 && K / (s * 2) >= 4 * BK) s *= 2;
+  if ((size_t)s * cap * N > part_elems) s = 1;
+  return s;
+}
+
+}  // namespace
 
 void gemm_bf16_qkv(GemmA A, Rows rows, int K, const void *wq, const void *wk, const void *wv, int dq,
-                   int dkv, float *out, hipStream_t s) {
-  gemm_f32_qkv(BF16, A, rows, K, wq, wk, wv, dq, dkv, out, s);
+                   int dkv, float *out, float *part, size_t part_elems, hipStream_t s) {
+  if (rows.cap <= 0) return;
+  WSeg seg;
+  seg.w[0] = wq; seg.w[1] = wk; seg.w[2] = wv;
+  seg.n_end[0] = dq; seg.n_end[1] = dq + dkv; seg.n_end[2] = dq + 2 * dkv;
+  const int N = dq + 2 * dkv;
+  EpiStoreF32 e{out, N};
+  if (rows.cap <= SKINNY_MAX_ROWS)
+    run_tiles<SkinnyS>(A, rows, K, N, seg, nullptr, e, pick_splitk(N, K, SkinnyS::BN, part_elems, rows.cap), part, s);
+  else
+    run_tiles<LargeS>(A, rows, K, N, seg, nullptr, e, 1, part, s);
 }
+
 void gemm_bf16_oproj(GemmA A, Rows rows, int K, int N, const void *wo, const void *x, float *h,
-                     hipStream_t s) {
-  gemm_f32_oproj(BF16, A, rows, K, N, wo, x, h, s);
+                     float *part, size_t part_elems, hipStream_t s) {
+  if (rows.cap <= 0) return;
+  EpiOProj<bf16_t> e{(const bf16_t *)x, h, N};
+  if (rows.cap <= SKINNY_MAX_ROWS)
+    run_tiles<SkinnyS>(A, rows, K, N, one(wo, N), nullptr, e, pick_splitk(N, K, SkinnyS::BN, part_elems, rows.cap), part, s);
+  else
+    run_tiles<LargeS>(A, rows, K, N, one(wo, N), nullptr, e, 1, part, s);
 }
+
 void gemm_bf16_swiglu(GemmA A, Rows rows, int K, int N, const void *wg, const void *wu, void *act,
-                      hipStream_t s) {
-  gemm_f32_swiglu(BF16, A, rows, K, N, wg, wu, act, s);
+                      float *part, size_t part_elems, hipStream_t s) {
+  (void)part; (void)part_elems;
+  if (rows.cap <= 0) return;
+  EpiSwiGLU<bf16_t> e{(bf16_t *)act, N};
+  if (rows.cap <= SKINNY_MAX_ROWS) run_tiles<SkinnyD>(A, rows, K, N, one(wg, N), wu, e, 1, nullptr, s);
+  else run_tiles<LargeD>(A, rows, K, N, one(wg, N), wu, e, 1, nullptr, s);
 }
+
 void gemm_bf16_down(GemmA A, Rows rows, int K, int N, const void *wd, const float *h, void *out,
-                    hipStream_t s) {
-  gemm_f32_down(BF16, A, rows, K, N, wd, h, out, s);
+                    float *part, size_t part_elems, hipStream_t s) {
+  if (rows.cap <= 0) return;
+  EpiDown<bf16_t> e{h, (bf16_t *)out, N};
+  if (rows.cap <= SKINNY_MAX_ROWS)
+    run_tiles<SkinnyS>(A, rows, K, N, one(wd, N), nullptr, e, pick_splitk(N, K, SkinnyS::BN, part_elems, rows.cap), part, s);
+  else
+    run_tiles<LargeS>(A, rows, K, N, one(wd, N), nullptr, e, 1, part, s);
 }
 
 }  // namespace dy

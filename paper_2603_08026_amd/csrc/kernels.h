@@ -60,17 +60,20 @@ struct GemmA {
   int lda;
 };
 // qkv: out[j, 0:dq | dq:dq+dkv | dq+dkv:] = A[j,:] * (wq | wk | wv)^T, fp32 out [cap, dq+2dkv]
+// `scratch` (fp32, scratch_elems) holds K-split partial sums when a launcher decides to split K.
 void launch_gemm_qkv(DType t, GemmA A, Rows rows, int K, const void *wq, const void *wk,
-                     const void *wv, int dq, int dkv, float *out, hipStream_t s);
+                     const void *wv, int dq, int dkv, float *out, float *scratch,
+                     size_t scratch_elems, hipStream_t s);
 // o-proj: h[j,:] = x[row_j,:] + A[j,:] * wo^T, fp32 out [cap, N]; x T-typed [T, N]
 void launch_gemm_oproj(DType t, GemmA A, Rows rows, int K, int N, const void *wo, const void *x,
-                       float *h, hipStream_t s);
+                       float *h, float *scratch, size_t scratch_elems, hipStream_t s);
 // up: act[j,:] = silu(A w_gate^T) * (A w_up^T), T-typed out [cap, N]
 void launch_gemm_swiglu(DType t, GemmA A, Rows rows, int K, int N, const void *w_gate,
-                        const void *w_up, void *act, hipStream_t s);
+                        const void *w_up, void *act, float *scratch, size_t scratch_elems,
+                        hipStream_t s);
 // down: out_cache[row_j,:] = h[j,:] + A[j,:] * w_down^T, T-typed scatter into [T, N]
 void launch_gemm_down(DType t, GemmA A, Rows rows, int K, int N, const void *w_down, const float *h,
-                      void *out_cache, hipStream_t s);
+                      void *out_cache, float *scratch, size_t scratch_elems, hipStream_t s);
 
 void launch_fill_i32(int32_t *p, int32_t v, int n, hipStream_t s);
 
