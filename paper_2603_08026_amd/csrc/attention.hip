@@ -42,7 +42,7 @@ void launch_attn_combine(DType t, const AttnArgs &a, hipStream_t s) {
 // (sequence, head, query tile) triples, bounded by the partial buffer and by one key tile per split.
 void attention_plan(DType t, int B, int L, int H, int dh, int cap, size_t part_elems, int *splits,
                     int *chunk) {
-  const int BQ = (t == F32) ? 16 : 64, BK = 64;
+  const int BQ = (t == F32) ? 16 : 64, BK = (t == F32) ? 64 : 128;
   const long tiles = (long)((cap + BQ - 1) / BQ + B) * H;
   int s = (int)((1024 + tiles - 1) / tiles);
   const int max_by_keys = (L + BK - 1) / BK;

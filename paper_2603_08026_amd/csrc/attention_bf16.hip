@@ -1,6 +1,355 @@
-// bf16 partial attention (placeholder: routes through the fp32-arithmetic kernel).
+// Partial (row-sparse) attention for bf16 storage on the gfx950 matrix cores: exact attention rows
+// for the salient queries against all keys/values of their sequence, no mask.
+// [Sec. 3.3 salient path; Alg. 3: C_sal]
+//
+// Everything is computed transposed so that no operand ever has to be re-laid-out between the two
+// matrix products:
+//   S^T = K Q^T   A = K tile rows (LDS, [key][dh]),   B = Q rows (registers, loaded once)
+//                 -> a lane owns ONE query (column l%32) and 16 keys per 32-key block, so the row
+//                    maximum / sum of the online softmax are 32 register operations and one
+//                    cross-half shuffle, and the rescale of the running output is a plain multiply.
+//   O^T = V^T P^T A = V^T (LDS, [dh][key], transposed while it is written), B = P^T straight from
+//                    the S^T accumulator registers: element i of the lane's operand is register
+//                    8*ks+i, i.e. key 16*ks + 8*(i/4) + 4*(l/32) + i%4 -- the V^T operand is read
+//                    with the same key order (two 8-byte LDS reads), and a matrix product does not
+//                    care in which order k is summed as long as both operands agree.
+// A workgroup of 4 waves owns BQ = 64*WQ query rows of one (sequence, head); the keys of a tile are
+// split over the WK = 4/WQ wave columns (32 keys each), whose partial (max, sum, output) are merged
+// through LDS at the end.  K/V tiles are double-buffered in LDS with a register-staged prefetch.
+// The key range of a sequence can additionally be split over workgroups (few query rows): then
+// un-normalised partials go to global memory and k_attn_combine merges them.
 #include "attention_common.h"
 
 namespace dy {
-void launch_attention_bf16(const AttnArgs &a, hipStream_t s) { launch_attention_f32(BF16, a, s); }
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+template <int DH, int WQ> struct ATile {
+  static constexpr int WK = 4 / WQ;       // wave columns over the keys of a tile
+  static constexpr int BQ = 64 * WQ;      // query rows per workgroup
+  static constexpr int TK = 32 * WK;      // keys per tile
+  static constexpr int KSTR = DH + 8;     // K tile row stride (elements): 16-byte reads conflict-free
+  static constexpr int VSTR = TK + 4;     // V^T row stride (elements): 8-byte reads conflict-free
+  static constexpr int STAGE = TK * KSTR + DH * VSTR;
+  static constexpr int DB = DH / 32, KK = DH / 16;
+  static constexpr int K_CH = TK * DH / 8 / 256;       // 16-byte K chunks per thread and tile
+  static constexpr int V_CH = TK * DH / 8 / 2 / 256;   // pairs of V chunks per thread and tile
+  static constexpr size_t LDS_BYTES = (size_t)2 * STAGE * 2;
+  // merge scratch (reuses the tile buffers): (WK-1)*WQ waves x (2*DB*16 + 4) floats x 64 lanes
+  static constexpr size_t MERGE_BYTES = (size_t)(WK - 1) * WQ * (2 * DB * 16 + 4) * 64 * 4;
+  static_assert(MERGE_BYTES <= LDS_BYTES, "merge scratch must fit in the tile buffers");
+};
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+}
+
+// global -> registers: one K/V tile (keys past k_hi are clamped to the last valid key; their scores
+// are masked later)
+template <int DH, int WQ, int KCH, int VCH>
+__device__ __forceinline__ void load_kv_tile(uint4 (&rk)[KCH], uint4 (&rv)[VCH][2],
+                                             const bf16_t *kc, const bf16_t *vc, size_t kv_stride, int k0,
+                                             int k_hi, int tid) {
+  using T = ATile<DH, WQ>;
+#pragma unroll
+  for (int i = 0; i < T::K_CH; ++i) {
+    const int c = tid + 256 * i;
+    int key = k0 + c / (DH / 8);
+    key = key < k_hi ? key : k_hi - 1;
+    rk[i] = *reinterpret_cast<const uint4 *>(kc + (size_t)key * kv_stride + (c % (DH / 8)) * 8);
+  }
+#pragma unroll
+  for (int i = 0; i < T::V_CH; ++i) {
+    const int u = tid + 256 * i;
+    const int rest = u / 64;
+    const int ch = (u % 4) + 4 * (rest % (DH / 32));
+    const int kp = ((u / 4) % 16) + 16 * (rest / (DH / 32));
+    int key0 = k0 + 2 * kp, key1 = key0 + 1;
+    key0 = key0 < k_hi ? key0 : k_hi - 1;
+    key1 = key1 < k_hi ? key1 : k_hi - 1;
+    rv[i][0] = *reinterpret_cast<const uint4 *>(vc + (size_t)key0 * kv_stride + ch * 8);
+    rv[i][1] = *reinterpret_cast<const uint4 *>(vc + (size_t)key1 * kv_stride + ch * 8);
+  }
+}
+
+__device__ __forceinline__ uint32_t half_of(const uint4 &v, int e) {
+  const uint32_t w = (e >> 1) == 0 ? v.x : (e >> 1) == 1 ? v.y : (e >> 1) == 2 ? v.z : v.w;
+  return (e & 1) ? (w >> 16) : (w & 0xffffu);
+}
+
+// registers -> LDS stage: K rows as they are, V transposed ([dh][key]): element e of two
+// neighbouring keys forms one 32-bit word, so a wave's 64 stores hit 32 banks twice.
+template <int DH, int WQ, int KCH, int VCH>
+__device__ __forceinline__ void store_kv_tile(const uint4 (&rk)[KCH], const uint4 (&rv)[VCH][2],
+                                              bf16_t *stage, int tid) {
+  using T = ATile<DH, WQ>;
+  bf16_t *sk = stage, *sv = stage + T::TK * T::KSTR;
+#pragma unroll
+  for (int i = 0; i < T::K_CH; ++i) {
+    const int c = tid + 256 * i;
+    *reinterpret_cast<uint4 *>(sk + (c / (DH / 8)) * T::KSTR + (c % (DH / 8)) * 8) = rk[i];
+  }
+#pragma unroll
+  for (int i = 0; i < T::V_CH; ++i) {
+    const int u = tid + 256 * i;
+    const int rest = u / 64;
+    const int ch = (u % 4) + 4 * (rest % (DH / 32));
+    const int kp = ((u / 4) % 16) + 16 * (rest / (DH / 32));
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      *reinterpret_cast<uint32_t *>(sv + (ch * 8 + e) * T::VSTR + 2 * kp) =
+          half_of(rv[i][0], e) | (half_of(rv[i][1], e) << 16);
+  }
+}
+
+template <int DH, int WQ>
+__global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
+  using T = ATile<DH, WQ>;
+  constexpr int WK = T::WK, BQ = T::BQ, TK = T::TK, KSTR = T::KSTR, VSTR = T::VSTR, DB = T::DB, KK = T::KK;
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t *smem = reinterpret_cast<bf16_t *>(smem_raw);
+  __shared__ int tile_info[3];
+
+  const int tid = threadIdx.x, lane = tid % WAVE, wave = tid / WAVE;
+  const int l32 = lane % 32, lhi = lane / 32;
+  const int wq = wave / WK, wk = wave % WK;
+  if (tid == 0) find_tile(a, BQ, blockIdx.x, tile_info);
+  __syncthreads();
+  const int b = tile_info[0];
+  if (b < 0) return;  // uniform: no such tile
+  const int j0 = tile_info[1], nq = tile_info[2];
+  const int h = blockIdx.y, kvh = h / (a.H / a.Hkv), split = blockIdx.z;
+  const int k_lo = split * a.chunk, k_hi = min(a.L, k_lo + a.chunk);
+  if (k_lo >= k_hi) return;  // uniform
+
+  const size_t kv_stride = (size_t)a.Hkv * DH;
+  const bf16_t *kc = (const bf16_t *)a.k + ((size_t)b * a.L * a.Hkv + kvh) * DH;
+  const bf16_t *vc = (const bf16_t *)a.v + ((size_t)b * a.L * a.Hkv + kvh) * DH;
+
+  // query operands: 2 blocks of 32 queries per wave, kept in registers for the whole key sweep
+  bf16x8 qf[2][KK];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    int r = wq * 64 + qb * 32 + l32;
+    r = r < nq ? r : nq - 1;  // rows past the end are clamped; their results are never stored
+    const bf16_t *qp = (const bf16_t *)a.q + ((size_t)(j0 + r) * a.H + h) * DH + lhi * 8;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) qf[qb][kk] = *reinterpret_cast<const bf16x8 *>(qp + kk * 16);
+  }
+
+  floatx16 acc_o[2][DB];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc_o[qb][db][e] = 0.f;
+  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+  const float sc = LOG2E / sqrtf((float)DH);  // scores are kept in the log2 domain
+
+  uint4 rk[T::K_CH], rv[T::V_CH][2];
+  const int n_tiles = (k_hi - k_lo + TK - 1) / TK;
+  load_kv_tile<DH, WQ, T::K_CH, T::V_CH>(rk, rv, kc, vc, kv_stride, k_lo, k_hi, tid);
+  store_kv_tile<DH, WQ, T::K_CH, T::V_CH>(rk, rv, smem, tid);
+  __syncthreads();
+  for (int t = 0; t < n_tiles; ++t) {
+    const int k0 = k_lo + t * TK;
+    const bf16_t *stage = smem + (t & 1) * T::STAGE;
+    // prefetch the next tile (the last iteration re-reads its own tile: harmless, keeps the loop uniform)
+    load_kv_tile<DH, WQ, T::K_CH, T::V_CH>(rk, rv, kc, vc, kv_stride, t + 1 < n_tiles ? k0 + TK : k0, k_hi, tid);
+
+    // S^T block of this wave: 32 keys x 64 queries
+    floatx16 s[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[qb][e] = 0.f;
+    const bf16_t *skp = stage + (wk * 32 + l32) * KSTR + lhi * 8;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(skp + kk * 16);
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][kk], s[qb], 0, 0, 0);
+    }
+
+    // online softmax per query (= per lane), keys of this wave only
+    const int key_base = k0 + wk * 32 + 4 * lhi;
+    bf16x8 pf[2][2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int key = key_base + 8 * (e / 4) + (e % 4);
+        const float v = key < k_hi ? s[qb][e] * sc : -INFINITY;
+        s[qb][e] = v;
+        mx = fmaxf(mx, v);
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+      const float m_new = fmaxf(m_run[qb], mx);
+      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+      const float corr = __builtin_amdgcn_exp2f(m_run[qb] - m_safe);
+      float ps = 0.f;
+      uint32_t pw[8];
+#pragma unroll
+      for (int e = 0; e < 16; e += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(s[qb][e] - m_safe);
+        const float p1 = __builtin_amdgcn_exp2f(s[qb][e + 1] - m_safe);
+        // the sum uses the rounded values that enter the matrix product
+        const uint32_t w = pack_bf16(p0, p1);
+        ps += __uint_as_float(w << 16) + __uint_as_float(w & 0xffff0000u);
+        pw[e >> 1] = w;
+      }
+      ps += __shfl_xor(ps, 32, WAVE);
+      l_run[qb] = l_run[qb] * corr + ps;
+      m_run[qb] = m_new;
+      uint4 v0{pw[0], pw[1], pw[2], pw[3]}, v1{pw[4], pw[5], pw[6], pw[7]};
+      pf[qb][0] = __builtin_bit_cast(bf16x8, v0);
+      pf[qb][1] = __builtin_bit_cast(bf16x8, v1);
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc_o[qb][db][e] *= corr;
+    }
+
+    // O^T += V^T P^T over the wave's 32 keys
+    const bf16_t *svp = stage + TK * KSTR + l32 * VSTR + wk * 32 + 4 * lhi;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const bf16_t *p = svp + db * 32 * VSTR + ks * 16;
+        const uint2 a0 = *reinterpret_cast<const uint2 *>(p);
+        const uint2 a1 = *reinterpret_cast<const uint2 *>(p + 8);
+        const uint4 av{a0.x, a0.y, a1.x, a1.y};
+        const bf16x8 vf = __builtin_bit_cast(bf16x8, av);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+          acc_o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][ks], acc_o[qb][db], 0, 0, 0);
+      }
+
+    store_kv_tile<DH, WQ, T::K_CH, T::V_CH>(rk, rv, smem + ((t + 1) & 1) * T::STAGE, tid);
+    __syncthreads();
+  }
+
+  // merge the WK wave columns of each query block through LDS (tile buffers are free now)
+  float *mg = reinterpret_cast<float *>(smem_raw);
+  constexpr int PER_WAVE = (2 * DB * 16 + 4) * 64;
+  if (WK > 1) {
+    if (wk > 0) {
+      float *dst = mg + (size_t)((wk - 1) * WQ + wq) * PER_WAVE + lane;
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) dst[((qb * DB + db) * 16 + e) * 64] = acc_o[qb][db][e];
+        dst[(2 * DB * 16 + qb) * 64] = m_run[qb];
+        dst[(2 * DB * 16 + 2 + qb) * 64] = l_run[qb];
+      }
+    }
+    __syncthreads();
+    if (wk == 0) {
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        float M = m_run[qb];
+#pragma unroll
+        for (int w = 1; w < WK; ++w)
+          M = fmaxf(M, mg[(size_t)((w - 1) * WQ + wq) * PER_WAVE + (2 * DB * 16 + qb) * 64 + lane]);
+        const float Ms = (M == -INFINITY) ? 0.f : M;
+        const float c0 = __builtin_amdgcn_exp2f(m_run[qb] - Ms);
+        float lsum = l_run[qb] * c0;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc_o[qb][db][e] *= c0;
+#pragma unroll
+        for (int w = 1; w < WK; ++w) {
+          const float *src = mg + (size_t)((w - 1) * WQ + wq) * PER_WAVE + lane;
+          const float cw = __builtin_amdgcn_exp2f(src[(2 * DB * 16 + qb) * 64] - Ms);
+          lsum += src[(2 * DB * 16 + 2 + qb) * 64] * cw;
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc_o[qb][db][e] += src[((qb * DB + db) * 16 + e) * 64] * cw;
+        }
+        m_run[qb] = M;
+        l_run[qb] = lsum;
+      }
+    }
+  }
+
+  if (wk == 0) {
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const int r = wq * 64 + qb * 32 + l32;
+      if (r < nq) {
+        const int j = j0 + r;
+        if (a.splits == 1) {
+          bf16_t *out = (bf16_t *)a.out + ((size_t)j * a.H + h) * DH + 4 * lhi;
+          const float inv = 1.0f / l_run[qb];
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              uint2 w;
+              w.x = pack_bf16(acc_o[qb][db][4 * g] * inv, acc_o[qb][db][4 * g + 1] * inv);
+              w.y = pack_bf16(acc_o[qb][db][4 * g + 2] * inv, acc_o[qb][db][4 * g + 3] * inv);
+              *reinterpret_cast<uint2 *>(out + db * 32 + 8 * g) = w;
+            }
+        } else {
+          float *po = a.part_o + (((size_t)split * a.rows.cap + j) * a.H + h) * DH + 4 * lhi;
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              float4 w{acc_o[qb][db][4 * g], acc_o[qb][db][4 * g + 1], acc_o[qb][db][4 * g + 2],
+                       acc_o[qb][db][4 * g + 3]};
+              *reinterpret_cast<float4 *>(po + db * 32 + 8 * g) = w;
+            }
+          if (lhi == 0) {
+            float *ml = a.part_ml + (((size_t)split * a.rows.cap + j) * a.H + h) * 2;
+            ml[0] = m_run[qb] * LN2;  // partials carry the maximum in natural-log units
+            ml[1] = l_run[qb];
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int DH, int WQ> void launch_cfg(const AttnArgs &a, hipStream_t s) {
+  using T = ATile<DH, WQ>;
+  static bool done = false;
+  if (!done) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<DH, WQ>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::LDS_BYTES);
+    done = true;
+  }
+  dim3 grid(max_q_tiles(a, T::BQ), a.H, a.splits);
+  k_attn_bf16<DH, WQ><<<grid, 256, T::LDS_BYTES, s>>>(a);
+}
+
+}  // namespace
+
+int attention_bf16_bq(int B, int cap) {
+  // 128-row query tiles when sequences bring that many rows on average, else 64-row tiles
+  return (cap + B - 1) / B > 80 ? 128 : 64;
+}
+
+void launch_attention_bf16(const AttnArgs &a, hipStream_t s) {
+  const bool wide = a.offsets ? attention_bf16_bq(a.B, a.rows.cap) == 128 : a.L > 80;
+  if (a.dh == 128) {
+    if (wide) launch_cfg<128, 2>(a, s); else launch_cfg<128, 1>(a, s);
+  } else {
+    if (wide) launch_cfg<64, 2>(a, s); else launch_cfg<64, 1>(a, s);
+  }
+}
+
 }  // namespace dy

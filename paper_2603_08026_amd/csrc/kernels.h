@@ -43,7 +43,7 @@ struct AttnArgs {
   const int32_t *offsets;  // [B+1] per-sequence offsets into rows, or nullptr = every sequence has L rows
   int B, L, H, Hkv, dh;
   int splits;           // key range split into this many parts (>= 1), none of them empty
-  int chunk;            // keys per split (multiple of 64); split s covers [s*chunk, min(L,(s+1)*chunk))
+  int chunk;            // keys per split (multiple of the key tile); split s covers [s*chunk, min(L,(s+1)*chunk))
   float *part_o;        // [splits, cap, H*dh] fp32 un-normalised partial outputs (splits > 1)
   float *part_ml;       // [splits, cap, H, 2] fp32 (running max, running sum)     (splits > 1)
   void *out;            // [cap, H*dh] T-typed
