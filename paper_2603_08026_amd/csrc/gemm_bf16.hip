@@ -1,5 +1,5 @@
 // bf16 salient-row GEMMs: tile-shape choice per regime and the four fused launchers.
-#include "gemm_bf16_kernel.h"
+#include "gemm_bf16_dma.h"
 
 namespace dy {
 
@@ -7,14 +7,19 @@ using namespace mm;
 
 namespace {
 
-// Large regime: 128 x 128 tile (128 x (64 + 64) when gate and up are fused), waves 2 x 2.
-typedef Shape<128, 128, 2, 2, false> LargeS;
-typedef Shape<128, 64, 2, 2, true> LargeD;
-// Skinny regime (weight streaming): every row in one 128-row tile; 64-column tiles and a K split so
-// that about two workgroups per CU are in flight (fused gate/up: 32 + 32 columns, no split).
-typedef Shape<128, 64, 2, 2, false> SkinnyS;
-typedef Shape<128, 32, 4, 1, true> SkinnyD;
+// Tile shapes per regime (rows = capacity of the row list):
+//  large   256 x 128 tile (256 x (64+64) when gate and up are fused), 8 waves, 2 LDS stages
+//  mid     128 x 128 tile, 4 waves, 2 stages (two workgroups per CU) for a few hundred rows
+//  skinny  all rows in one 128-row tile, 64-column tiles, 4 stages in flight and a K split so that
+//          about one workgroup per CU streams weights (weight-streaming-bound regime)
+typedef Shape<256, 128, 4, 2, false, 2> LargeS;
+typedef Shape<256, 64, 4, 2, true, 2> LargeD;
+typedef Shape<128, 128, 2, 2, false, 2> MidS;
+typedef Shape<128, 64, 2, 2, true, 2> MidD;
+typedef Shape<128, 64, 4, 2, false, 4> SkinnyS;
+typedef Shape<128, 32, 4, 1, true, 4> SkinnyD;
 
+constexpr int MID_MAX_ROWS = 384;
 constexpr int SKINNY_MAX_ROWS = 128;
 
 template <typename SH, typename Epi>
@@ -27,14 +32,14 @@ void run_tiles(GemmA A, Rows rows, int K, int N, WSeg seg, const void *w2, Epi e
   gx = (gx + N_XCD - 1) / N_XCD * N_XCD;  // multiple of the XCD count: p % 8 is then the XCD of p
   SplitStore sp{splitk > 1 ? part : nullptr, (size_t)rows.cap * N, N};
   dim3 grid(gx, splitk);
-  k_gemm_bf16<SH, Epi><<<grid, NT, SH::LDS_BYTES, s>>>(
+  k_gemm_bf16<SH, Epi><<<grid, SH::NT, SH::LDS_BYTES, s>>>(
       (const bf16_t *)A.a, A.gather, A.lda, rows, N, seg, (const bf16_t *)w2, K, K / splitk,
       /*group_m=*/4, epi, sp);
   if (splitk > 1) {
     size_t total = (size_t)rows.cap * N;
-    int gr = (int)((total + NT - 1) / NT);
+    int gr = (int)((total + 255) / 256);
     if (gr > 4096) gr = 4096;
-    k_split_reduce<Epi><<<gr, NT, 0, s>>>(sp, splitk, rows, epi);
+    k_split_reduce<Epi><<<gr, 256, 0, s>>>(sp, splitk, rows, epi);
   }
 }
 
@@ -42,7 +47,7 @@ void run_tiles(GemmA A, Rows rows, int K, int N, WSeg seg, const void *w2, Epi e
 inline int pick_splitk(int N, int K, int bn, size_t part_elems, int cap) {
   const int tiles = N / bn;
   int s = 1;
-  while (tiles * s < 384 && s < 8 && (K / (s * 2)) % BK == 0 && K / (s * 2) >= 4 * BK) s *= 2;
+  while (tiles * s < 192 && s < 8 && (K / (s * 2)) % BK == 0 && K / (s * 2) >= 4 * BK) s *= 2;
   if ((size_t)s * cap * N > part_elems) s = 1;
   return s;
 }
@@ -59,6 +64,8 @@ void gemm_bf16_qkv(GemmA A, Rows rows, int K, const void *wq, const void *wk, co
   EpiStoreF32 e{out, N};
   if (rows.cap <= SKINNY_MAX_ROWS)
     run_tiles<SkinnyS>(A, rows, K, N, seg, nullptr, e, pick_splitk(N, K, SkinnyS::BN, part_elems, rows.cap), part, s);
+  else if (rows.cap <= MID_MAX_ROWS)
+    run_tiles<MidS>(A, rows, K, N, seg, nullptr, e, 1, part, s);
   else
     run_tiles<LargeS>(A, rows, K, N, seg, nullptr, e, 1, part, s);
 }
@@ -69,6 +76,8 @@ void gemm_bf16_oproj(GemmA A, Rows rows, int K, int N, const void *wo, const voi
   EpiOProj<bf16_t> e{(const bf16_t *)x, h, N};
   if (rows.cap <= SKINNY_MAX_ROWS)
     run_tiles<SkinnyS>(A, rows, K, N, one(wo, N), nullptr, e, pick_splitk(N, K, SkinnyS::BN, part_elems, rows.cap), part, s);
+  else if (rows.cap <= MID_MAX_ROWS)
+    run_tiles<MidS>(A, rows, K, N, one(wo, N), nullptr, e, 1, part, s);
   else
     run_tiles<LargeS>(A, rows, K, N, one(wo, N), nullptr, e, 1, part, s);
 }
@@ -79,6 +88,7 @@ void gemm_bf16_swiglu(GemmA A, Rows rows, int K, int N, const void *wg, const vo
   if (rows.cap <= 0) return;
   EpiSwiGLU<bf16_t> e{(bf16_t *)act, N};
   if (rows.cap <= SKINNY_MAX_ROWS) run_tiles<SkinnyD>(A, rows, K, N, one(wg, N), wu, e, 1, nullptr, s);
+  else if (rows.cap <= MID_MAX_ROWS) run_tiles<MidD>(A, rows, K, N, one(wg, N), wu, e, 1, nullptr, s);
   else run_tiles<LargeD>(A, rows, K, N, one(wg, N), wu, e, 1, nullptr, s);
 }
 
@@ -88,6 +98,8 @@ void gemm_bf16_down(GemmA A, Rows rows, int K, int N, const void *wd, const floa
   EpiDown<bf16_t> e{h, (bf16_t *)out, N};
   if (rows.cap <= SKINNY_MAX_ROWS)
     run_tiles<SkinnyS>(A, rows, K, N, one(wd, N), nullptr, e, pick_splitk(N, K, SkinnyS::BN, part_elems, rows.cap), part, s);
+  else if (rows.cap <= MID_MAX_ROWS)
+    run_tiles<MidS>(A, rows, K, N, one(wd, N), nullptr, e, 1, part, s);
   else
     run_tiles<LargeS>(A, rows, K, N, one(wd, N), nullptr, e, 1, part, s);
 }

@@ -1,0 +1,282 @@
+// bf16 salient-row GEMM for the gfx950 matrix cores with asynchronous global -> LDS copies.
+//   C[j,n] = sum_k A[row_j,k] * W[n,k]      (both operands K-contiguous)
+//
+// Data path.  K is cut into slices of 64 elements (128 bytes per tile row).  A slice of the
+// (BM + BN) tile rows is copied straight from global memory into LDS by global_load_lds_dwordx4:
+// every lane names its own 16-byte global source, the hardware writes lane i's data to
+// LDS[M0 + 16*i].  One such instruction therefore fills 8 tile rows x 128 bytes.  No register is
+// used for staging, so NS-1 slices can be in flight per workgroup while the MFMAs of the current
+// slice run; the only synchronisation is one s_waitcnt vmcnt + one barrier per slice.
+//
+// LDS layout.  Rows are 128 bytes, unpadded (the copy engine writes lanes back to back), with an
+// XOR swizzle instead: the 16-byte chunk c of tile row r lives at chunk position c ^ ((r/2) % 8).
+// The copy applies it on the global side (the lane that fills position p of row r fetches chunk
+// p ^ ((r/2) % 8)), the MFMA operand reads apply it on the LDS side.  The LDS of gfx950 has 64 banks
+// (256 bytes per clock) and serves a 16-byte-per-lane read 16 lanes at a time: 16 neighbouring
+// lanes (16 rows, same k) then touch 8 different positions in each of the two 128-byte bank halves
+// (even rows / odd rows) = all 64 banks once.
+//
+// MFMA.  v_mfma_f32_32x32x16_bf16: lane l supplies 8 consecutive k of row (l%32) for A and of
+// column (l%32) for B at k offset 8*(l/32); the accumulator block holds
+//   row = 8*(r/4) + 4*(l/32) + (r%4),  col = l%32   in register r of lane l.
+//
+// Tile walk.  The row count lives on the device; the grid is sized from the list capacity and each
+// workgroup walks the existing tiles in a grouped order, remapped so that neighbouring tiles run on
+// one XCD (workgroup i is dispatched to XCD i % 8) and share A / weight tiles in its L2.
+#pragma once
+#include "gemm_epilogues.h"
+#include "kernels.h"
+
+namespace dy {
+namespace mm {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+
+constexpr int BK = 64;    // K slice (elements)
+constexpr int ROWB = 128; // bytes per tile row and slice
+constexpr int N_XCD = 8;
+
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, bool DUAL_, int NS_> struct Shape {
+  static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, NS = NS_;
+  static constexpr bool DUAL = DUAL_;
+  static constexpr int NMAT = DUAL ? 2 : 1;
+  static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  static constexpr int MB = WM / 32, NB = WN / 32;
+  static constexpr int NW = WAVES_M * WAVES_N;  // waves per workgroup (4 or 8)
+  static constexpr int NT = NW * 64;
+  static constexpr int A_LD = BM / (8 * NW);  // copy instructions per wave and slice (8 rows each)
+  static constexpr int B_LD = BN / (8 * NW);
+  static constexpr int LPS = A_LD + NMAT * B_LD;  // copies per wave and slice
+  static constexpr int STAGE_BYTES = (BM + NMAT * BN) * ROWB;
+  static constexpr size_t LDS_BYTES = (size_t)NS * STAGE_BYTES;
+  static_assert(NW == 4 || NW == 8, "four or eight waves per workgroup");
+  static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile is made of 32x32 blocks");
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows are copied in blocks of 8 per wave");
+  static_assert(NS >= 2 && NS <= 4, "2 to 4 LDS stages");
+  static_assert((NS - 2) * LPS < 64, "vmcnt immediate");
+};
+
+struct SplitStore {  // K-split: fp32 partial tile part[z][j][n] instead of the fused epilogue
+  float *part;
+  size_t split_stride;
+  int N;
+};
+
+// lane i: 16 bytes from its global address g -> LDS[lds_base + 16*i]; lds_base is wave-uniform.
+__device__ __forceinline__ void dma16(const void *g, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :
+               : "s"(lds_base), "v"(g)
+               : "memory", "m0");
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_offset_of(const void *p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+
+template <typename SH, typename Epi>
+__global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__ A,
+                                                   const int32_t *__restrict__ gather, int lda,
+                                                   Rows rows, int N, WSeg seg,
+                                                   const bf16_t *__restrict__ W2, int ldw, int kchunk,
+                                                   int group_m, Epi epi, SplitStore split) {
+  extern __shared__ __align__(1024) unsigned char smem_raw[];
+  constexpr int BM = SH::BM, BN = SH::BN, MB = SH::MB, NB = SH::NB, NMAT = SH::NMAT, NS = SH::NS;
+
+  const int M = rows.count ? min(*rows.count, rows.cap) : rows.cap;
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+  const int total = tiles_m * tiles_n;
+  const int tid = threadIdx.x, lane = tid % WAVE;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);  // wave-uniform, kept scalar
+  const int wm0 = (wave / SH::WAVES_N) * SH::WM, wn0 = (wave % SH::WAVES_N) * SH::WN;
+  const int l32 = lane % 32, lhi = lane / 32;
+  const int z = blockIdx.y;  // K split
+  const int kbeg = z * kchunk;
+  const int KT = kchunk / BK;
+  const uint32_t lds0 = lds_offset_of(smem_raw);
+
+  // copy mapping of this lane inside an 8-row block: tile row r8, chunk position p, source chunk c
+  const int r8 = lane / 8, cpos = lane % 8;
+  // tile row of this lane in copy i is (i*NW + wave)*8 + r8, so (row/2) % 8 = ((wave & 1) * 4 + r8 / 2)
+  const int csrc = cpos ^ (((wave & 1) << 2) | (r8 >> 1));
+  // operand-read swizzle of this lane: chunk position of logical chunk (2*kk + lhi)
+  int rd_off[BK / 16];
+#pragma unroll
+  for (int kk = 0; kk < BK / 16; ++kk) rd_off[kk] = (((2 * kk + lhi) ^ ((l32 >> 1) & 7)) * 16);
+
+  const int per_xcd = (total + N_XCD - 1) / N_XCD;
+  const int total_pad = per_xcd * N_XCD;
+
+  for (int p = blockIdx.x; p < total_pad; p += gridDim.x) {
+    const int logical = (p % N_XCD) * per_xcd + p / N_XCD;
+    if (logical >= total) continue;  // uniform for the workgroup
+    const int gsz = group_m * tiles_n;
+    const int g = logical / gsz, r = logical % gsz;
+    const int gm = min(group_m, tiles_m - g * group_m);
+    const int tm = g * group_m + r % gm, tn = r / gm;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    // per-lane global sources of the copies it issues every slice
+    const bf16_t *ap[SH::A_LD];
+#pragma unroll
+    for (int i = 0; i < SH::A_LD; ++i) {
+      int j = m0 + (i * SH::NW + wave) * 8 + r8;
+      j = j < M ? j : M - 1;  // rows past the end are clamped; their results are never stored
+      const int src = gather ? gather[j] : j;
+      ap[i] = A + (size_t)src * lda + kbeg + csrc * 8;
+    }
+    int sg = 0;
+    while (sg < 2 && n0 >= seg.n_end[sg]) ++sg;
+    const int seg_start = sg ? seg.n_end[sg - 1] : 0;
+    const bf16_t *wp[NMAT][SH::B_LD];
+#pragma unroll
+    for (int i = 0; i < SH::B_LD; ++i) {
+      const size_t roff = (size_t)((i * SH::NW + wave) * 8 + r8) * ldw + kbeg + csrc * 8;
+      wp[0][i] = (const bf16_t *)seg.w[sg] + (size_t)(n0 - seg_start) * ldw + roff;
+      if (SH::DUAL) wp[NMAT - 1][i] = W2 + (size_t)n0 * ldw + roff;
+    }
+
+    floatx16 acc[NMAT][MB][NB];
+#pragma unroll
+    for (int t = 0; t < NMAT; ++t)
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[t][i][j][e] = 0.f;
+
+    auto issue = [&](int kt) {  // slice kt -> stage kt % NS
+      const uint32_t sb = lds0 + (uint32_t)(kt % NS) * SH::STAGE_BYTES + (uint32_t)wave * 1024u;
+      const int ko = kt * BK;
+#pragma unroll
+      for (int i = 0; i < SH::A_LD; ++i) dma16(ap[i] + ko, sb + i * (SH::NW * 1024u));
+#pragma unroll
+      for (int t = 0; t < NMAT; ++t)
+#pragma unroll
+        for (int i = 0; i < SH::B_LD; ++i)
+          dma16(wp[t][i] + ko, sb + (uint32_t)(BM + t * BN) * ROWB + i * (SH::NW * 1024u));
+    };
+
+    __syncthreads();  // LDS free: the previous tile of this workgroup is fully consumed
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+      if (s < KT) issue(s);
+
+    for (int kt = 0; kt < KT; ++kt) {
+      if (kt + NS - 2 < KT) wait_vmcnt<(NS - 2) * SH::LPS>();  // slice kt has landed (this wave's part)
+      else wait_vmcnt<0>();
+      __syncthreads();  // ... all waves' parts; and everyone is done with slice kt-1
+      if (kt + NS - 1 < KT) issue(kt + NS - 1);  // into the stage slice kt-1 occupied
+
+      const unsigned char *st = smem_raw + (size_t)(kt % NS) * SH::STAGE_BYTES;
+      const unsigned char *sa = st + (wm0 + l32) * ROWB;
+      const unsigned char *sb = st + BM * ROWB + (wn0 + l32) * ROWB;
+      // operand fragments of slice step kk+1 are fetched while the MFMAs of step kk run
+      bf16x8 af[2][MB], bfr[2][NMAT][NB];
+#pragma unroll
+      for (int i = 0; i < MB; ++i) af[0][i] = *reinterpret_cast<const bf16x8 *>(sa + i * 32 * ROWB + rd_off[0]);
+#pragma unroll
+      for (int t = 0; t < NMAT; ++t)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+          bfr[0][t][j] = *reinterpret_cast<const bf16x8 *>(sb + (t * BN + j * 32) * ROWB + rd_off[0]);
+#pragma unroll
+      for (int kk = 0; kk < BK / 16; ++kk) {
+        const int c = kk & 1, n = c ^ 1;
+        if (kk + 1 < BK / 16) {
+#pragma unroll
+          for (int i = 0; i < MB; ++i)
+            af[n][i] = *reinterpret_cast<const bf16x8 *>(sa + i * 32 * ROWB + rd_off[kk + 1]);
+#pragma unroll
+          for (int t = 0; t < NMAT; ++t)
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+              bfr[n][t][j] = *reinterpret_cast<const bf16x8 *>(sb + (t * BN + j * 32) * ROWB + rd_off[kk + 1]);
+        }
+#pragma unroll
+        for (int t = 0; t < NMAT; ++t)
+#pragma unroll
+          for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+              acc[t][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[c][i], bfr[c][t][j], acc[t][i][j], 0, 0, 0);
+      }
+      // Instruction order of the slice: the first step's operand reads, then the LDS reads of step
+      // kk+1 spread one by one between the MFMAs of step kk (the scheduler alone fetches each
+      // operand right before its use and leaves the matrix pipe waiting on the LDS).
+      {
+        constexpr int RD = MB + NMAT * NB, MM = NMAT * MB * NB;
+        __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
+#pragma unroll
+        for (int kk = 0; kk + 1 < BK / 16; ++kk) {
+#pragma unroll
+          for (int q = 0; q < RD; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          }
+          if (MM > RD) __builtin_amdgcn_sched_group_barrier(0x008, MM - RD, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, MM, 0);
+      }
+    }
+
+    // epilogue
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
+        if (j < M) {
+          if (split.part) {
+#pragma unroll
+            for (int jn = 0; jn < NB; ++jn)
+              split.part[(size_t)z * split.split_stride + (size_t)j * split.N + n0 + wn0 + jn * 32 + l32] =
+                  acc[0][i][jn][e];
+          } else {
+            const int row = rows.idx ? rows.idx[j] : j;
+#pragma unroll
+            for (int jn = 0; jn < NB; ++jn)
+              epi(j, row, n0 + wn0 + jn * 32 + l32, acc[0][i][jn][e], acc[NMAT - 1][i][jn][e]);
+          }
+        }
+      }
+  }
+}
+
+// Sum of K-split partials, then the real epilogue, one thread per output element.
+template <typename Epi>
+__global__ __launch_bounds__(256) void k_split_reduce(SplitStore split, int splits, Rows rows, Epi epi) {
+  const int M = rows.count ? min(*rows.count, rows.cap) : rows.cap;
+  const size_t total = (size_t)M * split.N;
+  for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
+    const int j = (int)(e / split.N), n = (int)(e % split.N);
+    float s = 0.f;
+    for (int z = 0; z < splits; ++z) s += split.part[(size_t)z * split.split_stride + e];
+    epi(j, rows.idx ? rows.idx[j] : j, n, s, 0.f);
+  }
+}
+
+inline WSeg one(const void *w, int N) {
+  WSeg s;
+  s.w[0] = s.w[1] = s.w[2] = w;
+  s.n_end[0] = s.n_end[1] = s.n_end[2] = N;
+  return s;
+}
+
+template <typename SH, typename Epi> void set_lds_once() {
+  static bool done = false;
+  if (!done) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<SH, Epi>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)SH::LDS_BYTES);
+    done = true;
+  }
+}
+
+}  // namespace mm
+}  // namespace dy
