@@ -24,10 +24,9 @@ struct dyllm_ctx {
   void *ns;        // [R, d]        normalised salient rows
   float *qkv;      // [R, dq+2dkv]  fp32 projections before rotation
   void *qs;        // [R, dq]       rotated queries
-  float *part_o;   // attention split partials
+  float *part_o;   // fp32 scratch shared by consecutive stages: raw GEMM results / attention partials
   float *part_ml;
   size_t part_elems;
-  void *cs;        // [R, dq]       new contexts of the candidate rows
   float *cosb;     // [R]
   uint8_t *flag;   // [R]
   float *hs;       // [R, d]        x + Wo c (fp32)
@@ -45,7 +44,7 @@ struct dyllm_ctx {
 namespace {
 
 struct Layout {
-  size_t ns, qkv, qs, part_o, part_ml, cs, cosb, flag, hs, fs, act, status, rope, total;
+  size_t ns, qkv, qs, part_o, part_ml, cosb, flag, hs, fs, act, status, rope, total;
   size_t part_elems;
 };
 
@@ -61,12 +60,12 @@ Layout make_layout(const dyllm_layer_cfg &c) {
   l.ns = take(R * d * e);
   l.qkv = take(R * (dq + 2 * dkv) * 4);
   l.qs = take(R * dq * e);
-  // split partials: room for 16 splits of up to 2048 rows, or one set of R rows
+  // fp32 scratch: 16 attention splits of up to 2048 rows, or one raw GEMM result of R rows
   const size_t prow = R < 2048 ? R : 2048;
-  l.part_elems = (16 * prow > R ? 16 * prow : R) * dq;
+  const size_t widest = dq + 2 * dkv > d ? dq + 2 * dkv : d;
+  l.part_elems = 16 * prow * dq > R * widest ? 16 * prow * dq : R * widest;
   l.part_o = take(l.part_elems * 4);
   l.part_ml = take(l.part_elems / c.head_dim * 2 * 4);
-  l.cs = take(R * dq * e);
   l.cosb = take(R * 4);
   l.flag = take(R);
   l.hs = take(R * d * 4);
@@ -149,45 +148,59 @@ void prof_mark(dyllm_ctx *ctx, int stage, hipStream_t s) {
   if (ctx->prof_cur) (void)hipEventRecord(ctx->prof_cur[stage + 1], s);
 }
 
-// a-1..a-3: gather + norm, q/k/v projection, rotation, K/V merge
+// gather + norm, q/k/v projection, rotation, K/V merge  [Alg. 3: norm / q_proj / k_proj / v_proj lines]
 int enqueue_qkv(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x, Rows rows, int L,
                 dyllm_layer_cache *cache, void *q_out, hipStream_t s) {
   const dyllm_layer_cfg &c = ctx->cfg;
   launch_gather_rmsnorm(dt(ctx), x, w->g_attn, rows, c.hidden, c.rms_eps, ctx->ns, s);
   prof_mark(ctx, ST_GATHER_NORM, s);
-  launch_gemm_qkv(dt(ctx), GemmA{ctx->ns, nullptr, c.hidden}, rows, c.hidden, w->wq, w->wk, w->wv,
-                  ctx->dq, ctx->dkv, ctx->qkv, ctx->part_o, ctx->part_elems, s);
+  WSeg seg;
+  seg.w[0] = w->wq; seg.w[1] = w->wk; seg.w[2] = w->wv;
+  seg.n_end[0] = ctx->dq; seg.n_end[1] = ctx->dq + ctx->dkv; seg.n_end[2] = ctx->dq + 2 * ctx->dkv;
+  const int splits = launch_gemm_raw(dt(ctx), GemmA{ctx->ns, nullptr, c.hidden}, rows, c.hidden, seg,
+                                     ctx->part_o, ctx->part_elems, s);
   prof_mark(ctx, ST_GEMM_QKV, s);
-  launch_rope_scatter(dt(ctx), ctx->qkv, ctx->rope, rows, L, c.n_heads, c.n_kv_heads, c.head_dim,
-                      w->bq, w->bk, w->bv, q_out, cache->k, cache->v, s);
+  launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)rows.cap * seg.n_end[2], ctx->rope, rows, L,
+                      c.n_heads, c.n_kv_heads, c.head_dim, w->bq, w->bk, w->bv, q_out, cache->k,
+                      cache->v, s);
   prof_mark(ctx, ST_ROPE_SCATTER, s);
   return check_launch(ctx, "qkv refresh");
 }
 
-int enqueue_attention(dyllm_ctx *ctx, const void *q, const void *k, const void *v, Rows rows,
-                      const int32_t *offsets, int B, int L, void *out, hipStream_t s) {
+AttnArgs attn_args(dyllm_ctx *ctx, const void *q, const void *k, const void *v, Rows rows,
+                   const int32_t *offsets, int B, int L, void *out, int partial) {
   const dyllm_layer_cfg &c = ctx->cfg;
   AttnArgs a;
   a.q = q; a.k = k; a.v = v; a.rows = rows; a.offsets = offsets;
   a.B = B; a.L = L; a.H = c.n_heads; a.Hkv = c.n_kv_heads; a.dh = c.head_dim;
   attention_plan(dt(ctx), B, L, c.n_heads, c.head_dim, rows.cap, ctx->part_elems, &a.splits, &a.chunk);
+  a.partial = partial;
   a.part_o = ctx->part_o; a.part_ml = ctx->part_ml; a.out = out;
+  return a;
+}
+
+// exact attention rows, merged into `out`  [Alg. 3: C_sal]
+int enqueue_attention(dyllm_ctx *ctx, const void *q, const void *k, const void *v, Rows rows,
+                      const int32_t *offsets, int B, int L, void *out, hipStream_t s) {
+  const AttnArgs a = attn_args(ctx, q, k, v, rows, offsets, B, L, out, 0);
   launch_attention(dt(ctx), a, s);
   prof_mark(ctx, ST_ATTENTION, s);
   return check_launch(ctx, "partial attention");
 }
 
-// a-7..a-9: out-projection + residual, norm, SwiGLU FFN + residual, scatter into the output cache
+// out-projection + residual, norm, SwiGLU FFN + residual, scatter into the output cache
+// [Alg. 3: out_proj / FFN / cache lines]
 int enqueue_ffn(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x, const void *c_all,
                 Rows rows, void *out_cache, hipStream_t s) {
   const dyllm_layer_cfg &c = ctx->cfg;
-  launch_gemm_oproj(dt(ctx), GemmA{c_all, rows.idx, ctx->dq}, rows, ctx->dq, c.hidden, w->wo, x,
-                    ctx->hs, ctx->part_o, ctx->part_elems, s);
+  const int splits = launch_gemm_raw(dt(ctx), GemmA{c_all, rows.idx, ctx->dq}, rows, ctx->dq,
+                                     wseg_one(w->wo, c.hidden), ctx->part_o, ctx->part_elems, s);
   prof_mark(ctx, ST_GEMM_OPROJ, s);
-  launch_rmsnorm_f32in(dt(ctx), ctx->hs, w->g_ffn, rows, c.hidden, c.rms_eps, ctx->fs, s);
+  launch_oproj_finalize(dt(ctx), ctx->part_o, splits, (size_t)rows.cap * c.hidden, x, w->g_ffn, rows,
+                        c.hidden, c.rms_eps, ctx->hs, ctx->fs, s);
   prof_mark(ctx, ST_NORM_FFN, s);
   launch_gemm_swiglu(dt(ctx), GemmA{ctx->fs, nullptr, c.hidden}, rows, c.hidden, c.ffn_dim, w->w_gate,
-                     w->w_up, ctx->act, ctx->part_o, ctx->part_elems, s);
+                     w->w_up, ctx->act, s);
   prof_mark(ctx, ST_GEMM_SWIGLU, s);
   launch_gemm_down(dt(ctx), GemmA{ctx->act, nullptr, c.ffn_dim}, rows, c.ffn_dim, c.hidden, w->w_down,
                    ctx->hs, out_cache, ctx->part_o, ctx->part_elems, s);
@@ -260,7 +273,7 @@ int dyllm_create(const dyllm_layer_cfg *cfg, dyllm_ctx **out) {
   ctx->ns = b + l.ns; ctx->qkv = (float *)(b + l.qkv); ctx->qs = b + l.qs;
   ctx->part_o = (float *)(b + l.part_o); ctx->part_ml = (float *)(b + l.part_ml);
   ctx->part_elems = l.part_elems;
-  ctx->cs = b + l.cs; ctx->cosb = (float *)(b + l.cosb); ctx->flag = (uint8_t *)(b + l.flag);
+  ctx->cosb = (float *)(b + l.cosb); ctx->flag = (uint8_t *)(b + l.flag);
   ctx->hs = (float *)(b + l.hs); ctx->fs = b + l.fs; ctx->act = b + l.act;
   ctx->status = (int32_t *)(b + l.status); ctx->rope = (float *)(b + l.rope);
 
@@ -445,11 +458,14 @@ int dyllm_layer_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_c
   const Rows rin = rows_of(idx_in, B);
   prof_begin_call(ctx, s);
   if ((rc = enqueue_qkv(ctx, w, x, rin, L, cache, ctx->qs, s))) return rc;
-  if ((rc = enqueue_attention(ctx, ctx->qs, cache->k, cache->v, rin, idx_in->offsets, B, L, ctx->cs, s)))
-    return rc;
-  launch_saliency(dt(ctx), ctx->cs, cache->c, rin, ctx->dq, tau, cos_out ? cos_out : ctx->cosb,
-                  ctx->flag, 1, s);
-  prof_mark(ctx, ST_SALIENCY, s);
+  {
+    // attention leaves per-split partials; their merge is fused with the cosine test and the commit
+    const AttnArgs a = attn_args(ctx, ctx->qs, cache->k, cache->v, rin, idx_in->offsets, B, L, nullptr, 1);
+    launch_attention(dt(ctx), a, s);
+    prof_mark(ctx, ST_ATTENTION, s);
+    launch_attn_finalize(dt(ctx), a, cache->c, tau, cos_out ? cos_out : ctx->cosb, ctx->flag, s);
+    prof_mark(ctx, ST_SALIENCY, s);
+  }
   launch_compact(ctx->flag, rin, B, L, idx_out->idx, idx_out->offsets, idx_out->cap, ctx->status, s);
   prof_mark(ctx, ST_COMPACT, s);
   if ((rc = check_launch(ctx, "saliency / compact"))) return rc;

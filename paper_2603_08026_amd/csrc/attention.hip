@@ -5,26 +5,72 @@ namespace dy {
 
 namespace {
 
-// One workgroup per query row.  For every head: M = max_s m_s, l = sum_s l_s e^{m_s - M},
-// out = sum_s o_s e^{m_s - M} / l  (the usual merge of online-softmax partials).
+// One workgroup per query row, a thread per 4 neighbouring columns (all of one head).  For every
+// head: M = max_s m_s, l = sum_s l_s e^{m_s - M}, out = sum_s o_s e^{m_s - M} / l  (the usual merge
+// of online-softmax partials).
+__device__ __forceinline__ float4 merge_splits(const AttnArgs &a, int j, int c, int D) {
+  const int h = c / a.dh;
+  float M = -INFINITY;
+  for (int s = 0; s < a.splits; ++s) M = fmaxf(M, a.part_ml[(((size_t)s * a.rows.cap + j) * a.H + h) * 2]);
+  float l = 0.f;
+  float4 acc{0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < a.splits; ++s) {
+    const float2 ml = *reinterpret_cast<const float2 *>(a.part_ml + (((size_t)s * a.rows.cap + j) * a.H + h) * 2);
+    const float w = __expf(ml.x - M);
+    const float4 o = *reinterpret_cast<const float4 *>(a.part_o + ((size_t)s * a.rows.cap + j) * D + c);
+    l += ml.y * w;
+    acc.x += o.x * w; acc.y += o.y * w; acc.z += o.z * w; acc.w += o.w * w;
+  }
+  const float inv = 1.0f / l;
+  return float4{acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv};
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void k_attn_combine(AttnArgs a) {
   const int n = a.rows.count ? min(*a.rows.count, a.rows.cap) : a.rows.cap;
   const int D = a.H * a.dh;
   for (int j = blockIdx.x; j < n; j += gridDim.x) {
-    for (int c = threadIdx.x; c < D; c += 256) {
-      const int h = c / a.dh;
-      float M = -INFINITY;
-      for (int s = 0; s < a.splits; ++s)
-        M = fmaxf(M, a.part_ml[(((size_t)s * a.rows.cap + j) * a.H + h) * 2]);
-      float l = 0.f, acc = 0.f;
-      for (int s = 0; s < a.splits; ++s) {
-        const float *ml = a.part_ml + (((size_t)s * a.rows.cap + j) * a.H + h) * 2;
-        const float wgt = __expf(ml[0] - M);
-        l += ml[1] * wgt;
-        acc += a.part_o[((size_t)s * a.rows.cap + j) * D + c] * wgt;
-      }
-      ((T *)a.out)[(size_t)j * D + c] = from_f<T>(acc / l);
+    T *orow = (T *)a.out + (size_t)j * D;
+    for (int c = threadIdx.x * 4; c < D; c += 1024) {
+      const float4 o = merge_splits(a, j, c, D);
+      orow[c] = from_f<T>(o.x); orow[c + 1] = from_f<T>(o.y);
+      orow[c + 2] = from_f<T>(o.z); orow[c + 3] = from_f<T>(o.w);
+    }
+  }
+}
+
+// Merge of the partials fused with the temporal cosine similarity, the salient test and the context
+// commit  [Sec. 3.1, Sec. 3.2; Alg. 3: cosine line and cache commit].  The new context is rounded to
+// the storage type first; the cosine is taken over the stored values (so an unchanged context gives
+// exactly the cached row and s = 1), the old cache row is read before it is overwritten.
+template <typename T>
+__global__ __launch_bounds__(256) void k_attn_finalize(AttnArgs a, T *c_cache, float tau,
+                                                        float *__restrict__ cos_out,
+                                                        uint8_t *__restrict__ flag_out) {
+  __shared__ float red[256 / WAVE];
+  const int n = a.rows.count ? min(*a.rows.count, a.rows.cap) : a.rows.cap;
+  const int D = a.H * a.dh;
+  for (int j = blockIdx.x; j < n; j += gridDim.x) {
+    const int r = a.rows.idx ? a.rows.idx[j] : j;
+    T *crow = c_cache + (size_t)r * D;
+    float dot = 0.f, na = 0.f, nb = 0.f;
+    for (int c = threadIdx.x * 4; c < D; c += 1024) {
+      const float4 o = merge_splits(a, j, c, D);
+      const T n0 = from_f<T>(o.x), n1 = from_f<T>(o.y), n2 = from_f<T>(o.z), n3 = from_f<T>(o.w);
+      const float f0 = to_f<T>(n0), f1 = to_f<T>(n1), f2 = to_f<T>(n2), f3 = to_f<T>(n3);
+      const float b0 = to_f<T>(crow[c]), b1 = to_f<T>(crow[c + 1]), b2 = to_f<T>(crow[c + 2]), b3 = to_f<T>(crow[c + 3]);
+      dot += f0 * b0 + f1 * b1 + f2 * b2 + f3 * b3;
+      na += f0 * f0 + f1 * f1 + f2 * f2 + f3 * f3;
+      nb += b0 * b0 + b1 * b1 + b2 * b2 + b3 * b3;
+      crow[c] = n0; crow[c + 1] = n1; crow[c + 2] = n2; crow[c + 3] = n3;
+    }
+    dot = block_sum<256>(dot, red);
+    na = block_sum<256>(na, red);
+    nb = block_sum<256>(nb, red);
+    if (threadIdx.x == 0) {
+      const float s = dot / (fmaxf(sqrtf(na), 1e-8f) * fmaxf(sqrtf(nb), 1e-8f));
+      if (cos_out) cos_out[j] = s;
+      flag_out[j] = (s < tau) ? 1 : 0;
     }
   }
 }
@@ -36,6 +82,14 @@ void launch_attn_combine(DType t, const AttnArgs &a, hipStream_t s) {
   if (grid < 1) return;
   if (t == F32) k_attn_combine<float><<<grid, 256, 0, s>>>(a);
   else k_attn_combine<bf16_t><<<grid, 256, 0, s>>>(a);
+}
+
+void launch_attn_finalize(DType t, const AttnArgs &a, void *c_cache, float tau, float *cos_out,
+                          uint8_t *flag_out, hipStream_t s) {
+  int grid = a.rows.cap > 8192 ? 8192 : a.rows.cap;
+  if (grid < 1) return;
+  if (t == F32) k_attn_finalize<float><<<grid, 256, 0, s>>>(a, (float *)c_cache, tau, cos_out, flag_out);
+  else k_attn_finalize<bf16_t><<<grid, 256, 0, s>>>(a, (bf16_t *)c_cache, tau, cos_out, flag_out);
 }
 
 // Splits of the key range: enough workgroups to cover the chip a few times over when there are few
@@ -60,7 +114,7 @@ void launch_attention(DType t, const AttnArgs &a, hipStream_t s) {
   if (a.rows.cap <= 0) return;
   if (t == F32) launch_attention_f32(t, a, s);
   else launch_attention_bf16(a, s);
-  if (a.splits > 1) launch_attn_combine(t, a, s);
+  if (a.splits > 1 && !a.partial) launch_attn_combine(t, a, s);
 }
 
 }  // namespace dy

@@ -291,7 +291,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
       const int r = wq * 64 + qb * 32 + l32;
       if (r < nq) {
         const int j = j0 + r;
-        if (a.splits == 1) {
+        if (a.splits == 1 && !a.partial) {
           bf16_t *out = (bf16_t *)a.out + ((size_t)j * a.H + h) * DH + 4 * lhi;
           const float inv = 1.0f / l_run[qb];
 #pragma unroll

@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void k_attn_f32(AttnArgs a) {
 
   if (row < nq) {
     const int j = j0 + row;
-    if (a.splits == 1) {
+    if (a.splits == 1 && !a.partial) {
       T *out = (T *)a.out + ((size_t)j * a.H + h) * DH;
       const float inv = 1.0f / l_run;
 #pragma unroll

@@ -30,17 +30,11 @@ void run_tiles(GemmA A, Rows rows, int K, int N, WSeg seg, const void *w2, Epi e
   int gx = tiles < 1 ? 1 : tiles;
   if (gx > 2048) gx = 2048;
   gx = (gx + N_XCD - 1) / N_XCD * N_XCD;  // multiple of the XCD count: p % 8 is then the XCD of p
-  SplitStore sp{splitk > 1 ? part : nullptr, (size_t)rows.cap * N, N};
+  SplitStore sp{part, (size_t)rows.cap * N, N};
   dim3 grid(gx, splitk);
   k_gemm_bf16<SH, Epi><<<grid, SH::NT, SH::LDS_BYTES, s>>>(
       (const bf16_t *)A.a, A.gather, A.lda, rows, N, seg, (const bf16_t *)w2, K, K / splitk,
       /*group_m=*/4, epi, sp);
-  if (splitk > 1) {
-    size_t total = (size_t)rows.cap * N;
-    int gr = (int)((total + 255) / 256);
-    if (gr > 4096) gr = 4096;
-    k_split_reduce<Epi><<<gr, 256, 0, s>>>(sp, splitk, rows, epi);
-  }
 }
 
 // K split for the skinny regime when the column tiles alone cannot fill the chip.
@@ -48,60 +42,53 @@ inline int pick_splitk(int N, int K, int bn, size_t part_elems, int cap) {
   const int tiles = N / bn;
   int s = 1;
   while (tiles * s < 192 && s < 8 && (K / (s * 2)) % BK == 0 && K / (s * 2) >= 4 * BK) s *= 2;
-  if ((size_t)s * cap * N > part_elems) s = 1;
+  while (s > 1 && (size_t)s * cap * N > part_elems) s /= 2;
   return s;
 }
 
 }  // namespace
 
-void gemm_bf16_qkv(GemmA A, Rows rows, int K, const void *wq, const void *wk, const void *wv, int dq,
-                   int dkv, float *out, float *part, size_t part_elems, hipStream_t s) {
-  if (rows.cap <= 0) return;
-  WSeg seg;
-  seg.w[0] = wq; seg.w[1] = wk; seg.w[2] = wv;
-  seg.n_end[0] = dq; seg.n_end[1] = dq + dkv; seg.n_end[2] = dq + 2 * dkv;
-  const int N = dq + 2 * dkv;
-  EpiStoreF32 e{out, N};
-  if (rows.cap <= SKINNY_MAX_ROWS)
-    run_tiles<SkinnyS>(A, rows, K, N, seg, nullptr, e, pick_splitk(N, K, SkinnyS::BN, part_elems, rows.cap), part, s);
-  else if (rows.cap <= MID_MAX_ROWS)
-    run_tiles<MidS>(A, rows, K, N, seg, nullptr, e, 1, part, s);
-  else
-    run_tiles<LargeS>(A, rows, K, N, seg, nullptr, e, 1, part, s);
-}
-
-void gemm_bf16_oproj(GemmA A, Rows rows, int K, int N, const void *wo, const void *x, float *h,
-                     float *part, size_t part_elems, hipStream_t s) {
-  if (rows.cap <= 0) return;
-  EpiOProj<bf16_t> e{(const bf16_t *)x, h, N};
-  if (rows.cap <= SKINNY_MAX_ROWS)
-    run_tiles<SkinnyS>(A, rows, K, N, one(wo, N), nullptr, e, pick_splitk(N, K, SkinnyS::BN, part_elems, rows.cap), part, s);
-  else if (rows.cap <= MID_MAX_ROWS)
-    run_tiles<MidS>(A, rows, K, N, one(wo, N), nullptr, e, 1, part, s);
-  else
-    run_tiles<LargeS>(A, rows, K, N, one(wo, N), nullptr, e, 1, part, s);
+// raw result part[z][j][n]; returns the number of K splits
+int gemm_bf16_raw(GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_elems, hipStream_t s) {
+  if (rows.cap <= 0) return 1;
+  const int N = seg.n_end[2];
+  EpiStoreF32 e{part, N};
+  if (rows.cap <= SKINNY_MAX_ROWS) {
+    const int sk = pick_splitk(N, K, SkinnyS::BN, part_elems, rows.cap);
+    run_tiles<SkinnyS>(A, rows, K, N, seg, nullptr, e, sk, part, s);
+    return sk;
+  }
+  if (rows.cap <= MID_MAX_ROWS) run_tiles<MidS>(A, rows, K, N, seg, nullptr, e, 1, part, s);
+  else run_tiles<LargeS>(A, rows, K, N, seg, nullptr, e, 1, part, s);
+  return 1;
 }
 
 void gemm_bf16_swiglu(GemmA A, Rows rows, int K, int N, const void *wg, const void *wu, void *act,
-                      float *part, size_t part_elems, hipStream_t s) {
-  (void)part; (void)part_elems;
+                      hipStream_t s) {
   if (rows.cap <= 0) return;
   EpiSwiGLU<bf16_t> e{(bf16_t *)act, N};
-  if (rows.cap <= SKINNY_MAX_ROWS) run_tiles<SkinnyD>(A, rows, K, N, one(wg, N), wu, e, 1, nullptr, s);
-  else if (rows.cap <= MID_MAX_ROWS) run_tiles<MidD>(A, rows, K, N, one(wg, N), wu, e, 1, nullptr, s);
-  else run_tiles<LargeD>(A, rows, K, N, one(wg, N), wu, e, 1, nullptr, s);
+  if (rows.cap <= SKINNY_MAX_ROWS) run_tiles<SkinnyD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
+  else if (rows.cap <= MID_MAX_ROWS) run_tiles<MidD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
+  else run_tiles<LargeD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
 }
 
 void gemm_bf16_down(GemmA A, Rows rows, int K, int N, const void *wd, const float *h, void *out,
                     float *part, size_t part_elems, hipStream_t s) {
   if (rows.cap <= 0) return;
   EpiDown<bf16_t> e{h, (bf16_t *)out, N};
-  if (rows.cap <= SKINNY_MAX_ROWS)
-    run_tiles<SkinnyS>(A, rows, K, N, one(wd, N), nullptr, e, pick_splitk(N, K, SkinnyS::BN, part_elems, rows.cap), part, s);
-  else if (rows.cap <= MID_MAX_ROWS)
-    run_tiles<MidS>(A, rows, K, N, one(wd, N), nullptr, e, 1, part, s);
-  else
-    run_tiles<LargeS>(A, rows, K, N, one(wd, N), nullptr, e, 1, part, s);
+  if (rows.cap <= SKINNY_MAX_ROWS) {
+    const int sk = pick_splitk(N, K, SkinnyS::BN, part_elems, rows.cap);
+    if (sk > 1) {
+      run_tiles<SkinnyS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, sk, part, s);
+      launch_down_finalize(BF16, part, sk, (size_t)rows.cap * N, h, rows, N, out, s);
+    } else {
+      run_tiles<SkinnyS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, 1, nullptr, s);
+    }
+  } else if (rows.cap <= MID_MAX_ROWS) {
+    run_tiles<MidS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, 1, nullptr, s);
+  } else {
+    run_tiles<LargeS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, 1, nullptr, s);
+  }
 }
 
 }  // namespace dy

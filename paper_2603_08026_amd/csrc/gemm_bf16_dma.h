@@ -57,7 +57,7 @@ template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, bool DUAL_, int NS_> str
   static_assert((NS - 2) * LPS < 64, "vmcnt immediate");
 };
 
-struct SplitStore {  // K-split: fp32 partial tile part[z][j][n] instead of the fused epilogue
+struct SplitStore {  // part != nullptr: raw fp32 tile part[z][j][n] instead of the fused epilogue
   float *part;
   size_t split_stride;
   int N;
@@ -247,26 +247,6 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
         }
       }
   }
-}
-
-// Sum of K-split partials, then the real epilogue, one thread per output element.
-template <typename Epi>
-__global__ __launch_bounds__(256) void k_split_reduce(SplitStore split, int splits, Rows rows, Epi epi) {
-  const int M = rows.count ? min(*rows.count, rows.cap) : rows.cap;
-  const size_t total = (size_t)M * split.N;
-  for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
-    const int j = (int)(e / split.N), n = (int)(e % split.N);
-    float s = 0.f;
-    for (int z = 0; z < splits; ++z) s += split.part[(size_t)z * split.split_stride + e];
-    epi(j, rows.idx ? rows.idx[j] : j, n, s, 0.f);
-  }
-}
-
-inline WSeg one(const void *w, int N) {
-  WSeg s;
-  s.w[0] = s.w[1] = s.w[2] = w;
-  s.n_end[0] = s.n_end[1] = s.n_end[2] = N;
-  return s;
 }
 
 template <typename SH, typename Epi> void set_lds_once() {

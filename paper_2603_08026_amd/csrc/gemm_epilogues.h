@@ -1,11 +1,11 @@
 // Epilogues of the salient-row GEMMs.  Each takes the fp32 accumulator(s) of output element
 // (j, n) -- j = position in the row list, n = output column -- and finishes the fused step:
-//   EpiStoreF32 ... plain fp32 store (q/k/v projection; bias and rotation follow in a row kernel)
-//   EpiOProj ...... h = x[row_j] + acc                      [Alg. 3: out_proj, with the residual]
+//   EpiStoreF32 ... plain fp32 store (raw result; a finalize row kernel follows)
 //   EpiSwiGLU ..... act = silu(acc_gate) * acc_up           [Alg. 3: FFN, first half]
 //   EpiDown ....... out_cache[row_j] = h + acc              [Alg. 3: FFN second half + cache commit]
 #pragma once
 #include "common.h"
+#include "kernels.h"
 
 namespace dy {
 
@@ -16,16 +16,6 @@ struct EpiStoreF32 {
   __device__ __forceinline__ void operator()(int j, int row, int n, float acc, float) const {
     (void)row;
     out[(size_t)j * ldo + n] = acc;
-  }
-};
-
-template <typename T> struct EpiOProj {
-  static constexpr bool DUAL = false;
-  const T *x;  // [T, N]
-  float *h;    // [cap, N]
-  int N;
-  __device__ __forceinline__ void operator()(int j, int row, int n, float acc, float) const {
-    h[(size_t)j * N + n] = to_f<T>(x[(size_t)row * N + n]) + acc;
   }
 };
 
@@ -48,12 +38,6 @@ template <typename T> struct EpiDown {
   __device__ __forceinline__ void operator()(int j, int row, int n, float acc, float) const {
     out[(size_t)row * N + n] = from_f<T>(h[(size_t)j * N + n] + acc);
   }
-};
-
-// Up to three weight matrices stacked along N (q | k | v); a tile never straddles two of them.
-struct WSeg {
-  const void *w[3];
-  int n_end[3];  // exclusive end column of each segment
 };
 
 }  // namespace dy

@@ -99,42 +99,25 @@ void run(GemmA A, Rows rows, int K, int N, WSeg seg, const void *w2, Epi epi, hi
                                                             N, seg, (const T *)w2, epi);
 }
 
-inline WSeg one(const void *w, int N) {
-  WSeg s;
-  s.w[0] = s.w[1] = s.w[2] = w;
-  s.n_end[0] = s.n_end[1] = s.n_end[2] = N;
-  return s;
-}
-
 }  // namespace
 
-void gemm_f32_qkv(DType t, GemmA A, Rows rows, int K, const void *wq, const void *wk, const void *wv,
-                  int dq, int dkv, float *out, hipStream_t s) {
-  WSeg seg;
-  seg.w[0] = wq; seg.w[1] = wk; seg.w[2] = wv;
-  seg.n_end[0] = dq; seg.n_end[1] = dq + dkv; seg.n_end[2] = dq + 2 * dkv;
-  const int N = dq + 2 * dkv;
-  EpiStoreF32 e{out, N};
+void gemm_f32_raw(DType t, GemmA A, Rows rows, int K, WSeg seg, float *part, hipStream_t s) {
+  const int N = seg.n_end[2];
+  EpiStoreF32 e{part, N};
   if (t == F32) run<float>(A, rows, K, N, seg, nullptr, e, s);
   else run<bf16_t>(A, rows, K, N, seg, nullptr, e, s);
 }
 
-void gemm_f32_oproj(DType t, GemmA A, Rows rows, int K, int N, const void *wo, const void *x,
-                    float *h, hipStream_t s) {
-  if (t == F32) run<float>(A, rows, K, N, one(wo, N), nullptr, EpiOProj<float>{(const float *)x, h, N}, s);
-  else run<bf16_t>(A, rows, K, N, one(wo, N), nullptr, EpiOProj<bf16_t>{(const bf16_t *)x, h, N}, s);
-}
-
 void gemm_f32_swiglu(DType t, GemmA A, Rows rows, int K, int N, const void *w_gate, const void *w_up,
                      void *act, hipStream_t s) {
-  if (t == F32) run<float>(A, rows, K, N, one(w_gate, N), w_up, EpiSwiGLU<float>{(float *)act, N}, s);
-  else run<bf16_t>(A, rows, K, N, one(w_gate, N), w_up, EpiSwiGLU<bf16_t>{(bf16_t *)act, N}, s);
+  if (t == F32) run<float>(A, rows, K, N, wseg_one(w_gate, N), w_up, EpiSwiGLU<float>{(float *)act, N}, s);
+  else run<bf16_t>(A, rows, K, N, wseg_one(w_gate, N), w_up, EpiSwiGLU<bf16_t>{(bf16_t *)act, N}, s);
 }
 
 void gemm_f32_down(DType t, GemmA A, Rows rows, int K, int N, const void *w_down, const float *h,
                    void *out_cache, hipStream_t s) {
-  if (t == F32) run<float>(A, rows, K, N, one(w_down, N), nullptr, EpiDown<float>{h, (float *)out_cache, N}, s);
-  else run<bf16_t>(A, rows, K, N, one(w_down, N), nullptr, EpiDown<bf16_t>{h, (bf16_t *)out_cache, N}, s);
+  if (t == F32) run<float>(A, rows, K, N, wseg_one(w_down, N), nullptr, EpiDown<float>{h, (float *)out_cache, N}, s);
+  else run<bf16_t>(A, rows, K, N, wseg_one(w_down, N), nullptr, EpiDown<bf16_t>{h, (bf16_t *)out_cache, N}, s);
 }
 
 }  // namespace dy

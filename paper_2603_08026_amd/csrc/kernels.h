@@ -19,15 +19,23 @@ struct Rows {
 // out[j,:] = RMSNorm(x[row_j,:]) * gain            x: [T,d] T-typed, out: [cap,d] T-typed
 void launch_gather_rmsnorm(DType t, const void *x, const void *gain, Rows rows, int d, float eps,
                            void *out, hipStream_t s);
-// out[j,:] = RMSNorm(h[j,:]) * gain                h: [cap,d] fp32, out: [cap,d] T-typed
-void launch_rmsnorm_f32in(DType t, const float *h, const void *gain, Rows rows, int d, float eps,
-                          void *out, hipStream_t s);
-// qkv: [cap, dq+2dkv] fp32 (unrotated, bias not yet added).  Adds bias, rotates q and k by the
-// table entry of position (row mod L), writes q_out[j] (T-typed [cap,dq]) and scatters k, v rows
-// into the caches at row_j.  rope_tab: [max_seq, dh/2, 2] fp32 (cos, sin).
-void launch_rope_scatter(DType t, const float *qkv, const float *rope_tab, Rows rows, int L, int H,
-                         int Hkv, int dh, const void *bq, const void *bk, const void *bv,
-                         void *q_out, void *k_cache, void *v_cache, hipStream_t s);
+// The GEMMs leave fp32 "raw" results part[z][j][n] (z = K split, j = position in the row list); the
+// finalize kernels below sum the splits and apply the fused tail of the step, one workgroup per row.
+//
+// q/k/v: sum of splits + bias, rotary embedding of q and k by the table entry of position
+// (row mod L), q_out[j] (T-typed [cap,dq]), k and v rows scattered into the caches at row_j.
+// rope_tab: [max_seq, dh/2, 2] fp32 (cos, sin).  dh is 64 or 128.
+void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_stride,
+                         const float *rope_tab, Rows rows, int L, int H, int Hkv, int dh,
+                         const void *bq, const void *bk, const void *bv, void *q_out, void *k_cache,
+                         void *v_cache, hipStream_t s);
+// out-projection: h[j] = x[row_j] + sum of splits (fp32 [cap,d]); f[j] = RMSNorm(h[j]) * gain (T-typed)
+void launch_oproj_finalize(DType t, const float *part, int splits, size_t split_stride, const void *x,
+                           const void *gain, Rows rows, int d, float eps, float *h, void *f,
+                           hipStream_t s);
+// down projection after a K split: out_cache[row_j] = h[j] + sum of splits
+void launch_down_finalize(DType t, const float *part, int splits, size_t split_stride, const float *h,
+                          Rows rows, int d, void *out_cache, hipStream_t s);
 // cosine of c_new[j] vs c_cache[row_j], flag = cos < tau, optional commit of the new row.
 void launch_saliency(DType t, const void *c_new, void *c_cache, Rows rows, int D, float tau,
                      float *cos_out, uint8_t *flag_out, int commit, hipStream_t s);
@@ -44,11 +52,17 @@ struct AttnArgs {
   int B, L, H, Hkv, dh;
   int splits;           // key range split into this many parts (>= 1), none of them empty
   int chunk;            // keys per split (multiple of the key tile); split s covers [s*chunk, min(L,(s+1)*chunk))
-  float *part_o;        // [splits, cap, H*dh] fp32 un-normalised partial outputs (splits > 1)
-  float *part_ml;       // [splits, cap, H, 2] fp32 (running max, running sum)     (splits > 1)
-  void *out;            // [cap, H*dh] T-typed
+  int partial;          // 1: leave partials even for a single split (a finalize kernel follows)
+  float *part_o;        // [splits, cap, H*dh] fp32 un-normalised partial outputs
+  float *part_ml;       // [splits, cap, H, 2] fp32 (running max in natural-log units, running sum)
+  void *out;            // [cap, H*dh] T-typed (unused when partials are left)
 };
+// attention rows; merges the splits into a.out unless a.partial is set
 void launch_attention(DType t, const AttnArgs &a, hipStream_t s);
+// merge of the attention partials fused with the saliency test and the context commit:
+// new = merged row (rounded to T), cos against c_cache[row_j], flag = cos < tau, c_cache[row_j] = new.
+void launch_attn_finalize(DType t, const AttnArgs &a, void *c_cache, float tau, float *cos_out,
+                          uint8_t *flag_out, hipStream_t s);
 // Chooses splits and chunk for a call (host).
 void attention_plan(DType t, int B, int L, int H, int dh, int cap, size_t part_elems, int *splits,
                     int *chunk);
@@ -59,19 +73,26 @@ struct GemmA {
   const int32_t *gather;  // nullptr, or row j of the GEMM reads a[gather[j], :]
   int lda;
 };
-// qkv: out[j, 0:dq | dq:dq+dkv | dq+dkv:] = A[j,:] * (wq | wk | wv)^T, fp32 out [cap, dq+2dkv]
-// `scratch` (fp32, scratch_elems) holds K-split partial sums when a launcher decides to split K.
-void launch_gemm_qkv(DType t, GemmA A, Rows rows, int K, const void *wq, const void *wk,
-                     const void *wv, int dq, int dkv, float *out, float *scratch,
-                     size_t scratch_elems, hipStream_t s);
-// o-proj: h[j,:] = x[row_j,:] + A[j,:] * wo^T, fp32 out [cap, N]; x T-typed [T, N]
-void launch_gemm_oproj(DType t, GemmA A, Rows rows, int K, int N, const void *wo, const void *x,
-                       float *h, float *scratch, size_t scratch_elems, hipStream_t s);
+// Up to three weight matrices stacked along N (q | k | v); a tile never straddles two of them.
+struct WSeg {
+  const void *w[3];
+  int n_end[3];  // exclusive end column of each segment; N = n_end[2]
+};
+inline WSeg wseg_one(const void *w, int N) {
+  WSeg s;
+  s.w[0] = s.w[1] = s.w[2] = w;
+  s.n_end[0] = s.n_end[1] = s.n_end[2] = N;
+  return s;
+}
+// raw GEMM: part[z][j][n] = sum over K split z of A[j,:] * W[n,:] (fp32, split stride cap*N);
+// returns the number of splits used (>= 1), chosen from the capacity, N and K.
+int launch_gemm_raw(DType t, GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_elems,
+                    hipStream_t s);
 // up: act[j,:] = silu(A w_gate^T) * (A w_up^T), T-typed out [cap, N]
 void launch_gemm_swiglu(DType t, GemmA A, Rows rows, int K, int N, const void *w_gate,
-                        const void *w_up, void *act, float *scratch, size_t scratch_elems,
-                        hipStream_t s);
-// down: out_cache[row_j,:] = h[j,:] + A[j,:] * w_down^T, T-typed scatter into [T, N]
+                        const void *w_up, void *act, hipStream_t s);
+// down: out_cache[row_j,:] = h[j,:] + A[j,:] * w_down^T, T-typed scatter into [T, N]; `scratch`
+// holds K-split partials when the launcher decides to split.
 void launch_gemm_down(DType t, GemmA A, Rows rows, int K, int N, const void *w_down, const float *h,
                       void *out_cache, float *scratch, size_t scratch_elems, hipStream_t s);
 

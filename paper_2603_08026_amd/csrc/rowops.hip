@@ -43,76 +43,132 @@ __global__ __launch_bounds__(RB) void k_gather_rmsnorm(const T *__restrict__ x,
   }
 }
 
-// ---- RMSNorm of fp32 rows (input of the FFN) ---------------------------------------------------
+// ---- out-projection tail  [Alg. 3: x <- layernorm(out_proj(C)), with the residual] ---------------
+// h[j] = x[row_j] + sum_z part[z][j] (kept in fp32 for the second residual), f[j] = RMSNorm(h[j]) * gain
 template <typename T>
-__global__ __launch_bounds__(RB) void k_rmsnorm_f32in(const float *__restrict__ h,
-                                                       const T *__restrict__ gain, Rows rows, int d,
-                                                       float eps, T *__restrict__ out) {
+__global__ __launch_bounds__(RB) void k_oproj_finalize(const float *__restrict__ part, int splits,
+                                                        size_t split_stride, const T *__restrict__ x,
+                                                        const T *__restrict__ gain, Rows rows, int d,
+                                                        float eps, float *__restrict__ h,
+                                                        T *__restrict__ f) {
   __shared__ float red[RB / WAVE];
   const int n = row_count(rows), nv = d / 4;
   for (int j = blockIdx.x; j < n; j += gridDim.x) {
-    const float *hr = h + (size_t)j * d;
+    const int r = rows.idx ? rows.idx[j] : j;
+    const T *xr = x + (size_t)r * d;
+    float *hr = h + (size_t)j * d;
     float ss = 0.f;
     for (int v = threadIdx.x; v < nv; v += RB) {
-      float4 a = *reinterpret_cast<const float4 *>(hr + v * 4);
+      float4 a = *reinterpret_cast<const float4 *>(part + (size_t)j * d + v * 4);
+      for (int z = 1; z < splits; ++z) {
+        const float4 b = *reinterpret_cast<const float4 *>(part + z * split_stride + (size_t)j * d + v * 4);
+        a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+      }
+      a.x += to_f<T>(xr[v * 4 + 0]); a.y += to_f<T>(xr[v * 4 + 1]);
+      a.z += to_f<T>(xr[v * 4 + 2]); a.w += to_f<T>(xr[v * 4 + 3]);
+      *reinterpret_cast<float4 *>(hr + v * 4) = a;
       ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
     }
     ss = block_sum<RB>(ss, red);
     const float sc = 1.0f / sqrtf(ss / (float)d + eps);
-    T *orow = out + (size_t)j * d;
+    T *fr = f + (size_t)j * d;
     for (int v = threadIdx.x; v < nv; v += RB) {
-      float4 a = *reinterpret_cast<const float4 *>(hr + v * 4);
+      const float4 a = *reinterpret_cast<const float4 *>(hr + v * 4);  // written by this thread above
       const T *g = gain + v * 4;
-      orow[v * 4 + 0] = from_f<T>(a.x * sc * to_f<T>(g[0]));
-      orow[v * 4 + 1] = from_f<T>(a.y * sc * to_f<T>(g[1]));
-      orow[v * 4 + 2] = from_f<T>(a.z * sc * to_f<T>(g[2]));
-      orow[v * 4 + 3] = from_f<T>(a.w * sc * to_f<T>(g[3]));
+      fr[v * 4 + 0] = from_f<T>(a.x * sc * to_f<T>(g[0]));
+      fr[v * 4 + 1] = from_f<T>(a.y * sc * to_f<T>(g[1]));
+      fr[v * 4 + 2] = from_f<T>(a.z * sc * to_f<T>(g[2]));
+      fr[v * 4 + 3] = from_f<T>(a.w * sc * to_f<T>(g[3]));
     }
   }
 }
 
-// ---- bias + rotary embedding + K/V merge  [Alg. 3: K[idx] <- k_proj(x[idx]), same for V] -------
-// Half-split pairing: element p of a head couples with element p + dh/2, rotated by the angle
-// pos * theta^(-2p/dh); the table holds (cos, sin) per (pos, p).
+// ---- down-projection tail after a K split  [Alg. 3: FFN second half + cache commit] ---------------
 template <typename T>
-__global__ __launch_bounds__(RB) void k_rope_scatter(const float *__restrict__ qkv,
-                                                      const float *__restrict__ tab, Rows rows, int L,
-                                                      int H, int Hkv, int dh, const T *__restrict__ bq,
-                                                      const T *__restrict__ bk,
+__global__ __launch_bounds__(RB) void k_down_finalize(const float *__restrict__ part, int splits,
+                                                       size_t split_stride, const float *__restrict__ h,
+                                                       Rows rows, int d, T *__restrict__ out) {
+  const int n = row_count(rows), nv = d / 4;
+  for (int j = blockIdx.x; j < n; j += gridDim.x) {
+    const int r = rows.idx ? rows.idx[j] : j;
+    T *orow = out + (size_t)r * d;
+    for (int v = threadIdx.x; v < nv; v += RB) {
+      float4 a = *reinterpret_cast<const float4 *>(h + (size_t)j * d + v * 4);
+      for (int z = 0; z < splits; ++z) {
+        const float4 b = *reinterpret_cast<const float4 *>(part + z * split_stride + (size_t)j * d + v * 4);
+        a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+      }
+      orow[v * 4 + 0] = from_f<T>(a.x); orow[v * 4 + 1] = from_f<T>(a.y);
+      orow[v * 4 + 2] = from_f<T>(a.z); orow[v * 4 + 3] = from_f<T>(a.w);
+    }
+  }
+}
+
+// ---- q/k/v tail: bias + rotary embedding + K/V merge  [Alg. 3: K[idx] <- k_proj(x[idx]), same V] --
+// Half-split pairing: element p of a head couples with element p + dh/2, rotated by the angle
+// pos * theta^(-2p/dh); the table holds (cos, sin) per (pos, p).  A thread handles 4 neighbouring
+// pairs of one head (two float4 of the raw result, two float4 of the table).
+template <typename T>
+__global__ __launch_bounds__(RB) void k_qkv_finalize(const float *__restrict__ part, int splits,
+                                                      size_t split_stride, const float *__restrict__ tab,
+                                                      Rows rows, int L, int H, int Hkv, int dh,
+                                                      const T *__restrict__ bq, const T *__restrict__ bk,
                                                       const T *__restrict__ bv, T *__restrict__ q_out,
                                                       T *__restrict__ kc, T *__restrict__ vc) {
   const int n = row_count(rows);
   const int half = dh / 2, dq = H * dh, dkv = Hkv * dh, ld = dq + 2 * dkv;
-  const int qpairs = H * half, kpairs = Hkv * half;
+  const int per_head = half / 4;  // items of 4 pairs per head
+  const int qk_items = (H + Hkv) * per_head, v_items = dkv / 4;
   for (int j = blockIdx.x; j < n; j += gridDim.x) {
     const int r = rows.idx ? rows.idx[j] : j;
     const int pos = r % L;
-    const float *src = qkv + (size_t)j * ld;
+    const float *src = part + (size_t)j * ld;
     const float *t = tab + (size_t)pos * half * 2;
-    for (int e = threadIdx.x; e < qpairs + kpairs; e += RB) {
-      const bool isq = e < qpairs;
-      const int ee = isq ? e : e - qpairs;
-      const int head = ee / half, p = ee % half;
-      const int c0 = head * dh + p, c1 = c0 + half;
-      const float *s = isq ? src : src + dq;
-      const T *b = isq ? bq : bk;
-      float x1 = s[c0], x2 = s[c1];
-      if (b) {
-        x1 += to_f<T>(b[c0]);
-        x2 += to_f<T>(b[c1]);
+    for (int it = threadIdx.x; it < qk_items + v_items; it += RB) {
+      if (it < qk_items) {
+        const int head = it / per_head, p4 = (it % per_head) * 4;
+        const bool isq = head < H;
+        const int hh = isq ? head : head - H;
+        const int c0 = hh * dh + p4;              // column inside q or k
+        const int s0 = (isq ? 0 : dq) + c0;       // column inside the raw row
+        float4 x1 = *reinterpret_cast<const float4 *>(src + s0);
+        float4 x2 = *reinterpret_cast<const float4 *>(src + s0 + half);
+        for (int z = 1; z < splits; ++z) {
+          const float4 y1 = *reinterpret_cast<const float4 *>(src + z * split_stride + s0);
+          const float4 y2 = *reinterpret_cast<const float4 *>(src + z * split_stride + s0 + half);
+          x1.x += y1.x; x1.y += y1.y; x1.z += y1.z; x1.w += y1.w;
+          x2.x += y2.x; x2.y += y2.y; x2.z += y2.z; x2.w += y2.w;
+        }
+        const T *b = isq ? bq : bk;
+        if (b) {
+          x1.x += to_f<T>(b[c0]); x1.y += to_f<T>(b[c0 + 1]); x1.z += to_f<T>(b[c0 + 2]); x1.w += to_f<T>(b[c0 + 3]);
+          x2.x += to_f<T>(b[c0 + half]); x2.y += to_f<T>(b[c0 + half + 1]);
+          x2.z += to_f<T>(b[c0 + half + 2]); x2.w += to_f<T>(b[c0 + half + 3]);
+        }
+        const float4 t0 = *reinterpret_cast<const float4 *>(t + 2 * p4);      // cos0 sin0 cos1 sin1
+        const float4 t1 = *reinterpret_cast<const float4 *>(t + 2 * p4 + 4);  // cos2 sin2 cos3 sin3
+        T *dst = isq ? q_out + (size_t)j * dq : kc + (size_t)r * dkv;
+        dst[c0 + 0] = from_f<T>(x1.x * t0.x - x2.x * t0.y);
+        dst[c0 + 1] = from_f<T>(x1.y * t0.z - x2.y * t0.w);
+        dst[c0 + 2] = from_f<T>(x1.z * t1.x - x2.z * t1.y);
+        dst[c0 + 3] = from_f<T>(x1.w * t1.z - x2.w * t1.w);
+        dst[c0 + half + 0] = from_f<T>(x2.x * t0.x + x1.x * t0.y);
+        dst[c0 + half + 1] = from_f<T>(x2.y * t0.z + x1.y * t0.w);
+        dst[c0 + half + 2] = from_f<T>(x2.z * t1.x + x1.z * t1.y);
+        dst[c0 + half + 3] = from_f<T>(x2.w * t1.z + x1.w * t1.w);
+      } else {
+        const int c0 = (it - qk_items) * 4;
+        float4 x = *reinterpret_cast<const float4 *>(src + dq + dkv + c0);
+        for (int z = 1; z < splits; ++z) {
+          const float4 y = *reinterpret_cast<const float4 *>(src + z * split_stride + dq + dkv + c0);
+          x.x += y.x; x.y += y.y; x.z += y.z; x.w += y.w;
+        }
+        if (bv) {
+          x.x += to_f<T>(bv[c0]); x.y += to_f<T>(bv[c0 + 1]); x.z += to_f<T>(bv[c0 + 2]); x.w += to_f<T>(bv[c0 + 3]);
+        }
+        T *dv = vc + (size_t)r * dkv + c0;
+        dv[0] = from_f<T>(x.x); dv[1] = from_f<T>(x.y); dv[2] = from_f<T>(x.z); dv[3] = from_f<T>(x.w);
       }
-      const float cs = t[2 * p], sn = t[2 * p + 1];
-      const float y1 = x1 * cs - x2 * sn, y2 = x2 * cs + x1 * sn;
-      T *dst = isq ? q_out + (size_t)j * dq : kc + (size_t)r * dkv;
-      dst[c0] = from_f<T>(y1);
-      dst[c1] = from_f<T>(y2);
-    }
-    const float *sv = src + dq + dkv;
-    T *dv = vc + (size_t)r * dkv;
-    for (int e = threadIdx.x; e < dkv; e += RB) {
-      float v = sv[e];
-      if (bv) v += to_f<T>(bv[e]);
-      dv[e] = from_f<T>(v);
     }
   }
 }
@@ -224,28 +280,42 @@ void launch_gather_rmsnorm(DType t, const void *x, const void *gain, Rows rows, 
                                                                rows, d, eps, (bf16_t *)out);
 }
 
-void launch_rmsnorm_f32in(DType t, const float *h, const void *gain, Rows rows, int d, float eps,
-                          void *out, hipStream_t s) {
+void launch_oproj_finalize(DType t, const float *part, int splits, size_t split_stride, const void *x,
+                           const void *gain, Rows rows, int d, float eps, float *h, void *f,
+                           hipStream_t s) {
   if (rows.cap <= 0) return;
   if (t == F32)
-    k_rmsnorm_f32in<float><<<row_grid(rows.cap), RB, 0, s>>>(h, (const float *)gain, rows, d, eps,
-                                                             (float *)out);
+    k_oproj_finalize<float><<<row_grid(rows.cap), RB, 0, s>>>(part, splits, split_stride, (const float *)x,
+                                                              (const float *)gain, rows, d, eps, h, (float *)f);
   else
-    k_rmsnorm_f32in<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>(h, (const bf16_t *)gain, rows, d, eps,
-                                                              (bf16_t *)out);
+    k_oproj_finalize<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>(part, splits, split_stride, (const bf16_t *)x,
+                                                               (const bf16_t *)gain, rows, d, eps, h,
+                                                               (bf16_t *)f);
 }
 
-void launch_rope_scatter(DType t, const float *qkv, const float *rope_tab, Rows rows, int L, int H,
-                         int Hkv, int dh, const void *bq, const void *bk, const void *bv,
-                         void *q_out, void *k_cache, void *v_cache, hipStream_t s) {
+void launch_down_finalize(DType t, const float *part, int splits, size_t split_stride, const float *h,
+                          Rows rows, int d, void *out_cache, hipStream_t s) {
   if (rows.cap <= 0) return;
   if (t == F32)
-    k_rope_scatter<float><<<row_grid(rows.cap), RB, 0, s>>>(
-        qkv, rope_tab, rows, L, H, Hkv, dh, (const float *)bq, (const float *)bk, (const float *)bv,
-        (float *)q_out, (float *)k_cache, (float *)v_cache);
+    k_down_finalize<float><<<row_grid(rows.cap), RB, 0, s>>>(part, splits, split_stride, h, rows, d,
+                                                             (float *)out_cache);
   else
-    k_rope_scatter<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>(
-        qkv, rope_tab, rows, L, H, Hkv, dh, (const bf16_t *)bq, (const bf16_t *)bk,
+    k_down_finalize<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>(part, splits, split_stride, h, rows, d,
+                                                              (bf16_t *)out_cache);
+}
+
+void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_stride,
+                         const float *rope_tab, Rows rows, int L, int H, int Hkv, int dh,
+                         const void *bq, const void *bk, const void *bv, void *q_out, void *k_cache,
+                         void *v_cache, hipStream_t s) {
+  if (rows.cap <= 0) return;
+  if (t == F32)
+    k_qkv_finalize<float><<<row_grid(rows.cap), RB, 0, s>>>(
+        part, splits, split_stride, rope_tab, rows, L, H, Hkv, dh, (const float *)bq, (const float *)bk,
+        (const float *)bv, (float *)q_out, (float *)k_cache, (float *)v_cache);
+  else
+    k_qkv_finalize<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>(
+        part, splits, split_stride, rope_tab, rows, L, H, Hkv, dh, (const bf16_t *)bq, (const bf16_t *)bk,
         (const bf16_t *)bv, (bf16_t *)q_out, (bf16_t *)k_cache, (bf16_t *)v_cache);
 }
 
