@@ -32,8 +32,8 @@ def stage_work(shape, B, L, M_in, M_out, esz):
     w["gemm_qkv"] = (2.0 * M_in * d * nq, nq * d * esz + M_in * d * esz + M_in * nq * 4)
     w["rope_scatter"] = (6.0 * M_in * nq, M_in * nq * 4 + M_in * nq * esz)
     w["partial_attention"] = (4.0 * M_in * L * dq, 2 * B * L * dkv * esz + 2 * M_in * dq * esz)
-    w["saliency"] = (6.0 * M_in * dq, 3 * M_in * dq * esz)
-    w["compact"] = (0.0, M_in + 4 * M_out)
+    w["saliency_compact"] = (6.0 * M_in * dq, 3 * M_in * dq * esz + M_in + 4 * M_out)
+    w["marker_overhead"] = (0.0, 0.0)  # two stream events with no work between them
     w["gemm_oproj"] = (2.0 * M_out * dq * d, d * dq * esz + M_out * dq * esz + M_out * d * (esz + 4))
     w["rmsnorm_ffn"] = (4.0 * M_out * d, M_out * d * (4 + esz))
     w["gemm_swiglu"] = (4.0 * M_out * d * F, 2 * F * d * esz + M_out * d * esz + M_out * F * esz)
@@ -162,12 +162,16 @@ def main():
 
     m_in = float(np.mean([m for _, _, m in steps[Wu:Wu + K]]))
     work = stage_work(s, wl.batch, wl.seq, m_in, m_in, esz)  # every candidate passes the test here
+    # every stage time runs from one stream event to the next; the cost of the event itself is
+    # measured by the stage that has no kernel and taken off the others
+    ev = stage_ms.get("marker_overhead", 0.0)
+    stage_ms = {n: (max(ms - ev, 1e-6) if n != "marker_overhead" else ms) for n, ms in stage_ms.items()}
     stages = {}
     for name, ms in stage_ms.items():
         fl, by = work[name]
-        stages[name] = {"ms": round(ms, 5), "gbps": round(by / (ms * 1e-3) / 1e9, 1) if ms > 0 else None,
-                        "tflops": round(fl / (ms * 1e-3) / 1e12, 2) if ms > 0 else None}
-    dom = max(stage_ms, key=lambda n: stage_ms[n])
+        stages[name] = {"ms": round(ms, 5), "gbps": round(by / (ms * 1e-3) / 1e9, 1) if by else None,
+                        "tflops": round(fl / (ms * 1e-3) / 1e12, 2) if fl else None}
+    dom = max((n for n in stage_ms if n != "marker_overhead"), key=lambda n: stage_ms[n])
     fl, by = work[dom]
     ms = stage_ms[dom]
     is_gemm_or_attn = dom.startswith("gemm") or dom == "partial_attention"

@@ -64,6 +64,8 @@ Layout make_layout(const dyllm_layer_cfg &c) {
   const size_t prow = R < 2048 ? R : 2048;
   const size_t widest = dq + 2 * dkv > d ? dq + 2 * dkv : d;
   l.part_elems = 16 * prow * dq > R * widest ? 16 * prow * dq : R * widest;
+  const size_t skinny_ffn = (R < 128 ? R : 128) * 2 * (size_t)c.ffn_dim;  // raw gate|up of the skinny regime
+  if (l.part_elems < skinny_ffn) l.part_elems = skinny_ffn;
   l.part_o = take(l.part_elems * 4);
   l.part_ml = take(l.part_elems / c.head_dim * 2 * 4);
   l.cosb = take(R * 4);
@@ -88,6 +90,7 @@ int check_cfg(const dyllm_layer_cfg *c) {
   if ((long)c->max_batch * c->max_seq > (1l << 30)) return DYLLM_ERR_UNSUPPORTED;
   if (c->max_rows > 0 && (long)c->max_rows > (long)c->max_batch * c->max_seq) return DYLLM_ERR_BAD_SHAPE;
   if (c->head_dim != 64 && c->head_dim != 128) return DYLLM_ERR_UNSUPPORTED;
+  if (c->hidden > 16384) return DYLLM_ERR_UNSUPPORTED;  // a row kernel keeps one row per workgroup in registers
   const int q = c->dtype == DYLLM_BF16 ? 128 : 64;
   if (c->hidden % q || c->ffn_dim % q || (c->n_heads * c->head_dim) % q) return DYLLM_ERR_UNSUPPORTED;
   return DYLLM_OK;
@@ -134,7 +137,7 @@ enum Stage {
   ST_NORM_FFN, ST_GEMM_SWIGLU, ST_GEMM_DOWN, N_STAGES
 };
 const char *const kStageNames[N_STAGES] = {
-    "gather_rmsnorm", "gemm_qkv", "rope_scatter", "partial_attention", "saliency", "compact",
+    "gather_rmsnorm", "gemm_qkv", "rope_scatter", "partial_attention", "saliency_compact", "marker_overhead",
     "gemm_oproj", "rmsnorm_ffn", "gemm_swiglu", "gemm_down"};
 
 void prof_begin_call(dyllm_ctx *ctx, hipStream_t s) {
@@ -200,7 +203,7 @@ int enqueue_ffn(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x, con
                         c.hidden, c.rms_eps, ctx->hs, ctx->fs, s);
   prof_mark(ctx, ST_NORM_FFN, s);
   launch_gemm_swiglu(dt(ctx), GemmA{ctx->fs, nullptr, c.hidden}, rows, c.hidden, c.ffn_dim, w->w_gate,
-                     w->w_up, ctx->act, s);
+                     w->w_up, ctx->act, ctx->part_o, ctx->part_elems, s);
   prof_mark(ctx, ST_GEMM_SWIGLU, s);
   launch_gemm_down(dt(ctx), GemmA{ctx->act, nullptr, c.ffn_dim}, rows, c.ffn_dim, c.hidden, w->w_down,
                    ctx->hs, out_cache, ctx->part_o, ctx->part_elems, s);
@@ -463,11 +466,12 @@ int dyllm_layer_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_c
     const AttnArgs a = attn_args(ctx, ctx->qs, cache->k, cache->v, rin, idx_in->offsets, B, L, nullptr, 1);
     launch_attention(dt(ctx), a, s);
     prof_mark(ctx, ST_ATTENTION, s);
-    launch_attn_finalize(dt(ctx), a, cache->c, tau, cos_out ? cos_out : ctx->cosb, ctx->flag, s);
+    // ... and the last workgroup of that kernel compacts the flags into idx_out
+    launch_attn_finalize(dt(ctx), a, cache->c, tau, cos_out ? cos_out : ctx->cosb, ctx->flag,
+                         idx_out->idx, idx_out->offsets, idx_out->cap, ctx->status, ctx->status + 1, s);
     prof_mark(ctx, ST_SALIENCY, s);
+    prof_mark(ctx, ST_COMPACT, s);
   }
-  launch_compact(ctx->flag, rin, B, L, idx_out->idx, idx_out->offsets, idx_out->cap, ctx->status, s);
-  prof_mark(ctx, ST_COMPACT, s);
   if ((rc = check_launch(ctx, "saliency / compact"))) return rc;
   // idx_out is a subset of idx_in: its count never exceeds idx_in's capacity, which sizes the grids
   Rows rout = rows_of(idx_out, B);

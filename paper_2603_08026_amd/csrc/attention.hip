@@ -1,5 +1,6 @@
 // Partial attention: dispatch, key-split choice and the merge of split partial results.
 #include "attention_common.h"
+#include "compact.h"
 
 namespace dy {
 
@@ -26,12 +27,12 @@ __device__ __forceinline__ float4 merge_splits(const AttnArgs &a, int j, int c, 
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void k_attn_combine(AttnArgs a) {
+__global__ __launch_bounds__(1024) void k_attn_combine(AttnArgs a) {
   const int n = a.rows.count ? min(*a.rows.count, a.rows.cap) : a.rows.cap;
   const int D = a.H * a.dh;
   for (int j = blockIdx.x; j < n; j += gridDim.x) {
     T *orow = (T *)a.out + (size_t)j * D;
-    for (int c = threadIdx.x * 4; c < D; c += 1024) {
+    for (int c = threadIdx.x * 4; c < D; c += 4096) {
       const float4 o = merge_splits(a, j, c, D);
       orow[c] = from_f<T>(o.x); orow[c + 1] = from_f<T>(o.y);
       orow[c + 2] = from_f<T>(o.z); orow[c + 3] = from_f<T>(o.w);
@@ -43,18 +44,27 @@ __global__ __launch_bounds__(256) void k_attn_combine(AttnArgs a) {
 // commit  [Sec. 3.1, Sec. 3.2; Alg. 3: cosine line and cache commit].  The new context is rounded to
 // the storage type first; the cosine is taken over the stored values (so an unchanged context gives
 // exactly the cached row and s = 1), the old cache row is read before it is overwritten.
+// Tail: the workgroup that finishes last (device counter) compacts the flags of the whole launch
+// into the next index list, which saves a launch on a latency-bound step.
+struct CompactOut {
+  int32_t *idx, *off, *status, *counter;
+  int cap, B, L, overflow_code;
+};
+
 template <typename T>
-__global__ __launch_bounds__(256) void k_attn_finalize(AttnArgs a, T *c_cache, float tau,
-                                                        float *__restrict__ cos_out,
-                                                        uint8_t *__restrict__ flag_out) {
-  __shared__ float red[256 / WAVE];
+__global__ __launch_bounds__(1024) void k_attn_finalize(AttnArgs a, T *c_cache, float tau,
+                                                        float *__restrict__ cos_out, uint8_t *flag_out,
+                                                        CompactOut co) {
+  __shared__ float red[1024 / WAVE];
+  __shared__ int wave_cnt[CB / WAVE];
+  __shared__ int is_last;
   const int n = a.rows.count ? min(*a.rows.count, a.rows.cap) : a.rows.cap;
   const int D = a.H * a.dh;
   for (int j = blockIdx.x; j < n; j += gridDim.x) {
     const int r = a.rows.idx ? a.rows.idx[j] : j;
     T *crow = c_cache + (size_t)r * D;
     float dot = 0.f, na = 0.f, nb = 0.f;
-    for (int c = threadIdx.x * 4; c < D; c += 1024) {
+    for (int c = threadIdx.x * 4; c < D; c += 4096) {
       const float4 o = merge_splits(a, j, c, D);
       const T n0 = from_f<T>(o.x), n1 = from_f<T>(o.y), n2 = from_f<T>(o.z), n3 = from_f<T>(o.w);
       const float f0 = to_f<T>(n0), f1 = to_f<T>(n1), f2 = to_f<T>(n2), f3 = to_f<T>(n3);
@@ -64,14 +74,27 @@ __global__ __launch_bounds__(256) void k_attn_finalize(AttnArgs a, T *c_cache, f
       nb += b0 * b0 + b1 * b1 + b2 * b2 + b3 * b3;
       crow[c] = n0; crow[c + 1] = n1; crow[c + 2] = n2; crow[c + 3] = n3;
     }
-    dot = block_sum<256>(dot, red);
-    na = block_sum<256>(na, red);
-    nb = block_sum<256>(nb, red);
+    dot = block_sum<1024>(dot, red);
+    na = block_sum<1024>(na, red);
+    nb = block_sum<1024>(nb, red);
     if (threadIdx.x == 0) {
       const float s = dot / (fmaxf(sqrtf(na), 1e-8f) * fmaxf(sqrtf(nb), 1e-8f));
       if (cos_out) cos_out[j] = s;
       flag_out[j] = (s < tau) ? 1 : 0;
     }
+  }
+  // flags of this workgroup are out (thread 0 wrote them); count finished workgroups
+  if (threadIdx.x == 0) {
+    __threadfence();
+    const int done = atomicAdd(co.counter, 1);
+    is_last = (done == (int)gridDim.x - 1);
+    if (is_last) *co.counter = 0;  // ready for the next launch on the stream
+  }
+  __syncthreads();
+  if (is_last) {
+    __threadfence();
+    compact_block(flag_out, a.rows, n, co.B, co.L, co.idx, co.off, co.cap, co.status, co.overflow_code,
+                  true, wave_cnt);
   }
 }
 
@@ -80,16 +103,21 @@ __global__ __launch_bounds__(256) void k_attn_finalize(AttnArgs a, T *c_cache, f
 void launch_attn_combine(DType t, const AttnArgs &a, hipStream_t s) {
   int grid = a.rows.cap > 8192 ? 8192 : a.rows.cap;
   if (grid < 1) return;
-  if (t == F32) k_attn_combine<float><<<grid, 256, 0, s>>>(a);
-  else k_attn_combine<bf16_t><<<grid, 256, 0, s>>>(a);
+  if (t == F32) k_attn_combine<float><<<grid, 1024, 0, s>>>(a);
+  else k_attn_combine<bf16_t><<<grid, 1024, 0, s>>>(a);
 }
 
 void launch_attn_finalize(DType t, const AttnArgs &a, void *c_cache, float tau, float *cos_out,
-                          uint8_t *flag_out, hipStream_t s) {
+                          uint8_t *flag_out, int32_t *out_idx, int32_t *out_offsets, int out_cap,
+                          int32_t *status, int32_t *counter, hipStream_t s) {
+  // an empty list still needs its offsets written: one workgroup runs the (empty) compaction
   int grid = a.rows.cap > 8192 ? 8192 : a.rows.cap;
-  if (grid < 1) return;
-  if (t == F32) k_attn_finalize<float><<<grid, 256, 0, s>>>(a, (float *)c_cache, tau, cos_out, flag_out);
-  else k_attn_finalize<bf16_t><<<grid, 256, 0, s>>>(a, (bf16_t *)c_cache, tau, cos_out, flag_out);
+  if (grid < 1) grid = 1;
+  CompactOut co{out_idx, out_offsets, status, counter, out_cap, a.B, a.L, -6};
+  if (t == F32)
+    k_attn_finalize<float><<<grid, 1024, 0, s>>>(a, (float *)c_cache, tau, cos_out, flag_out, co);
+  else
+    k_attn_finalize<bf16_t><<<grid, 1024, 0, s>>>(a, (bf16_t *)c_cache, tau, cos_out, flag_out, co);
 }
 
 // Splits of the key range: enough workgroups to cover the chip a few times over when there are few

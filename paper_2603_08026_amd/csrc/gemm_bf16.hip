@@ -17,7 +17,10 @@ typedef Shape<256, 64, 4, 2, true, 2> LargeD;
 typedef Shape<128, 128, 2, 2, false, 2> MidS;
 typedef Shape<128, 64, 2, 2, true, 2> MidD;
 typedef Shape<128, 64, 4, 2, false, 4> SkinnyS;
-typedef Shape<128, 32, 4, 1, true, 4> SkinnyD;
+// gate|up in the skinny regime: one raw GEMM over both weight matrices (wide column tiles keep the
+// re-reads of the activation tile down), SwiGLU applied by a row kernel
+typedef Shape<128, 96, 4, 1, false, 4> SkinnyW96;
+typedef Shape<128, 128, 4, 2, false, 3> SkinnyW128;
 
 constexpr int MID_MAX_ROWS = 384;
 constexpr int SKINNY_MAX_ROWS = 128;
@@ -64,11 +67,18 @@ int gemm_bf16_raw(GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_
 }
 
 void gemm_bf16_swiglu(GemmA A, Rows rows, int K, int N, const void *wg, const void *wu, void *act,
-                      hipStream_t s) {
+                      float *part, size_t part_elems, hipStream_t s) {
   if (rows.cap <= 0) return;
   EpiSwiGLU<bf16_t> e{(bf16_t *)act, N};
-  if (rows.cap <= SKINNY_MAX_ROWS) run_tiles<SkinnyD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
-  else if (rows.cap <= MID_MAX_ROWS) run_tiles<MidD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
+  if (rows.cap <= SKINNY_MAX_ROWS && (size_t)rows.cap * 2 * N <= part_elems) {
+    WSeg seg;
+    seg.w[0] = wg; seg.w[1] = wu; seg.w[2] = wu;
+    seg.n_end[0] = N; seg.n_end[1] = 2 * N; seg.n_end[2] = 2 * N;
+    EpiStoreF32 raw{part, 2 * N};
+    if (N % 96 == 0) run_tiles<SkinnyW96>(A, rows, K, 2 * N, seg, nullptr, raw, 1, part, s);
+    else run_tiles<SkinnyW128>(A, rows, K, 2 * N, seg, nullptr, raw, 1, part, s);
+    launch_swiglu_finalize(BF16, part, 1, (size_t)rows.cap * 2 * N, rows, N, act, s);
+  } else if (rows.cap <= MID_MAX_ROWS) run_tiles<MidD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
   else run_tiles<LargeD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
 }
 

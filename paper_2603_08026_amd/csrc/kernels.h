@@ -33,6 +33,10 @@ void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_st
 void launch_oproj_finalize(DType t, const float *part, int splits, size_t split_stride, const void *x,
                            const void *gain, Rows rows, int d, float eps, float *h, void *f,
                            hipStream_t s);
+// gate|up: act[j] = silu(sum of splits of the gate columns) * (sum of splits of the up columns);
+// part rows are [2F] wide, gate columns first
+void launch_swiglu_finalize(DType t, const float *part, int splits, size_t split_stride, Rows rows,
+                            int F, void *act, hipStream_t s);
 // down projection after a K split: out_cache[row_j] = h[j] + sum of splits
 void launch_down_finalize(DType t, const float *part, int splits, size_t split_stride, const float *h,
                           Rows rows, int d, void *out_cache, hipStream_t s);
@@ -61,8 +65,11 @@ struct AttnArgs {
 void launch_attention(DType t, const AttnArgs &a, hipStream_t s);
 // merge of the attention partials fused with the saliency test and the context commit:
 // new = merged row (rounded to T), cos against c_cache[row_j], flag = cos < tau, c_cache[row_j] = new.
+// The workgroup that finishes last also compacts the flags into (out_idx, out_offsets) like
+// launch_compact; `counter` is a zero-initialised device word the kernel leaves at zero.
 void launch_attn_finalize(DType t, const AttnArgs &a, void *c_cache, float tau, float *cos_out,
-                          uint8_t *flag_out, hipStream_t s);
+                          uint8_t *flag_out, int32_t *out_idx, int32_t *out_offsets, int out_cap,
+                          int32_t *status, int32_t *counter, hipStream_t s);
 // Chooses splits and chunk for a call (host).
 void attention_plan(DType t, int B, int L, int H, int dh, int cap, size_t part_elems, int *splits,
                     int *chunk);
@@ -89,8 +96,11 @@ inline WSeg wseg_one(const void *w, int N) {
 int launch_gemm_raw(DType t, GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_elems,
                     hipStream_t s);
 // up: act[j,:] = silu(A w_gate^T) * (A w_up^T), T-typed out [cap, N]
+// `scratch` holds the raw gate|up result in the weight-streaming regime (then a row kernel applies
+// the SwiGLU); otherwise the epilogue is fused.
 void launch_gemm_swiglu(DType t, GemmA A, Rows rows, int K, int N, const void *w_gate,
-                        const void *w_up, void *act, hipStream_t s);
+                        const void *w_up, void *act, float *scratch, size_t scratch_elems,
+                        hipStream_t s);
 // down: out_cache[row_j,:] = h[j,:] + A[j,:] * w_down^T, T-typed scatter into [T, N]; `scratch`
 // holds K-split partials when the launcher decides to split.
 void launch_gemm_down(DType t, GemmA A, Rows rows, int K, int N, const void *w_down, const float *h,

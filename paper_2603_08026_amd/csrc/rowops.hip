@@ -2,13 +2,15 @@
 // cosine saliency (+ context commit), stream compaction.  All are HBM-bound: one workgroup walks
 // one token row with 16-byte loads, reductions in fp32.
 #include "common.h"
+#include "compact.h"
 #include "kernels.h"
 
 namespace dy {
 
 namespace {
 
-constexpr int RB = 256;  // threads per row workgroup
+constexpr int RB = 1024;  // threads per row workgroup: a row of up to 16384 elements in one pass
+constexpr int KEEP = 4;   // 16-byte vectors a thread keeps in registers between the two passes of a row
 
 __device__ __forceinline__ int row_count(const Rows &rows) {
   return rows.count ? min(*rows.count, rows.cap) : rows.cap;
@@ -26,19 +28,28 @@ __global__ __launch_bounds__(RB) void k_gather_rmsnorm(const T *__restrict__ x,
     const int r = rows.idx ? rows.idx[j] : j;
     const T *xr = x + (size_t)r * d;
     float ss = 0.f;
-    for (int v = threadIdx.x; v < nv; v += RB) {
-      Vec16<T> a = ld16(xr + v * N);
+    Vec16<T> keep[KEEP];
 #pragma unroll
-      for (int i = 0; i < N; ++i) ss += a.get(i) * a.get(i);
+    for (int it = 0; it < KEEP; ++it) {
+      const int v = threadIdx.x + it * RB;
+      if (v < nv) {
+        keep[it] = ld16(xr + v * N);
+#pragma unroll
+        for (int i = 0; i < N; ++i) ss += keep[it].get(i) * keep[it].get(i);
+      }
     }
     ss = block_sum<RB>(ss, red);
     const float sc = 1.0f / sqrtf(ss / (float)d + eps);
     T *orow = out + (size_t)j * d;
-    for (int v = threadIdx.x; v < nv; v += RB) {
-      Vec16<T> a = ld16(xr + v * N), g = ld16(gain + v * N), o;
 #pragma unroll
-      for (int i = 0; i < N; ++i) o.set(i, a.get(i) * sc * g.get(i));
-      st16(orow + v * N, o);
+    for (int it = 0; it < KEEP; ++it) {
+      const int v = threadIdx.x + it * RB;
+      if (v < nv) {
+        Vec16<T> g = ld16(gain + v * N), o;
+#pragma unroll
+        for (int i = 0; i < N; ++i) o.set(i, keep[it].get(i) * sc * g.get(i));
+        st16(orow + v * N, o);
+      }
     }
   }
 }
@@ -58,27 +69,37 @@ __global__ __launch_bounds__(RB) void k_oproj_finalize(const float *__restrict__
     const T *xr = x + (size_t)r * d;
     float *hr = h + (size_t)j * d;
     float ss = 0.f;
-    for (int v = threadIdx.x; v < nv; v += RB) {
-      float4 a = *reinterpret_cast<const float4 *>(part + (size_t)j * d + v * 4);
-      for (int z = 1; z < splits; ++z) {
-        const float4 b = *reinterpret_cast<const float4 *>(part + z * split_stride + (size_t)j * d + v * 4);
-        a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    float4 keep[KEEP];
+#pragma unroll
+    for (int it = 0; it < KEEP; ++it) {
+      const int v = threadIdx.x + it * RB;
+      if (v < nv) {
+        float4 a = *reinterpret_cast<const float4 *>(part + (size_t)j * d + v * 4);
+        for (int z = 1; z < splits; ++z) {
+          const float4 b = *reinterpret_cast<const float4 *>(part + z * split_stride + (size_t)j * d + v * 4);
+          a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+        }
+        a.x += to_f<T>(xr[v * 4 + 0]); a.y += to_f<T>(xr[v * 4 + 1]);
+        a.z += to_f<T>(xr[v * 4 + 2]); a.w += to_f<T>(xr[v * 4 + 3]);
+        *reinterpret_cast<float4 *>(hr + v * 4) = a;
+        ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+        keep[it] = a;
       }
-      a.x += to_f<T>(xr[v * 4 + 0]); a.y += to_f<T>(xr[v * 4 + 1]);
-      a.z += to_f<T>(xr[v * 4 + 2]); a.w += to_f<T>(xr[v * 4 + 3]);
-      *reinterpret_cast<float4 *>(hr + v * 4) = a;
-      ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
     }
     ss = block_sum<RB>(ss, red);
     const float sc = 1.0f / sqrtf(ss / (float)d + eps);
     T *fr = f + (size_t)j * d;
-    for (int v = threadIdx.x; v < nv; v += RB) {
-      const float4 a = *reinterpret_cast<const float4 *>(hr + v * 4);  // written by this thread above
-      const T *g = gain + v * 4;
-      fr[v * 4 + 0] = from_f<T>(a.x * sc * to_f<T>(g[0]));
-      fr[v * 4 + 1] = from_f<T>(a.y * sc * to_f<T>(g[1]));
-      fr[v * 4 + 2] = from_f<T>(a.z * sc * to_f<T>(g[2]));
-      fr[v * 4 + 3] = from_f<T>(a.w * sc * to_f<T>(g[3]));
+#pragma unroll
+    for (int it = 0; it < KEEP; ++it) {
+      const int v = threadIdx.x + it * RB;
+      if (v < nv) {
+        const float4 a = keep[it];
+        const T *g = gain + v * 4;
+        fr[v * 4 + 0] = from_f<T>(a.x * sc * to_f<T>(g[0]));
+        fr[v * 4 + 1] = from_f<T>(a.y * sc * to_f<T>(g[1]));
+        fr[v * 4 + 2] = from_f<T>(a.z * sc * to_f<T>(g[2]));
+        fr[v * 4 + 3] = from_f<T>(a.w * sc * to_f<T>(g[3]));
+      }
     }
   }
 }
@@ -101,6 +122,33 @@ __global__ __launch_bounds__(RB) void k_down_finalize(const float *__restrict__ 
       orow[v * 4 + 0] = from_f<T>(a.x); orow[v * 4 + 1] = from_f<T>(a.y);
       orow[v * 4 + 2] = from_f<T>(a.z); orow[v * 4 + 3] = from_f<T>(a.w);
     }
+  }
+}
+
+// ---- SwiGLU after a raw gate|up GEMM: act = silu(gate) * up  [Alg. 3: FFN, first half] ------------
+// part: [splits][cap][2F] fp32 with the gate columns first, then the up columns.
+template <typename T>
+__global__ __launch_bounds__(256) void k_swiglu_finalize(const float *__restrict__ part, int splits,
+                                                          size_t split_stride, Rows rows, int F,
+                                                          T *__restrict__ act) {
+  const int n = row_count(rows), nv = F / 4;
+  const size_t total = (size_t)n * nv;
+  for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
+    const int j = (int)(e / nv), v = (int)(e % nv);
+    const float *src = part + (size_t)j * 2 * F + v * 4;
+    float4 g = *reinterpret_cast<const float4 *>(src);
+    float4 u = *reinterpret_cast<const float4 *>(src + F);
+    for (int z = 1; z < splits; ++z) {
+      const float4 g2 = *reinterpret_cast<const float4 *>(src + z * split_stride);
+      const float4 u2 = *reinterpret_cast<const float4 *>(src + z * split_stride + F);
+      g.x += g2.x; g.y += g2.y; g.z += g2.z; g.w += g2.w;
+      u.x += u2.x; u.y += u2.y; u.z += u2.z; u.w += u2.w;
+    }
+    T *dst = act + (size_t)j * F + v * 4;
+    dst[0] = from_f<T>(g.x / (1.0f + __expf(-g.x)) * u.x);
+    dst[1] = from_f<T>(g.y / (1.0f + __expf(-g.y)) * u.y);
+    dst[2] = from_f<T>(g.z / (1.0f + __expf(-g.z)) * u.z);
+    dst[3] = from_f<T>(g.w / (1.0f + __expf(-g.w)) * u.w);
   }
 }
 
@@ -210,54 +258,13 @@ __global__ __launch_bounds__(RB) void k_saliency(const T *__restrict__ c_new, T 
   }
 }
 
-// ---- stream compaction  [Alg. 3: idx_sal <- where(cos < tau)] ----------------------------------
-// One workgroup of 1024 threads sweeps the flags in chunks of 1024: wave64 ballot + popcount give
-// each flagged lane its rank inside the wave, 16 per-wave totals are combined through LDS.  The
-// output keeps the input order, so it is ascending.  Per-sequence offsets are found afterwards by
-// binary search for b*L in the list just written.
-constexpr int CB = 1024;
-
+// ---- stream compaction as a kernel of its own (one workgroup) -------------------------------------
 __global__ __launch_bounds__(CB) void k_compact(const uint8_t *__restrict__ flag, Rows rows, int B,
                                                  int L, int32_t *out_idx, int32_t *out_off,
                                                  int out_cap, int32_t *status, int overflow_code) {
   __shared__ int wave_cnt[CB / WAVE];
-  const int n = row_count(rows);
-  const int tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
-  int base = 0;
-  for (int start = 0; start < n; start += CB) {
-    const int j = start + tid;
-    const bool f = (j < n) && (flag[j] != 0);
-    const unsigned long long bal = __ballot(f);
-    const int before = __popcll(bal & ((1ull << lane) - 1ull));
-    if (lane == 0) wave_cnt[w] = __popcll(bal);
-    __syncthreads();
-    int woff = 0, tot = 0;
-#pragma unroll
-    for (int i = 0; i < CB / WAVE; ++i) {
-      const int c = wave_cnt[i];
-      woff += (i < w) ? c : 0;
-      tot += c;
-    }
-    if (f) {
-      const int p = base + woff + before;
-      if (p < out_cap) out_idx[p] = rows.idx ? rows.idx[j] : j;
-    }
-    base += tot;
-    __syncthreads();
-  }
-  const int m = min(base, out_cap);
-  if (base > out_cap && tid == 0) *status = overflow_code;
-  __threadfence_block();
-  __syncthreads();
-  for (int b = tid; b <= B; b += CB) {
-    const int key = b * L;
-    int lo = 0, hi = m;
-    while (lo < hi) {
-      const int mid = (lo + hi) >> 1;
-      if (out_idx[mid] < key) lo = mid + 1; else hi = mid;
-    }
-    out_off[b] = lo;
-  }
+  compact_block(flag, rows, row_count(rows), B, L, out_idx, out_off, out_cap, status, overflow_code,
+                false, wave_cnt);
 }
 
 __global__ void k_fill_i32(int32_t *p, int32_t v, int n) {
@@ -302,6 +309,16 @@ void launch_down_finalize(DType t, const float *part, int splits, size_t split_s
   else
     k_down_finalize<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>(part, splits, split_stride, h, rows, d,
                                                               (bf16_t *)out_cache);
+}
+
+void launch_swiglu_finalize(DType t, const float *part, int splits, size_t split_stride, Rows rows,
+                            int F, void *act, hipStream_t s) {
+  if (rows.cap <= 0) return;
+  size_t total = (size_t)rows.cap * (F / 4);
+  int grid = (int)((total + 255) / 256);
+  if (grid > 4096) grid = 4096;
+  if (t == F32) k_swiglu_finalize<float><<<grid, 256, 0, s>>>(part, splits, split_stride, rows, F, (float *)act);
+  else k_swiglu_finalize<bf16_t><<<grid, 256, 0, s>>>(part, splits, split_stride, rows, F, (bf16_t *)act);
 }
 
 void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_stride,
