@@ -46,10 +46,6 @@ template <int DH, int WQ> struct ATile {
   static_assert(MERGE_BYTES <= LDS_BYTES, "merge scratch must fit in the tile buffers");
 };
 
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
-}
-
 // global -> registers: one K/V tile (keys past k_hi are clamped to the last valid key; their scores
 // are masked later)
 template <int DH, int WQ, int KCH, int VCH>
@@ -178,44 +174,51 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
       for (int qb = 0; qb < 2; ++qb) s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][kk], s[qb], 0, 0, 0);
     }
 
-    // online softmax per query (= per lane), keys of this wave only
+    // online softmax per query (= per lane), keys of this wave only.  The running reference m_run is
+    // only moved when the block maximum exceeds it by more than 2^8: until then exp2(s - m_run) stays
+    // below 256, which bf16 probabilities and fp32 sums hold without loss, and the 128-register
+    // rescale of the output accumulator is skipped for the whole wave.
     const int key_base = k0 + wk * 32 + 4 * lhi;
+    const bool tail = k0 + TK > k_hi;  // wave-uniform: only the last tile can hold keys past the end
     bf16x8 pf[2][2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-      float mx = -INFINITY;
+      if (tail) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int key = key_base + 8 * (e / 4) + (e % 4);
-        const float v = key < k_hi ? s[qb][e] * sc : -INFINITY;
-        s[qb][e] = v;
-        mx = fmaxf(mx, v);
+        for (int e = 0; e < 16; ++e)
+          if (key_base + 8 * (e / 4) + (e % 4) >= k_hi) s[qb][e] = -INFINITY;
       }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
-      const float m_new = fmaxf(m_run[qb], mx);
-      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-      const float corr = __builtin_amdgcn_exp2f(m_run[qb] - m_safe);
+      float mx = s[qb][0];
+#pragma unroll
+      for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s[qb][e]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE)) * sc;
+      const bool need = mx > m_run[qb] + 8.0f;
+      if (__any(need)) {
+        const float corr = need ? __builtin_amdgcn_exp2f(m_run[qb] - mx) : 1.0f;
+        m_run[qb] = need ? mx : m_run[qb];
+        l_run[qb] *= corr;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc_o[qb][db][e] *= corr;
+      }
+      const float neg_ref = (m_run[qb] == -INFINITY) ? 0.f : -m_run[qb];
       float ps = 0.f;
       uint32_t pw[8];
 #pragma unroll
       for (int e = 0; e < 16; e += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(s[qb][e] - m_safe);
-        const float p1 = __builtin_amdgcn_exp2f(s[qb][e + 1] - m_safe);
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[qb][e], sc, neg_ref));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[qb][e + 1], sc, neg_ref));
         // the sum uses the rounded values that enter the matrix product
         const uint32_t w = pack_bf16(p0, p1);
         ps += __uint_as_float(w << 16) + __uint_as_float(w & 0xffff0000u);
         pw[e >> 1] = w;
       }
       ps += __shfl_xor(ps, 32, WAVE);
-      l_run[qb] = l_run[qb] * corr + ps;
-      m_run[qb] = m_new;
+      l_run[qb] += ps;
       uint4 v0{pw[0], pw[1], pw[2], pw[3]}, v1{pw[4], pw[5], pw[6], pw[7]};
       pf[qb][0] = __builtin_bit_cast(bf16x8, v0);
       pf[qb][1] = __builtin_bit_cast(bf16x8, v1);
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc_o[qb][db][e] *= corr;
     }
 
     // O^T += V^T P^T over the wave's 32 keys
