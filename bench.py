@@ -108,6 +108,14 @@ def main():
     esz = 4 if s.dtype == "f32" else 2
     K, Wu = args.steps, args.warmup
 
+    # traffic calibration dispatch: one plain device copy of a known size, larger than every cache
+    # (512 MiB read + 512 MiB written), so that a counter run can scale FETCH_SIZE / WRITE_SIZE
+    calib_src = torch.ones(512 << 20, dtype=torch.uint8, device="cuda")
+    calib_dst = torch.empty_like(calib_src)
+    calib_dst.copy_(calib_src)
+    torch.cuda.synchronize()
+    del calib_src, calib_dst
+
     lay = Layer.from_shape(s, wl.batch, wl.seq)
     lay.set_weights(W.make_weights(s))
     dense_x, steps = [], []
