@@ -176,7 +176,8 @@ AttnArgs attn_args(dyllm_ctx *ctx, const void *q, const void *k, const void *v, 
   AttnArgs a;
   a.q = q; a.k = k; a.v = v; a.rows = rows; a.offsets = offsets;
   a.B = B; a.L = L; a.H = c.n_heads; a.Hkv = c.n_kv_heads; a.dh = c.head_dim;
-  attention_plan(dt(ctx), B, L, c.n_heads, c.head_dim, rows.cap, ctx->part_elems, &a.splits, &a.chunk);
+  const int rows_per_seq = offsets ? (rows.cap + B - 1) / B : L;
+  attention_plan(dt(ctx), B, L, c.n_heads, c.head_dim, rows.cap, rows_per_seq, ctx->part_elems, &a);
   a.partial = partial;
   a.part_o = ctx->part_o; a.part_ml = ctx->part_ml; a.out = out;
   return a;

@@ -55,7 +55,7 @@ template <typename T>
 __global__ __launch_bounds__(1024) void k_attn_finalize(AttnArgs a, T *c_cache, float tau,
                                                         float *__restrict__ cos_out, uint8_t *flag_out,
                                                         CompactOut co) {
-  __shared__ float red[1024 / WAVE];
+  __shared__ float red[3 * 1024 / WAVE];
   __shared__ int wave_cnt[CB / WAVE];
   __shared__ int is_last;
   const int n = a.rows.count ? min(*a.rows.count, a.rows.cap) : a.rows.cap;
@@ -74,9 +74,7 @@ __global__ __launch_bounds__(1024) void k_attn_finalize(AttnArgs a, T *c_cache, 
       nb += b0 * b0 + b1 * b1 + b2 * b2 + b3 * b3;
       crow[c] = n0; crow[c + 1] = n1; crow[c + 2] = n2; crow[c + 3] = n3;
     }
-    dot = block_sum<1024>(dot, red);
-    na = block_sum<1024>(na, red);
-    nb = block_sum<1024>(nb, red);
+    block_sum3<1024>(dot, na, nb, red);
     if (threadIdx.x == 0) {
       const float s = dot / (fmaxf(sqrtf(na), 1e-8f) * fmaxf(sqrtf(nb), 1e-8f));
       if (cos_out) cos_out[j] = s;
@@ -120,13 +118,21 @@ void launch_attn_finalize(DType t, const AttnArgs &a, void *c_cache, float tau, 
     k_attn_finalize<bf16_t><<<grid, 1024, 0, s>>>(a, (bf16_t *)c_cache, tau, cos_out, flag_out, co);
 }
 
-// Splits of the key range: enough workgroups to cover the chip a few times over when there are few
-// (sequence, head, query tile) triples, bounded by the partial buffer and by one key tile per split.
-void attention_plan(DType t, int B, int L, int H, int dh, int cap, size_t part_elems, int *splits,
-                    int *chunk) {
-  const int BQ = (t == F32) ? 16 : 64, BK = (t == F32) ? 64 : 128;
-  const long tiles = (long)((cap + BQ - 1) / BQ + B) * H;
-  int s = (int)((1024 + tiles - 1) / tiles);
+// Query tile and key splits: enough workgroups to cover the chip once when there are few
+// (sequence, head, query tile) triples; the splits' partials cost HBM traffic and a merge, so no more
+// than that.  Bounded by the partial buffer and by one key tile per split.
+void attention_plan(DType t, int B, int L, int H, int dh, int cap, int rows_per_seq, size_t part_elems,
+                    AttnArgs *a) {
+  const int BK = (t == F32) ? 64 : 128;
+  const int n_opt = (t == F32) ? 1 : 2;
+  const int bq_opt[2] = {(t == F32) ? 16 : 128, 64};
+  const long target = 256;  // workgroups that cover the 256 CUs once
+  // 128-row query tiles when sequences bring that many rows, else 64-row tiles
+  const int best_bq = (n_opt == 1) ? bq_opt[0] : (rows_per_seq > 80 ? 128 : 64);
+  long tiles = (long)((rows_per_seq + best_bq - 1) / best_bq) * B * H;
+  if (tiles < 1) tiles = 1;  // empty list
+  const int best_s = (int)((target + tiles - 1) / tiles);
+  int s = best_s;
   const int max_by_keys = (L + BK - 1) / BK;
   if (s > max_by_keys) s = max_by_keys;
   if (s > 16) s = 16;
@@ -134,8 +140,9 @@ void attention_plan(DType t, int B, int L, int H, int dh, int cap, size_t part_e
   if (per_split > 0 && (size_t)s * per_split > part_elems) s = (int)(part_elems / per_split);
   if (s < 1) s = 1;
   const int c = split_chunk(L, s, BK);
-  *chunk = c;
-  *splits = (L + c - 1) / c;  // drops splits that would be empty
+  a->bq = best_bq;
+  a->chunk = c;
+  a->splits = (L + c - 1) / c;  // drops splits that would be empty
 }
 
 void launch_attention(DType t, const AttnArgs &a, hipStream_t s) {

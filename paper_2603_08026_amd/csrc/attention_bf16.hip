@@ -341,13 +341,8 @@ template <int DH, int WQ> void launch_cfg(const AttnArgs &a, hipStream_t s) {
 
 }  // namespace
 
-int attention_bf16_bq(int B, int cap) {
-  // 128-row query tiles when sequences bring that many rows on average, else 64-row tiles
-  return (cap + B - 1) / B > 80 ? 128 : 64;
-}
-
 void launch_attention_bf16(const AttnArgs &a, hipStream_t s) {
-  const bool wide = a.offsets ? attention_bf16_bq(a.B, a.rows.cap) == 128 : a.L > 80;
+  const bool wide = a.bq == 128;
   if (a.dh == 128) {
     if (wide) launch_cfg<128, 2>(a, s); else launch_cfg<128, 1>(a, s);
   } else {

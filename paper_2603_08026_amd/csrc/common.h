@@ -85,4 +85,17 @@ template <int NT> __device__ __forceinline__ float block_sum(float v, float *red
   return s;
 }
 
+// Sums of three values over a workgroup in one pass (two barriers); red: 3*NT/64 floats of LDS.
+template <int NT>
+__device__ __forceinline__ void block_sum3(float &a, float &b, float &c, float *red) {
+  a = wave_sum(a); b = wave_sum(b); c = wave_sum(c);
+  const int w = threadIdx.x / WAVE, l = threadIdx.x % WAVE;
+  __syncthreads();
+  if (l == 0) { red[3 * w] = a; red[3 * w + 1] = b; red[3 * w + 2] = c; }
+  __syncthreads();
+  a = b = c = 0.f;
+#pragma unroll
+  for (int i = 0; i < NT / WAVE; ++i) { a += red[3 * i]; b += red[3 * i + 1]; c += red[3 * i + 2]; }
+}
+
 }  // namespace dy

@@ -56,6 +56,7 @@ struct AttnArgs {
   int B, L, H, Hkv, dh;
   int splits;           // key range split into this many parts (>= 1), none of them empty
   int chunk;            // keys per split (multiple of the key tile); split s covers [s*chunk, min(L,(s+1)*chunk))
+  int bq;               // query rows per workgroup the plan chose (bf16: 128 or 64; fp32: 16)
   int partial;          // 1: leave partials even for a single split (a finalize kernel follows)
   float *part_o;        // [splits, cap, H*dh] fp32 un-normalised partial outputs
   float *part_ml;       // [splits, cap, H, 2] fp32 (running max in natural-log units, running sum)
@@ -70,9 +71,10 @@ void launch_attention(DType t, const AttnArgs &a, hipStream_t s);
 void launch_attn_finalize(DType t, const AttnArgs &a, void *c_cache, float tau, float *cos_out,
                           uint8_t *flag_out, int32_t *out_idx, int32_t *out_offsets, int out_cap,
                           int32_t *status, int32_t *counter, hipStream_t s);
-// Chooses splits and chunk for a call (host).
-void attention_plan(DType t, int B, int L, int H, int dh, int cap, size_t part_elems, int *splits,
-                    int *chunk);
+// Chooses the query tile, the number of key splits and the keys per split for a call (host);
+// rows_per_seq = expected query rows per sequence (capacity / B for a row list, L for a dense step).
+void attention_plan(DType t, int B, int L, int H, int dh, int cap, int rows_per_seq, size_t part_elems,
+                    AttnArgs *a);
 
 // ---- GEMMs  C[m,n] = sum_k A[m,k] * W[n,k]  (W is [N,K] row-major) -----------------------------
 struct GemmA {
