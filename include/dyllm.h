@@ -179,6 +179,26 @@ int dyllm_layer_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_c
 int dyllm_full_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
                     const void *x, int32_t B, int32_t L, void *stream);
 
+/* SparseStep through a stack of n_layers layers, enqueued as one sequence.  [Alg. 3, loop over l]
+ * w, caches and idx_out are HOST arrays of n_layers entries (their members are device pointers).
+ * Layer 0 reads x and idx_in; layer l > 0 reads caches[l-1].out (all rows: recomputed and reused
+ * alike) as its input and idx_out[l-1] as its candidates, and writes idx_out[l]; idx_out[n_layers-1]
+ * is the set carried to the next denoising step.  idx_out[l] must not share buffers with
+ * idx_out[l-1] (or idx_in for l = 0); lists two layers apart may share them.  Every selection is a
+ * subset of idx_in, so a capacity of idx_in->cap suffices for each list.  cos_out: NULL, or
+ * [n_layers, idx_in->cap] (row l: cosines of layer l's candidates).  All arguments of all layers
+ * are checked before the first launch. */
+int dyllm_stack_step(dyllm_ctx *ctx, int32_t n_layers, const dyllm_layer_weights *w,
+                     dyllm_layer_cache *caches, const void *x, const dyllm_index_list *idx_in,
+                     int32_t B, int32_t L, float tau, dyllm_index_list *idx_out, float *cos_out,
+                     void *stream);
+
+/* FullStep through a stack of n_layers layers: layer l > 0 reads caches[l-1].out.  [Alg. 2, loop
+ * over l]  w and caches are host arrays of n_layers entries. */
+int dyllm_stack_full_step(dyllm_ctx *ctx, int32_t n_layers, const dyllm_layer_weights *w,
+                          dyllm_layer_cache *caches, const void *x, int32_t B, int32_t L,
+                          void *stream);
+
 /* Per-stage timing of dyllm_layer_step / dyllm_full_step for measurement.  After
  * dyllm_profile_begin the next max_calls (<= 4096) step calls on this context record a HIP event on
  * their stream after every stage (gather+norm, q/k/v GEMM, rotation+merge, attention, saliency,

@@ -15,6 +15,9 @@ What each function follows:
                                     its layer loop restricted to the salient
                                     (row-sparse) path
   full_step ....................... App. C.2, Alg. 2 (FullStep), one layer
+  stack_step, stack_full_step ..... the layer loops of Alg. 3 and Alg. 2: a layer
+                                    reads the previous layer's output cache and,
+                                    in Alg. 3, the previous layer's salient set
   compact ......................... the where(...) of Alg. 3
   rmsnorm ......................... App. E, proof of Prop. 1 (RMSNorm definition)
 
@@ -341,6 +344,31 @@ def layer_step(x: np.ndarray, idx_in: np.ndarray, w: Dict[str, np.ndarray], cfg:
     # (6) out-projection and FFN for the newly selected rows
     salient_ffn(xf, cc, idx_out, w, cfg, oc)
     return idx_out, offsets_out, cos
+
+
+def stack_step(x: np.ndarray, idx_in: np.ndarray, ws, cfg: LayerCfg, caches, tau: float):
+    """SparseStep over a stack of layers.  [Alg. 3, loop over l]
+
+    ws / caches: one weight dict / cache dict per layer.  Layer 1 reads x and
+    idx_in; layer l > 1 reads the output cache of layer l-1 (its full [B, L, d]
+    content: recomputed rows and reused rows alike) and the salient set that
+    layer l-1 selected.  Returns the per-layer (idx_out, offsets_out, cos).
+    """
+    h, idx = x, idx_in
+    per_layer = []
+    for w, c in zip(ws, caches):
+        idx, off, cos = layer_step(h, idx, w, cfg, c, tau)
+        per_layer.append((idx, off, cos))
+        h = c["out"]
+    return per_layer
+
+
+def stack_full_step(x: np.ndarray, ws, cfg: LayerCfg, caches) -> None:
+    """FullStep over a stack of layers.  [Alg. 2, loop over l]"""
+    h = x
+    for w, c in zip(ws, caches):
+        full_step(h, w, cfg, c)
+        h = c["out"]
 
 
 def kv_only_bytes_per_token(cfg: LayerCfg, elem: int) -> int:

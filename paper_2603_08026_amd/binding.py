@@ -18,12 +18,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdyllm.so")
 
 F32, BF16 = 0, 1
-ERR_CAPACITY = -6
+OK, ERR_INVALID_ARG, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_NO_MEM, ERR_HIP, ERR_CAPACITY = 0, -1, -2, -3, -4, -5, -6
 
 SYMBOLS = [
     "dyllm_workspace_bytes", "dyllm_create", "dyllm_destroy", "dyllm_strerror", "dyllm_last_error",
     "dyllm_poll_status", "dyllm_saliency", "dyllm_compact", "dyllm_qkv_refresh",
     "dyllm_partial_attention", "dyllm_salient_ffn", "dyllm_layer_step", "dyllm_full_step",
+    "dyllm_stack_step", "dyllm_stack_full_step",
     "dyllm_profile_begin", "dyllm_profile_end", "dyllm_stage_count", "dyllm_stage_name",
 ]
 
@@ -86,6 +87,9 @@ def load_library() -> C.CDLL:
     lib.dyllm_layer_step.argtypes = [vp, P(LayerWeights), P(LayerCache), vp, P(IndexListC), i32, i32, f32,
                                      P(IndexListC), vp, vp]
     lib.dyllm_full_step.argtypes = [vp, P(LayerWeights), P(LayerCache), vp, i32, i32, vp]
+    lib.dyllm_stack_step.argtypes = [vp, i32, P(LayerWeights), P(LayerCache), vp, P(IndexListC), i32, i32, f32,
+                                     P(IndexListC), vp, vp]
+    lib.dyllm_stack_full_step.argtypes = [vp, i32, P(LayerWeights), P(LayerCache), vp, i32, i32, vp]
     lib.dyllm_profile_begin.argtypes = [vp, i32]
     lib.dyllm_profile_end.argtypes = [vp, P(f32), P(i32)]
     lib.dyllm_stage_count.argtypes = []
@@ -230,3 +234,19 @@ class Context:
 
     def full_step(self, w: LayerWeights, cache: LayerCache, x, B, L):
         self._check(self.lib.dyllm_full_step(self.h, C.byref(w), C.byref(cache), _ptr(x), B, L, _stream()))
+
+    def stack_step(self, ws, caches, x, idx_in: IndexList, B, L, tau, idx_outs, cos_out=None):
+        """ws / caches / idx_outs: one LayerWeights / LayerCache / IndexList per layer."""
+        n = len(ws)
+        wa = (LayerWeights * n)(*ws)
+        ca = (LayerCache * n)(*caches)
+        oa = (IndexListC * n)(*[o.c() for o in idx_outs])
+        i = idx_in.c()
+        self._check(self.lib.dyllm_stack_step(self.h, n, wa, ca, _ptr(x), C.byref(i), B, L, tau, oa,
+                                              _ptr(cos_out), _stream()))
+
+    def stack_full_step(self, ws, caches, x, B, L):
+        n = len(ws)
+        wa = (LayerWeights * n)(*ws)
+        ca = (LayerCache * n)(*caches)
+        self._check(self.lib.dyllm_stack_full_step(self.h, n, wa, ca, _ptr(x), B, L, _stream()))

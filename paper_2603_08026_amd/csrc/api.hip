@@ -226,6 +226,71 @@ int check_cache(dyllm_ctx *ctx, const dyllm_layer_cache *c) {
   return DYLLM_OK;
 }
 
+int check_dense_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, const dyllm_layer_cache *cache,
+                      const void *x) {
+  int rc;
+  if ((rc = check_weights(ctx, w, true, true))) return rc;
+  if ((rc = check_cache(ctx, cache))) return rc;
+  if (!x) return fail(ctx, DYLLM_ERR_INVALID_ARG, "x is NULL");
+  if (x == cache->out) return fail(ctx, DYLLM_ERR_INVALID_ARG, "x aliases cache->out");
+  return DYLLM_OK;
+}
+
+int check_sparse_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, const dyllm_layer_cache *cache,
+                       const void *x, const dyllm_index_list *idx_in, const dyllm_index_list *idx_out) {
+  int rc;
+  if ((rc = check_dense_layer(ctx, w, cache, x))) return rc;
+  if ((rc = check_list(ctx, idx_in, "idx_in"))) return rc;
+  if ((rc = check_list(ctx, idx_out, "idx_out"))) return rc;
+  if ((idx_out->idx && idx_out->idx == idx_in->idx) || idx_out->offsets == idx_in->offsets)
+    return fail(ctx, DYLLM_ERR_INVALID_ARG, "idx_out aliases idx_in");
+  return DYLLM_OK;
+}
+
+// one layer of the sparse step, arguments already checked  [Alg. 3 layer body]
+int enqueue_sparse_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
+                         const void *x, const dyllm_index_list *idx_in, int B, int L, float tau,
+                         dyllm_index_list *idx_out, float *cos_out, hipStream_t s) {
+  int rc;
+  const Rows rin = rows_of(idx_in, B);
+  prof_begin_call(ctx, s);
+  if ((rc = enqueue_qkv(ctx, w, x, rin, L, cache, ctx->qs, s))) return rc;
+  {
+    // attention leaves per-split partials; their merge is fused with the cosine test and the commit
+    const AttnArgs a = attn_args(ctx, ctx->qs, cache->k, cache->v, rin, idx_in->offsets, B, L, nullptr, 1);
+    launch_attention(dt(ctx), a, s);
+    prof_mark(ctx, ST_ATTENTION, s);
+    // ... and the last workgroup of that kernel compacts the flags into idx_out
+    launch_attn_finalize(dt(ctx), a, cache->c, tau, cos_out ? cos_out : ctx->cosb, ctx->flag,
+                         idx_out->idx, idx_out->offsets, idx_out->cap, ctx->status, ctx->status + 1, s);
+    prof_mark(ctx, ST_SALIENCY, s);
+    prof_mark(ctx, ST_COMPACT, s);
+  }
+  if ((rc = check_launch(ctx, "saliency / compact"))) return rc;
+  // idx_out is a subset of idx_in: its count never exceeds idx_in's capacity, which sizes the grids
+  Rows rout = rows_of(idx_out, B);
+  if (rout.cap > idx_in->cap) rout.cap = idx_in->cap;
+  rc = enqueue_ffn(ctx, w, x, cache->c, rout, cache->out, s);
+  ctx->prof_cur = nullptr;
+  return rc;
+}
+
+// dense pass of one layer, arguments already checked  [Alg. 2 layer body]
+int enqueue_dense_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
+                        const void *x, int B, int L, hipStream_t s) {
+  int rc;
+  const Rows all{nullptr, nullptr, B * L};
+  prof_begin_call(ctx, s);
+  if ((rc = enqueue_qkv(ctx, w, x, all, L, cache, ctx->qs, s))) return rc;
+  // every row is a query: the context cache is written directly
+  if ((rc = enqueue_attention(ctx, ctx->qs, cache->k, cache->v, all, nullptr, B, L, cache->c, s))) return rc;
+  prof_mark(ctx, ST_SALIENCY, s);
+  prof_mark(ctx, ST_COMPACT, s);
+  rc = enqueue_ffn(ctx, w, x, cache->c, all, cache->out, s);
+  ctx->prof_cur = nullptr;
+  return rc;
+}
+
 }  // namespace
 
 extern "C" {
@@ -449,60 +514,65 @@ int dyllm_layer_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_c
                      dyllm_index_list *idx_out, float *cos_out, void *stream) {
   if (!ctx) return DYLLM_ERR_INVALID_ARG;
   int rc;
-  if ((rc = check_weights(ctx, w, true, true))) return rc;
-  if ((rc = check_cache(ctx, cache))) return rc;
-  if (!x) return fail(ctx, DYLLM_ERR_INVALID_ARG, "x is NULL");
-  if (x == cache->out) return fail(ctx, DYLLM_ERR_INVALID_ARG, "x aliases cache->out");
   if ((rc = check_bl(ctx, B, L))) return rc;
-  if ((rc = check_list(ctx, idx_in, "idx_in"))) return rc;
-  if ((rc = check_list(ctx, idx_out, "idx_out"))) return rc;
-  if ((idx_out->idx && idx_out->idx == idx_in->idx) || idx_out->offsets == idx_in->offsets)
-    return fail(ctx, DYLLM_ERR_INVALID_ARG, "idx_out aliases idx_in");
-  hipStream_t s = (hipStream_t)stream;
-  const Rows rin = rows_of(idx_in, B);
-  prof_begin_call(ctx, s);
-  if ((rc = enqueue_qkv(ctx, w, x, rin, L, cache, ctx->qs, s))) return rc;
-  {
-    // attention leaves per-split partials; their merge is fused with the cosine test and the commit
-    const AttnArgs a = attn_args(ctx, ctx->qs, cache->k, cache->v, rin, idx_in->offsets, B, L, nullptr, 1);
-    launch_attention(dt(ctx), a, s);
-    prof_mark(ctx, ST_ATTENTION, s);
-    // ... and the last workgroup of that kernel compacts the flags into idx_out
-    launch_attn_finalize(dt(ctx), a, cache->c, tau, cos_out ? cos_out : ctx->cosb, ctx->flag,
-                         idx_out->idx, idx_out->offsets, idx_out->cap, ctx->status, ctx->status + 1, s);
-    prof_mark(ctx, ST_SALIENCY, s);
-    prof_mark(ctx, ST_COMPACT, s);
-  }
-  if ((rc = check_launch(ctx, "saliency / compact"))) return rc;
-  // idx_out is a subset of idx_in: its count never exceeds idx_in's capacity, which sizes the grids
-  Rows rout = rows_of(idx_out, B);
-  if (rout.cap > idx_in->cap) rout.cap = idx_in->cap;
-  rc = enqueue_ffn(ctx, w, x, cache->c, rout, cache->out, s);
-  ctx->prof_cur = nullptr;
-  return rc;
+  if ((rc = check_sparse_layer(ctx, w, cache, x, idx_in, idx_out))) return rc;
+  return enqueue_sparse_layer(ctx, w, cache, x, idx_in, B, L, tau, idx_out, cos_out, (hipStream_t)stream);
 }
 
 int dyllm_full_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
                     const void *x, int32_t B, int32_t L, void *stream) {
   if (!ctx) return DYLLM_ERR_INVALID_ARG;
   int rc;
-  if ((rc = check_weights(ctx, w, true, true))) return rc;
-  if ((rc = check_cache(ctx, cache))) return rc;
-  if (!x) return fail(ctx, DYLLM_ERR_INVALID_ARG, "x is NULL");
-  if (x == cache->out) return fail(ctx, DYLLM_ERR_INVALID_ARG, "x aliases cache->out");
   if ((rc = check_bl(ctx, B, L))) return rc;
   if ((long)B * L > ctx->rows_cap) return fail(ctx, DYLLM_ERR_CAPACITY, "B*L exceeds the context's max_rows");
-  hipStream_t s = (hipStream_t)stream;
-  const Rows all{nullptr, nullptr, B * L};
-  prof_begin_call(ctx, s);
-  if ((rc = enqueue_qkv(ctx, w, x, all, L, cache, ctx->qs, s))) return rc;
-  // every row is a query: the context cache is written directly
-  if ((rc = enqueue_attention(ctx, ctx->qs, cache->k, cache->v, all, nullptr, B, L, cache->c, s))) return rc;
-  prof_mark(ctx, ST_SALIENCY, s);
-  prof_mark(ctx, ST_COMPACT, s);
-  rc = enqueue_ffn(ctx, w, x, cache->c, all, cache->out, s);
-  ctx->prof_cur = nullptr;
-  return rc;
+  if ((rc = check_dense_layer(ctx, w, cache, x))) return rc;
+  return enqueue_dense_layer(ctx, w, cache, x, B, L, (hipStream_t)stream);
+}
+
+int dyllm_stack_step(dyllm_ctx *ctx, int32_t n_layers, const dyllm_layer_weights *w,
+                     dyllm_layer_cache *caches, const void *x, const dyllm_index_list *idx_in,
+                     int32_t B, int32_t L, float tau, dyllm_index_list *idx_out, float *cos_out,
+                     void *stream) {
+  if (!ctx) return DYLLM_ERR_INVALID_ARG;
+  if (n_layers <= 0 || !w || !caches || !idx_out) return fail(ctx, DYLLM_ERR_INVALID_ARG, "empty stack or NULL array");
+  int rc;
+  if ((rc = check_bl(ctx, B, L))) return rc;
+  // every argument of every layer is checked before the first launch
+  for (int l = 0; l < n_layers; ++l) {
+    const void *xl = l ? caches[l - 1].out : x;
+    const dyllm_index_list *in = l ? &idx_out[l - 1] : idx_in;
+    if ((rc = check_sparse_layer(ctx, &w[l], &caches[l], xl, in, &idx_out[l]))) return rc;
+  }
+  // a layer's selection is a subset of the first layer's candidates: that capacity sizes every grid
+  const int cap0 = idx_in->cap;
+  dyllm_index_list in = *idx_in;
+  for (int l = 0; l < n_layers; ++l) {
+    dyllm_index_list out = idx_out[l];
+    if (out.cap > cap0) out.cap = cap0;
+    float *cos_l = cos_out ? cos_out + (size_t)l * cap0 : nullptr;
+    if ((rc = enqueue_sparse_layer(ctx, &w[l], &caches[l], l ? caches[l - 1].out : x, &in, B, L, tau,
+                                   &out, cos_l, (hipStream_t)stream)))
+      return rc;
+    in = out;
+  }
+  return DYLLM_OK;
+}
+
+int dyllm_stack_full_step(dyllm_ctx *ctx, int32_t n_layers, const dyllm_layer_weights *w,
+                          dyllm_layer_cache *caches, const void *x, int32_t B, int32_t L,
+                          void *stream) {
+  if (!ctx) return DYLLM_ERR_INVALID_ARG;
+  if (n_layers <= 0 || !w || !caches) return fail(ctx, DYLLM_ERR_INVALID_ARG, "empty stack or NULL array");
+  int rc;
+  if ((rc = check_bl(ctx, B, L))) return rc;
+  if ((long)B * L > ctx->rows_cap) return fail(ctx, DYLLM_ERR_CAPACITY, "B*L exceeds the context's max_rows");
+  for (int l = 0; l < n_layers; ++l)
+    if ((rc = check_dense_layer(ctx, &w[l], &caches[l], l ? caches[l - 1].out : x))) return rc;
+  for (int l = 0; l < n_layers; ++l)
+    if ((rc = enqueue_dense_layer(ctx, &w[l], &caches[l], l ? caches[l - 1].out : x, B, L,
+                                  (hipStream_t)stream)))
+      return rc;
+  return DYLLM_OK;
 }
 
 }  // extern "C"

@@ -130,15 +130,17 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
       const int src = gather ? gather[j] : j;
       ap[i] = A + (size_t)src * lda + kbeg + csrc * 8;
     }
-    int sg = 0;
-    while (sg < 2 && n0 >= seg.n_end[sg]) ++sg;
-    const int seg_start = sg ? seg.n_end[sg - 1] : 0;
+    // a column tile may span two of the stacked weight matrices: the matrix is looked up per row
     const bf16_t *wp[NMAT][SH::B_LD];
 #pragma unroll
     for (int i = 0; i < SH::B_LD; ++i) {
-      const size_t roff = (size_t)((i * SH::NW + wave) * 8 + r8) * ldw + kbeg + csrc * 8;
-      wp[0][i] = (const bf16_t *)seg.w[sg] + (size_t)(n0 - seg_start) * ldw + roff;
-      if (SH::DUAL) wp[NMAT - 1][i] = W2 + (size_t)n0 * ldw + roff;
+      const int nrow = (i * SH::NW + wave) * 8 + r8;
+      const int n = n0 + nrow;
+      const bool in1 = n >= seg.n_end[0], in2 = n >= seg.n_end[1];
+      const bf16_t *wbase = (const bf16_t *)(in2 ? seg.w[2] : in1 ? seg.w[1] : seg.w[0]);
+      const int wstart = in2 ? seg.n_end[1] : in1 ? seg.n_end[0] : 0;
+      wp[0][i] = wbase + (size_t)(n - wstart) * ldw + kbeg + csrc * 8;
+      if (SH::DUAL) wp[NMAT - 1][i] = W2 + (size_t)n * ldw + kbeg + csrc * 8;
     }
 
     floatx16 acc[NMAT][MB][NB];

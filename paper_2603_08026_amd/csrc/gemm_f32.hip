@@ -32,11 +32,11 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const T *__restrict__ A, const
     const int jm = m0 + lr;
     const T *arow = nullptr;
     if (jm < M) arow = A + (size_t)(gather ? gather[jm] : jm) * lda;
-    // weight row of this thread's load slot
-    int sg = 0;
-    while (sg < 2 && n0 >= seg.n_end[sg]) ++sg;
-    const int seg_start = sg ? seg.n_end[sg - 1] : 0;
-    const T *wrow = (const T *)seg.w[sg] + (size_t)(n0 - seg_start + lr) * K;
+    // weight row of this thread's load slot, looked up in the stacked weight matrices
+    const int nw = n0 + lr;
+    const bool in1 = nw >= seg.n_end[0], in2 = nw >= seg.n_end[1];
+    const int seg_start = in2 ? seg.n_end[1] : in1 ? seg.n_end[0] : 0;
+    const T *wrow = (const T *)(in2 ? seg.w[2] : in1 ? seg.w[1] : seg.w[0]) + (size_t)(nw - seg_start) * K;
     const T *w2row = Epi::DUAL ? W2 + (size_t)(n0 + lr) * K : nullptr;
 
     float acc[4][4], acc2[4][4];

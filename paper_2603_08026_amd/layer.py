@@ -30,7 +30,7 @@ def to_host(t: torch.Tensor) -> np.ndarray:
 
 class Layer:
     def __init__(self, hidden, n_heads, n_kv_heads, head_dim, ffn, dtype: str, batch: int, seq: int,
-                 max_rows: int = 0, rms_eps: float = 1e-5, rope_theta: float = 10000.0):
+                 max_rows: int = 0, rms_eps: float = 1e-5, rope_theta: float = 10000.0, ctx=None):
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the dyllm library only runs on a HIP device")
         self.dtype = dtype
@@ -39,7 +39,7 @@ class Layer:
         self.dq, self.dkv = n_heads * head_dim, n_kv_heads * head_dim
         self.cfg = B_.LayerCfg(hidden, n_heads, n_kv_heads, head_dim, ffn, batch, seq, max_rows,
                                B_.F32 if dtype == "f32" else B_.BF16, rms_eps, rope_theta)
-        self.ctx = B_.Context(self.cfg)
+        self.ctx = B_.Context(self.cfg) if ctx is None else ctx  # layers of a stack share one
         td = torch_dtype(dtype)
         T = batch * seq
         self.k = torch.zeros(batch, seq, n_kv_heads, head_dim, dtype=td, device="cuda")
@@ -54,12 +54,17 @@ class Layer:
         self.w = None
 
     @classmethod
-    def from_shape(cls, shape, batch, seq, max_rows=0):
+    def from_shape(cls, shape, batch, seq, max_rows=0, ctx=None):
         return cls(shape.hidden, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.ffn, shape.dtype,
-                   batch, seq, max_rows, shape.rms_eps, shape.rope_theta)
+                   batch, seq, max_rows, shape.rms_eps, shape.rope_theta, ctx)
 
     def set_weights(self, w: Dict[str, np.ndarray]):
         self.wt = {k: to_device(v, self.dtype) for k, v in w.items() if v is not None}
+        self.w = B_.make_weights(self.wt)
+
+    def set_device_weights(self, wt: Dict[str, torch.Tensor]):
+        """Weights that already live on the device in the storage type (large synthetic stacks)."""
+        self.wt = dict(wt)
         self.w = B_.make_weights(self.wt)
 
     def set_caches(self, caches: Dict[str, np.ndarray]):
@@ -94,6 +99,39 @@ class Layer:
         off = il.offsets.cpu().numpy()
         n = int(off[-1])
         return il.idx[:n].cpu().numpy(), off
+
+    def close(self):
+        self.ctx.close()
+
+
+class Stack:
+    """n_layers layers sharing one library context; layer l reads layer l-1's output cache."""
+
+    def __init__(self, shape, n_layers: int, batch: int, seq: int, max_rows: int = 0):
+        first = Layer.from_shape(shape, batch, seq, max_rows)
+        self.layers = [first] + [Layer.from_shape(shape, batch, seq, max_rows, ctx=first.ctx)
+                                 for _ in range(n_layers - 1)]
+        self.ctx, self.B, self.L, self.dtype = first.ctx, batch, seq, first.dtype
+        cap = first.rows_cap
+        self.idx_outs = [l.idx_out for l in self.layers]
+        self.cos = torch.zeros(n_layers, cap, dtype=torch.float32, device="cuda")
+
+    def upload(self, x: np.ndarray) -> torch.Tensor:
+        return to_device(x, self.dtype)
+
+    def make_list(self, idx, offsets, cap=None):
+        return self.layers[0].make_list(idx, offsets, cap)
+
+    def full_step(self, x_dev: torch.Tensor):
+        self.ctx.stack_full_step([l.w for l in self.layers], [l.cache for l in self.layers], x_dev,
+                                 self.B, self.L)
+
+    def stack_step(self, x_dev: torch.Tensor, idx_in: B_.IndexList, tau: float, want_cos: bool = True):
+        """cos rows are strided by idx_in's capacity, as the library writes them."""
+        cos = self.cos.view(-1)[:len(self.layers) * idx_in.cap] if want_cos else None
+        self.ctx.stack_step([l.w for l in self.layers], [l.cache for l in self.layers], x_dev, idx_in,
+                            self.B, self.L, tau, self.idx_outs, cos)
+        return self.idx_outs
 
     def close(self):
         self.ctx.close()

@@ -203,3 +203,42 @@ def test_8b_shapes_teacher_forced(name, nb, steps):
 def test_c2_free_running():
     wl = replace(W.CONFIGS["c2"], t_full=2)
     _run_stream(wl, 5, teacher_forced=False)
+
+
+@pytest.mark.parametrize("dtype,dh", [("f32", 64), ("bf16", 64), ("bf16", 128)])
+def test_weights_between_poisoned_guard_bands(dtype, dh):
+    """Every weight tensor sits between NaN-filled guard bands, so a read past either end of a
+    matrix (e.g. a column tile that spans the stacked q/k/v weights) poisons the result."""
+    _say("guard bands", dtype, dh)
+    s = small_shape(dtype, gqa=True, dh=dh)
+    cfg = oracle_cfg(s)
+    B, L = 2, 100
+    w = rand_weights(s, 97, bias=True)
+    lay = Layer.from_shape(s, B, L)
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    held, wt = [], {}
+    for name, a in w.items():
+        if a is None:
+            continue
+        guard = 70000
+        buf = torch.full((a.size + 2 * guard,), float("nan"), dtype=td, device="cuda")
+        view = buf[guard:guard + a.size].view(*a.shape)
+        view.copy_(torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(td))
+        held.append(buf)
+        wt[name] = view
+    lay.set_device_weights(wt)
+    x0 = W.philox(98, "x").standard_normal((B, L, s.hidden), dtype=np.float32)
+    x1 = W.philox(99, "x").standard_normal((B, L, s.hidden), dtype=np.float32)
+    if dtype == "bf16":
+        x0, x1 = W.round_bf16(x0), W.round_bf16(x1)
+    ref = O.new_caches(B, L, cfg)
+    O.full_step(x0, w, cfg, ref)
+    lay.full_step(lay.upload(x0))
+    _compare_caches(lay, ref, TOL[dtype], "guarded dense")
+    for counts in ([9, 30], [70, 64]):  # one-tile and several-tile row counts
+        idx, off = rand_rows(100 + counts[0], B, L, counts)
+        idx_ref, _, cos_ref = O.layer_step(x1, idx, w, cfg, ref, 0.99)
+        out = lay.layer_step(lay.upload(x1), lay.make_list(idx, off), 0.99)
+        assert_index_sets_match(lay.read_list(out)[0], idx_ref, idx, cos_ref, 0.99, "guarded sparse")
+        _compare_caches(lay, ref, TOL[dtype], "guarded sparse")
+    lay.close()

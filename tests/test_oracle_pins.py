@@ -432,3 +432,79 @@ def test_context_delta_decomposition_identity():
     S = np.exp(q[:, 0] @ k[:, 0].T / math.sqrt(dh))
     S /= S.sum(axis=1, keepdims=True)
     assert np.allclose(c1 - c0, S[:, [2, 5]] @ (v1 - v0)[[2, 5], 0], atol=1e-13)
+
+
+# ---------------------------------------------------------------- stack of layers
+
+def _stack_setup(n_layers=3, seed=21, B=2, L=10):
+    r = _rng(seed)
+    cfg = O.LayerCfg(hidden=16, n_heads=4, n_kv_heads=2, head_dim=4, ffn=24, rope_theta=50.0)
+    ws = [_weights(cfg, r, std=0.3) for _ in range(n_layers)]
+    x0 = r.normal(size=(B, L, 16))
+    caches = [O.new_caches(B, L, cfg) for _ in range(n_layers)]
+    O.stack_full_step(x0, ws, cfg, caches)
+    return r, cfg, ws, x0, caches
+
+
+def test_dense_stack_is_the_composition_of_library_layers():
+    # each layer of the dense stack against the torch-library layer applied to the previous output
+    r, cfg, ws, x0, caches = _stack_setup()
+    h = x0
+    for w, c in zip(ws, caches):
+        k, v, ctx, y = _dense_layer_torch(h, w, cfg)
+        assert np.allclose(c["k"], k, atol=1e-10) and np.allclose(c["c"], ctx, atol=1e-10)
+        assert np.allclose(c["out"], y, atol=1e-9)
+        h = y
+
+
+def test_stack_with_all_rows_salient_equals_dense_stack():
+    r, cfg, ws, x0, caches = _stack_setup()
+    x1 = r.normal(size=x0.shape)
+    dense = [O.new_caches(2, 10, cfg) for _ in ws]
+    O.stack_full_step(x1, ws, cfg, dense)
+    per_layer = O.stack_step(x1, np.arange(20), ws, cfg, caches, 1.5)
+    for (idx, off, cos), c, dn in zip(per_layer, caches, dense):
+        assert idx.tolist() == list(range(20)) and off.tolist() == [0, 10, 20]
+        for k in c:
+            assert np.allclose(c[k], dn[k], rtol=1e-10, atol=1e-11), k
+
+
+def test_stack_carries_the_salient_set_and_the_output_cache_between_layers():
+    r, cfg, ws, x0, caches = _stack_setup(n_layers=4)
+    before = [_copy(c) for c in caches]
+    x1 = x0.copy()
+    idx = np.array([0, 3, 8, 11, 15, 16])
+    # three rows change a lot, three hardly at all: the set shrinks on the way down
+    x1.reshape(20, -1)[idx[:3]] = r.normal(size=(3, 16))
+    x1.reshape(20, -1)[idx[3:]] += 1e-7 * r.normal(size=(3, 16))
+    per_layer = O.stack_step(x1, idx, ws, cfg, caches, 0.9999)
+    prev = idx
+    for l, ((out, off, cos), c, b) in enumerate(zip(per_layer, caches, before)):
+        assert cos.size == prev.size                      # candidates = previous layer's selection
+        assert set(out.tolist()) <= set(prev.tolist())
+        assert off[-1] == out.size
+        untouched = np.setdiff1d(np.arange(20), prev)
+        for k in c:                                      # rows outside the candidates: all caches kept
+            a = c[k].reshape(20, -1)
+            assert np.array_equal(a[untouched], b[k].reshape(20, -1)[untouched]), (l, k)
+        kept = np.setdiff1d(np.arange(20), out)           # rows not selected keep the cached output
+        assert np.array_equal(c["out"].reshape(20, -1)[kept], b["out"].reshape(20, -1)[kept])
+        prev = out
+    # sequence 1 holds only the barely moved rows: their contexts stay put and they drop out at layer 1
+    assert per_layer[0][0].tolist() == [0, 3, 8] and per_layer[-1][0].tolist() == [0, 3, 8]
+    assert np.all(per_layer[0][2][3:] > 1 - 1e-9)
+    # a one-layer stack is the layer step
+    one = [_copy(before[0])]
+    (o1, f1, c1), = O.stack_step(x1, idx, ws[:1], cfg, one, 0.9999)
+    assert np.array_equal(o1, per_layer[0][0]) and np.array_equal(c1, per_layer[0][2])
+    # layer l's recomputed rows equal a dense layer applied to the layer input it actually saw
+    h = x1
+    for l, ((out, off, cos), c, w) in enumerate(zip(per_layer, caches, ws)):
+        if out.size:
+            # context of selected rows against a dense evaluation with the merged K/V of this layer
+            for t in out[:2]:
+                bsel, i = divmod(int(t), 10)
+                q = O.project_qkv(O.rmsnorm(h.reshape(20, -1)[[t]], w["g_attn"], cfg.rms_eps), np.array([i]), w, cfg)[0]
+                ref = O.attention_rows(q, c["k"][bsel], c["v"][bsel]).reshape(-1)
+                assert np.allclose(c["c"][bsel, i], ref, atol=1e-12)
+        h = c["out"]
