@@ -3,9 +3,11 @@
 
 A "step" is one dyllm_layer_step (the whole hot path: gather+norm, q/k/v GEMM, rotation and K/V
 merge, partial attention, cosine saliency + commit, compaction, out-projection, FFN, scatter-back)
-over one batch of synthetic input that is already resident in HBM.  Prints ONE JSON line.
+over one batch of synthetic input that is already resident in HBM; for the 32-layer configuration
+(c5) a step is one dyllm_stack_step, i.e. 32 such layer steps chained through the output caches and
+the salient sets.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2|c3|c4] [--frac 0.10]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2|c3|c4|c5] [--frac 0.10]
 """
 import argparse
 import json
@@ -80,9 +82,10 @@ def cpu_baseline(wl, budget_s=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default 40; 6 for c5)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default 5; 2 for c5)")
+    ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--layers", type=int, default=None, help="stack depth override for c5")
     ap.add_argument("--frac", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dense-iters", type=int, default=3)
@@ -94,7 +97,8 @@ def main():
 
     import numpy as np
     import torch
-    from paper_2603_08026_amd.layer import Layer
+    from dataclasses import replace
+    from paper_2603_08026_amd.layer import Layer, Stack
     from synth import workload as W
 
     if not torch.cuda.is_available():
@@ -104,9 +108,13 @@ def main():
     wl = W.CONFIGS[args.config]
     if args.frac is not None:
         wl = W.with_frac(wl, args.frac)
+    if args.layers is not None:
+        wl = replace(wl, n_layers=args.layers)
     s = wl.shape
     esz = 4 if s.dtype == "f32" else 2
-    K, Wu = args.steps, args.warmup
+    NL = wl.n_layers
+    K = args.steps if args.steps is not None else (40 if NL == 1 else 6)
+    Wu = args.warmup if args.warmup is not None else (5 if NL == 1 else 2)
 
     # traffic calibration dispatch: one plain device copy of a known size, larger than every cache
     # (512 MiB read + 512 MiB written), so that a counter run can scale FETCH_SIZE / WRITE_SIZE
@@ -116,8 +124,28 @@ def main():
     torch.cuda.synchronize()
     del calib_src, calib_dst
 
-    lay = Layer.from_shape(s, wl.batch, wl.seq)
-    lay.set_weights(W.make_weights(s))
+    if NL == 1:
+        lay = Layer.from_shape(s, wl.batch, wl.seq)
+        lay.set_weights(W.make_weights(s))
+        layers, last = [lay], lay
+        full, sparse = lay.full_step, (lambda xd, il: lay.layer_step(xd, il, wl.tau, want_cos=False))
+    else:
+        # the stack's 14 GB of weights are drawn on the device (same distribution as the host
+        # generator of the single-layer configurations: N(0, 0.02^2) matrices, gains 1 + 0.1 N(0,1))
+        lay = Stack(s, NL, wl.batch, wl.seq)
+        td = torch.float32 if s.dtype == "f32" else torch.bfloat16
+        shapes = {"wq": (s.dq, s.hidden), "wk": (s.dkv, s.hidden), "wv": (s.dkv, s.hidden),
+                  "wo": (s.hidden, s.dq), "w_gate": (s.ffn, s.hidden), "w_up": (s.ffn, s.hidden),
+                  "w_down": (s.hidden, s.ffn)}
+        for l, one in enumerate(lay.layers):
+            g = torch.Generator(device="cuda")
+            g.manual_seed(W.SEED_W + l)
+            wt = {n: (torch.randn(*sh, generator=g, device="cuda") * 0.02).to(td) for n, sh in shapes.items()}
+            for n in ("g_attn", "g_ffn"):
+                wt[n] = (1 + 0.1 * torch.randn(s.hidden, generator=g, device="cuda")).to(td)
+            one.set_device_weights(wt)
+        layers, last = lay.layers, lay.layers[-1]
+        full, sparse = lay.full_step, (lambda xd, il: lay.stack_step(xd, il, wl.tau, want_cos=False))
     dense_x, steps = [], []
     for st in W.step_stream(wl, wl.t_full + Wu + K):
         xd = lay.upload(st.x)
@@ -127,30 +155,31 @@ def main():
             steps.append((xd, lay.make_list(st.idx, st.offsets), int(st.idx.size)))
     # cache warm-up: T_full dense steps (Sec. 3.2)
     for xd in dense_x:
-        lay.full_step(xd)
+        full(xd)
     torch.cuda.synchronize()
 
     def run(range_):
         for i in range_:
             xd, il, _ = steps[i]
-            lay.layer_step(xd, il, wl.tau, want_cos=False)
+            sparse(xd, il)
 
     run(range(Wu))
     torch.cuda.synchronize()
-    snap = {k: getattr(lay, k).clone() for k in ("k", "v", "c", "out")}
+    snap = [{k: getattr(one, k).clone() for k in ("k", "v", "c", "out")} for one in layers]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run(range(Wu, Wu + K))
     torch.cuda.synchronize()
     t_step = (time.perf_counter() - t0) / K
-    m_out_last = int(lay.idx_out.offsets[-1].item())
+    m_out_last = int(last.idx_out.offsets[-1].item())
 
     # the same K steps again, from the same cache state, with one HIP event after every stage
     # (recorded on the stream of the launches)
-    for k_, v_ in snap.items():
-        getattr(lay, k_).copy_(v_)
+    for one, sn in zip(layers, snap):
+        for k_, v_ in sn.items():
+            getattr(one, k_).copy_(v_)
     torch.cuda.synchronize()
-    lay.ctx.profile_begin(K)
+    lay.ctx.profile_begin(K * NL)
     t0 = time.perf_counter()
     run(range(Wu, Wu + K))
     torch.cuda.synchronize()
@@ -160,11 +189,11 @@ def main():
 
     # dense step of the same shape on the same GPU
     xd = dense_x[-1] if dense_x else steps[0][0]
-    lay.full_step(xd)
+    full(xd)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.dense_iters):
-        lay.full_step(xd)
+        full(xd)
     torch.cuda.synchronize()
     t_dense = (time.perf_counter() - t0) / args.dense_iters
 
@@ -202,17 +231,27 @@ def main():
 
     out = {
         "metric": "denoised tokens/s per layer-step at 8B shape; speedup vs dense step",
-        "value": wl.tokens / t_step, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wu,
+        # tokens advanced through one layer per second: a stack step advances every token through NL layers
+        "value": wl.tokens * NL / t_step, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wu,
         "ms_per_step": t_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": s.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "batch": wl.batch, "seq_len": wl.seq, "salient_frac": wl.frac,
                    "salient_rows_mean": m_in, "salient_rows_out_last": m_out_last, "tau": wl.tau,
-                   "hidden": s.hidden, "n_heads": s.n_heads, "n_kv_heads": s.n_kv_heads, "ffn": s.ffn},
+                   "hidden": s.hidden, "n_heads": s.n_heads, "n_kv_heads": s.n_kv_heads, "ffn": s.ffn,
+                   "layers": NL},
         "dense_ms_per_step": t_dense * 1e3, "speedup_vs_dense": t_dense / t_step,
         "salient_rows_per_s": m_in / t_step,
         "ms_per_step_with_stage_events": t_step_instr * 1e3, "stage_calls": calls, "stages": stages,
         "roofline": roof,
     }
+    if NL > 1:
+        # stack only: generated tokens per second of the paper's kind over the layer stack alone
+        # (no embedding, logits or sampling): B * L_R over T_full dense and the remaining sparse steps
+        total = wl.t_full * t_dense + (wl.steps - wl.t_full) * t_step
+        out["ms_per_layer_step"] = t_step * 1e3 / NL
+        out["stack_generated_tokens_per_s"] = wl.batch * wl.resp_len / total
+        out["stack_generated_tokens_per_s_dense_only"] = wl.batch * wl.resp_len / (wl.steps * t_dense)
+        out["data"] = "synthetic (weights drawn on the device)"
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     lay.close()
