@@ -8,10 +8,16 @@ using namespace mm;
 namespace {
 
 // Tile shapes per regime (rows = capacity of the row list):
+//  xlarge  256 x 256 tile (256 x (128+128) when gate and up are fused), 8 waves of 128 x 64, 2 LDS
+//          stages: a third fewer bytes per flop through the CU's L1 -> LDS path (measured at about
+//          54 bytes per clock and CU, which a 256 x 128 tile nearly saturates) and a quarter fewer
+//          LDS operand reads; taken when its coarser tiles still fill the rounds of the chip
 //  large   256 x 128 tile (256 x (64+64) when gate and up are fused), 8 waves, 2 LDS stages
 //  mid     128 x 128 tile, 4 waves, 2 stages (two workgroups per CU) for a few hundred rows
 //  skinny  all rows in one 128-row tile, 64-column tiles, 4 stages in flight and a K split so that
 //          about one workgroup per CU streams weights (weight-streaming-bound regime)
+typedef Shape<256, 256, 2, 4, false, 2> XLargeS;
+typedef Shape<256, 128, 2, 4, true, 2> XLargeD;
 typedef Shape<256, 128, 4, 2, false, 2> LargeS;
 typedef Shape<256, 64, 4, 2, true, 2> LargeD;
 typedef Shape<128, 128, 2, 2, false, 2> MidS;
@@ -24,6 +30,25 @@ typedef Shape<128, 128, 4, 2, false, 3> SkinnyW128;
 
 constexpr int MID_MAX_ROWS = 384;
 constexpr int SKINNY_MAX_ROWS = 128;
+
+int cu_count() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+  }
+  return n;
+}
+
+// 256-row tiles with n_l (large) or n_x (xlarge, twice as wide) column tiles: one workgroup per CU and
+// round; an xlarge tile takes about 1.63 times as long as a large one (measured at many rounds).
+bool prefer_xlarge(int cap, int n_l, int n_x) {
+  const long rows = (cap + 255) / 256, cu = cu_count();
+  const long rounds_l = (rows * n_l + cu - 1) / cu, rounds_x = (rows * n_x + cu - 1) / cu;
+  return 1.63 * (double)rounds_x < (double)rounds_l;
+}
 
 template <typename SH, typename Epi>
 void run_tiles(GemmA A, Rows rows, int K, int N, WSeg seg, const void *w2, Epi epi, int splitk,
@@ -62,6 +87,8 @@ int gemm_bf16_raw(GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_
     return sk;
   }
   if (rows.cap <= MID_MAX_ROWS) run_tiles<MidS>(A, rows, K, N, seg, nullptr, e, 1, part, s);
+  else if (N % XLargeS::BN == 0 && prefer_xlarge(rows.cap, N / LargeS::BN, N / XLargeS::BN))
+    run_tiles<XLargeS>(A, rows, K, N, seg, nullptr, e, 1, part, s);
   else run_tiles<LargeS>(A, rows, K, N, seg, nullptr, e, 1, part, s);
   return 1;
 }
@@ -79,6 +106,8 @@ void gemm_bf16_swiglu(GemmA A, Rows rows, int K, int N, const void *wg, const vo
     else run_tiles<SkinnyW128>(A, rows, K, 2 * N, seg, nullptr, raw, 1, part, s);
     launch_swiglu_finalize(BF16, part, 1, (size_t)rows.cap * 2 * N, rows, N, act, s);
   } else if (rows.cap <= MID_MAX_ROWS) run_tiles<MidD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
+  else if (N % XLargeD::BN == 0 && prefer_xlarge(rows.cap, N / LargeD::BN, N / XLargeD::BN))
+    run_tiles<XLargeD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
   else run_tiles<LargeD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
 }
 
@@ -96,6 +125,8 @@ void gemm_bf16_down(GemmA A, Rows rows, int K, int N, const void *wd, const floa
     }
   } else if (rows.cap <= MID_MAX_ROWS) {
     run_tiles<MidS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, 1, nullptr, s);
+  } else if (N % XLargeS::BN == 0 && prefer_xlarge(rows.cap, N / LargeS::BN, N / XLargeS::BN)) {
+    run_tiles<XLargeS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, 1, nullptr, s);
   } else {
     run_tiles<LargeS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, 1, nullptr, s);
   }
