@@ -13,9 +13,13 @@
 //                    8*ks+i, i.e. key 16*ks + 8*(i/4) + 4*(l/32) + i%4 -- the V^T operand is read
 //                    with the same key order (two 8-byte LDS reads), and a matrix product does not
 //                    care in which order k is summed as long as both operands agree.
-// A workgroup of 4 waves owns BQ = 64*WQ query rows of one (sequence, head); the keys of a tile are
-// split over the WK = 4/WQ wave columns (32 keys each), whose partial (max, sum, output) are merged
-// through LDS at the end.  K/V tiles are double-buffered in LDS with a register-staged prefetch.
+// A workgroup of NW waves owns BQ = 32*QB*WQ query rows of one (sequence, head): WQ wave rows of QB
+// blocks of 32 queries each; the keys of a tile are split over the WK = NW/WQ wave columns (32 keys
+// each), whose partial (max, sum, output) are merged through LDS at the end.  For head_dim 128 a wave
+// holds one query block (QB = 1) and a workgroup has 8 waves: about 150 registers per lane, so two
+// waves share a SIMD and the softmax arithmetic of one overlaps the matrix products of the other
+// (two blocks per wave need more than 256 registers, one wave per SIMD, everything serialised).
+// K/V tiles are double-buffered in LDS with a register-staged prefetch.
 // The key range of a sequence can additionally be split over workgroups (few query rows): then
 // un-normalised partials go to global memory and k_attn_combine merges them.
 #include "attention_common.h"
@@ -30,39 +34,42 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
-template <int DH, int WQ> struct ATile {
-  static constexpr int WK = 4 / WQ;       // wave columns over the keys of a tile
-  static constexpr int BQ = 64 * WQ;      // query rows per workgroup
+template <int DH, int WQ, int NW, int QB> struct ATile {
+  static constexpr int NT = 64 * NW;      // threads per workgroup
+  static constexpr int WK = NW / WQ;      // wave columns over the keys of a tile
+  static constexpr int BQ = 32 * QB * WQ; // query rows per workgroup
   static constexpr int TK = 32 * WK;      // keys per tile
   static constexpr int KSTR = DH + 8;     // K tile row stride (elements): 16-byte reads conflict-free
   static constexpr int VSTR = TK + 4;     // V^T row stride (elements): 8-byte reads conflict-free
   static constexpr int STAGE = TK * KSTR + DH * VSTR;
   static constexpr int DB = DH / 32, KK = DH / 16;
-  static constexpr int K_CH = TK * DH / 8 / 256;       // 16-byte K chunks per thread and tile
-  static constexpr int V_CH = TK * DH / 8 / 2 / 256;   // pairs of V chunks per thread and tile
+  static constexpr int K_CH = TK * DH / 8 / NT;       // 16-byte K chunks per thread and tile
+  static constexpr int V_CH = TK * DH / 8 / 2 / NT;   // pairs of V chunks per thread and tile
   static constexpr size_t LDS_BYTES = (size_t)2 * STAGE * 2;
-  // merge scratch (reuses the tile buffers): (WK-1)*WQ waves x (2*DB*16 + 4) floats x 64 lanes
-  static constexpr size_t MERGE_BYTES = (size_t)(WK - 1) * WQ * (2 * DB * 16 + 4) * 64 * 4;
+  // merge scratch (reuses the tile buffers): (WK-1)*WQ waves x (QB*DB*16 + 2*QB) floats x 64 lanes
+  static constexpr int PER_WAVE = (QB * DB * 16 + 2 * QB) * 64;
+  static constexpr size_t MERGE_BYTES = (size_t)(WK - 1) * WQ * PER_WAVE * 4;
   static_assert(MERGE_BYTES <= LDS_BYTES, "merge scratch must fit in the tile buffers");
+  static_assert(K_CH >= 1 && V_CH >= 1 && K_CH * NT * 8 == TK * DH && V_CH * NT * 16 == TK * DH,
+                "the tile is copied in whole 16-byte chunks per thread");
 };
 
 // global -> registers: one K/V tile (keys past k_hi are clamped to the last valid key; their scores
 // are masked later)
-template <int DH, int WQ, int KCH, int VCH>
+template <typename T, int DH, int KCH, int VCH>
 __device__ __forceinline__ void load_kv_tile(uint4 (&rk)[KCH], uint4 (&rv)[VCH][2],
                                              const bf16_t *kc, const bf16_t *vc, size_t kv_stride, int k0,
                                              int k_hi, int tid) {
-  using T = ATile<DH, WQ>;
 #pragma unroll
   for (int i = 0; i < T::K_CH; ++i) {
-    const int c = tid + 256 * i;
+    const int c = tid + T::NT * i;
     int key = k0 + c / (DH / 8);
     key = key < k_hi ? key : k_hi - 1;
     rk[i] = *reinterpret_cast<const uint4 *>(kc + (size_t)key * kv_stride + (c % (DH / 8)) * 8);
   }
 #pragma unroll
   for (int i = 0; i < T::V_CH; ++i) {
-    const int u = tid + 256 * i;
+    const int u = tid + T::NT * i;
     const int rest = u / 64;
     const int ch = (u % 4) + 4 * (rest % (DH / 32));
     const int kp = ((u / 4) % 16) + 16 * (rest / (DH / 32));
@@ -81,19 +88,18 @@ __device__ __forceinline__ uint32_t half_of(const uint4 &v, int e) {
 
 // registers -> LDS stage: K rows as they are, V transposed ([dh][key]): element e of two
 // neighbouring keys forms one 32-bit word, so a wave's 64 stores hit 32 banks twice.
-template <int DH, int WQ, int KCH, int VCH>
+template <typename T, int DH, int KCH, int VCH>
 __device__ __forceinline__ void store_kv_tile(const uint4 (&rk)[KCH], const uint4 (&rv)[VCH][2],
                                               bf16_t *stage, int tid) {
-  using T = ATile<DH, WQ>;
   bf16_t *sk = stage, *sv = stage + T::TK * T::KSTR;
 #pragma unroll
   for (int i = 0; i < T::K_CH; ++i) {
-    const int c = tid + 256 * i;
+    const int c = tid + T::NT * i;
     *reinterpret_cast<uint4 *>(sk + (c / (DH / 8)) * T::KSTR + (c % (DH / 8)) * 8) = rk[i];
   }
 #pragma unroll
   for (int i = 0; i < T::V_CH; ++i) {
-    const int u = tid + 256 * i;
+    const int u = tid + T::NT * i;
     const int rest = u / 64;
     const int ch = (u % 4) + 4 * (rest % (DH / 32));
     const int kp = ((u / 4) % 16) + 16 * (rest / (DH / 32));
@@ -104,9 +110,9 @@ __device__ __forceinline__ void store_kv_tile(const uint4 (&rk)[KCH], const uint
   }
 }
 
-template <int DH, int WQ>
-__global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
-  using T = ATile<DH, WQ>;
+template <int DH, int WQ, int NW, int QB>
+__global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
+  using T = ATile<DH, WQ, NW, QB>;
   constexpr int WK = T::WK, BQ = T::BQ, TK = T::TK, KSTR = T::KSTR, VSTR = T::VSTR, DB = T::DB, KK = T::KK;
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t *smem = reinterpret_cast<bf16_t *>(smem_raw);
@@ -128,42 +134,44 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
   const bf16_t *kc = (const bf16_t *)a.k + ((size_t)b * a.L * a.Hkv + kvh) * DH;
   const bf16_t *vc = (const bf16_t *)a.v + ((size_t)b * a.L * a.Hkv + kvh) * DH;
 
-  // query operands: 2 blocks of 32 queries per wave, kept in registers for the whole key sweep
-  bf16x8 qf[2][KK];
+  // query operands: QB blocks of 32 queries per wave, kept in registers for the whole key sweep
+  bf16x8 qf[QB][KK];
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    int r = wq * 64 + qb * 32 + l32;
+  for (int qb = 0; qb < QB; ++qb) {
+    int r = wq * (32 * QB) + qb * 32 + l32;
     r = r < nq ? r : nq - 1;  // rows past the end are clamped; their results are never stored
     const bf16_t *qp = (const bf16_t *)a.q + ((size_t)(j0 + r) * a.H + h) * DH + lhi * 8;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) qf[qb][kk] = *reinterpret_cast<const bf16x8 *>(qp + kk * 16);
   }
 
-  floatx16 acc_o[2][DB];
+  floatx16 acc_o[QB][DB];
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb)
+  for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc_o[qb][db][e] = 0.f;
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+  float m_run[QB], l_run[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
   const float sc = LOG2E / sqrtf((float)DH);  // scores are kept in the log2 domain
 
   uint4 rk[T::K_CH], rv[T::V_CH][2];
   const int n_tiles = (k_hi - k_lo + TK - 1) / TK;
-  load_kv_tile<DH, WQ, T::K_CH, T::V_CH>(rk, rv, kc, vc, kv_stride, k_lo, k_hi, tid);
-  store_kv_tile<DH, WQ, T::K_CH, T::V_CH>(rk, rv, smem, tid);
+  load_kv_tile<T, DH, T::K_CH, T::V_CH>(rk, rv, kc, vc, kv_stride, k_lo, k_hi, tid);
+  store_kv_tile<T, DH, T::K_CH, T::V_CH>(rk, rv, smem, tid);
   __syncthreads();
   for (int t = 0; t < n_tiles; ++t) {
     const int k0 = k_lo + t * TK;
     const bf16_t *stage = smem + (t & 1) * T::STAGE;
     // prefetch the next tile (the last iteration re-reads its own tile: harmless, keeps the loop uniform)
-    load_kv_tile<DH, WQ, T::K_CH, T::V_CH>(rk, rv, kc, vc, kv_stride, t + 1 < n_tiles ? k0 + TK : k0, k_hi, tid);
+    load_kv_tile<T, DH, T::K_CH, T::V_CH>(rk, rv, kc, vc, kv_stride, t + 1 < n_tiles ? k0 + TK : k0, k_hi, tid);
 
     // S^T block of this wave: 32 keys x 64 queries
-    floatx16 s[2];
+    floatx16 s[QB];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+    for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) s[qb][e] = 0.f;
     const bf16_t *skp = stage + (wk * 32 + l32) * KSTR + lhi * 8;
@@ -171,7 +179,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
     for (int kk = 0; kk < KK; ++kk) {
       const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(skp + kk * 16);
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb) s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][kk], s[qb], 0, 0, 0);
+      for (int qb = 0; qb < QB; ++qb) s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][kk], s[qb], 0, 0, 0);
     }
 
     // online softmax per query (= per lane), keys of this wave only.  The running reference m_run is
@@ -180,9 +188,9 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
     // rescale of the output accumulator is skipped for the whole wave.
     const int key_base = k0 + wk * 32 + 4 * lhi;
     const bool tail = k0 + TK > k_hi;  // wave-uniform: only the last tile can hold keys past the end
-    bf16x8 pf[2][2];
+    bf16x8 pf[QB][2];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
       if (tail) {
 #pragma unroll
         for (int e = 0; e < 16; ++e)
@@ -233,38 +241,38 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
         const uint4 av{a0.x, a0.y, a1.x, a1.y};
         const bf16x8 vf = __builtin_bit_cast(bf16x8, av);
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+        for (int qb = 0; qb < QB; ++qb)
           acc_o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][ks], acc_o[qb][db], 0, 0, 0);
       }
 
-    store_kv_tile<DH, WQ, T::K_CH, T::V_CH>(rk, rv, smem + ((t + 1) & 1) * T::STAGE, tid);
+    store_kv_tile<T, DH, T::K_CH, T::V_CH>(rk, rv, smem + ((t + 1) & 1) * T::STAGE, tid);
     __syncthreads();
   }
 
   // merge the WK wave columns of each query block through LDS (tile buffers are free now)
   float *mg = reinterpret_cast<float *>(smem_raw);
-  constexpr int PER_WAVE = (2 * DB * 16 + 4) * 64;
+  constexpr int PER_WAVE = T::PER_WAVE;
   if (WK > 1) {
     if (wk > 0) {
       float *dst = mg + (size_t)((wk - 1) * WQ + wq) * PER_WAVE + lane;
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
+      for (int qb = 0; qb < QB; ++qb) {
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
           for (int e = 0; e < 16; ++e) dst[((qb * DB + db) * 16 + e) * 64] = acc_o[qb][db][e];
-        dst[(2 * DB * 16 + qb) * 64] = m_run[qb];
-        dst[(2 * DB * 16 + 2 + qb) * 64] = l_run[qb];
+        dst[(QB * DB * 16 + qb) * 64] = m_run[qb];
+        dst[(QB * DB * 16 + QB + qb) * 64] = l_run[qb];
       }
     }
     __syncthreads();
     if (wk == 0) {
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
+      for (int qb = 0; qb < QB; ++qb) {
         float M = m_run[qb];
 #pragma unroll
         for (int w = 1; w < WK; ++w)
-          M = fmaxf(M, mg[(size_t)((w - 1) * WQ + wq) * PER_WAVE + (2 * DB * 16 + qb) * 64 + lane]);
+          M = fmaxf(M, mg[(size_t)((w - 1) * WQ + wq) * PER_WAVE + (QB * DB * 16 + qb) * 64 + lane]);
         const float Ms = (M == -INFINITY) ? 0.f : M;
         const float c0 = __builtin_amdgcn_exp2f(m_run[qb] - Ms);
         float lsum = l_run[qb] * c0;
@@ -275,8 +283,8 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
 #pragma unroll
         for (int w = 1; w < WK; ++w) {
           const float *src = mg + (size_t)((w - 1) * WQ + wq) * PER_WAVE + lane;
-          const float cw = __builtin_amdgcn_exp2f(src[(2 * DB * 16 + qb) * 64] - Ms);
-          lsum += src[(2 * DB * 16 + 2 + qb) * 64] * cw;
+          const float cw = __builtin_amdgcn_exp2f(src[(QB * DB * 16 + qb) * 64] - Ms);
+          lsum += src[(QB * DB * 16 + QB + qb) * 64] * cw;
 #pragma unroll
           for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -290,8 +298,8 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
 
   if (wk == 0) {
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      const int r = wq * 64 + qb * 32 + l32;
+    for (int qb = 0; qb < QB; ++qb) {
+      const int r = wq * (32 * QB) + qb * 32 + l32;
       if (r < nq) {
         const int j = j0 + r;
         if (a.splits == 1 && !a.partial) {
@@ -327,26 +335,26 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
   }
 }
 
-template <int DH, int WQ> void launch_cfg(const AttnArgs &a, hipStream_t s) {
-  using T = ATile<DH, WQ>;
+template <int DH, int WQ, int NW, int QB> void launch_cfg(const AttnArgs &a, hipStream_t s) {
+  using T = ATile<DH, WQ, NW, QB>;
   static bool done = false;
   if (!done) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<DH, WQ>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<DH, WQ, NW, QB>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::LDS_BYTES);
     done = true;
   }
   dim3 grid(max_q_tiles(a, T::BQ), a.H, a.splits);
-  k_attn_bf16<DH, WQ><<<grid, 256, T::LDS_BYTES, s>>>(a);
+  k_attn_bf16<DH, WQ, NW, QB><<<grid, T::NT, T::LDS_BYTES, s>>>(a);
 }
 
 }  // namespace
 
 void launch_attention_bf16(const AttnArgs &a, hipStream_t s) {
-  const bool wide = a.bq == 128;
+  const bool wide = a.bq == 128;  // 128 or 64 query rows per workgroup
   if (a.dh == 128) {
-    if (wide) launch_cfg<128, 2>(a, s); else launch_cfg<128, 1>(a, s);
+    if (wide) launch_cfg<128, 4, 8, 1>(a, s); else launch_cfg<128, 2, 8, 1>(a, s);
   } else {
-    if (wide) launch_cfg<64, 2>(a, s); else launch_cfg<64, 1>(a, s);
+    if (wide) launch_cfg<64, 2, 4, 2>(a, s); else launch_cfg<64, 1, 4, 2>(a, s);
   }
 }
 
