@@ -335,6 +335,269 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
   }
 }
 
+// ---- head_dim 128: K and V tiles by asynchronous global -> LDS copies -----------------------------
+// No register staging: NS LDS stages, so a tile has NS - 1 tile computations to arrive from HBM.
+// Both tiles keep the cache layout [key][dh] (256-byte rows, written 4 rows per copy instruction).
+//   K rows feed S^T = K Q^T directly (16-byte reads); the 16-byte chunk c of row r sits at chunk
+//     position c ^ (r % 16), so the 16 rows a read serves at a time cover all 64 banks once.
+//   V^T operands come from the LDS transpose read (ds_read_b64_tr_b16): within 16 lanes, lane j
+//     names the 8 bytes of row key0 + j/4 at columns dh0 + 4*(j%4) .. +3 and lane i receives column
+//     dh0 + i of the rows key0 .. key0+3 -- four consecutive keys of one dh, which is exactly one half
+//     of the operand in the key order the P^T registers have.  The 32-byte pair p of row r sits at
+//     pair position p ^ (r % 8): the 4 rows x 64 bytes that 32 lanes read hit every bank once.
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+
+template <int WQ> struct DTile {
+  static constexpr int DH = 128, NW = 8, NT = 64 * NW;
+  static constexpr int WK = NW / WQ;      // wave columns over the keys of a tile
+  static constexpr int BQ = 32 * WQ;      // query rows per workgroup
+  static constexpr int TK = 32 * WK;      // keys per tile
+  static constexpr int ROWB = DH * 2;     // bytes per key row
+  static constexpr int REGION = TK * ROWB;          // K rows, then V rows
+  static constexpr int STAGE_BYTES = 2 * REGION;
+  static constexpr int NS = (128 * 1024) / STAGE_BYTES;  // LDS stages
+  static constexpr int LPW = 2 * (TK / 4) / NW;          // copy instructions per wave and tile
+  static constexpr int DB = DH / 32, KK = DH / 16;
+  static constexpr int PER_WAVE = (DB * 16 + 2) * 64;    // merge scratch per wave (floats)
+  static constexpr size_t LDS_BYTES = (size_t)NS * STAGE_BYTES;
+  static_assert(NS >= 2 && (NS - 2) * LPW < 64, "stages and vmcnt immediate");
+  static_assert((size_t)(WK - 1) * WQ * PER_WAVE * 4 <= LDS_BYTES, "merge scratch must fit in the tile buffers");
+};
+
+template <int WQ>
+__global__ __launch_bounds__(512) void k_attn_bf16_dma(AttnArgs a) {
+  using T = DTile<WQ>;
+  constexpr int DH = T::DH, NW = T::NW, WK = T::WK, BQ = T::BQ, TK = T::TK, ROWB = T::ROWB, NS = T::NS,
+                DB = T::DB, KK = T::KK, LPW = T::LPW;
+  extern __shared__ __align__(1024) unsigned char smem_raw[];
+  __shared__ int tile_info[3];
+
+  const int tid = threadIdx.x, lane = tid % WAVE;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
+  const int l32 = lane % 32, lhi = lane / 32;
+  const int wq = wave / WK, wk = wave % WK;
+  if (tid == 0) find_tile(a, BQ, blockIdx.x, tile_info);
+  __syncthreads();
+  const int b = tile_info[0];
+  if (b < 0) return;  // uniform: no such tile
+  const int j0 = tile_info[1], nq = tile_info[2];
+  const int h = blockIdx.y, kvh = h / (a.H / a.Hkv), split = blockIdx.z;
+  const int k_lo = split * a.chunk, k_hi = min(a.L, k_lo + a.chunk);
+  if (k_lo >= k_hi) return;  // uniform
+
+  const size_t kv_stride = (size_t)a.Hkv * DH;
+  const bf16_t *kc = (const bf16_t *)a.k + ((size_t)b * a.L * a.Hkv + kvh) * DH;
+  const bf16_t *vc = (const bf16_t *)a.v + ((size_t)b * a.L * a.Hkv + kvh) * DH;
+
+  // query operand: the wave's 32 queries, in registers for the whole key sweep
+  bf16x8 qf[KK];
+  {
+    int r = wq * 32 + l32;
+    r = r < nq ? r : nq - 1;  // rows past the end are clamped; their results are never stored
+    const bf16_t *qp = (const bf16_t *)a.q + ((size_t)(j0 + r) * a.H + h) * DH + lhi * 8;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8 *>(qp + kk * 16);
+  }
+  floatx16 acc_o[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc_o[db][e] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float sc = LOG2E / sqrtf((float)DH);  // scores are kept in the log2 domain
+
+  const uint32_t lds0 = lds_offset_of(smem_raw);
+  const int n_tiles = (k_hi - k_lo + TK - 1) / TK;
+  // copy mapping: an instruction fills 4 key rows; this lane holds chunk position cpos of row r4
+  const int r4 = lane / 16, cpos = lane % 16;
+  auto issue = [&](int t) {  // tile t -> stage t % NS (keys past k_hi re-read the last key; masked later)
+    const uint32_t sb = lds0 + (uint32_t)(t % NS) * T::STAGE_BYTES;
+    const int kbase = k_lo + t * TK;
+#pragma unroll
+    for (int i = 0; i < LPW / 2; ++i) {
+      const int ii = i * NW + wave;  // rows 4*ii .. 4*ii+3 of the tile
+      const int row = ii * 4 + r4;
+      int key = kbase + row;
+      key = key < k_hi ? key : k_hi - 1;
+      const int ck = cpos ^ (row & 15);
+      const int cv = (((cpos >> 1) ^ (row & 7)) << 1) | (cpos & 1);
+      dma16(kc + (size_t)key * kv_stride + ck * 8, sb + (uint32_t)ii * 1024u);
+      dma16(vc + (size_t)key * kv_stride + cv * 8, sb + (uint32_t)T::REGION + (uint32_t)ii * 1024u);
+    }
+  };
+
+  // per-lane constants of the operand reads
+  const int krow = wk * 32 + l32, ksw = l32 & 15;
+  const int vq = (lane % 16) / 4;                       // row of this lane inside a 4-key group
+  const int vrow = wk * 32 + 4 * lhi + vq, vsw = (4 * lhi + vq) & 7, hb = (lane / 16) & 1;
+  const int key_lane = wk * 32 + 4 * lhi;
+
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < n_tiles) issue(s);
+
+  for (int t = 0; t < n_tiles; ++t) {
+    if (t + NS - 2 < n_tiles) wait_vmcnt<(NS - 2) * LPW>();  // tile t has landed (this wave's part)
+    else wait_vmcnt<0>();
+    __syncthreads();  // ... all waves' parts; and everyone is done with tile t-1
+    if (t + NS - 1 < n_tiles) issue(t + NS - 1);  // into the stage tile t-1 occupied
+    const unsigned char *st = smem_raw + (size_t)(t % NS) * T::STAGE_BYTES;
+    const int k0 = k_lo + t * TK;
+
+    // S^T block of this wave: 32 keys x 32 queries
+    floatx16 s;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s[e] = 0.f;
+    const unsigned char *skp = st + krow * ROWB;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(skp + (((2 * kk + lhi) ^ ksw) * 16));
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
+    }
+
+    // online softmax per query (= per lane), keys of this wave only; lazily moved reference
+    const int key_base = k0 + key_lane;
+    if (k0 + TK > k_hi) {  // wave-uniform: only the last tile can hold keys past the end
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (key_base + 8 * (e / 4) + (e % 4) >= k_hi) s[e] = -INFINITY;
+    }
+    float mx = s[0];
+#pragma unroll
+    for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s[e]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE)) * sc;
+    const bool need = mx > m_run + 8.0f;
+    if (__any(need)) {
+      const float corr = need ? __builtin_amdgcn_exp2f(m_run - mx) : 1.0f;
+      m_run = need ? mx : m_run;
+      l_run *= corr;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc_o[db][e] *= corr;
+    }
+    const float neg_ref = (m_run == -INFINITY) ? 0.f : -m_run;
+    float ps = 0.f;
+    uint32_t pw[8];
+#pragma unroll
+    for (int e = 0; e < 16; e += 2) {
+      const float p0 = __builtin_amdgcn_exp2f(fmaf(s[e], sc, neg_ref));
+      const float p1 = __builtin_amdgcn_exp2f(fmaf(s[e + 1], sc, neg_ref));
+      // the sum uses the rounded values that enter the matrix product
+      const uint32_t w = pack_bf16(p0, p1);
+      ps += __uint_as_float(w << 16) + __uint_as_float(w & 0xffff0000u);
+      pw[e >> 1] = w;
+    }
+    ps += __shfl_xor(ps, 32, WAVE);
+    l_run += ps;
+    bf16x8 pf[2];
+    {
+      const uint4 v0{pw[0], pw[1], pw[2], pw[3]}, v1{pw[4], pw[5], pw[6], pw[7]};
+      pf[0] = __builtin_bit_cast(bf16x8, v0);
+      pf[1] = __builtin_bit_cast(bf16x8, v1);
+    }
+
+    // O^T += V^T P^T over the wave's 32 keys
+    const unsigned char *svp = st + T::REGION + vrow * ROWB + 8 * (lane % 4);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const unsigned char *p = svp + ks * 16 * ROWB + (((db * 2 + hb) ^ vsw) * 32);
+        typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
+        const shortx4 g0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(p));
+        const shortx4 g1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(p + 8 * ROWB));
+        typedef short shortx8 __attribute__((ext_vector_type(8)));
+        const shortx8 av = __builtin_shufflevector(g0, g1, 0, 1, 2, 3, 4, 5, 6, 7);
+        const bf16x8 vf = __builtin_bit_cast(bf16x8, av);
+        acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ks], acc_o[db], 0, 0, 0);
+      }
+  }
+  __syncthreads();  // every wave is done with the last tile: the stages become merge scratch
+
+  // merge the WK wave columns of each query block through LDS
+  float *mg = reinterpret_cast<float *>(smem_raw);
+  constexpr int PER_WAVE = T::PER_WAVE;
+  if (wk > 0) {
+    float *dst = mg + (size_t)((wk - 1) * WQ + wq) * PER_WAVE + lane;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) dst[(db * 16 + e) * 64] = acc_o[db][e];
+    dst[(DB * 16) * 64] = m_run;
+    dst[(DB * 16 + 1) * 64] = l_run;
+  }
+  __syncthreads();
+  if (wk != 0) return;
+  {
+    float M = m_run;
+#pragma unroll
+    for (int w = 1; w < WK; ++w) M = fmaxf(M, mg[(size_t)((w - 1) * WQ + wq) * PER_WAVE + (DB * 16) * 64 + lane]);
+    const float Ms = (M == -INFINITY) ? 0.f : M;
+    const float c0 = __builtin_amdgcn_exp2f(m_run - Ms);
+    float lsum = l_run * c0;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc_o[db][e] *= c0;
+#pragma unroll
+    for (int w = 1; w < WK; ++w) {
+      const float *src = mg + (size_t)((w - 1) * WQ + wq) * PER_WAVE + lane;
+      const float cw = __builtin_amdgcn_exp2f(src[(DB * 16) * 64] - Ms);
+      lsum += src[(DB * 16 + 1) * 64] * cw;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc_o[db][e] += src[(db * 16 + e) * 64] * cw;
+    }
+    m_run = M;
+    l_run = lsum;
+  }
+
+  const int r = wq * 32 + l32;
+  if (r >= nq) return;
+  const int j = j0 + r;
+  if (a.splits == 1 && !a.partial) {
+    bf16_t *out = (bf16_t *)a.out + ((size_t)j * a.H + h) * DH + 4 * lhi;
+    const float inv = 1.0f / l_run;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        uint2 w;
+        w.x = pack_bf16(acc_o[db][4 * g] * inv, acc_o[db][4 * g + 1] * inv);
+        w.y = pack_bf16(acc_o[db][4 * g + 2] * inv, acc_o[db][4 * g + 3] * inv);
+        *reinterpret_cast<uint2 *>(out + db * 32 + 8 * g) = w;
+      }
+  } else {
+    float *po = a.part_o + (((size_t)split * a.rows.cap + j) * a.H + h) * DH + 4 * lhi;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 w{acc_o[db][4 * g], acc_o[db][4 * g + 1], acc_o[db][4 * g + 2], acc_o[db][4 * g + 3]};
+        *reinterpret_cast<float4 *>(po + db * 32 + 8 * g) = w;
+      }
+    if (lhi == 0) {
+      float *ml = a.part_ml + (((size_t)split * a.rows.cap + j) * a.H + h) * 2;
+      ml[0] = m_run * LN2;  // partials carry the maximum in natural-log units
+      ml[1] = l_run;
+    }
+  }
+}
+
+template <int WQ> void launch_dma(const AttnArgs &a, hipStream_t s) {
+  using T = DTile<WQ>;
+  static bool done = false;
+  if (!done) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16_dma<WQ>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::LDS_BYTES);
+    done = true;
+  }
+  dim3 grid(max_q_tiles(a, T::BQ), a.H, a.splits);
+  k_attn_bf16_dma<WQ><<<grid, T::NT, T::LDS_BYTES, s>>>(a);
+}
+
 template <int DH, int WQ, int NW, int QB> void launch_cfg(const AttnArgs &a, hipStream_t s) {
   using T = ATile<DH, WQ, NW, QB>;
   static bool done = false;
@@ -352,7 +615,7 @@ template <int DH, int WQ, int NW, int QB> void launch_cfg(const AttnArgs &a, hip
 void launch_attention_bf16(const AttnArgs &a, hipStream_t s) {
   const bool wide = a.bq == 128;  // 128 or 64 query rows per workgroup
   if (a.dh == 128) {
-    if (wide) launch_cfg<128, 4, 8, 1>(a, s); else launch_cfg<128, 2, 8, 1>(a, s);
+    if (wide) launch_dma<4>(a, s); else launch_dma<2>(a, s);
   } else {
     if (wide) launch_cfg<64, 2, 4, 2>(a, s); else launch_cfg<64, 1, 4, 2>(a, s);
   }

@@ -98,4 +98,21 @@ __device__ __forceinline__ void block_sum3(float &a, float &b, float &c, float *
   for (int i = 0; i < NT / WAVE; ++i) { a += red[3 * i]; b += red[3 * i + 1]; c += red[3 * i + 2]; }
 }
 
+// Asynchronous global -> LDS copy: lane i moves the 16 bytes at its own global address g to
+// LDS[lds_base + 16*i]; lds_base is wave-uniform.  Completion is tracked by vmcnt.
+__device__ __forceinline__ void dma16(const void *g, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :
+               : "s"(lds_base), "v"(g)
+               : "memory", "m0");
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_offset_of(const void *p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+
 }  // namespace dy

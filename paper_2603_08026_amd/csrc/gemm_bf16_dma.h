@@ -63,22 +63,6 @@ struct SplitStore {  // part != nullptr: raw fp32 tile part[z][j][n] instead of 
   int N;
 };
 
-// lane i: 16 bytes from its global address g -> LDS[lds_base + 16*i]; lds_base is wave-uniform.
-__device__ __forceinline__ void dma16(const void *g, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-               :
-               : "s"(lds_base), "v"(g)
-               : "memory", "m0");
-}
-
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-
-__device__ __forceinline__ uint32_t lds_offset_of(const void *p) {
-  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
-}
-
 template <typename SH, typename Epi>
 __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__ A,
                                                    const int32_t *__restrict__ gather, int lda,
