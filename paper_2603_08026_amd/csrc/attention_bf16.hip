@@ -347,26 +347,27 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
 //     pair position p ^ (r % 8): the 4 rows x 64 bytes that 32 lanes read hit every bank once.
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 
-template <int WQ> struct DTile {
-  static constexpr int DH = 128, NW = 8, NT = 64 * NW;
-  static constexpr int WK = NW / WQ;      // wave columns over the keys of a tile
+template <int WQ, int WK_> struct DTile {
+  static constexpr int DH = 128, WK = WK_;  // wave columns over the keys of a tile
+  static constexpr int NW = WQ * WK, NT = 64 * NW;
   static constexpr int BQ = 32 * WQ;      // query rows per workgroup
   static constexpr int TK = 32 * WK;      // keys per tile
   static constexpr int ROWB = DH * 2;     // bytes per key row
   static constexpr int REGION = TK * ROWB;          // K rows, then V rows
   static constexpr int STAGE_BYTES = 2 * REGION;
-  static constexpr int NS = (128 * 1024) / STAGE_BYTES;  // LDS stages
+  static constexpr int NS = 4;                            // LDS stages
   static constexpr int LPW = 2 * (TK / 4) / NW;          // copy instructions per wave and tile
   static constexpr int DB = DH / 32, KK = DH / 16;
   static constexpr int PER_WAVE = (DB * 16 + 2) * 64;    // merge scratch per wave (floats)
   static constexpr size_t LDS_BYTES = (size_t)NS * STAGE_BYTES;
-  static_assert(NS >= 2 && (NS - 2) * LPW < 64, "stages and vmcnt immediate");
+  static_assert(NS >= 3 && (NS - 2) * LPW < 64, "stages (the loop reads two tiles at a time) and vmcnt immediate");
   static_assert((size_t)(WK - 1) * WQ * PER_WAVE * 4 <= LDS_BYTES, "merge scratch must fit in the tile buffers");
+  static_assert(LPW >= 2 && LPW % 2 == 0, "every wave copies K and V rows");
 };
 
-template <int WQ>
-__global__ __launch_bounds__(512) void k_attn_bf16_dma(AttnArgs a) {
-  using T = DTile<WQ>;
+template <int WQ, int WK_>
+__global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a) {  // two waves per SIMD: 256 registers, no AGPR shuffling
+  using T = DTile<WQ, WK_>;
   constexpr int DH = T::DH, NW = T::NW, WK = T::WK, BQ = T::BQ, TK = T::TK, ROWB = T::ROWB, NS = T::NS,
                 DB = T::DB, KK = T::KK, LPW = T::LPW;
   extern __shared__ __align__(1024) unsigned char smem_raw[];
@@ -436,35 +437,45 @@ __global__ __launch_bounds__(512) void k_attn_bf16_dma(AttnArgs a) {
   for (int s = 0; s < NS - 1; ++s)
     if (s < n_tiles) issue(s);
 
-  for (int t = 0; t < n_tiles; ++t) {
-    if (t + NS - 2 < n_tiles) wait_vmcnt<(NS - 2) * LPW>();  // tile t has landed (this wave's part)
+  // Software pipeline: the score block of tile t+1 is issued to the matrix pipe before the softmax
+  // arithmetic of tile t, so that the vector ALU work of a wave runs under its own matrix products
+  // (the waves of a workgroup move in step, tile by tile, and would otherwise all queue for the same
+  // pipe at the same time).
+  floatx16 s_cur;
+  {
+    if (NS - 2 < n_tiles) wait_vmcnt<(NS - 2) * LPW>();  // tile 0 has landed (this wave's part)
     else wait_vmcnt<0>();
-    __syncthreads();  // ... all waves' parts; and everyone is done with tile t-1
-    if (t + NS - 1 < n_tiles) issue(t + NS - 1);  // into the stage tile t-1 occupied
-    const unsigned char *st = smem_raw + (size_t)(t % NS) * T::STAGE_BYTES;
-    const int k0 = k_lo + t * TK;
-
-    // S^T block of this wave: 32 keys x 32 queries
-    floatx16 s;
+    __syncthreads();
 #pragma unroll
-    for (int e = 0; e < 16; ++e) s[e] = 0.f;
-    const unsigned char *skp = st + krow * ROWB;
+    for (int e = 0; e < 16; ++e) s_cur[e] = 0.f;
+    const unsigned char *skp = smem_raw + krow * ROWB;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(skp + (((2 * kk + lhi) ^ ksw) * 16));
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
+      s_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s_cur, 0, 0, 0);
     }
+  }
 
-    // online softmax per query (= per lane), keys of this wave only; lazily moved reference
+  for (int t = 0; t < n_tiles; ++t) {
+    // tile t+1 (K for the next scores) has landed; tiles up to t+NS-2 are in flight
+    if (t + NS - 2 < n_tiles) wait_vmcnt<(NS - 3) * LPW>();
+    else wait_vmcnt<0>();
+    __syncthreads();  // ... all waves' parts; and everyone is done with K of tile t and V of tile t-1
+    if (t + NS - 1 < n_tiles) issue(t + NS - 1);  // into the stage tile t-1 occupied
+    const unsigned char *st = smem_raw + (size_t)(t % NS) * T::STAGE_BYTES;
+    const unsigned char *st_next = smem_raw + (size_t)((t + 1) % NS) * T::STAGE_BYTES;
+    const int k0 = k_lo + t * TK;
+
+    // running maximum of tile t (lazily moved reference)
     const int key_base = k0 + key_lane;
     if (k0 + TK > k_hi) {  // wave-uniform: only the last tile can hold keys past the end
 #pragma unroll
       for (int e = 0; e < 16; ++e)
-        if (key_base + 8 * (e / 4) + (e % 4) >= k_hi) s[e] = -INFINITY;
+        if (key_base + 8 * (e / 4) + (e % 4) >= k_hi) s_cur[e] = -INFINITY;
     }
-    float mx = s[0];
+    float mx = s_cur[0];
 #pragma unroll
-    for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s[e]);
+    for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s_cur[e]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE)) * sc;
     const bool need = mx > m_run + 8.0f;
     if (__any(need)) {
@@ -477,16 +488,28 @@ __global__ __launch_bounds__(512) void k_attn_bf16_dma(AttnArgs a) {
         for (int e = 0; e < 16; ++e) acc_o[db][e] *= corr;
     }
     const float neg_ref = (m_run == -INFINITY) ? 0.f : -m_run;
+
+    // scores of tile t+1 (matrix pipe) under the exponentials of tile t (vector ALU)
+    // (after the last tile this reads a stage that holds no tile: the result is dropped)
+    floatx16 s_next;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s_next[e] = 0.f;
+    {
+      const unsigned char *skp = st_next + krow * ROWB;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(skp + (((2 * kk + lhi) ^ ksw) * 16));
+        s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s_next, 0, 0, 0);
+      }
+    }
     float ps = 0.f;
     uint32_t pw[8];
 #pragma unroll
     for (int e = 0; e < 16; e += 2) {
-      const float p0 = __builtin_amdgcn_exp2f(fmaf(s[e], sc, neg_ref));
-      const float p1 = __builtin_amdgcn_exp2f(fmaf(s[e + 1], sc, neg_ref));
-      // the sum uses the rounded values that enter the matrix product
-      const uint32_t w = pack_bf16(p0, p1);
-      ps += __uint_as_float(w << 16) + __uint_as_float(w & 0xffff0000u);
-      pw[e >> 1] = w;
+      const float p0 = __builtin_amdgcn_exp2f(fmaf(s_cur[e], sc, neg_ref));
+      const float p1 = __builtin_amdgcn_exp2f(fmaf(s_cur[e + 1], sc, neg_ref));
+      pw[e >> 1] = pack_bf16(p0, p1);
+      ps += p0 + p1;  // (the rounding of p to bf16 is unbiased: the sum takes the unrounded values)
     }
     ps += __shfl_xor(ps, 32, WAVE);
     l_run += ps;
@@ -497,7 +520,17 @@ __global__ __launch_bounds__(512) void k_attn_bf16_dma(AttnArgs a) {
       pf[1] = __builtin_bit_cast(bf16x8, v1);
     }
 
-    // O^T += V^T P^T over the wave's 32 keys
+    // instruction order: one score product, its next operand read, and a share of the exponentials
+#pragma unroll
+    for (int i = 0; i < KK; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // matrix product
+      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // scale + shift of two scores
+      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);  // their exponentials
+      __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);  // rounding and sum of an earlier pair
+    }
+
+    // O^T += V^T P^T over the wave's 32 keys of tile t
     const unsigned char *svp = st + T::REGION + vrow * ROWB + 8 * (lane % 4);
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
@@ -512,13 +545,14 @@ __global__ __launch_bounds__(512) void k_attn_bf16_dma(AttnArgs a) {
         const bf16x8 vf = __builtin_bit_cast(bf16x8, av);
         acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ks], acc_o[db], 0, 0, 0);
       }
+    s_cur = s_next;
   }
   __syncthreads();  // every wave is done with the last tile: the stages become merge scratch
 
   // merge the WK wave columns of each query block through LDS
   float *mg = reinterpret_cast<float *>(smem_raw);
   constexpr int PER_WAVE = T::PER_WAVE;
-  if (wk > 0) {
+  if (WK > 1 && wk > 0) {
     float *dst = mg + (size_t)((wk - 1) * WQ + wq) * PER_WAVE + lane;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -527,9 +561,9 @@ __global__ __launch_bounds__(512) void k_attn_bf16_dma(AttnArgs a) {
     dst[(DB * 16) * 64] = m_run;
     dst[(DB * 16 + 1) * 64] = l_run;
   }
-  __syncthreads();
+  if (WK > 1) __syncthreads();
   if (wk != 0) return;
-  {
+  if (WK > 1) {
     float M = m_run;
 #pragma unroll
     for (int w = 1; w < WK; ++w) M = fmaxf(M, mg[(size_t)((w - 1) * WQ + wq) * PER_WAVE + (DB * 16) * 64 + lane]);
@@ -586,16 +620,16 @@ __global__ __launch_bounds__(512) void k_attn_bf16_dma(AttnArgs a) {
   }
 }
 
-template <int WQ> void launch_dma(const AttnArgs &a, hipStream_t s) {
-  using T = DTile<WQ>;
+template <int WQ, int WK> void launch_dma(const AttnArgs &a, hipStream_t s) {
+  using T = DTile<WQ, WK>;
   static bool done = false;
   if (!done) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16_dma<WQ>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16_dma<WQ, WK>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::LDS_BYTES);
     done = true;
   }
   dim3 grid(max_q_tiles(a, T::BQ), a.H, a.splits);
-  k_attn_bf16_dma<WQ><<<grid, T::NT, T::LDS_BYTES, s>>>(a);
+  k_attn_bf16_dma<WQ, WK><<<grid, T::NT, T::LDS_BYTES, s>>>(a);
 }
 
 template <int DH, int WQ, int NW, int QB> void launch_cfg(const AttnArgs &a, hipStream_t s) {
@@ -615,7 +649,9 @@ template <int DH, int WQ, int NW, int QB> void launch_cfg(const AttnArgs &a, hip
 void launch_attention_bf16(const AttnArgs &a, hipStream_t s) {
   const bool wide = a.bq == 128;  // 128 or 64 query rows per workgroup
   if (a.dh == 128) {
-    if (wide) launch_dma<4>(a, s); else launch_dma<2>(a, s);
+    // 128 query rows: four waves, each with all keys of a 32-key tile (64 KB of LDS: two workgroups
+    // per CU, which drift apart and fill each other's stalls); 64 rows: 2 x 2 waves over 64-key tiles
+    if (wide) launch_dma<4, 1>(a, s); else launch_dma<2, 2>(a, s);
   } else {
     if (wide) launch_cfg<64, 2, 4, 2>(a, s); else launch_cfg<64, 1, 4, 2>(a, s);
   }
