@@ -6,36 +6,49 @@ namespace dy {
 
 namespace {
 
-// One workgroup per query row, a thread per 4 neighbouring columns (all of one head).  For every
-// head: M = max_s m_s, l = sum_s l_s e^{m_s - M}, out = sum_s o_s e^{m_s - M} / l  (the usual merge
-// of online-softmax partials).
-__device__ __forceinline__ float4 merge_splits(const AttnArgs &a, int j, int c, int D) {
+// One workgroup per query row, a thread per 16 bytes of the row in the storage type (V = 4 or 8
+// neighbouring columns, all of one head).  For every head: M = max_s m_s, l = sum_s l_s e^{m_s - M},
+// out = sum_s o_s e^{m_s - M} / l  (the usual merge of online-softmax partials).
+template <int V>
+__device__ __forceinline__ void merge_splits(const AttnArgs &a, int j, int c, int D, float (&out)[V]) {
   const int h = c / a.dh;
   float M = -INFINITY;
   for (int s = 0; s < a.splits; ++s) M = fmaxf(M, a.part_ml[(((size_t)s * a.rows.cap + j) * a.H + h) * 2]);
   float l = 0.f;
-  float4 acc{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int e = 0; e < V; ++e) out[e] = 0.f;
   for (int s = 0; s < a.splits; ++s) {
     const float2 ml = *reinterpret_cast<const float2 *>(a.part_ml + (((size_t)s * a.rows.cap + j) * a.H + h) * 2);
     const float w = __expf(ml.x - M);
-    const float4 o = *reinterpret_cast<const float4 *>(a.part_o + ((size_t)s * a.rows.cap + j) * D + c);
+    const float4 *po = reinterpret_cast<const float4 *>(a.part_o + ((size_t)s * a.rows.cap + j) * D + c);
     l += ml.y * w;
-    acc.x += o.x * w; acc.y += o.y * w; acc.z += o.z * w; acc.w += o.w * w;
+#pragma unroll
+    for (int q = 0; q < V / 4; ++q) {
+      const float4 o = po[q];
+      out[4 * q] += o.x * w; out[4 * q + 1] += o.y * w; out[4 * q + 2] += o.z * w; out[4 * q + 3] += o.w * w;
+    }
   }
   const float inv = 1.0f / l;
-  return float4{acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv};
+#pragma unroll
+  for (int e = 0; e < V; ++e) out[e] *= inv;
 }
 
+constexpr int FIN_NT = 512;  // threads of the merge kernels
+
 template <typename T>
-__global__ __launch_bounds__(1024) void k_attn_combine(AttnArgs a) {
+__global__ __launch_bounds__(FIN_NT) void k_attn_combine(AttnArgs a) {
+  constexpr int V = Vec16<T>::N;
   const int n = a.rows.count ? min(*a.rows.count, a.rows.cap) : a.rows.cap;
   const int D = a.H * a.dh;
   for (int j = blockIdx.x; j < n; j += gridDim.x) {
     T *orow = (T *)a.out + (size_t)j * D;
-    for (int c = threadIdx.x * 4; c < D; c += 4096) {
-      const float4 o = merge_splits(a, j, c, D);
-      orow[c] = from_f<T>(o.x); orow[c + 1] = from_f<T>(o.y);
-      orow[c + 2] = from_f<T>(o.z); orow[c + 3] = from_f<T>(o.w);
+    for (int c = threadIdx.x * V; c < D; c += FIN_NT * V) {
+      float o[V];
+      merge_splits<V>(a, j, c, D, o);
+      Vec16<T> v;
+#pragma unroll
+      for (int e = 0; e < V; ++e) v.set(e, o[e]);
+      st16(orow + c, v);
     }
   }
 }
@@ -52,11 +65,12 @@ struct CompactOut {
 };
 
 template <typename T>
-__global__ __launch_bounds__(1024) void k_attn_finalize(AttnArgs a, T *c_cache, float tau,
-                                                        float *__restrict__ cos_out, uint8_t *flag_out,
-                                                        CompactOut co) {
-  __shared__ float red[3 * 1024 / WAVE];
-  __shared__ int wave_cnt[CB / WAVE];
+__global__ __launch_bounds__(FIN_NT) void k_attn_finalize(AttnArgs a, T *c_cache, float tau,
+                                                          float *__restrict__ cos_out, uint8_t *flag_out,
+                                                          CompactOut co) {
+  constexpr int V = Vec16<T>::N;
+  __shared__ float red[3 * FIN_NT / WAVE];
+  __shared__ int wave_cnt[FIN_NT / WAVE];
   __shared__ int is_last;
   const int n = a.rows.count ? min(*a.rows.count, a.rows.cap) : a.rows.cap;
   const int D = a.H * a.dh;
@@ -64,34 +78,42 @@ __global__ __launch_bounds__(1024) void k_attn_finalize(AttnArgs a, T *c_cache, 
     const int r = a.rows.idx ? a.rows.idx[j] : j;
     T *crow = c_cache + (size_t)r * D;
     float dot = 0.f, na = 0.f, nb = 0.f;
-    for (int c = threadIdx.x * 4; c < D; c += 4096) {
-      const float4 o = merge_splits(a, j, c, D);
-      const T n0 = from_f<T>(o.x), n1 = from_f<T>(o.y), n2 = from_f<T>(o.z), n3 = from_f<T>(o.w);
-      const float f0 = to_f<T>(n0), f1 = to_f<T>(n1), f2 = to_f<T>(n2), f3 = to_f<T>(n3);
-      const float b0 = to_f<T>(crow[c]), b1 = to_f<T>(crow[c + 1]), b2 = to_f<T>(crow[c + 2]), b3 = to_f<T>(crow[c + 3]);
-      dot += f0 * b0 + f1 * b1 + f2 * b2 + f3 * b3;
-      na += f0 * f0 + f1 * f1 + f2 * f2 + f3 * f3;
-      nb += b0 * b0 + b1 * b1 + b2 * b2 + b3 * b3;
-      crow[c] = n0; crow[c + 1] = n1; crow[c + 2] = n2; crow[c + 3] = n3;
+    for (int c = threadIdx.x * V; c < D; c += FIN_NT * V) {
+      float o[V];
+      merge_splits<V>(a, j, c, D, o);
+      const Vec16<T> old = ld16(crow + c);
+      Vec16<T> nw;
+#pragma unroll
+      for (int e = 0; e < V; ++e) nw.set(e, o[e]);
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        const float f = nw.get(e), b = old.get(e);  // the stored (rounded) values
+        dot += f * b;
+        na += f * f;
+        nb += b * b;
+      }
+      st16(crow + c, nw);
     }
-    block_sum3<1024>(dot, na, nb, red);
+    block_sum3<FIN_NT>(dot, na, nb, red);
     if (threadIdx.x == 0) {
       const float s = dot / (fmaxf(sqrtf(na), 1e-8f) * fmaxf(sqrtf(nb), 1e-8f));
       if (cos_out) cos_out[j] = s;
-      flag_out[j] = (s < tau) ? 1 : 0;
+      // device-scope store: written through, so that the compacting workgroup sees it without any
+      // cache flush (a release fence per workgroup would write back the whole L2 each time)
+      __hip_atomic_store(flag_out + j, (uint8_t)((s < tau) ? 1 : 0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
   // flags of this workgroup are out (thread 0 wrote them); count finished workgroups
   if (threadIdx.x == 0) {
-    __threadfence();
-    const int done = atomicAdd(co.counter, 1);
+    wait_vmcnt<0>();  // the flag stores have been acknowledged
+    const int done = __hip_atomic_fetch_add(co.counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     is_last = (done == (int)gridDim.x - 1);
-    if (is_last) *co.counter = 0;  // ready for the next launch on the stream
+    if (is_last)  // ready for the next launch on the stream
+      __hip_atomic_store(co.counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();
   if (is_last) {
-    __threadfence();
-    compact_block(flag_out, a.rows, n, co.B, co.L, co.idx, co.off, co.cap, co.status, co.overflow_code,
+    compact_block<FIN_NT>(flag_out, a.rows, n, co.B, co.L, co.idx, co.off, co.cap, co.status, co.overflow_code,
                   true, wave_cnt);
   }
 }
@@ -101,8 +123,8 @@ __global__ __launch_bounds__(1024) void k_attn_finalize(AttnArgs a, T *c_cache, 
 void launch_attn_combine(DType t, const AttnArgs &a, hipStream_t s) {
   int grid = a.rows.cap > 8192 ? 8192 : a.rows.cap;
   if (grid < 1) return;
-  if (t == F32) k_attn_combine<float><<<grid, 1024, 0, s>>>(a);
-  else k_attn_combine<bf16_t><<<grid, 1024, 0, s>>>(a);
+  if (t == F32) k_attn_combine<float><<<grid, FIN_NT, 0, s>>>(a);
+  else k_attn_combine<bf16_t><<<grid, FIN_NT, 0, s>>>(a);
 }
 
 void launch_attn_finalize(DType t, const AttnArgs &a, void *c_cache, float tau, float *cos_out,
@@ -113,9 +135,9 @@ void launch_attn_finalize(DType t, const AttnArgs &a, void *c_cache, float tau, 
   if (grid < 1) grid = 1;
   CompactOut co{out_idx, out_offsets, status, counter, out_cap, a.B, a.L, -6};
   if (t == F32)
-    k_attn_finalize<float><<<grid, 1024, 0, s>>>(a, (float *)c_cache, tau, cos_out, flag_out, co);
+    k_attn_finalize<float><<<grid, FIN_NT, 0, s>>>(a, (float *)c_cache, tau, cos_out, flag_out, co);
   else
-    k_attn_finalize<bf16_t><<<grid, 1024, 0, s>>>(a, (bf16_t *)c_cache, tau, cos_out, flag_out, co);
+    k_attn_finalize<bf16_t><<<grid, FIN_NT, 0, s>>>(a, (bf16_t *)c_cache, tau, cos_out, flag_out, co);
 }
 
 // Query tile and key splits: enough workgroups to cover the chip once when there are few

@@ -263,7 +263,7 @@ __global__ __launch_bounds__(CB) void k_compact(const uint8_t *__restrict__ flag
                                                  int L, int32_t *out_idx, int32_t *out_off,
                                                  int out_cap, int32_t *status, int overflow_code) {
   __shared__ int wave_cnt[CB / WAVE];
-  compact_block(flag, rows, row_count(rows), B, L, out_idx, out_off, out_cap, status, overflow_code,
+  compact_block<CB>(flag, rows, row_count(rows), B, L, out_idx, out_off, out_cap, status, overflow_code,
                 false, wave_cnt);
 }
 
