@@ -26,7 +26,7 @@ typedef Shape<128, 64, 4, 2, false, 4> SkinnyS;
 // gate|up in the skinny regime: one raw GEMM over both weight matrices (wide column tiles keep the
 // re-reads of the activation tile down), SwiGLU applied by a row kernel
 typedef Shape<128, 96, 4, 1, false, 4> SkinnyW96;
-typedef Shape<128, 128, 4, 2, false, 3> SkinnyW128;
+typedef Shape<128, 128, 4, 2, false, 4> SkinnyW128;
 
 constexpr int MID_MAX_ROWS = 384;
 constexpr int SKINNY_MAX_ROWS = 128;
