@@ -74,6 +74,42 @@ inline int pick_splitk(int N, int K, int bn, size_t part_elems, int cap) {
   return s;
 }
 
+// K split for the mid / large regimes when the tiles alone leave most of the chip idle (few rows and a
+// narrow N): `slots` workgroups run at a time; each split keeps at least 8 slices.
+inline int pick_split_tiles(long tiles, int slots, int K, int cap, int N, size_t part_elems) {
+  if (tiles <= 0 || tiles * 10 >= (long)slots * 7) return 1;
+  int s = (int)(slots / tiles);
+  if (s > 8) s = 8;
+  while (s > 1 && ((K / BK) % s != 0 || K / BK / s < 8 || (size_t)s * cap * N > part_elems)) --s;
+  return s;
+}
+template <typename SH> inline long tiles_of(int cap, int N) { return (long)((cap + SH::BM - 1) / SH::BM) * (N / SH::BN); }
+
+// Large regime: tile shape (256x128 or 256x256) and K split with the least estimated time, in units
+// of one 256x128 tile over the whole K: rounds of the chip x tile cost / split, plus the cost of
+// writing and re-reading the fp32 partials of a split (dear when N is wide and K short).
+struct LargePlan { bool xlarge; int splitk; };
+inline LargePlan plan_large(int cap, int N, int K, size_t part_elems, bool x_ok) {
+  const long cu = cu_count(), rows = (cap + 255) / 256;
+  LargePlan best{false, 1};
+  double best_cost = 1e30;
+  for (int x = 0; x <= (x_ok ? 1 : 0); ++x) {
+    const long tiles = rows * (N / (x ? XLargeS::BN : LargeS::BN));
+    const double tile_cost = x ? 1.63 : 1.0;
+    for (int sk = 1; sk <= 8; ++sk) {
+      if ((K / BK) % sk != 0 || K / BK / sk < 8) continue;
+      if (sk > 1 && (size_t)sk * cap * N > part_elems) continue;
+      const long rounds = (tiles * sk + cu - 1) / cu;
+      // partials: sk * cap * N floats written and read again (~4 TB/s) against a round of tiles
+      // (256 tiles x 2*256*128*K flop at ~1 PFLOP/s)
+      const double partials = sk > 1 ? 1.2e-4 * sk * (double)cap * N / K + 0.02 : 0.0;
+      const double cost = rounds * tile_cost / sk + partials;
+      if (cost < best_cost - 1e-9) { best_cost = cost; best = LargePlan{x == 1, sk}; }
+    }
+  }
+  return best;
+}
+
 }  // namespace
 
 // raw result part[z][j][n]; returns the number of K splits
@@ -86,11 +122,15 @@ int gemm_bf16_raw(GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_
     run_tiles<SkinnyS>(A, rows, K, N, seg, nullptr, e, sk, part, s);
     return sk;
   }
-  if (rows.cap <= MID_MAX_ROWS) run_tiles<MidS>(A, rows, K, N, seg, nullptr, e, 1, part, s);
-  else if (N % XLargeS::BN == 0 && prefer_xlarge(rows.cap, N / LargeS::BN, N / XLargeS::BN))
-    run_tiles<XLargeS>(A, rows, K, N, seg, nullptr, e, 1, part, s);
-  else run_tiles<LargeS>(A, rows, K, N, seg, nullptr, e, 1, part, s);
-  return 1;
+  if (rows.cap <= MID_MAX_ROWS) {
+    const int sk = pick_split_tiles(tiles_of<MidS>(rows.cap, N), 2 * cu_count(), K, rows.cap, N, part_elems);
+    run_tiles<MidS>(A, rows, K, N, seg, nullptr, e, sk, part, s);
+    return sk;
+  }
+  const LargePlan pl = plan_large(rows.cap, N, K, part_elems, N % XLargeS::BN == 0);
+  if (pl.xlarge) run_tiles<XLargeS>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s);
+  else run_tiles<LargeS>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s);
+  return pl.splitk;
 }
 
 void gemm_bf16_swiglu(GemmA A, Rows rows, int K, int N, const void *wg, const void *wu, void *act,
@@ -124,11 +164,15 @@ void gemm_bf16_down(GemmA A, Rows rows, int K, int N, const void *wd, const floa
       run_tiles<SkinnyS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, 1, nullptr, s);
     }
   } else if (rows.cap <= MID_MAX_ROWS) {
-    run_tiles<MidS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, 1, nullptr, s);
-  } else if (N % XLargeS::BN == 0 && prefer_xlarge(rows.cap, N / LargeS::BN, N / XLargeS::BN)) {
-    run_tiles<XLargeS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, 1, nullptr, s);
+    const int sk = pick_split_tiles(tiles_of<MidS>(rows.cap, N), 2 * cu_count(), K, rows.cap, N, part_elems);
+    run_tiles<MidS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, sk, sk > 1 ? part : nullptr, s);
+    if (sk > 1) launch_down_finalize(BF16, part, sk, (size_t)rows.cap * N, h, rows, N, out, s);
   } else {
-    run_tiles<LargeS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, 1, nullptr, s);
+    const LargePlan pl = plan_large(rows.cap, N, K, part_elems, N % XLargeS::BN == 0);
+    float *pp = pl.splitk > 1 ? part : nullptr;
+    if (pl.xlarge) run_tiles<XLargeS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, pl.splitk, pp, s);
+    else run_tiles<LargeS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, pl.splitk, pp, s);
+    if (pl.splitk > 1) launch_down_finalize(BF16, part, pl.splitk, (size_t)rows.cap * N, h, rows, N, out, s);
   }
 }
 
