@@ -242,3 +242,39 @@ def test_weights_between_poisoned_guard_bands(dtype, dh):
         assert_index_sets_match(lay.read_list(out)[0], idx_ref, idx, cos_ref, 0.99, "guarded sparse")
         _compare_caches(lay, ref, TOL[dtype], "guarded sparse")
     lay.close()
+
+
+@pytest.mark.parametrize("name,seqs", [("c3", (5, 15)), ("c4", (0, 9))])
+def test_full_batch_at_bench_size_on_sampled_sequences(name, seqs):
+    """The launch configuration bench.py times (all 16 sequences, about 2000 salient rows: the
+    256-row GEMM tiles with gathered rows, unsplit attention) checked on sampled sequences:
+    sequences are independent, so the oracle runs the same two steps on each sampled one alone."""
+    wl = replace(W.CONFIGS[name], t_full=1)
+    s = wl.shape
+    cfg = oracle_cfg(s)
+    w = W.make_weights(s)
+    lay = Layer.from_shape(s, wl.batch, wl.seq)
+    lay.set_weights(w)
+    steps = list(W.step_stream(wl, 2))
+    _say(wl.name, "full batch: dense step, then sparse step with M=%d" % steps[1].idx.size)
+    lay.full_step(lay.upload(steps[0].x))
+    st = steps[1]
+    out = lay.layer_step(lay.upload(st.x), lay.make_list(st.idx, st.offsets), wl.tau)
+    idx_g, off_g = lay.read_list(out)
+    cos_g = lay.cos[:st.idx.size].cpu().numpy()
+    got = lay.get_caches()
+    assert lay.ctx.poll_status() == 0
+    L = wl.seq
+    for b in seqs:
+        _say(wl.name, "oracle for sequence", b)
+        ref = O.new_caches(1, L, cfg)
+        O.full_step(steps[0].x[b:b + 1], w, cfg, ref)
+        lo, hi = int(st.offsets[b]), int(st.offsets[b + 1])
+        rows_b = st.idx[lo:hi] - b * L
+        idx_ref, _, cos_ref = O.layer_step(st.x[b:b + 1], rows_b, w, cfg, ref, wl.tau)
+        sel_g = idx_g[off_g[b]:off_g[b + 1]] - b * L
+        assert_index_sets_match(sel_g, idx_ref, rows_b, cos_ref, wl.tau, "sequence %d" % b)
+        assert np.max(np.abs(cos_g[lo:hi] - cos_ref)) < 2e-2
+        for cname in ("k", "v", "c", "out"):
+            assert_close(got[cname][b], ref[cname][0], TOL["bf16"], "%s sequence %d cache %s" % (wl.name, b, cname))
+    lay.close()

@@ -234,3 +234,38 @@ def test_c5_slice_four_layers_teacher_forced():
     wl = replace(W.CONFIGS["c5"], batch=2, t_full=1, n_layers=4, name="c5-first2-4layers")
     ws = [W.make_weights(wl.shape, layer=l) for l in range(4)]
     _run_stack(wl, ws, 3, teacher_forced=True)
+
+
+def test_c5_full_batch_three_layers_on_a_sampled_sequence():
+    """All 16 sequences of the stack configuration (about 3300 salient rows per layer, the launch
+    configuration bench.py times), three layers deep; the oracle follows one sampled sequence."""
+    wl = replace(W.CONFIGS["c5"], t_full=1, n_layers=3)
+    s = wl.shape
+    cfg = oracle_cfg(s)
+    ws = [W.make_weights(s, layer=l) for l in range(3)]
+    stk = Stack(s, 3, wl.batch, wl.seq)
+    for lay, w in zip(stk.layers, ws):
+        lay.set_weights(w)
+    steps = list(W.step_stream(wl, 2))
+    st = steps[1]
+    _say(wl.name, "full batch, 3 layers: dense step, then sparse step with M=%d" % st.idx.size)
+    stk.full_step(stk.upload(steps[0].x))
+    il = stk.make_list(st.idx, st.offsets)
+    outs = stk.stack_step(stk.upload(st.x), il, wl.tau)
+    assert stk.ctx.poll_status() == 0
+    b, L = 11, wl.seq
+    refs = [O.new_caches(1, L, cfg) for _ in ws]
+    O.stack_full_step(steps[0].x[b:b + 1], ws, cfg, refs)
+    rows_b = st.idx[int(st.offsets[b]):int(st.offsets[b + 1])] - b * L
+    per_layer = O.stack_step(st.x[b:b + 1], rows_b, ws, cfg, refs, wl.tau)
+    cand = rows_b
+    for l, (idx_ref, _, cos_ref) in enumerate(per_layer):
+        idx_g, off_g = stk.layers[l].read_list(outs[l])
+        sel_g = idx_g[off_g[b]:off_g[b + 1]] - b * L
+        assert_index_sets_match(sel_g, idx_ref, cand, cos_ref, wl.tau, "layer %d" % l)
+        assert np.array_equal(sel_g, idx_ref), "a candidate inside the tolerance band: deeper layers not comparable"
+        got = stk.layers[l].get_caches()
+        for cname in ("k", "v", "c", "out"):
+            assert_close(got[cname][b], refs[l][cname][0], TOL["bf16"], "layer %d cache %s" % (l, cname))
+        cand = idx_ref
+    stk.close()
