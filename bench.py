@@ -43,6 +43,53 @@ def stage_work(shape, B, L, M_in, M_out, esz):
     return w
 
 
+def standalone_kernels(s, torch, rows=32768, iters=20):
+    """The bandwidth-bound kernels on their own, over `rows` token rows (the token count of the 32-layer
+    configuration): all-rows temporal cosine + salient test (Sec. 3.1-3.2), compaction of all flags
+    (the where(...) of Alg. 3).  Times from events on the launch stream; bytes = both context buffers
+    read once (+ outputs) / one flag byte in and four index bytes out per selected token."""
+    from paper_2603_08026_amd import binding as Bd
+    td = torch.float32 if s.dtype == "f32" else torch.bfloat16
+    esz = 4 if s.dtype == "f32" else 2
+    B = 16
+    L = rows // B
+    T = B * L
+    # a context of its own: these calls need the batch and sequence bounds, not the row workspace
+    ctx = Bd.Context(Bd.LayerCfg(s.hidden, s.n_heads, s.n_kv_heads, s.head_dim, s.ffn, B, L, 128,
+                                 Bd.F32 if s.dtype == "f32" else Bd.BF16, s.rms_eps, s.rope_theta))
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    old = torch.randn(T, s.dq, generator=g, device="cuda").to(td)
+    new = old.clone()
+    moved = torch.rand(T, generator=g, device="cuda") < 0.1  # a tenth of the contexts changed
+    new[moved] = torch.randn(int(moved.sum()), s.dq, generator=g, device="cuda").to(td)
+    cos = torch.empty(T, dtype=torch.float32, device="cuda")
+    flag = torch.empty(T, dtype=torch.uint8, device="cuda")
+    outl = Bd.IndexList.empty(T, B)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    ms_sal = timed(lambda: ctx.saliency(new, old, None, B, L, 0.99, cos, flag, False))
+    ms_cmp = timed(lambda: ctx.compact(flag, None, B, L, outl))
+    n_sel = int(outl.offsets[-1].item())
+    by_sal = 2.0 * T * s.dq * esz + 5.0 * T
+    by_cmp = 1.0 * T + 4.0 * n_sel + 4.0 * (B + 1)
+    ctx.close()
+    return {"rows": T, "selected": n_sel,
+            "saliency_all_rows": {"ms": round(ms_sal, 5), "gbps": round(by_sal / ms_sal / 1e6, 1),
+                                  "frac_of_hbm_peak": round(by_sal / ms_sal / 1e6 / HBM_PEAK_GBS, 3)},
+            "compact_all_rows": {"ms": round(ms_cmp, 5), "gbps": round(by_cmp / ms_cmp / 1e6, 2)}}
+
+
 def cpu_baseline(wl, budget_s=20.0):
     """Times the CPU oracle as it stands on a bounded sample of the same workload."""
     import numpy as np
@@ -244,6 +291,7 @@ def main():
         "ms_per_step_with_stage_events": t_step_instr * 1e3, "stage_calls": calls, "stages": stages,
         "roofline": roof,
     }
+    out["standalone"] = standalone_kernels(s, torch)
     if NL > 1:
         # stack only: generated tokens per second of the paper's kind over the layer stack alone
         # (no embedding, logits or sampling): B * L_R over T_full dense and the remaining sparse steps

@@ -224,11 +224,13 @@ __global__ __launch_bounds__(RB) void k_qkv_finalize(const float *__restrict__ p
 // ---- temporal cosine similarity + salient test (+ commit)  [Sec. 3.1, Sec. 3.2] ----------------
 // s = <a,b> / (max(|a|,1e-8) max(|b|,1e-8)), flag = s < tau.  The old cache row b is read before
 // the same thread overwrites the same elements with a.
+constexpr int SAL_NT = 256;  // a row per workgroup: many small workgroups keep the loads of a CU in flight
+
 template <typename T>
-__global__ __launch_bounds__(RB) void k_saliency(const T *__restrict__ c_new, T *c_cache, Rows rows,
-                                                  int D, float tau, float *__restrict__ cos_out,
-                                                  uint8_t *__restrict__ flag_out, int commit) {
-  __shared__ float red[RB / WAVE];
+__global__ __launch_bounds__(SAL_NT) void k_saliency(const T *__restrict__ c_new, T *c_cache, Rows rows,
+                                                      int D, float tau, float *__restrict__ cos_out,
+                                                      uint8_t *__restrict__ flag_out, int commit) {
+  __shared__ float red[3 * SAL_NT / WAVE];
   constexpr int N = Vec16<T>::N;
   const int n = row_count(rows), nv = D / N;
   for (int j = blockIdx.x; j < n; j += gridDim.x) {
@@ -236,7 +238,7 @@ __global__ __launch_bounds__(RB) void k_saliency(const T *__restrict__ c_new, T 
     const T *a = c_new + (size_t)j * D;
     T *b = c_cache + (size_t)r * D;
     float dot = 0.f, na = 0.f, nb = 0.f;
-    for (int v = threadIdx.x; v < nv; v += RB) {
+    for (int v = threadIdx.x; v < nv; v += SAL_NT) {
       Vec16<T> va = ld16(a + v * N), vb = ld16(b + v * N);
 #pragma unroll
       for (int i = 0; i < N; ++i) {
@@ -247,9 +249,7 @@ __global__ __launch_bounds__(RB) void k_saliency(const T *__restrict__ c_new, T 
       }
       if (commit) st16(b + v * N, va);
     }
-    dot = block_sum<RB>(dot, red);
-    na = block_sum<RB>(na, red);
-    nb = block_sum<RB>(nb, red);
+    block_sum3<SAL_NT>(dot, na, nb, red);
     if (threadIdx.x == 0) {
       const float s = dot / (fmaxf(sqrtf(na), 1e-8f) * fmaxf(sqrtf(nb), 1e-8f));
       if (cos_out) cos_out[j] = s;
@@ -336,14 +336,16 @@ void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_st
         (const bf16_t *)bv, (bf16_t *)q_out, (bf16_t *)k_cache, (bf16_t *)v_cache);
 }
 
+inline int sal_grid(int cap) { return cap < 1 ? 1 : (cap > 65536 ? 65536 : cap); }
+
 void launch_saliency(DType t, const void *c_new, void *c_cache, Rows rows, int D, float tau,
                      float *cos_out, uint8_t *flag_out, int commit, hipStream_t s) {
   if (rows.cap <= 0) return;
   if (t == F32)
-    k_saliency<float><<<row_grid(rows.cap), RB, 0, s>>>((const float *)c_new, (float *)c_cache, rows,
+    k_saliency<float><<<sal_grid(rows.cap), SAL_NT, 0, s>>>((const float *)c_new, (float *)c_cache, rows,
                                                         D, tau, cos_out, flag_out, commit);
   else
-    k_saliency<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>((const bf16_t *)c_new, (bf16_t *)c_cache,
+    k_saliency<bf16_t><<<sal_grid(rows.cap), SAL_NT, 0, s>>>((const bf16_t *)c_new, (bf16_t *)c_cache,
                                                          rows, D, tau, cos_out, flag_out, commit);
 }
 
