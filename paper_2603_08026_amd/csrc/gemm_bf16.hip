@@ -118,6 +118,11 @@ int gemm_bf16_raw(GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_
   const int N = seg.n_end[2];
   EpiStoreF32 e{part, N};
   if (rows.cap <= SKINNY_MAX_ROWS) {
+    if (N % SkinnyW96::BN == 0) {  // wider column tiles: fewer re-reads of the activation tile
+      const int sk = pick_splitk(N, K, SkinnyW96::BN, part_elems, rows.cap);
+      run_tiles<SkinnyW96>(A, rows, K, N, seg, nullptr, e, sk, part, s);
+      return sk;
+    }
     const int sk = pick_splitk(N, K, SkinnyS::BN, part_elems, rows.cap);
     run_tiles<SkinnyS>(A, rows, K, N, seg, nullptr, e, sk, part, s);
     return sk;

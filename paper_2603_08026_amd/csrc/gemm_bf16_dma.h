@@ -62,7 +62,7 @@ template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, bool DUAL_, int NS_, int
   static_assert(NW == 4 || NW == 8, "four or eight waves per workgroup");
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile is made of 32x32 blocks");
   static_assert(BM % (8 * NWC) == 0 && BN % (8 * NWC) == 0, "tile rows are copied in blocks of 8 per wave");
-  static_assert(NS >= 2 && NSA >= 2 && (ROLES ? NS <= 8 : NS <= 4), "LDS stages");
+  static_assert(NS >= 2 && NSA >= 2 && (ROLES ? NS <= 16 : NS <= 4), "LDS stages");
   static_assert((NS - 2) * (ROLES ? NMAT * B_LD : LPS) < 64 && (NSA - 2) * A_LD < 64, "vmcnt immediate");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS of one CU");
 };
