@@ -15,6 +15,12 @@ What each function follows:
                                     its layer loop restricted to the salient
                                     (row-sparse) path
   full_step ....................... App. C.2, Alg. 2 (FullStep), one layer
+  approx_attention ................ App. C.4, Alg. 4 (approximate attention): the
+                                    salient columns of the full softmax times the
+                                    value residual of the salient tokens  [Eq. 3]
+  layer_step_approx ............... Alg. 3 layer body with both attention paths
+                                    (exact rows for the salient set, approximate
+                                    context update for all other rows)
   stack_step, stack_full_step ..... the layer loops of Alg. 3 and Alg. 2: a layer
                                     reads the previous layer's output cache and,
                                     in Alg. 3, the previous layer's salient set
@@ -342,6 +348,79 @@ def layer_step(x: np.ndarray, idx_in: np.ndarray, w: Dict[str, np.ndarray], cfg:
     cc[idx_in] = c_new
     idx_out, offsets_out = compact(flag, idx_in, B, L)
     # (6) out-projection and FFN for the newly selected rows
+    salient_ffn(xf, cc, idx_out, w, cfg, oc)
+    return idx_out, offsets_out, cos
+
+
+def approx_attention(q_all: np.ndarray, k_cache: np.ndarray, dv: np.ndarray, idx_sal: np.ndarray,
+                     B: int, L: int) -> np.ndarray:
+    """Residual update of the attention context of EVERY token.  [Alg. 4; Eq. 3, first term]
+
+    q_all: [B*L, H, dh] queries of all tokens; k_cache: [B, L, Hkv, dh] (merged keys);
+    dv: [M, Hkv, dh] value residual V_new - V_cached of the tokens idx_sal (ascending flat ids).
+    Steps of Alg. 4 per sequence and head: scores of all queries against ALL keys, softmax over all
+    keys, the columns of the salient tokens, times their value residual.  Returns [B*L, H*dh].
+    """
+    idx_sal = np.asarray(idx_sal, dtype=np.int64)
+    T, H, dh = q_all.shape
+    Hkv = k_cache.shape[2]
+    g = H // Hkv
+    out = np.zeros((T, H * dh), dtype=F64)
+    qa, dv = _f64(q_all), _f64(dv)
+    for b in range(B):
+        sel = np.nonzero((idx_sal >= b * L) & (idx_sal < (b + 1) * L))[0]
+        if sel.size == 0:
+            continue
+        cols = idx_sal[sel] - b * L
+        for h in range(H):
+            S = qa[b * L:(b + 1) * L, h] @ _f64(k_cache[b, :, h // g]).T / np.sqrt(dh)  # [L, L]
+            E = np.exp(S - S.max(axis=1, keepdims=True))
+            A = E / E.sum(axis=1, keepdims=True)
+            out[b * L:(b + 1) * L, h * dh:(h + 1) * dh] = A[:, cols] @ dv[sel, h // g]
+    return out
+
+
+def layer_step_approx(x: np.ndarray, idx_in: np.ndarray, w: Dict[str, np.ndarray], cfg: LayerCfg,
+                      caches: Dict[str, np.ndarray], tau: float):
+    """One layer of SparseStep with both attention paths.  [Alg. 3 layer body; Sec. 3.3]
+
+    As layer_step, plus: queries are projected for ALL tokens; the value residual dV of the idx_in
+    tokens is taken before their V rows are merged; every token outside idx_in gets
+    C = C_cached + approx_attention(...) (Sec. 3.3, non-salient path); the cosine test then runs over
+    ALL tokens, so idx_out may hold tokens that were not in idx_in.  Returns (idx_out, offsets_out,
+    cos) with cos of length B*L.
+    """
+    x = _f64(x)
+    B, L, d = x.shape
+    T = B * L
+    idx_in = np.asarray(idx_in, dtype=np.int64)
+    xf = x.reshape(T, d)
+    kc = caches["k"].reshape(T, cfg.n_kv_heads, cfg.head_dim)
+    vc = caches["v"].reshape(T, cfg.n_kv_heads, cfg.head_dim)
+    cc = caches["c"].reshape(T, cfg.n_heads * cfg.head_dim)
+    oc = caches["out"].reshape(T, d)
+    pos_all = np.arange(T) % L
+    # norm and q projection of every token; k, v of the salient tokens only
+    n_all = rmsnorm(xf, w["g_attn"], cfg.rms_eps)
+    q_all = n_all @ _f64(w["wq"]).T
+    if w.get("bq") is not None:
+        q_all = q_all + _f64(w["bq"])
+    q_all = rope(q_all.reshape(T, cfg.n_heads, cfg.head_dim), pos_all, cfg.rope_theta)
+    c_new = cc.copy()
+    if idx_in.size:
+        _, k, v = project_qkv(n_all[idx_in], idx_in % L, w, cfg)
+        dv = v - vc[idx_in]            # before the merge
+        kc[idx_in] = k
+        vc[idx_in] = v
+        c_sal = partial_attention(q_all[idx_in], caches["k"], caches["v"], idx_in, B, L)
+        dc = approx_attention(q_all, caches["k"], dv, idx_in, B, L)
+        others = np.setdiff1d(np.arange(T), idx_in)
+        c_new[others] = cc[others] + dc[others]
+        c_new[idx_in] = c_sal
+    cos = cosine_rows(c_new, cc)
+    flag = salient_mask(cos, tau)
+    cc[:] = c_new
+    idx_out, offsets_out = compact(flag, None, B, L)
     salient_ffn(xf, cc, idx_out, w, cfg, oc)
     return idx_out, offsets_out, cos
 

@@ -508,3 +508,114 @@ def test_stack_carries_the_salient_set_and_the_output_cache_between_layers():
                 ref = O.attention_rows(q, c["k"][bsel], c["v"][bsel]).reshape(-1)
                 assert np.allclose(c["c"][bsel, i], ref, atol=1e-12)
         h = c["out"]
+
+
+# ---------------------------------------------------------------- approximate attention (Alg. 4)
+
+def _dense_attention(q, k, v):
+    """q [L,H,dh], k,v [L,Hkv,dh] -> [L, H*dh], through torch's library attention."""
+    H, Hkv = q.shape[1], k.shape[1]
+    tq = torch.from_numpy(q).transpose(0, 1)[None]
+    tk = torch.from_numpy(k).repeat_interleave(H // Hkv, 1).transpose(0, 1)[None]
+    tv = torch.from_numpy(v).repeat_interleave(H // Hkv, 1).transpose(0, 1)[None]
+    o = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv)[0].transpose(0, 1)
+    return o.reshape(q.shape[0], -1).numpy()
+
+
+@pytest.mark.parametrize("H,Hkv", [(4, 4), (6, 2)])
+def test_approx_attention_is_exact_when_only_values_change(H, Hkv):
+    # Eq. 3 with unchanged scores: C_old + A[:, idx] dV == exact attention with the new values
+    r = _rng(31)
+    B, L, dh = 2, 11, 8
+    q = r.normal(size=(B * L, H, dh))
+    k = r.normal(size=(B, L, Hkv, dh))
+    v_old = r.normal(size=(B, L, Hkv, dh))
+    idx = np.array([1, 4, 9, 12, 13, 21])
+    v_new = v_old.copy()
+    v_new.reshape(B * L, Hkv, dh)[idx] = r.normal(size=(idx.size, Hkv, dh))
+    dv = (v_new - v_old).reshape(B * L, Hkv, dh)[idx]
+    dc = O.approx_attention(q, k, dv, idx, B, L)
+    for b in range(B):
+        c_old = _dense_attention(q[b * L:(b + 1) * L], k[b], v_old[b])
+        c_new = _dense_attention(q[b * L:(b + 1) * L], k[b], v_new[b])
+        assert np.allclose(c_old + dc[b * L:(b + 1) * L], c_new, atol=1e-12)
+
+
+def test_approx_attention_bruteforce_and_degenerate_cases():
+    r = _rng(32)
+    B, L, H, Hkv, dh = 2, 5, 4, 2, 4
+    q = r.normal(size=(B * L, H, dh))
+    k = r.normal(size=(B, L, Hkv, dh))
+    idx = np.array([0, 3, 7])
+    dv = r.normal(size=(3, Hkv, dh))
+    got = O.approx_attention(q, k, dv, idx, B, L)
+    ref = np.zeros_like(got)
+    for t in range(B * L):           # scalar loops
+        b = t // L
+        for h in range(H):
+            z = [sum(q[t, h, e] * k[b, j, h // 2, e] for e in range(dh)) / math.sqrt(dh) for j in range(L)]
+            m = max(z)
+            den = sum(math.exp(zj - m) for zj in z)
+            for jj, tok in enumerate(idx):
+                if tok // L != b:
+                    continue
+                a = math.exp(z[tok % L] - m) / den
+                for e in range(dh):
+                    ref[t, h * dh + e] += a * dv[jj, h // 2, e]
+    assert np.allclose(got, ref, atol=1e-13)
+    # no residual, or no salient token: no update; sequence 1 has one salient token only
+    assert np.all(O.approx_attention(q, k, np.zeros_like(dv), idx, B, L) == 0)
+    assert np.all(O.approx_attention(q, k, dv[:0], idx[:0], B, L) == 0)
+    # every token salient: the full softmax times dV, i.e. library attention with V := dV
+    allidx = np.arange(B * L)
+    dv_all = r.normal(size=(B * L, Hkv, dh))
+    got = O.approx_attention(q, k, dv_all, allidx, B, L)
+    for b in range(B):
+        assert np.allclose(got[b * L:(b + 1) * L],
+                           _dense_attention(q[b * L:(b + 1) * L], k[b], dv_all[b * L:(b + 1) * L]), atol=1e-12)
+
+
+def test_layer_step_approx_structure():
+    r, cfg, w, x0, caches = _setup(seed=33)
+    T = 20
+    # (i) empty salient set: nothing changes, every cosine is 1
+    before = _copy(caches)
+    out, off, cos = O.layer_step_approx(r.normal(size=x0.shape), np.zeros(0, np.int64), w, cfg, caches, 0.99)
+    assert out.size == 0 and np.all(cos >= 1 - 1e-12)
+    for k in caches:
+        assert np.allclose(caches[k], before[k], atol=1e-14), k
+    # (ii) every token salient: the exact path only, equal to layer_step and to the dense step
+    x1 = r.normal(size=x0.shape)
+    a, b_ = _copy(caches), _copy(caches)
+    o1 = O.layer_step_approx(x1, np.arange(T), w, cfg, a, 1.5)
+    o2 = O.layer_step(x1, np.arange(T), w, cfg, b_, 1.5)
+    assert np.array_equal(o1[0], o2[0])
+    for k in a:
+        assert np.allclose(a[k], b_[k], rtol=1e-11, atol=1e-12), k
+    # (iii) a few salient tokens: K/V of the others untouched, contexts of the others move by the
+    #       approximate update, and tokens outside idx_in can become salient
+    idx = np.array([2, 5, 13])
+    x2 = x0.copy()
+    x2.reshape(T, -1)[idx] = 3.0 * r.normal(size=(3, 16))
+    c = _copy(caches)
+    v_before = c["v"].copy()
+    out, off, cos = O.layer_step_approx(x2, idx, w, cfg, c, 0.999)
+    others = np.setdiff1d(np.arange(T), idx)
+    assert np.array_equal(c["k"].reshape(T, -1)[others], caches["k"].reshape(T, -1)[others])
+    assert np.array_equal(c["v"].reshape(T, -1)[others], v_before.reshape(T, -1)[others])
+    assert cos.shape == (T,) and off[-1] == out.size
+    assert set(out.tolist()) - set(idx.tolist()), "some non-salient token should cross the threshold"
+    # the contexts of the other tokens: cached + (softmax columns of idx) x dV, recomputed here from
+    # the exact attention with old and new values (scores of non-salient queries use merged keys)
+    n_all = O.rmsnorm(x2.reshape(T, -1), w["g_attn"], cfg.rms_eps)
+    q_all = O.rope((n_all @ w["wq"].T).reshape(T, cfg.n_heads, cfg.head_dim), np.arange(T) % 10, cfg.rope_theta)
+    for b in range(2):
+        qs = q_all[b * 10:(b + 1) * 10]
+        exact_new = O.attention_rows(qs, c["k"][b], c["v"][b])
+        exact_oldv = O.attention_rows(qs, c["k"][b], v_before[b])
+        rows = others[(others >= b * 10) & (others < (b + 1) * 10)]
+        want = caches["c"].reshape(T, -1)[rows] + (exact_new - exact_oldv)[rows - b * 10]
+        assert np.allclose(c["c"].reshape(T, -1)[rows], want, atol=1e-12)
+    # rows not selected keep their cached output
+    kept = np.setdiff1d(np.arange(T), out)
+    assert np.array_equal(c["out"].reshape(T, -1)[kept], caches["out"].reshape(T, -1)[kept])
