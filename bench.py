@@ -232,6 +232,35 @@ def main():
     torch.cuda.synchronize()
     t_step_instr = (time.perf_counter() - t0) / K
     stage_ms, calls = lay.ctx.profile_end()
+
+    # single layer: the same K steps once more with the approximate update of all other tokens
+    # (Sec. 3.3, Alg. 4) in place of leaving their contexts untouched
+    approx = None
+    if NL == 1:
+        def restore():
+            for k_, v_ in snap[0].items():
+                getattr(lay, k_).copy_(v_)
+        restore()
+        lay.layer_step_approx(steps[Wu][0], steps[Wu][1], wl.tau)
+        restore()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(Wu, Wu + K):
+            lay.layer_step_approx(steps[i][0], steps[i][1], wl.tau)
+        torch.cuda.synchronize()
+        t_approx = (time.perf_counter() - t0) / K
+        approx = {"ms_per_step": t_approx * 1e3, "tokens_per_s": wl.tokens / t_approx,
+                  "salient_rows_out_last": int(lay.idx_out.offsets[-1].item())}
+        # the same with a threshold no cosine falls below: nothing is selected, the out-projection and
+        # FFN see an empty list, what remains is q of all tokens, k/v of the candidates, both
+        # attention passes and the cosine test over all tokens
+        restore()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(Wu, Wu + K):
+            lay.layer_step_approx(steps[i][0], steps[i][1], -2.0)
+        torch.cuda.synchronize()
+        approx["ms_per_step_nothing_selected"] = (time.perf_counter() - t0) / K * 1e3
     del snap
 
     # dense step of the same shape on the same GPU
@@ -291,6 +320,9 @@ def main():
         "ms_per_step_with_stage_events": t_step_instr * 1e3, "stage_calls": calls, "stages": stages,
         "roofline": roof,
     }
+    if approx is not None:
+        approx["speedup_vs_dense"] = t_dense * 1e3 / approx["ms_per_step"]
+        out["approx_step"] = approx
     out["standalone"] = standalone_kernels(s, torch)
     if NL > 1:
         # stack only: generated tokens per second of the paper's kind over the layer stack alone

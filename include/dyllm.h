@@ -174,6 +174,23 @@ int dyllm_layer_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_c
                      const void *x, const dyllm_index_list *idx_in, int32_t B, int32_t L, float tau,
                      dyllm_index_list *idx_out, float *cos_out, void *stream);
 
+/* One layer of SparseStep with both attention paths: exact rows for the tokens of idx_in, and for
+ * every other token the approximate update of its cached context.  [Sec. 3.3; Alg. 3 layer body;
+ * Alg. 4; Eq. 3]
+ *   q of ALL tokens is recomputed from x; K, V of the tokens in idx_in are recomputed and merged
+ *   into the caches, dV = V_new - V_cache of those tokens taken before the merge;
+ *   C[idx_in]  = softmax(q K^T / sqrt(dh)) V            (against the merged caches),
+ *   C[others] = C_cache + softmax(q K^T / sqrt(dh))[:, idx_in] dV   (normalised over ALL keys);
+ *   the cosine test then runs over ALL B*L tokens (new context against the cached one), the context
+ *   cache takes the new rows, and idx_out receives every token whose cosine fell below tau -- it may
+ *   hold tokens outside idx_in, so idx_out->cap should be B*L (overflow sets DYLLM_ERR_CAPACITY in
+ *   the status word as for dyllm_compact).  out-projection and FFN run for idx_out only.
+ * cos_out: [B*L] (by token) or NULL.  Needs a context with max_rows covering B*L.  An empty idx_in
+ * leaves every cache byte unchanged and yields an empty idx_out. */
+int dyllm_layer_step_approx(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
+                            const void *x, const dyllm_index_list *idx_in, int32_t B, int32_t L,
+                            float tau, dyllm_index_list *idx_out, float *cos_out, void *stream);
+
 /* Dense pass of one layer over all B*L rows; fills all four caches.  [App. C.2, Alg. 2]
  * Needs a context with max_rows covering B*L. */
 int dyllm_full_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,

@@ -23,7 +23,8 @@ OK, ERR_INVALID_ARG, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_NO_MEM, ERR_HIP, ERR_CA
 SYMBOLS = [
     "dyllm_workspace_bytes", "dyllm_create", "dyllm_destroy", "dyllm_strerror", "dyllm_last_error",
     "dyllm_poll_status", "dyllm_saliency", "dyllm_compact", "dyllm_qkv_refresh",
-    "dyllm_partial_attention", "dyllm_salient_ffn", "dyllm_layer_step", "dyllm_full_step",
+    "dyllm_partial_attention", "dyllm_salient_ffn", "dyllm_layer_step", "dyllm_layer_step_approx",
+    "dyllm_full_step",
     "dyllm_stack_step", "dyllm_stack_full_step",
     "dyllm_profile_begin", "dyllm_profile_end", "dyllm_stage_count", "dyllm_stage_name",
 ]
@@ -86,6 +87,7 @@ def load_library() -> C.CDLL:
     lib.dyllm_salient_ffn.argtypes = [vp, P(LayerWeights), vp, vp, P(IndexListC), i32, i32, vp, vp]
     lib.dyllm_layer_step.argtypes = [vp, P(LayerWeights), P(LayerCache), vp, P(IndexListC), i32, i32, f32,
                                      P(IndexListC), vp, vp]
+    lib.dyllm_layer_step_approx.argtypes = lib.dyllm_layer_step.argtypes
     lib.dyllm_full_step.argtypes = [vp, P(LayerWeights), P(LayerCache), vp, i32, i32, vp]
     lib.dyllm_stack_step.argtypes = [vp, i32, P(LayerWeights), P(LayerCache), vp, P(IndexListC), i32, i32, f32,
                                      P(IndexListC), vp, vp]
@@ -231,6 +233,12 @@ class Context:
         i, o = idx_in.c(), idx_out.c()
         self._check(self.lib.dyllm_layer_step(self.h, C.byref(w), C.byref(cache), _ptr(x), C.byref(i),
                                               B, L, tau, C.byref(o), _ptr(cos_out), _stream()))
+
+    def layer_step_approx(self, w: LayerWeights, cache: LayerCache, x, idx_in: IndexList, B, L, tau,
+                          idx_out: IndexList, cos_out=None):
+        i, o = idx_in.c(), idx_out.c()
+        self._check(self.lib.dyllm_layer_step_approx(self.h, C.byref(w), C.byref(cache), _ptr(x), C.byref(i),
+                                                     B, L, tau, C.byref(o), _ptr(cos_out), _stream()))
 
     def full_step(self, w: LayerWeights, cache: LayerCache, x, B, L):
         self._check(self.lib.dyllm_full_step(self.h, C.byref(w), C.byref(cache), _ptr(x), B, L, _stream()))

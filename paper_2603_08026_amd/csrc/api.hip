@@ -27,6 +27,10 @@ struct dyllm_ctx {
   float *part_o;   // fp32 scratch shared by consecutive stages: raw GEMM results / attention partials
   float *part_ml;
   size_t part_elems;
+  void *dv_full;   // [R, dkv] value residuals of the approximate path; all zero between calls
+  void *dc;        // [R, dq] approximate context residual of every token
+  void *csal;      // [R, dq] exact context rows of the salient tokens (approximate path)
+  int32_t *pos;    // [R] position+1 of a token in the salient list; all zero between calls
   float *cosb;     // [R]
   uint8_t *flag;   // [R]
   float *hs;       // [R, d]        x + Wo c (fp32)
@@ -44,7 +48,7 @@ struct dyllm_ctx {
 namespace {
 
 struct Layout {
-  size_t ns, qkv, qs, part_o, part_ml, cosb, flag, hs, fs, act, status, rope, total;
+  size_t ns, qkv, qs, part_o, part_ml, cosb, flag, hs, fs, act, status, rope, dv_full, dc, csal, pos, total;
   size_t part_elems;
 };
 
@@ -75,6 +79,10 @@ Layout make_layout(const dyllm_layer_cfg &c) {
   l.act = take(R * (size_t)c.ffn_dim * e);
   l.status = take(256);
   l.rope = take((size_t)c.max_seq * (c.head_dim / 2) * 2 * 4);
+  l.dv_full = take(R * dkv * e);
+  l.dc = take(R * dq * e);
+  l.csal = take(R * dq * e);
+  l.pos = take(R * 4);
   l.total = off;
   return l;
 }
@@ -165,7 +173,7 @@ int enqueue_qkv(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x, Row
   prof_mark(ctx, ST_GEMM_QKV, s);
   launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)rows.cap * seg.n_end[2], ctx->rope, rows, L,
                       c.n_heads, c.n_kv_heads, c.head_dim, w->bq, w->bk, w->bv, q_out, cache->k,
-                      cache->v, s);
+                      cache->v, nullptr, s);
   prof_mark(ctx, ST_ROPE_SCATTER, s);
   return check_launch(ctx, "qkv refresh");
 }
@@ -174,7 +182,7 @@ AttnArgs attn_args(dyllm_ctx *ctx, const void *q, const void *k, const void *v, 
                    const int32_t *offsets, int B, int L, void *out, int partial) {
   const dyllm_layer_cfg &c = ctx->cfg;
   AttnArgs a;
-  a.q = q; a.k = k; a.v = v; a.rows = rows; a.offsets = offsets;
+  a.q = q; a.q_by_token = 0; a.k = k; a.v = v; a.rows = rows; a.offsets = offsets;
   a.B = B; a.L = L; a.H = c.n_heads; a.Hkv = c.n_kv_heads; a.dh = c.head_dim;
   const int rows_per_seq = offsets ? (rows.cap + B - 1) / B : L;
   attention_plan(dt(ctx), B, L, c.n_heads, c.head_dim, rows.cap, rows_per_seq, ctx->part_elems, &a);
@@ -275,6 +283,59 @@ int enqueue_sparse_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
   return rc;
 }
 
+// one layer of the sparse step with both attention paths, arguments already checked
+// [Alg. 3 layer body; Sec. 3.3: exact rows for the salient tokens, approximate update for the others]
+int enqueue_approx_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
+                         const void *x, const dyllm_index_list *idx_in, int B, int L, float tau,
+                         dyllm_index_list *idx_out, float *cos_out, hipStream_t s) {
+  const dyllm_layer_cfg &c = ctx->cfg;
+  const int T = B * L;
+  const Rows all{nullptr, nullptr, T};
+  const Rows rin = rows_of(idx_in, B);
+  int rc;
+  ctx->prof_cur = nullptr;  // no per-stage timing on this path
+  // norm and q projection (+ rotation) of EVERY token  [Alg. 3: Q <- q_proj(x)]
+  launch_gather_rmsnorm(dt(ctx), x, w->g_attn, all, c.hidden, c.rms_eps, ctx->ns, s);
+  {
+    const int splits = launch_gemm_raw(dt(ctx), GemmA{ctx->ns, nullptr, c.hidden}, all, c.hidden,
+                                       wseg_one(w->wq, ctx->dq), ctx->part_o, ctx->part_elems, s);
+    launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)T * ctx->dq, ctx->rope, all, L, c.n_heads, 0,
+                        c.head_dim, w->bq, nullptr, nullptr, ctx->qs, nullptr, nullptr, nullptr, s);
+  }
+  // k, v of the salient tokens: rotation, value residual, merge into the caches
+  {
+    WSeg seg;
+    seg.w[0] = w->wk; seg.w[1] = w->wv; seg.w[2] = w->wv;
+    seg.n_end[0] = ctx->dkv; seg.n_end[1] = 2 * ctx->dkv; seg.n_end[2] = 2 * ctx->dkv;
+    const int splits = launch_gemm_raw(dt(ctx), GemmA{ctx->ns, rin.idx, c.hidden}, rin, c.hidden, seg,
+                                       ctx->part_o, ctx->part_elems, s);
+    launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)rin.cap * 2 * ctx->dkv, ctx->rope, rin, L, 0,
+                        c.n_kv_heads, c.head_dim, nullptr, w->bk, w->bv, nullptr, cache->k, cache->v,
+                        ctx->dv_full, s);
+  }
+  if ((rc = check_launch(ctx, "approx: projections"))) return rc;
+  // exact rows of the salient tokens  [Alg. 3: C_sal]
+  {
+    AttnArgs a = attn_args(ctx, ctx->qs, cache->k, cache->v, rin, idx_in->offsets, B, L, ctx->csal, 0);
+    a.q_by_token = 1;
+    launch_attention(dt(ctx), a, s);
+  }
+  // approximate residual of every token: the full softmax against the merged keys times the value
+  // residual, which is zero outside the salient rows  [Alg. 4]
+  {
+    const AttnArgs a = attn_args(ctx, ctx->qs, cache->k, ctx->dv_full, all, nullptr, B, L, ctx->dc, 0);
+    launch_attention(dt(ctx), a, s);
+  }
+  if ((rc = check_launch(ctx, "approx: attention"))) return rc;
+  // new contexts of all tokens, cosine test, commit; then the scratch maps go back to zero
+  launch_mark_rows(rin, ctx->pos, s);
+  launch_saliency_approx(dt(ctx), T, ctx->dq, ctx->csal, ctx->dc, ctx->pos, cache->c, tau, cos_out, ctx->flag, s);
+  launch_clear_rows(dt(ctx), rin, ctx->pos, ctx->dv_full, ctx->dkv, s);
+  launch_compact(ctx->flag, all, B, L, idx_out->idx, idx_out->offsets, idx_out->cap, ctx->status, s);
+  if ((rc = check_launch(ctx, "approx: saliency / compact"))) return rc;
+  return enqueue_ffn(ctx, w, x, cache->c, rows_of(idx_out, B), cache->out, s);
+}
+
 // dense pass of one layer, arguments already checked  [Alg. 2 layer body]
 int enqueue_dense_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
                         const void *x, int B, int L, hipStream_t s) {
@@ -345,6 +406,7 @@ int dyllm_create(const dyllm_layer_cfg *cfg, dyllm_ctx **out) {
   ctx->cosb = (float *)(b + l.cosb); ctx->flag = (uint8_t *)(b + l.flag);
   ctx->hs = (float *)(b + l.hs); ctx->fs = b + l.fs; ctx->act = b + l.act;
   ctx->status = (int32_t *)(b + l.status); ctx->rope = (float *)(b + l.rope);
+  ctx->dv_full = b + l.dv_full; ctx->dc = b + l.dc; ctx->csal = b + l.csal; ctx->pos = (int32_t *)(b + l.pos);
 
   // rotary table in double precision on the host, cleared status word
   const int half = cfg->head_dim / 2;
@@ -357,6 +419,8 @@ int dyllm_create(const dyllm_layer_cfg *cfg, dyllm_ctx **out) {
     }
   hipError_t e = hipMemcpy(ctx->rope, tab.data(), tab.size() * 4, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemset(ctx->status, 0, 256);
+  if (e == hipSuccess) e = hipMemset(ctx->dv_full, 0, l.dc - l.dv_full);
+  if (e == hipSuccess) e = hipMemset(ctx->pos, 0, l.total - l.pos);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     (void)hipFree(ctx->ws);
@@ -517,6 +581,17 @@ int dyllm_layer_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_c
   if ((rc = check_bl(ctx, B, L))) return rc;
   if ((rc = check_sparse_layer(ctx, w, cache, x, idx_in, idx_out))) return rc;
   return enqueue_sparse_layer(ctx, w, cache, x, idx_in, B, L, tau, idx_out, cos_out, (hipStream_t)stream);
+}
+
+int dyllm_layer_step_approx(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
+                            const void *x, const dyllm_index_list *idx_in, int32_t B, int32_t L, float tau,
+                            dyllm_index_list *idx_out, float *cos_out, void *stream) {
+  if (!ctx) return DYLLM_ERR_INVALID_ARG;
+  int rc;
+  if ((rc = check_bl(ctx, B, L))) return rc;
+  if ((long)B * L > ctx->rows_cap) return fail(ctx, DYLLM_ERR_CAPACITY, "B*L exceeds the context's max_rows");
+  if ((rc = check_sparse_layer(ctx, w, cache, x, idx_in, idx_out))) return rc;
+  return enqueue_approx_layer(ctx, w, cache, x, idx_in, B, L, tau, idx_out, cos_out, (hipStream_t)stream);
 }
 
 int dyllm_full_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,

@@ -140,7 +140,8 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
   for (int qb = 0; qb < QB; ++qb) {
     int r = wq * (32 * QB) + qb * 32 + l32;
     r = r < nq ? r : nq - 1;  // rows past the end are clamped; their results are never stored
-    const bf16_t *qp = (const bf16_t *)a.q + ((size_t)(j0 + r) * a.H + h) * DH + lhi * 8;
+    const size_t qrow = a.q_by_token ? (size_t)a.rows.idx[j0 + r] : (size_t)(j0 + r);
+    const bf16_t *qp = (const bf16_t *)a.q + (qrow * a.H + h) * DH + lhi * 8;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) qf[qb][kk] = *reinterpret_cast<const bf16x8 *>(qp + kk * 16);
   }
@@ -395,7 +396,8 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a) 
   {
     int r = wq * 32 + l32;
     r = r < nq ? r : nq - 1;  // rows past the end are clamped; their results are never stored
-    const bf16_t *qp = (const bf16_t *)a.q + ((size_t)(j0 + r) * a.H + h) * DH + lhi * 8;
+    const size_t qrow = a.q_by_token ? (size_t)a.rows.idx[j0 + r] : (size_t)(j0 + r);
+    const bf16_t *qp = (const bf16_t *)a.q + (qrow * a.H + h) * DH + lhi * 8;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8 *>(qp + kk * 16);
   }

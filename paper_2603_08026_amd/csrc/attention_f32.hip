@@ -45,7 +45,8 @@ __global__ __launch_bounds__(256) void k_attn_f32(AttnArgs a) {
 
   for (int e = tid; e < BQ * DH; e += 256) {
     const int r = e / DH, c = e % DH;
-    Qs[r][c] = (r < nq) ? to_f<T>(q[((size_t)(j0 + r) * a.H + h) * DH + c]) * scale : 0.f;
+    const size_t qrow = (r < nq) ? (a.q_by_token ? (size_t)a.rows.idx[j0 + r] : (size_t)(j0 + r)) : 0;
+    Qs[r][c] = (r < nq) ? to_f<T>(q[(qrow * a.H + h) * DH + c]) * scale : 0.f;
   }
 
   const int row = tid / 16, sub = tid % 16;

@@ -162,7 +162,8 @@ __global__ __launch_bounds__(RB) void k_qkv_finalize(const float *__restrict__ p
                                                       Rows rows, int L, int H, int Hkv, int dh,
                                                       const T *__restrict__ bq, const T *__restrict__ bk,
                                                       const T *__restrict__ bv, T *__restrict__ q_out,
-                                                      T *__restrict__ kc, T *__restrict__ vc) {
+                                                      T *__restrict__ kc, T *__restrict__ vc,
+                                                      T *__restrict__ dv_out) {
   const int n = row_count(rows);
   const int half = dh / 2, dq = H * dh, dkv = Hkv * dh, ld = dq + 2 * dkv;
   const int per_head = half / 4;  // items of 4 pairs per head
@@ -214,8 +215,14 @@ __global__ __launch_bounds__(RB) void k_qkv_finalize(const float *__restrict__ p
         if (bv) {
           x.x += to_f<T>(bv[c0]); x.y += to_f<T>(bv[c0 + 1]); x.z += to_f<T>(bv[c0 + 2]); x.w += to_f<T>(bv[c0 + 3]);
         }
-        T *dv = vc + (size_t)r * dkv + c0;
-        dv[0] = from_f<T>(x.x); dv[1] = from_f<T>(x.y); dv[2] = from_f<T>(x.z); dv[3] = from_f<T>(x.w);
+        T *vrow = vc + (size_t)r * dkv + c0;
+        const T n0 = from_f<T>(x.x), n1 = from_f<T>(x.y), n2 = from_f<T>(x.z), n3 = from_f<T>(x.w);
+        if (dv_out) {  // residual of the stored values, before the merge overwrites the cached row
+          T *d = dv_out + (size_t)r * dkv + c0;
+          d[0] = from_f<T>(to_f<T>(n0) - to_f<T>(vrow[0])); d[1] = from_f<T>(to_f<T>(n1) - to_f<T>(vrow[1]));
+          d[2] = from_f<T>(to_f<T>(n2) - to_f<T>(vrow[2])); d[3] = from_f<T>(to_f<T>(n3) - to_f<T>(vrow[3]));
+        }
+        vrow[0] = n0; vrow[1] = n1; vrow[2] = n2; vrow[3] = n3;
       }
     }
   }
@@ -324,16 +331,16 @@ void launch_swiglu_finalize(DType t, const float *part, int splits, size_t split
 void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_stride,
                          const float *rope_tab, Rows rows, int L, int H, int Hkv, int dh,
                          const void *bq, const void *bk, const void *bv, void *q_out, void *k_cache,
-                         void *v_cache, hipStream_t s) {
+                         void *v_cache, void *dv_out, hipStream_t s) {
   if (rows.cap <= 0) return;
   if (t == F32)
     k_qkv_finalize<float><<<row_grid(rows.cap), RB, 0, s>>>(
         part, splits, split_stride, rope_tab, rows, L, H, Hkv, dh, (const float *)bq, (const float *)bk,
-        (const float *)bv, (float *)q_out, (float *)k_cache, (float *)v_cache);
+        (const float *)bv, (float *)q_out, (float *)k_cache, (float *)v_cache, (float *)dv_out);
   else
     k_qkv_finalize<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>(
         part, splits, split_stride, rope_tab, rows, L, H, Hkv, dh, (const bf16_t *)bq, (const bf16_t *)bk,
-        (const bf16_t *)bv, (bf16_t *)q_out, (bf16_t *)k_cache, (bf16_t *)v_cache);
+        (const bf16_t *)bv, (bf16_t *)q_out, (bf16_t *)k_cache, (bf16_t *)v_cache, (bf16_t *)dv_out);
 }
 
 inline int sal_grid(int cap) { return cap < 1 ? 1 : (cap > 65536 ? 65536 : cap); }
@@ -352,6 +359,89 @@ void launch_saliency(DType t, const void *c_new, void *c_cache, Rows rows, int D
 void launch_compact(const uint8_t *flag, Rows rows, int B, int L, int32_t *out_idx,
                     int32_t *out_offsets, int out_cap, int32_t *status, hipStream_t s) {
   k_compact<<<1, CB, 0, s>>>(flag, rows, B, L, out_idx, out_offsets, out_cap, status, -6);
+}
+
+// ---- approximate context update of the non-salient rows  [Sec. 3.3; Alg. 3 lines C <- ..., cosine] --
+__global__ __launch_bounds__(256) void k_mark_rows(Rows rows, int32_t *pos) {
+  const int n = row_count(rows);
+  for (int j = blockIdx.x * 256 + threadIdx.x; j < n; j += gridDim.x * 256) pos[rows.idx ? rows.idx[j] : j] = j + 1;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_clear_rows(Rows rows, int32_t *pos, T *dv, int dkv) {
+  const int n = row_count(rows);
+  constexpr int N = Vec16<T>::N;
+  Vec16<T> zero;
+#pragma unroll
+  for (int e = 0; e < N; ++e) zero.set(e, 0.f);
+  for (int j = blockIdx.x; j < n; j += gridDim.x) {
+    const int r = rows.idx ? rows.idx[j] : j;
+    if (threadIdx.x == 0) pos[r] = 0;
+    for (int v = threadIdx.x; v < dkv / N; v += 256) st16(dv + (size_t)r * dkv + v * N, zero);
+  }
+}
+
+// One workgroup per token.  Salient tokens (pos != 0) take their exact row, all others the cached row
+// plus the approximate residual; the cosine is taken over the stored (rounded) values against the
+// cached row, which is read before it is overwritten.
+template <typename T>
+__global__ __launch_bounds__(SAL_NT) void k_saliency_approx(int n, int D, const T *__restrict__ c_sal,
+                                                             const T *__restrict__ dc,
+                                                             const int32_t *__restrict__ pos, T *c_cache,
+                                                             float tau, float *__restrict__ cos_out,
+                                                             uint8_t *__restrict__ flag_out) {
+  __shared__ float red[3 * SAL_NT / WAVE];
+  constexpr int N = Vec16<T>::N;
+  const int nv = D / N;
+  for (int r = blockIdx.x; r < n; r += gridDim.x) {
+    const int p = pos[r];
+    T *b = c_cache + (size_t)r * D;
+    const T *src = p ? c_sal + (size_t)(p - 1) * D : dc + (size_t)r * D;
+    float dot = 0.f, na = 0.f, nb = 0.f;
+    for (int v = threadIdx.x; v < nv; v += SAL_NT) {
+      const Vec16<T> vs = ld16(src + v * N), vb = ld16(b + v * N);
+      Vec16<T> vn;
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        const float fb = vb.get(i);
+        vn.set(i, p ? vs.get(i) : fb + vs.get(i));
+        const float fa = vn.get(i);
+        dot += fa * fb;
+        na += fa * fa;
+        nb += fb * fb;
+      }
+      st16(b + v * N, vn);
+    }
+    block_sum3<SAL_NT>(dot, na, nb, red);
+    if (threadIdx.x == 0) {
+      const float s = dot / (fmaxf(sqrtf(na), 1e-8f) * fmaxf(sqrtf(nb), 1e-8f));
+      if (cos_out) cos_out[r] = s;
+      flag_out[r] = (s < tau) ? 1 : 0;
+    }
+  }
+}
+
+void launch_mark_rows(Rows rows, int32_t *pos, hipStream_t s) {
+  if (rows.cap <= 0) return;
+  k_mark_rows<<<(rows.cap + 255) / 256, 256, 0, s>>>(rows, pos);
+}
+
+void launch_saliency_approx(DType t, int T, int D, const void *c_sal, const void *dc, const int32_t *pos,
+                            void *c_cache, float tau, float *cos_out, uint8_t *flag_out, hipStream_t s) {
+  if (T <= 0) return;
+  const int grid = T > 65536 ? 65536 : T;
+  if (t == F32)
+    k_saliency_approx<float><<<grid, SAL_NT, 0, s>>>(T, D, (const float *)c_sal, (const float *)dc, pos,
+                                                    (float *)c_cache, tau, cos_out, flag_out);
+  else
+    k_saliency_approx<bf16_t><<<grid, SAL_NT, 0, s>>>(T, D, (const bf16_t *)c_sal, (const bf16_t *)dc, pos,
+                                                     (bf16_t *)c_cache, tau, cos_out, flag_out);
+}
+
+void launch_clear_rows(DType t, Rows rows, int32_t *pos, void *dv, int dkv, hipStream_t s) {
+  if (rows.cap <= 0) return;
+  if (t == F32) k_clear_rows<float><<<row_grid(rows.cap), 256, 0, s>>>(rows, pos, (float *)dv, dkv);
+  else k_clear_rows<bf16_t><<<row_grid(rows.cap), 256, 0, s>>>(rows, pos, (bf16_t *)dv, dkv);
 }
 
 void launch_fill_i32(int32_t *p, int32_t v, int n, hipStream_t s) {

@@ -95,6 +95,14 @@ class Layer:
                             self.cos if want_cos else None)
         return out
 
+    def layer_step_approx(self, x_dev: torch.Tensor, idx_in: B_.IndexList, tau: float,
+                          idx_out: Optional[B_.IndexList] = None, cos_out: Optional[torch.Tensor] = None):
+        """Sparse step with the approximate update of the other tokens; the context must cover B*L rows.
+        cos_out: [B*L] fp32 (by token) or None."""
+        out = self.idx_out if idx_out is None else idx_out
+        self.ctx.layer_step_approx(self.w, self.cache, x_dev, idx_in, self.B, self.L, tau, out, cos_out)
+        return out
+
     def read_list(self, il: B_.IndexList) -> Tuple[np.ndarray, np.ndarray]:
         off = il.offsets.cpu().numpy()
         n = int(off[-1])

@@ -1,0 +1,184 @@
+"""Parity of dyllm_layer_step_approx (exact rows for idx_in, approximate context update for every
+other token) against the CPU oracle, through the C ABI: two consecutive steps with disjoint
+candidate sets on small fp32 / bf16 shapes (the second checks that the step's scratch maps were
+cleared), the structural cases, and one step at the 8B layer shape."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dyllm_oracle as O
+from paper_2603_08026_amd import binding as Bd
+from paper_2603_08026_amd.layer import Layer
+from synth import workload as W
+from tests.helpers import (BAND, TOL, assert_close, assert_index_sets_match, oracle_cfg, rand_rows,
+                           rand_weights, small_shape)
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print("[case]", *a, flush=True)
+
+
+def _round(v, dtype):
+    v = np.asarray(v, dtype=np.float32)
+    return W.round_bf16(v) if dtype == "bf16" else v
+
+
+def _teacher_force(lay, ref, dtype):
+    """Both sides start the step from the oracle's caches rounded to the storage type."""
+    start = {k: _round(v, dtype) for k, v in ref.items()}
+    lay.set_caches(start)
+    return {k: v.astype(np.float64) for k, v in start.items()}
+
+
+def _check_step(lay, ref, w, cfg, x, idx, off, tau, what, expect_outside=False):
+    s_dtype = lay.dtype
+    T = lay.B * lay.L
+    idx_ref, off_ref, cos_ref = O.layer_step_approx(x, idx, w, cfg, ref, tau)
+    outside_ref = np.setdiff1d(idx_ref, idx)
+    if expect_outside:
+        assert outside_ref.size > 0, "%s: the case does not select any token outside idx_in" % what
+    full = Bd.IndexList.empty(T, lay.B)
+    cos = torch.zeros(T, dtype=torch.float32, device="cuda")
+    out = lay.layer_step_approx(lay.upload(x), lay.make_list(idx, off), tau, full, cos)
+    assert lay.ctx.poll_status() == 0
+    idx_g, off_g = lay.read_list(out)
+    cos_g = cos.cpu().numpy()
+    assert np.max(np.abs(cos_g - cos_ref)) < (5e-5 if s_dtype == "f32" else 2e-2), what
+    assert_index_sets_match(idx_g, idx_ref, np.arange(T), cos_ref, tau, what)
+    if np.all(np.abs(cos_ref - tau) > BAND):
+        assert np.array_equal(idx_g, idx_ref) and np.array_equal(off_g, off_ref)
+    assert off_g[-1] == idx_g.size
+    for b in range(lay.B):
+        seg = idx_g[off_g[b]:off_g[b + 1]]
+        assert np.all((seg >= b * lay.L) & (seg < (b + 1) * lay.L))
+    got = lay.get_caches()
+    tol = TOL[s_dtype]
+    for name in ("k", "v", "c"):
+        assert_close(got[name].reshape(T, -1), ref[name].reshape(T, -1), tol, "%s: %s cache" % (what, name))
+    # output rows: those selected on both sides were recomputed on both sides
+    both = np.intersect1d(idx_g, idx_ref)
+    assert_close(got["out"].reshape(T, -1)[both], ref["out"].reshape(T, -1)[both], tol, "%s: out rows" % what)
+    return idx_g, idx_ref, cos_ref
+
+
+@pytest.mark.parametrize("dtype,gqa,dh", [("f32", False, 64), ("f32", True, 64), ("bf16", True, 128),
+                                          ("bf16", False, 64)])
+def test_two_steps_against_oracle(dtype, gqa, dh):
+    _say("approx two steps", dtype, "gqa" if gqa else "mha", dh)
+    s = small_shape(dtype, gqa=gqa, dh=dh)
+    cfg = oracle_cfg(s)
+    B, L = 2, 200  # several query / key tiles and a ragged tail in both precisions
+    T = B * L
+    w = rand_weights(s, 61, bias=gqa, std=0.08)
+    lay = Layer.from_shape(s, B, L)
+    lay.set_weights(w)
+    x0 = _round(W.philox(62, "x0").standard_normal((B, L, s.hidden), dtype=np.float32), dtype)
+    ref = O.new_caches(B, L, cfg)
+    O.full_step(x0, w, cfg, ref)
+    lay.full_step(lay.upload(x0))
+    ref = _teacher_force(lay, ref, dtype)
+
+    # step 1: 25 % / 10 % of the tokens move, a third of them a lot -> contexts of untouched tokens
+    # move too, and tau at the median cosine of the untouched tokens selects some of them
+    idx, off = rand_rows(63, B, L, [50, 21])
+    sig = 10.0 ** W.philox(64, "sig").uniform(-3, -0.5, idx.size)
+    sig[::3] = 2.0
+    x1 = x0.copy().reshape(T, -1)
+    x1[idx] = W.perturbed_rows(x1[idx], sig, 65)
+    x1 = _round(x1, dtype).reshape(B, L, -1)
+    probe = O.layer_step_approx(x1, idx, w, cfg, {k: v.copy() for k, v in ref.items()}, 0.5)[2]
+    others = np.setdiff1d(np.arange(T), idx)
+    tau = float(np.median(probe[others]))
+    idx_g, idx_ref, cos_ref = _check_step(lay, ref, w, cfg, x1, idx, off, tau, "step 1", expect_outside=True)
+    assert 0 < idx_ref.size < T
+    # rows that no side selected keep their output row
+    kept = np.setdiff1d(np.arange(T), np.union1d(idx_g, idx_ref))
+    assert kept.size > 0
+
+    # step 2: a smaller, disjoint candidate set; stale entries of the step-1 maps would show here
+    ref = _teacher_force(lay, ref, dtype)
+    pool = np.setdiff1d(np.arange(T), idx)
+    pick = np.sort(W.philox(66, "pick").choice(pool, size=17, replace=False)).astype(np.int32)
+    off2 = np.searchsorted(pick, np.arange(B + 1) * L).astype(np.int32)
+    x2 = x1.copy().reshape(T, -1)
+    x2[pick] = W.perturbed_rows(x2[pick], np.full(pick.size, 0.7), 67)
+    x2 = _round(x2, dtype).reshape(B, L, -1)
+    probe = O.layer_step_approx(x2, pick, w, cfg, {k: v.copy() for k, v in ref.items()}, 0.5)[2]
+    tau2 = float(np.quantile(probe, 0.2))
+    _check_step(lay, ref, w, cfg, x2, pick, off2, tau2, "step 2")
+    lay.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_structure(dtype):
+    _say("approx structure", dtype)
+    s = small_shape(dtype, gqa=True)
+    B, L = 2, 80
+    T = B * L
+    w = rand_weights(s, 71, bias=True)
+    lay = Layer.from_shape(s, B, L)
+    lay.set_weights(w)
+    x0 = _round(W.philox(72, "x").standard_normal((B, L, s.hidden), dtype=np.float32), dtype)
+    x1 = _round(W.philox(73, "x").standard_normal((B, L, s.hidden), dtype=np.float32), dtype)
+    lay.full_step(lay.upload(x0))
+    snap = {k: getattr(lay, k).clone() for k in ("k", "v", "c", "out")}
+    full = Bd.IndexList.empty(T, B)
+    # (i) empty idx_in: the residual is zero, every cosine is 1, nothing changes, nothing selected
+    for cap in (8, 0):
+        empty = lay.make_list(np.zeros(0, np.int32), np.zeros(B + 1, np.int32), cap=cap)
+        cos = torch.zeros(T, dtype=torch.float32, device="cuda")
+        out = lay.layer_step_approx(lay.upload(x1), empty, 0.99, full, cos)
+        idx_g, off_g = lay.read_list(out)
+        assert idx_g.size == 0 and off_g.tolist() == [0] * (B + 1)
+        assert float(cos.min()) >= 1 - 1e-5
+        for k in snap:
+            assert torch.equal(getattr(lay, k), snap[k]), k
+    # (ii) idx_in = all rows, tau > 1: no token takes the approximate path; equals the exact step
+    allrows = lay.make_list(np.arange(T, dtype=np.int32), np.arange(B + 1, dtype=np.int32) * L)
+    out = lay.layer_step_approx(lay.upload(x1), allrows, 1.5, full, None)
+    idx_g, off_g = lay.read_list(out)
+    assert np.array_equal(idx_g, np.arange(T)) and off_g.tolist() == [0, L, 2 * L]
+    approx = lay.get_caches()
+    for k in snap:
+        getattr(lay, k).copy_(snap[k])
+    lay.layer_step(lay.upload(x1), allrows, 1.5, full)
+    exact = lay.get_caches()
+    for k in exact:
+        assert_close(approx[k], exact[k], 1e-6 if dtype == "f32" else 1e-2, "all rows: %s" % k)
+    # (iii) a context too small for B*L rows is refused; a short output list reports the overflow
+    small = Layer.from_shape(s, B, L, max_rows=32)
+    small.set_weights(w)
+    some, off = rand_rows(74, B, L, [5, 6])
+    with pytest.raises(Bd.DyllmError) as ei:
+        small.layer_step_approx(small.upload(x1), small.make_list(some, off), 0.9)
+    assert ei.value.code == Bd.ERR_CAPACITY
+    small.close()
+    short = Bd.IndexList.empty(4, B)
+    lay.layer_step_approx(lay.upload(x0), allrows, 1.5, short, None)
+    torch.cuda.synchronize()
+    assert lay.ctx.poll_status() == Bd.ERR_CAPACITY
+    assert lay.ctx.poll_status() == 0
+    lay.close()
+
+
+def test_c2_shape_one_step():
+    """One sparse step with the approximate update at the 8B layer shape (batch 1, 1024 tokens)."""
+    wl = replace(W.CONFIGS["c2"], t_full=1)
+    _say("approx", wl.name)
+    s = wl.shape
+    cfg = oracle_cfg(s)
+    w = W.make_weights(s, layer=0)
+    lay = Layer.from_shape(s, wl.batch, wl.seq)
+    lay.set_weights(w)
+    ref = O.new_caches(wl.batch, wl.seq, cfg)
+    steps = list(W.step_stream(wl, 2))
+    O.full_step(steps[0].x, w, cfg, ref)
+    lay.full_step(lay.upload(steps[0].x))
+    ref = _teacher_force(lay, ref, s.dtype)
+    st = steps[1]
+    _check_step(lay, ref, w, cfg, st.x, st.idx, st.offsets, wl.tau, "c2 approx")
+    lay.close()
