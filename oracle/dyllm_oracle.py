@@ -24,6 +24,13 @@ What each function follows:
   stack_step, stack_full_step ..... the layer loops of Alg. 3 and Alg. 2: a layer
                                     reads the previous layer's output cache and,
                                     in Alg. 3, the previous layer's salient set
+  Schedule, step_kind, merge_lists,
+  denoise_step .................... App. C.1, Alg. 1 (the generation loop) without
+                                    its token side: dense warm-up steps, then sparse
+                                    steps that take the whole sequence every
+                                    full_period-th step and the response only
+                                    otherwise (Sec. 3.5), the salient set carried
+                                    from step to step
   compact ......................... the where(...) of Alg. 3
   rmsnorm ......................... App. E, proof of Prop. 1 (RMSNorm definition)
 
@@ -381,26 +388,32 @@ def approx_attention(q_all: np.ndarray, k_cache: np.ndarray, dv: np.ndarray, idx
 
 
 def layer_step_approx(x: np.ndarray, idx_in: np.ndarray, w: Dict[str, np.ndarray], cfg: LayerCfg,
-                      caches: Dict[str, np.ndarray], tau: float):
+                      caches: Dict[str, np.ndarray], tau: float, row_lo: int = 0):
     """One layer of SparseStep with both attention paths.  [Alg. 3 layer body; Sec. 3.3]
 
-    As layer_step, plus: queries are projected for ALL tokens; the value residual dV of the idx_in
-    tokens is taken before their V rows are merged; every token outside idx_in gets
+    As layer_step, plus: queries are projected for ALL tokens of the step; the value residual dV of
+    the idx_in tokens is taken before their V rows are merged; every other token of the step gets
     C = C_cached + approx_attention(...) (Sec. 3.3, non-salient path); the cosine test then runs over
-    ALL tokens, so idx_out may hold tokens that were not in idx_in.  Returns (idx_out, offsets_out,
-    cos) with cos of length B*L.
+    ALL tokens of the step, so idx_out may hold tokens that were not in idx_in.
+
+    row_lo > 0 is a response-only step (Sec. 3.5; Alg. 3, comment on its first line): the step's
+    tokens are the positions [row_lo, L) of every sequence, the keys and values still cover the whole
+    sequence (App. C.4), tokens below row_lo keep every cache row and take no part in the test.
+    Returns (idx_out, offsets_out, cos) with cos of length B*L (1 for tokens outside the step).
     """
     x = _f64(x)
     B, L, d = x.shape
     T = B * L
     idx_in = np.asarray(idx_in, dtype=np.int64)
+    assert np.all(idx_in % L >= row_lo), "a response-only step takes no prompt token"
     xf = x.reshape(T, d)
     kc = caches["k"].reshape(T, cfg.n_kv_heads, cfg.head_dim)
     vc = caches["v"].reshape(T, cfg.n_kv_heads, cfg.head_dim)
     cc = caches["c"].reshape(T, cfg.n_heads * cfg.head_dim)
     oc = caches["out"].reshape(T, d)
     pos_all = np.arange(T) % L
-    # norm and q projection of every token; k, v of the salient tokens only
+    step_rows = np.flatnonzero(pos_all >= row_lo)
+    # norm and q projection of every token of the step; k, v of the salient tokens only
     n_all = rmsnorm(xf, w["g_attn"], cfg.rms_eps)
     q_all = n_all @ _f64(w["wq"]).T
     if w.get("bq") is not None:
@@ -414,11 +427,13 @@ def layer_step_approx(x: np.ndarray, idx_in: np.ndarray, w: Dict[str, np.ndarray
         vc[idx_in] = v
         c_sal = partial_attention(q_all[idx_in], caches["k"], caches["v"], idx_in, B, L)
         dc = approx_attention(q_all, caches["k"], dv, idx_in, B, L)
-        others = np.setdiff1d(np.arange(T), idx_in)
+        others = np.setdiff1d(step_rows, idx_in)
         c_new[others] = cc[others] + dc[others]
         c_new[idx_in] = c_sal
-    cos = cosine_rows(c_new, cc)
-    flag = salient_mask(cos, tau)
+    cos = np.ones(T, dtype=F64)
+    cos[step_rows] = cosine_rows(c_new[step_rows], cc[step_rows])
+    flag = np.zeros(T, dtype=bool)
+    flag[step_rows] = salient_mask(cos[step_rows], tau)
     cc[:] = c_new
     idx_out, offsets_out = compact(flag, None, B, L)
     salient_ffn(xf, cc, idx_out, w, cfg, oc)
@@ -448,6 +463,67 @@ def stack_full_step(x: np.ndarray, ws, cfg: LayerCfg, caches) -> None:
     for w, c in zip(ws, caches):
         full_step(h, w, cfg, c)
         h = c["out"]
+
+
+def stack_step_approx(x: np.ndarray, idx_in: np.ndarray, ws, cfg: LayerCfg, caches, tau: float,
+                      row_lo: int = 0):
+    """SparseStep over a stack of layers with both attention paths.  [Alg. 3, loop over l]"""
+    h, idx = x, idx_in
+    per_layer = []
+    for w, c in zip(ws, caches):
+        idx, off, cos = layer_step_approx(h, idx, w, cfg, c, tau, row_lo)
+        per_layer.append((idx, off, cos))
+        h = c["out"]
+    return per_layer
+
+
+@dataclass(frozen=True)
+class Schedule:
+    """The step schedule of the generation loop.  [App. C.1, Alg. 1; Sec. 3.2; Sec. 3.5]"""
+    t_full: int        # leading dense steps
+    full_period: int   # a sparse step t with t % full_period == 0 takes the whole sequence ...
+    prompt_len: int    # ... every other one only the positions [prompt_len, L) of each sequence
+    approx: bool       # approximate update of the non-salient tokens (Sec. 3.3) on or off
+    tau: float
+
+
+def step_kind(t: int, sched: Schedule) -> str:
+    """'dense' for the first t_full steps, then 'full' (whole sequence) or 'response'.  [Alg. 1]"""
+    if t < sched.t_full:
+        return "dense"
+    return "full" if (sched.full_period <= 1 or t % sched.full_period == 0) else "response"
+
+
+def merge_lists(a: Optional[np.ndarray], b: Optional[np.ndarray], L: int, pos_lo: int) -> np.ndarray:
+    """Ascending unique union of two token lists, kept to positions >= pos_lo of their sequence."""
+    parts = [np.asarray(v, dtype=np.int64) for v in (a, b) if v is not None]
+    u = np.unique(np.concatenate(parts)) if parts else np.zeros(0, dtype=np.int64)
+    return u[u % L >= pos_lo]
+
+
+def denoise_step(t: int, sched: Schedule, x: np.ndarray, decoded: np.ndarray, carry: Optional[np.ndarray],
+                 ws, cfg: LayerCfg, caches):
+    """One iteration of the generation loop without its token side.  [App. C.1, Alg. 1]
+
+    x: hidden states of the whole sequence [B, L, d] (a response-only step reads the response rows
+    only); decoded: tokens unmasked by the previous step; carry: the salient set the previous sparse
+    step returned, or None after a dense step.  Dense step: FullStep, returns None.  Sparse step:
+    the candidates are the decoded positions when there is no carried set (Alg. 1), else the carried
+    set joined with the decoded positions (reading: a token whose input embedding just changed must
+    be recomputed), kept to the step's tokens; returns the last layer's salient set.
+    """
+    kind = step_kind(t, sched)
+    if kind == "dense":
+        stack_full_step(x, ws, cfg, caches)
+        return None
+    B, L, _ = np.asarray(x).shape
+    row_lo = 0 if kind == "full" else sched.prompt_len
+    idx = merge_lists(carry, decoded, L, row_lo)
+    if sched.approx:
+        per_layer = stack_step_approx(x, idx, ws, cfg, caches, sched.tau, row_lo)
+    else:
+        per_layer = stack_step(x, idx, ws, cfg, caches, sched.tau)
+    return per_layer[-1][0]
 
 
 def kv_only_bytes_per_token(cfg: LayerCfg, elem: int) -> int:

@@ -619,3 +619,106 @@ def test_layer_step_approx_structure():
     # rows not selected keep their cached output
     kept = np.setdiff1d(np.arange(T), out)
     assert np.array_equal(c["out"].reshape(T, -1)[kept], caches["out"].reshape(T, -1)[kept])
+
+
+# ---- response-only steps and the step schedule  [Sec. 3.5; App. C.1, Alg. 1] -----------------------
+
+def test_merge_lists_vs_python_sets():
+    r = _rng(41)
+    L = 12
+    for _ in range(20):
+        a = np.sort(r.choice(3 * L, size=int(r.integers(0, 15)), replace=False))
+        b = np.sort(r.choice(3 * L, size=int(r.integers(0, 15)), replace=False))
+        lo = int(r.integers(0, L))
+        want = sorted(t for t in set(a.tolist()) | set(b.tolist()) if t % L >= lo)
+        assert O.merge_lists(a, b, L, lo).tolist() == want
+        assert O.merge_lists(None, b, L, lo).tolist() == sorted(t for t in b.tolist() if t % L >= lo)
+    assert O.merge_lists(None, None, L, 0).size == 0
+
+
+def test_step_kinds_follow_the_schedule():
+    s = O.Schedule(t_full=4, full_period=4, prompt_len=6, approx=False, tau=0.99)
+    kinds = [O.step_kind(t, s) for t in range(16)]
+    assert kinds[:4] == ["dense"] * 4
+    assert [k for t, k in enumerate(kinds) if t >= 4 and t % 4 == 0] == ["full"] * 3
+    assert all(k == "response" for t, k in enumerate(kinds) if t >= 4 and t % 4)
+    # three of four sparse steps take the response only (Sec. 3.5 / App. C.1: 75 % of the steps)
+    sparse = [O.step_kind(t, s) for t in range(4, 4 + 400)]
+    assert sparse.count("response") / len(sparse) == 0.75
+    assert O.step_kind(9, O.Schedule(2, 1, 6, False, 0.9)) == "full"
+
+
+def test_response_only_step_of_the_approximate_path():
+    """A response-only step computes, for every response token, exactly what the whole-sequence step
+    computes for it (rows are independent given K, V), and leaves the prompt tokens alone."""
+    r, cfg, w, x0, caches = _setup(seed=43)
+    B, L, T, lo = 2, 10, 20, 4
+    idx = np.array([5, 8, 14, 19])  # response tokens only
+    x1 = x0.copy()
+    x1.reshape(T, -1)[idx] = 2.0 * r.normal(size=(idx.size, 16))
+    x1.reshape(T, -1)[[1, 12]] += 5.0  # prompt inputs differ too: a response-only step never reads them
+    full, resp = _copy(caches), _copy(caches)
+    of, _, cf = O.layer_step_approx(x1, idx, w, cfg, full, 0.999)
+    orr, offr, cr = O.layer_step_approx(x1, idx, w, cfg, resp, 0.999, row_lo=lo)
+    pos = np.arange(T) % L
+    in_resp = pos >= lo
+    assert np.array_equal(orr, of[in_resp[of]])
+    assert offr[-1] == orr.size and np.all(cr[~in_resp] == 1.0)
+    assert np.allclose(cr[in_resp], cf[in_resp], atol=1e-13)
+    for k in ("k", "v", "c", "out"):
+        a, b_ = resp[k].reshape(T, -1), full[k].reshape(T, -1)
+        assert np.allclose(a[in_resp], b_[in_resp], atol=1e-12), k
+        assert np.array_equal(a[~in_resp], caches[k].reshape(T, -1)[~in_resp]), k
+    # some prompt token does move in the whole-sequence step, so the restriction is not vacuous
+    assert not np.allclose(full["c"].reshape(T, -1)[~in_resp], caches["c"].reshape(T, -1)[~in_resp])
+    with pytest.raises(AssertionError):
+        O.layer_step_approx(x1, np.array([1, 5]), w, cfg, _copy(caches), 0.9, row_lo=lo)
+
+
+@pytest.mark.parametrize("approx", [False, True])
+def test_denoise_step_composes_the_schedule(approx):
+    r, cfg, ws, x, caches = _stack_setup(n_layers=2, seed=45)
+    B, L, T = 2, 10, 20
+    s = O.Schedule(t_full=2, full_period=4, prompt_len=4, approx=approx, tau=0.999)
+    # dense steps: FullStep through the stack, no carried set
+    a, b_ = [_copy(c) for c in caches], [_copy(c) for c in caches]
+    assert O.denoise_step(0, s, x, np.array([3]), None, ws, cfg, a) is None
+    O.stack_full_step(x, ws, cfg, b_)
+    for ca, cb in zip(a, b_):
+        for k in ca:
+            assert np.array_equal(ca[k], cb[k])
+    # first sparse step (t = 2, response-only): no carried set -> the decoded positions, kept to the response
+    decoded = np.array([2, 6, 17])
+    x1 = x.copy()
+    x1.reshape(T, -1)[decoded] = r.normal(size=(3, x.shape[-1]))
+    c1, c2 = [_copy(c) for c in a], [_copy(c) for c in a]
+    carry = O.denoise_step(2, s, x1, decoded, None, ws, cfg, c1)
+    cand = np.array([6, 17])
+    if approx:
+        want = O.stack_step_approx(x1, cand, ws, cfg, c2, s.tau, row_lo=4)[-1][0]
+    else:
+        want = O.stack_step(x1, cand, ws, cfg, c2, s.tau)[-1][0]
+    assert np.array_equal(carry, want)
+    for ca, cb in zip(c1, c2):
+        for k in ca:
+            assert np.array_equal(ca[k], cb[k])
+    # a whole-sequence step (t = 4): carried set joined with the newly decoded positions, prompt included
+    decoded2 = np.array([1, 13])
+    c3, c4 = [_copy(c) for c in c1], [_copy(c) for c in c1]
+    carry2 = O.denoise_step(4, s, x1, decoded2, carry, ws, cfg, c3)
+    cand2 = np.union1d(carry, decoded2)
+    if approx:
+        want2 = O.stack_step_approx(x1, cand2, ws, cfg, c4, s.tau)[-1][0]
+    else:
+        want2 = O.stack_step(x1, cand2, ws, cfg, c4, s.tau)[-1][0]
+    assert np.array_equal(carry2, want2)
+    # with the approximate path off, a response-only step equals the whole-sequence step whenever no
+    # prompt token is a candidate
+    if not approx:
+        c5, c6 = [_copy(c) for c in c1], [_copy(c) for c in c1]
+        r5 = O.denoise_step(5, s, x1, np.array([7]), np.array([6, 17]), ws, cfg, c5)   # response-only
+        r6 = O.denoise_step(8, s, x1, np.array([7]), np.array([6, 17]), ws, cfg, c6)   # whole sequence
+        assert np.array_equal(r5, r6)
+        for ca, cb in zip(c5, c6):
+            for k in ca:
+                assert np.array_equal(ca[k], cb[k])
