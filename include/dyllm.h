@@ -175,21 +175,80 @@ int dyllm_layer_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_c
                      dyllm_index_list *idx_out, float *cos_out, void *stream);
 
 /* One layer of SparseStep with both attention paths: exact rows for the tokens of idx_in, and for
- * every other token the approximate update of its cached context.  [Sec. 3.3; Alg. 3 layer body;
- * Alg. 4; Eq. 3]
- *   q of ALL tokens is recomputed from x; K, V of the tokens in idx_in are recomputed and merged
- *   into the caches, dV = V_new - V_cache of those tokens taken before the merge;
+ * every other token of the step the approximate update of its cached context.  [Sec. 3.3; Alg. 3
+ * layer body; Alg. 4; Eq. 3]
+ *   The step's tokens are the positions [row_lo, L) of every sequence: row_lo = 0 is a whole-sequence
+ *   step, row_lo = L_P a response-only step (Sec. 3.5), in which the tokens below row_lo keep every
+ *   cache row and take no part in the test, while keys and values still cover the whole sequence
+ *   (App. C.4).  idx_in must hold tokens of the step only.
+ *   q of ALL tokens of the step is recomputed from x; K, V of the tokens in idx_in are recomputed and
+ *   merged into the caches, dV = V_new - V_cache of those tokens taken before the merge;
  *   C[idx_in]  = softmax(q K^T / sqrt(dh)) V            (against the merged caches),
  *   C[others] = C_cache + softmax(q K^T / sqrt(dh))[:, idx_in] dV   (normalised over ALL keys);
- *   the cosine test then runs over ALL B*L tokens (new context against the cached one), the context
- *   cache takes the new rows, and idx_out receives every token whose cosine fell below tau -- it may
- *   hold tokens outside idx_in, so idx_out->cap should be B*L (overflow sets DYLLM_ERR_CAPACITY in
- *   the status word as for dyllm_compact).  out-projection and FFN run for idx_out only.
- * cos_out: [B*L] (by token) or NULL.  Needs a context with max_rows covering B*L.  An empty idx_in
- * leaves every cache byte unchanged and yields an empty idx_out. */
+ *   the cosine test then runs over ALL tokens of the step (new context against the cached one), the
+ *   context cache takes the new rows, and idx_out receives every token whose cosine fell below tau --
+ *   it may hold tokens outside idx_in, so idx_out->cap should be B*(L-row_lo) (overflow sets
+ *   DYLLM_ERR_CAPACITY in the status word as for dyllm_compact).  Out-projection and FFN run for
+ *   idx_out only.
+ * cos_out: [B*L] indexed by token (entries of tokens outside the step are not written) or NULL.
+ * Needs a context with max_rows covering B*L.  An empty idx_in leaves every cached value unchanged
+ * and yields an empty idx_out. */
 int dyllm_layer_step_approx(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
                             const void *x, const dyllm_index_list *idx_in, int32_t B, int32_t L,
-                            float tau, dyllm_index_list *idx_out, float *cos_out, void *stream);
+                            int32_t row_lo, float tau, dyllm_index_list *idx_out, float *cos_out,
+                            void *stream);
+
+/* dyllm_layer_step_approx through a stack of n_layers layers, chained like dyllm_stack_step.  [Alg. 3,
+ * loop over l]  The selections may grow from layer to layer: every idx_out[l] should have capacity
+ * B*(L-row_lo).  cos_out: NULL or [n_layers, B*L]. */
+int dyllm_stack_step_approx(dyllm_ctx *ctx, int32_t n_layers, const dyllm_layer_weights *w,
+                            dyllm_layer_cache *caches, const void *x, const dyllm_index_list *idx_in,
+                            int32_t B, int32_t L, int32_t row_lo, float tau, dyllm_index_list *idx_out,
+                            float *cos_out, void *stream);
+
+/* out = the ascending, duplicate-free union of the token lists a and b (either may be NULL), kept to
+ * the tokens at positions >= pos_lo of their sequence, with per-sequence offsets.  Serves the carry
+ * of the salient set from one denoising step to the next and the restriction of a response-only step
+ * to the response.  [App. C.1, Alg. 1: idx_sal across iterations; Sec. 3.5]
+ * out must not share buffers with a or b; more tokens than out->cap: the excess is dropped and the
+ * status word is set.  Needs a context with max_rows covering B*L. */
+int dyllm_merge_lists(dyllm_ctx *ctx, const dyllm_index_list *a, const dyllm_index_list *b, int32_t B,
+                      int32_t L, int32_t pos_lo, dyllm_index_list *out, void *stream);
+
+/* The step schedule of the generation loop.  [App. C.1, Alg. 1; Sec. 3.2; Sec. 3.5] */
+typedef struct {
+  int32_t t_full;      /* the first t_full steps are dense (FullStep) */
+  int32_t full_period; /* a later step t takes the whole sequence when t % full_period == 0 (the paper
+                          uses 4), the response only otherwise; <= 1: always the whole sequence */
+  int32_t prompt_len;  /* L_P: positions [0, L_P) of every sequence are the prompt */
+  int32_t approx;      /* non-zero: approximate update of the non-salient tokens (Sec. 3.3) */
+  float tau;
+} dyllm_schedule;
+#define DYLLM_STEP_DENSE 0
+#define DYLLM_STEP_FULL 1
+#define DYLLM_STEP_RESPONSE 2
+/* DYLLM_STEP_* of step t, or DYLLM_ERR_INVALID_ARG.  Host only. */
+int dyllm_step_kind(const dyllm_schedule *sched, int32_t t);
+
+/* One iteration of the generation loop without its token side (embedding, logits and unmasking stay
+ * with the caller).  [App. C.1, Alg. 1]
+ *   dense step:  dyllm_stack_full_step; decoded, carry, cand and idx_out are not used.
+ *   sparse step: cand = merge(carry, decoded) kept to the step's tokens (all, or the response), then
+ *     dyllm_stack_step (approx == 0; a response-only step then differs from a whole-sequence step only
+ *     by that restriction) or dyllm_stack_step_approx with cand as the first layer's idx_in.
+ * x: [B, L, d] hidden states of the whole sequence (a response-only step reads its response rows).
+ * decoded: tokens unmasked by the previous step, or NULL.  carry: idx_out[n_layers-1] of the previous
+ * sparse step, or NULL after a dense step (Alg. 1 then starts from the decoded positions alone).
+ * Reading taken where Alg. 1 is silent: later steps join the newly decoded positions to the carried
+ * set, since a token whose input embedding changed has to be recomputed.
+ * cand: scratch list that receives the candidates; idx_out: host array of n_layers lists as in
+ * dyllm_stack_step; idx_out[n_layers-1] is the next step's carry (it may be the same buffers as this
+ * step's carry: the carry is consumed before any layer writes).  cand must
+ * not share buffers with carry, decoded or idx_out[0]. */
+int dyllm_denoise_step(dyllm_ctx *ctx, const dyllm_schedule *sched, int32_t t, int32_t n_layers,
+                       const dyllm_layer_weights *w, dyllm_layer_cache *caches, const void *x,
+                       const dyllm_index_list *decoded, const dyllm_index_list *carry, int32_t B,
+                       int32_t L, dyllm_index_list *cand, dyllm_index_list *idx_out, void *stream);
 
 /* Dense pass of one layer over all B*L rows; fills all four caches.  [App. C.2, Alg. 2]
  * Needs a context with max_rows covering B*L. */

@@ -24,7 +24,7 @@ SYMBOLS = [
     "dyllm_workspace_bytes", "dyllm_create", "dyllm_destroy", "dyllm_strerror", "dyllm_last_error",
     "dyllm_poll_status", "dyllm_saliency", "dyllm_compact", "dyllm_qkv_refresh",
     "dyllm_partial_attention", "dyllm_salient_ffn", "dyllm_layer_step", "dyllm_layer_step_approx",
-    "dyllm_full_step",
+    "dyllm_stack_step_approx", "dyllm_merge_lists", "dyllm_step_kind", "dyllm_denoise_step", "dyllm_full_step",
     "dyllm_stack_step", "dyllm_stack_full_step",
     "dyllm_profile_begin", "dyllm_profile_end", "dyllm_stage_count", "dyllm_stage_name",
 ]
@@ -58,6 +58,14 @@ class IndexListC(C.Structure):
     _fields_ = [("idx", C.c_void_p), ("offsets", C.c_void_p), ("cap", C.c_int32)]
 
 
+class Schedule(C.Structure):
+    _fields_ = [("t_full", C.c_int32), ("full_period", C.c_int32), ("prompt_len", C.c_int32),
+                ("approx", C.c_int32), ("tau", C.c_float)]
+
+
+STEP_DENSE, STEP_FULL, STEP_RESPONSE = 0, 1, 2
+
+
 _lib = None
 
 
@@ -87,7 +95,14 @@ def load_library() -> C.CDLL:
     lib.dyllm_salient_ffn.argtypes = [vp, P(LayerWeights), vp, vp, P(IndexListC), i32, i32, vp, vp]
     lib.dyllm_layer_step.argtypes = [vp, P(LayerWeights), P(LayerCache), vp, P(IndexListC), i32, i32, f32,
                                      P(IndexListC), vp, vp]
-    lib.dyllm_layer_step_approx.argtypes = lib.dyllm_layer_step.argtypes
+    lib.dyllm_layer_step_approx.argtypes = [vp, P(LayerWeights), P(LayerCache), vp, P(IndexListC), i32, i32, i32,
+                                            f32, P(IndexListC), vp, vp]
+    lib.dyllm_stack_step_approx.argtypes = [vp, i32, P(LayerWeights), P(LayerCache), vp, P(IndexListC), i32, i32,
+                                            i32, f32, P(IndexListC), vp, vp]
+    lib.dyllm_merge_lists.argtypes = [vp, P(IndexListC), P(IndexListC), i32, i32, i32, P(IndexListC), vp]
+    lib.dyllm_step_kind.argtypes = [P(Schedule), i32]
+    lib.dyllm_denoise_step.argtypes = [vp, P(Schedule), i32, i32, P(LayerWeights), P(LayerCache), vp,
+                                       P(IndexListC), P(IndexListC), i32, i32, P(IndexListC), P(IndexListC), vp]
     lib.dyllm_full_step.argtypes = [vp, P(LayerWeights), P(LayerCache), vp, i32, i32, vp]
     lib.dyllm_stack_step.argtypes = [vp, i32, P(LayerWeights), P(LayerCache), vp, P(IndexListC), i32, i32, f32,
                                      P(IndexListC), vp, vp]
@@ -235,10 +250,39 @@ class Context:
                                               B, L, tau, C.byref(o), _ptr(cos_out), _stream()))
 
     def layer_step_approx(self, w: LayerWeights, cache: LayerCache, x, idx_in: IndexList, B, L, tau,
-                          idx_out: IndexList, cos_out=None):
+                          idx_out: IndexList, cos_out=None, row_lo=0):
         i, o = idx_in.c(), idx_out.c()
         self._check(self.lib.dyllm_layer_step_approx(self.h, C.byref(w), C.byref(cache), _ptr(x), C.byref(i),
-                                                     B, L, tau, C.byref(o), _ptr(cos_out), _stream()))
+                                                     B, L, row_lo, tau, C.byref(o), _ptr(cos_out), _stream()))
+
+    def stack_step_approx(self, ws, caches, x, idx_in: IndexList, B, L, tau, idx_outs, cos_out=None, row_lo=0):
+        n = len(ws)
+        wa = (LayerWeights * n)(*ws)
+        ca = (LayerCache * n)(*caches)
+        oa = (IndexListC * n)(*[o.c() for o in idx_outs])
+        i = idx_in.c()
+        self._check(self.lib.dyllm_stack_step_approx(self.h, n, wa, ca, _ptr(x), C.byref(i), B, L, row_lo, tau,
+                                                     oa, _ptr(cos_out), _stream()))
+
+    def merge_lists(self, a, b, B, L, pos_lo, out: IndexList):
+        """a, b: IndexList or None."""
+        ac, bc, oc = (a.c() if a is not None else None), (b.c() if b is not None else None), out.c()
+        self._check(self.lib.dyllm_merge_lists(self.h, C.byref(ac) if ac is not None else None,
+                                               C.byref(bc) if bc is not None else None, B, L, pos_lo,
+                                               C.byref(oc), _stream()))
+
+    def denoise_step(self, sched: Schedule, t, ws, caches, x, decoded, carry, B, L, cand: IndexList, idx_outs):
+        """decoded, carry: IndexList or None.  Returns the step kind (STEP_*)."""
+        n = len(ws)
+        wa = (LayerWeights * n)(*ws)
+        ca = (LayerCache * n)(*caches)
+        oa = (IndexListC * n)(*[o.c() for o in idx_outs])
+        dc, cc, kc = (decoded.c() if decoded is not None else None), (carry.c() if carry is not None else None), cand.c()
+        self._check(self.lib.dyllm_denoise_step(self.h, C.byref(sched), t, n, wa, ca, _ptr(x),
+                                                C.byref(dc) if dc is not None else None,
+                                                C.byref(cc) if cc is not None else None, B, L, C.byref(kc), oa,
+                                                _stream()))
+        return int(self.lib.dyllm_step_kind(C.byref(sched), t))
 
     def full_step(self, w: LayerWeights, cache: LayerCache, x, B, L):
         self._check(self.lib.dyllm_full_step(self.h, C.byref(w), C.byref(cache), _ptr(x), B, L, _stream()))

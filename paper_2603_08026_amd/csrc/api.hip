@@ -31,6 +31,7 @@ struct dyllm_ctx {
   void *dc;        // [R, dq] approximate context residual of every token
   void *csal;      // [R, dq] exact context rows of the salient tokens (approximate path)
   int32_t *pos;    // [R] position+1 of a token in the salient list; all zero between calls
+  int32_t *win_idx, *win_off;  // [R], [max_batch+1]: the tokens of a response-only step as a list
   float *cosb;     // [R]
   uint8_t *flag;   // [R]
   float *hs;       // [R, d]        x + Wo c (fp32)
@@ -48,7 +49,7 @@ struct dyllm_ctx {
 namespace {
 
 struct Layout {
-  size_t ns, qkv, qs, part_o, part_ml, cosb, flag, hs, fs, act, status, rope, dv_full, dc, csal, pos, total;
+  size_t ns, qkv, qs, part_o, part_ml, cosb, flag, hs, fs, act, status, rope, dv_full, dc, csal, pos, win_idx, win_off, total;
   size_t part_elems;
 };
 
@@ -83,6 +84,8 @@ Layout make_layout(const dyllm_layer_cfg &c) {
   l.dc = take(R * dq * e);
   l.csal = take(R * dq * e);
   l.pos = take(R * 4);
+  l.win_idx = take(R * 4);
+  l.win_off = take(((size_t)c.max_batch + 1) * 4);
   l.total = off;
   return l;
 }
@@ -173,7 +176,7 @@ int enqueue_qkv(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x, Row
   prof_mark(ctx, ST_GEMM_QKV, s);
   launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)rows.cap * seg.n_end[2], ctx->rope, rows, L,
                       c.n_heads, c.n_kv_heads, c.head_dim, w->bq, w->bk, w->bv, q_out, cache->k,
-                      cache->v, nullptr, s);
+                      cache->v, nullptr, 0, s);
   prof_mark(ctx, ST_ROPE_SCATTER, s);
   return check_launch(ctx, "qkv refresh");
 }
@@ -283,57 +286,81 @@ int enqueue_sparse_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
   return rc;
 }
 
+// The tokens of a step: all B*L (row_lo = 0) or the positions [row_lo, L) of every sequence, as a list
+// in the context's workspace  [Sec. 3.5: response-only steps]
+struct Window { Rows rows; const int32_t *offsets; };
+Window make_window(dyllm_ctx *ctx, int B, int L, int row_lo, hipStream_t s) {
+  if (row_lo <= 0) return Window{Rows{nullptr, nullptr, B * L}, nullptr};
+  launch_make_window(B, L, row_lo, ctx->win_idx, ctx->win_off, s);
+  return Window{Rows{ctx->win_idx, nullptr, B * (L - row_lo)}, ctx->win_off};
+}
+
 // one layer of the sparse step with both attention paths, arguments already checked
 // [Alg. 3 layer body; Sec. 3.3: exact rows for the salient tokens, approximate update for the others]
 int enqueue_approx_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
-                         const void *x, const dyllm_index_list *idx_in, int B, int L, float tau,
+                         const void *x, const dyllm_index_list *idx_in, int B, int L, Window win, float tau,
                          dyllm_index_list *idx_out, float *cos_out, hipStream_t s) {
   const dyllm_layer_cfg &c = ctx->cfg;
-  const int T = B * L;
-  const Rows all{nullptr, nullptr, T};
+  const Rows all = win.rows;
   const Rows rin = rows_of(idx_in, B);
+  const int by_token = all.idx != nullptr;  // a window keeps q at its token's row, so that both
+                                            // attention passes find it from a token id
   int rc;
   ctx->prof_cur = nullptr;  // no per-stage timing on this path
-  // norm and q projection (+ rotation) of EVERY token  [Alg. 3: Q <- q_proj(x)]
+  // norm and q projection (+ rotation) of EVERY token of the step  [Alg. 3: Q <- q_proj(x)]
   launch_gather_rmsnorm(dt(ctx), x, w->g_attn, all, c.hidden, c.rms_eps, ctx->ns, s);
   {
     const int splits = launch_gemm_raw(dt(ctx), GemmA{ctx->ns, nullptr, c.hidden}, all, c.hidden,
                                        wseg_one(w->wq, ctx->dq), ctx->part_o, ctx->part_elems, s);
-    launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)T * ctx->dq, ctx->rope, all, L, c.n_heads, 0,
-                        c.head_dim, w->bq, nullptr, nullptr, ctx->qs, nullptr, nullptr, nullptr, s);
+    launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)all.cap * ctx->dq, ctx->rope, all, L, c.n_heads,
+                        0, c.head_dim, w->bq, nullptr, nullptr, ctx->qs, nullptr, nullptr, nullptr, by_token,
+                        s);
   }
-  // k, v of the salient tokens: rotation, value residual, merge into the caches
+  // k, v of the salient tokens: norm, projection, rotation, value residual, merge into the caches
+  launch_gather_rmsnorm(dt(ctx), x, w->g_attn, rin, c.hidden, c.rms_eps, ctx->fs, s);
   {
     WSeg seg;
     seg.w[0] = w->wk; seg.w[1] = w->wv; seg.w[2] = w->wv;
     seg.n_end[0] = ctx->dkv; seg.n_end[1] = 2 * ctx->dkv; seg.n_end[2] = 2 * ctx->dkv;
-    const int splits = launch_gemm_raw(dt(ctx), GemmA{ctx->ns, rin.idx, c.hidden}, rin, c.hidden, seg,
+    const int splits = launch_gemm_raw(dt(ctx), GemmA{ctx->fs, nullptr, c.hidden}, rin, c.hidden, seg,
                                        ctx->part_o, ctx->part_elems, s);
     launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)rin.cap * 2 * ctx->dkv, ctx->rope, rin, L, 0,
                         c.n_kv_heads, c.head_dim, nullptr, w->bk, w->bv, nullptr, cache->k, cache->v,
-                        ctx->dv_full, s);
+                        ctx->dv_full, 0, s);
   }
   if ((rc = check_launch(ctx, "approx: projections"))) return rc;
-  // exact rows of the salient tokens  [Alg. 3: C_sal]
+  // exact rows of the salient tokens  [Alg. 3: C_sal]; q is stored by token here
   {
     AttnArgs a = attn_args(ctx, ctx->qs, cache->k, cache->v, rin, idx_in->offsets, B, L, ctx->csal, 0);
     a.q_by_token = 1;
     launch_attention(dt(ctx), a, s);
   }
-  // approximate residual of every token: the full softmax against the merged keys times the value
-  // residual, which is zero outside the salient rows  [Alg. 4]
+  // approximate residual of every token of the step: the full softmax against the merged keys times
+  // the value residual, which is zero outside the salient rows  [Alg. 4]
   {
-    const AttnArgs a = attn_args(ctx, ctx->qs, cache->k, ctx->dv_full, all, nullptr, B, L, ctx->dc, 0);
+    AttnArgs a = attn_args(ctx, ctx->qs, cache->k, ctx->dv_full, all, win.offsets, B, L, ctx->dc, 0);
+    a.q_by_token = by_token;
     launch_attention(dt(ctx), a, s);
   }
   if ((rc = check_launch(ctx, "approx: attention"))) return rc;
-  // new contexts of all tokens, cosine test, commit; then the scratch maps go back to zero
+  // new contexts of the step's tokens, cosine test, commit; then the scratch maps go back to zero
   launch_mark_rows(rin, ctx->pos, s);
-  launch_saliency_approx(dt(ctx), T, ctx->dq, ctx->csal, ctx->dc, ctx->pos, cache->c, tau, cos_out, ctx->flag, s);
+  launch_saliency_approx(dt(ctx), all, ctx->dq, ctx->csal, ctx->dc, ctx->pos, cache->c, tau, cos_out, ctx->flag, s);
   launch_clear_rows(dt(ctx), rin, ctx->pos, ctx->dv_full, ctx->dkv, s);
   launch_compact(ctx->flag, all, B, L, idx_out->idx, idx_out->offsets, idx_out->cap, ctx->status, s);
   if ((rc = check_launch(ctx, "approx: saliency / compact"))) return rc;
   return enqueue_ffn(ctx, w, x, cache->c, rows_of(idx_out, B), cache->out, s);
+}
+
+// out = ascending unique union of a and b (either may be null), kept to positions >= pos_lo
+int enqueue_merge(dyllm_ctx *ctx, const dyllm_index_list *a, const dyllm_index_list *b, int B, int L,
+                  int pos_lo, dyllm_index_list *out, hipStream_t s) {
+  const int T = B * L;
+  launch_fill_i32((int32_t *)ctx->flag, 0, (T + 3) / 4, s);
+  if (a) launch_mark_flags(rows_of(a, B), L, pos_lo, ctx->flag, s);
+  if (b) launch_mark_flags(rows_of(b, B), L, pos_lo, ctx->flag, s);
+  launch_compact(ctx->flag, Rows{nullptr, nullptr, T}, B, L, out->idx, out->offsets, out->cap, ctx->status, s);
+  return check_launch(ctx, "list merge");
 }
 
 // dense pass of one layer, arguments already checked  [Alg. 2 layer body]
@@ -407,6 +434,7 @@ int dyllm_create(const dyllm_layer_cfg *cfg, dyllm_ctx **out) {
   ctx->hs = (float *)(b + l.hs); ctx->fs = b + l.fs; ctx->act = b + l.act;
   ctx->status = (int32_t *)(b + l.status); ctx->rope = (float *)(b + l.rope);
   ctx->dv_full = b + l.dv_full; ctx->dc = b + l.dc; ctx->csal = b + l.csal; ctx->pos = (int32_t *)(b + l.pos);
+  ctx->win_idx = (int32_t *)(b + l.win_idx); ctx->win_off = (int32_t *)(b + l.win_off);
 
   // rotary table in double precision on the host, cleared status word
   const int half = cfg->head_dim / 2;
@@ -420,7 +448,7 @@ int dyllm_create(const dyllm_layer_cfg *cfg, dyllm_ctx **out) {
   hipError_t e = hipMemcpy(ctx->rope, tab.data(), tab.size() * 4, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemset(ctx->status, 0, 256);
   if (e == hipSuccess) e = hipMemset(ctx->dv_full, 0, l.dc - l.dv_full);
-  if (e == hipSuccess) e = hipMemset(ctx->pos, 0, l.total - l.pos);
+  if (e == hipSuccess) e = hipMemset(ctx->pos, 0, l.win_idx - l.pos);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     (void)hipFree(ctx->ws);
@@ -583,15 +611,90 @@ int dyllm_layer_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_c
   return enqueue_sparse_layer(ctx, w, cache, x, idx_in, B, L, tau, idx_out, cos_out, (hipStream_t)stream);
 }
 
+int check_window(dyllm_ctx *ctx, int B, int L, int row_lo) {
+  if (row_lo < 0 || row_lo >= L) return fail(ctx, DYLLM_ERR_INVALID_ARG, "row_lo must lie in [0, L)");
+  if ((long)B * L > ctx->rows_cap) return fail(ctx, DYLLM_ERR_CAPACITY, "B*L exceeds the context's max_rows");
+  return DYLLM_OK;
+}
+
 int dyllm_layer_step_approx(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
-                            const void *x, const dyllm_index_list *idx_in, int32_t B, int32_t L, float tau,
-                            dyllm_index_list *idx_out, float *cos_out, void *stream) {
+                            const void *x, const dyllm_index_list *idx_in, int32_t B, int32_t L,
+                            int32_t row_lo, float tau, dyllm_index_list *idx_out, float *cos_out,
+                            void *stream) {
   if (!ctx) return DYLLM_ERR_INVALID_ARG;
   int rc;
   if ((rc = check_bl(ctx, B, L))) return rc;
-  if ((long)B * L > ctx->rows_cap) return fail(ctx, DYLLM_ERR_CAPACITY, "B*L exceeds the context's max_rows");
+  if ((rc = check_window(ctx, B, L, row_lo))) return rc;
   if ((rc = check_sparse_layer(ctx, w, cache, x, idx_in, idx_out))) return rc;
-  return enqueue_approx_layer(ctx, w, cache, x, idx_in, B, L, tau, idx_out, cos_out, (hipStream_t)stream);
+  const Window win = make_window(ctx, B, L, row_lo, (hipStream_t)stream);
+  return enqueue_approx_layer(ctx, w, cache, x, idx_in, B, L, win, tau, idx_out, cos_out, (hipStream_t)stream);
+}
+
+int dyllm_stack_step_approx(dyllm_ctx *ctx, int32_t n_layers, const dyllm_layer_weights *w,
+                            dyllm_layer_cache *caches, const void *x, const dyllm_index_list *idx_in,
+                            int32_t B, int32_t L, int32_t row_lo, float tau, dyllm_index_list *idx_out,
+                            float *cos_out, void *stream) {
+  if (!ctx) return DYLLM_ERR_INVALID_ARG;
+  if (n_layers <= 0 || !w || !caches || !idx_out) return fail(ctx, DYLLM_ERR_INVALID_ARG, "empty stack or NULL array");
+  int rc;
+  if ((rc = check_bl(ctx, B, L))) return rc;
+  if ((rc = check_window(ctx, B, L, row_lo))) return rc;
+  for (int l = 0; l < n_layers; ++l) {
+    const void *xl = l ? caches[l - 1].out : x;
+    const dyllm_index_list *in = l ? &idx_out[l - 1] : idx_in;
+    if ((rc = check_sparse_layer(ctx, &w[l], &caches[l], xl, in, &idx_out[l]))) return rc;
+  }
+  const Window win = make_window(ctx, B, L, row_lo, (hipStream_t)stream);
+  const dyllm_index_list *in = idx_in;
+  for (int l = 0; l < n_layers; ++l) {
+    float *cos_l = cos_out ? cos_out + (size_t)l * B * L : nullptr;
+    if ((rc = enqueue_approx_layer(ctx, &w[l], &caches[l], l ? caches[l - 1].out : x, in, B, L, win, tau,
+                                   &idx_out[l], cos_l, (hipStream_t)stream)))
+      return rc;
+    in = &idx_out[l];
+  }
+  return DYLLM_OK;
+}
+
+int dyllm_merge_lists(dyllm_ctx *ctx, const dyllm_index_list *a, const dyllm_index_list *b, int32_t B,
+                      int32_t L, int32_t pos_lo, dyllm_index_list *out, void *stream) {
+  if (!ctx) return DYLLM_ERR_INVALID_ARG;
+  int rc;
+  if ((rc = check_bl(ctx, B, L))) return rc;
+  if ((rc = check_window(ctx, B, L, pos_lo))) return rc;
+  if (a && (rc = check_list(ctx, a, "a"))) return rc;
+  if (b && (rc = check_list(ctx, b, "b"))) return rc;
+  if ((rc = check_list(ctx, out, "out"))) return rc;
+  if ((a && (out->offsets == a->offsets || (out->idx && out->idx == a->idx))) ||
+      (b && (out->offsets == b->offsets || (out->idx && out->idx == b->idx))))
+    return fail(ctx, DYLLM_ERR_INVALID_ARG, "out aliases an input list");
+  return enqueue_merge(ctx, a, b, B, L, pos_lo, out, (hipStream_t)stream);
+}
+
+int dyllm_step_kind(const dyllm_schedule *sched, int32_t t) {
+  if (!sched || t < 0) return DYLLM_ERR_INVALID_ARG;
+  if (t < sched->t_full) return DYLLM_STEP_DENSE;
+  return (sched->full_period <= 1 || t % sched->full_period == 0) ? DYLLM_STEP_FULL : DYLLM_STEP_RESPONSE;
+}
+
+int dyllm_denoise_step(dyllm_ctx *ctx, const dyllm_schedule *sched, int32_t t, int32_t n_layers,
+                       const dyllm_layer_weights *w, dyllm_layer_cache *caches, const void *x,
+                       const dyllm_index_list *decoded, const dyllm_index_list *carry, int32_t B,
+                       int32_t L, dyllm_index_list *cand, dyllm_index_list *idx_out, void *stream) {
+  if (!ctx) return DYLLM_ERR_INVALID_ARG;
+  if (!sched) return fail(ctx, DYLLM_ERR_INVALID_ARG, "schedule is NULL");
+  const int kind = dyllm_step_kind(sched, t);
+  if (kind < 0) return fail(ctx, DYLLM_ERR_INVALID_ARG, "negative step number");
+  if (sched->t_full < 0 || sched->prompt_len < 0) return fail(ctx, DYLLM_ERR_INVALID_ARG, "negative schedule field");
+  if (kind == DYLLM_STEP_DENSE) return dyllm_stack_full_step(ctx, n_layers, w, caches, x, B, L, stream);
+  if (!cand || !idx_out) return fail(ctx, DYLLM_ERR_INVALID_ARG, "cand / idx_out is NULL");
+  const int row_lo = kind == DYLLM_STEP_FULL ? 0 : sched->prompt_len;
+  int rc;
+  if ((rc = dyllm_merge_lists(ctx, carry, decoded, B, L, row_lo, cand, stream))) return rc;
+  if (sched->approx)
+    return dyllm_stack_step_approx(ctx, n_layers, w, caches, x, cand, B, L, row_lo, sched->tau, idx_out,
+                                   nullptr, stream);
+  return dyllm_stack_step(ctx, n_layers, w, caches, x, cand, B, L, sched->tau, idx_out, nullptr, stream);
 }
 
 int dyllm_full_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,

@@ -23,13 +23,14 @@ void launch_gather_rmsnorm(DType t, const void *x, const void *gain, Rows rows, 
 // finalize kernels below sum the splits and apply the fused tail of the step, one workgroup per row.
 //
 // q/k/v: sum of splits + bias, rotary embedding of q and k by the table entry of position
-// (row mod L), q_out[j] (T-typed [cap,dq]), k and v rows scattered into the caches at row_j.
+// (row mod L), q_out[j] (T-typed [cap,dq]; q_out[row_j] when q_by_token), k and v rows scattered into
+// the caches at row_j; dv_out (may be nullptr) takes v - v_cache of those rows before the merge.
 // rope_tab: [max_seq, dh/2, 2] fp32 (cos, sin).  dh is 64 or 128.
 // dv_out (optional, [T, Hkv*dh] T-typed): value residual new - cached of the rows, taken before the merge
 void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_stride,
                          const float *rope_tab, Rows rows, int L, int H, int Hkv, int dh,
                          const void *bq, const void *bk, const void *bv, void *q_out, void *k_cache,
-                         void *v_cache, void *dv_out, hipStream_t s);
+                         void *v_cache, void *dv_out, int q_by_token, hipStream_t s);
 // out-projection: h[j] = x[row_j] + sum of splits (fp32 [cap,d]); f[j] = RMSNorm(h[j]) * gain (T-typed)
 void launch_oproj_finalize(DType t, const float *part, int splits, size_t split_stride, const void *x,
                            const void *gain, Rows rows, int d, float eps, float *h, void *f,
@@ -115,10 +116,15 @@ void launch_fill_i32(int32_t *p, int32_t v, int n, hipStream_t s);
 // ---- approximate (column-sparse) context update of the non-salient rows  [Sec. 3.3; Alg. 3, Alg. 4]
 // pos[row_j] = j + 1 for the rows of the list (pos is zero elsewhere, before and after a step)
 void launch_mark_rows(Rows rows, int32_t *pos, hipStream_t s);
-// For every token r < T: new context = c_sal[pos[r]-1] where pos[r] != 0, else c_cache[r] + dc[r]
-// (rounded to T); cosine against the cached row, flag = cos < tau, commit.  cos_out may be nullptr.
-void launch_saliency_approx(DType t, int T, int D, const void *c_sal, const void *dc, const int32_t *pos,
+// For every entry j of the window `win` (token r = win.idx[j], or j): new context = c_sal[pos[r]-1]
+// where pos[r] != 0, else c_cache[r] + dc[j] (rounded to T); cosine against the cached row, commit;
+// cos_out[r] (may be nullptr), flag_out[j] = cos < tau.
+void launch_saliency_approx(DType t, Rows win, int D, const void *c_sal, const void *dc, const int32_t *pos,
                             void *c_cache, float tau, float *cos_out, uint8_t *flag_out, hipStream_t s);
+// idx/off := the tokens at positions [lo, L) of each of the B sequences, as an index list
+void launch_make_window(int B, int L, int lo, int32_t *idx, int32_t *off, hipStream_t s);
+// flag[r] = 1 for every token r of the list whose position in its sequence is >= lo
+void launch_mark_flags(Rows rows, int L, int lo, uint8_t *flag, hipStream_t s);
 // pos[row_j] = 0 and dv[row_j, :] = 0 for the rows of the list
 void launch_clear_rows(DType t, Rows rows, int32_t *pos, void *dv, int dkv, hipStream_t s);
 

@@ -163,7 +163,7 @@ __global__ __launch_bounds__(RB) void k_qkv_finalize(const float *__restrict__ p
                                                       const T *__restrict__ bq, const T *__restrict__ bk,
                                                       const T *__restrict__ bv, T *__restrict__ q_out,
                                                       T *__restrict__ kc, T *__restrict__ vc,
-                                                      T *__restrict__ dv_out) {
+                                                      T *__restrict__ dv_out, int q_by_token) {
   const int n = row_count(rows);
   const int half = dh / 2, dq = H * dh, dkv = Hkv * dh, ld = dq + 2 * dkv;
   const int per_head = half / 4;  // items of 4 pairs per head
@@ -196,7 +196,7 @@ __global__ __launch_bounds__(RB) void k_qkv_finalize(const float *__restrict__ p
         }
         const float4 t0 = *reinterpret_cast<const float4 *>(t + 2 * p4);      // cos0 sin0 cos1 sin1
         const float4 t1 = *reinterpret_cast<const float4 *>(t + 2 * p4 + 4);  // cos2 sin2 cos3 sin3
-        T *dst = isq ? q_out + (size_t)j * dq : kc + (size_t)r * dkv;
+        T *dst = isq ? q_out + (size_t)(q_by_token ? r : j) * dq : kc + (size_t)r * dkv;
         dst[c0 + 0] = from_f<T>(x1.x * t0.x - x2.x * t0.y);
         dst[c0 + 1] = from_f<T>(x1.y * t0.z - x2.y * t0.w);
         dst[c0 + 2] = from_f<T>(x1.z * t1.x - x2.z * t1.y);
@@ -331,16 +331,16 @@ void launch_swiglu_finalize(DType t, const float *part, int splits, size_t split
 void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_stride,
                          const float *rope_tab, Rows rows, int L, int H, int Hkv, int dh,
                          const void *bq, const void *bk, const void *bv, void *q_out, void *k_cache,
-                         void *v_cache, void *dv_out, hipStream_t s) {
+                         void *v_cache, void *dv_out, int q_by_token, hipStream_t s) {
   if (rows.cap <= 0) return;
   if (t == F32)
     k_qkv_finalize<float><<<row_grid(rows.cap), RB, 0, s>>>(
         part, splits, split_stride, rope_tab, rows, L, H, Hkv, dh, (const float *)bq, (const float *)bk,
-        (const float *)bv, (float *)q_out, (float *)k_cache, (float *)v_cache, (float *)dv_out);
+        (const float *)bv, (float *)q_out, (float *)k_cache, (float *)v_cache, (float *)dv_out, q_by_token);
   else
     k_qkv_finalize<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>(
         part, splits, split_stride, rope_tab, rows, L, H, Hkv, dh, (const bf16_t *)bq, (const bf16_t *)bk,
-        (const bf16_t *)bv, (bf16_t *)q_out, (bf16_t *)k_cache, (bf16_t *)v_cache, (bf16_t *)dv_out);
+        (const bf16_t *)bv, (bf16_t *)q_out, (bf16_t *)k_cache, (bf16_t *)v_cache, (bf16_t *)dv_out, q_by_token);
 }
 
 inline int sal_grid(int cap) { return cap < 1 ? 1 : (cap > 65536 ? 65536 : cap); }
@@ -381,11 +381,12 @@ __global__ __launch_bounds__(256) void k_clear_rows(Rows rows, int32_t *pos, T *
   }
 }
 
-// One workgroup per token.  Salient tokens (pos != 0) take their exact row, all others the cached row
-// plus the approximate residual; the cosine is taken over the stored (rounded) values against the
-// cached row, which is read before it is overwritten.
+// One workgroup per token of the step (entry j of `win`, token r).  Salient tokens (pos[r] != 0) take
+// their exact row, all others the cached row plus the approximate residual dc[j]; the cosine is taken
+// over the stored (rounded) values against the cached row, which is read before it is overwritten.
+// cos_out is indexed by token, flag_out by window entry.
 template <typename T>
-__global__ __launch_bounds__(SAL_NT) void k_saliency_approx(int n, int D, const T *__restrict__ c_sal,
+__global__ __launch_bounds__(SAL_NT) void k_saliency_approx(Rows win, int D, const T *__restrict__ c_sal,
                                                              const T *__restrict__ dc,
                                                              const int32_t *__restrict__ pos, T *c_cache,
                                                              float tau, float *__restrict__ cos_out,
@@ -393,10 +394,12 @@ __global__ __launch_bounds__(SAL_NT) void k_saliency_approx(int n, int D, const 
   __shared__ float red[3 * SAL_NT / WAVE];
   constexpr int N = Vec16<T>::N;
   const int nv = D / N;
-  for (int r = blockIdx.x; r < n; r += gridDim.x) {
+  const int n = row_count(win);
+  for (int j = blockIdx.x; j < n; j += gridDim.x) {
+    const int r = win.idx ? win.idx[j] : j;
     const int p = pos[r];
     T *b = c_cache + (size_t)r * D;
-    const T *src = p ? c_sal + (size_t)(p - 1) * D : dc + (size_t)r * D;
+    const T *src = p ? c_sal + (size_t)(p - 1) * D : dc + (size_t)j * D;
     float dot = 0.f, na = 0.f, nb = 0.f;
     for (int v = threadIdx.x; v < nv; v += SAL_NT) {
       const Vec16<T> vs = ld16(src + v * N), vb = ld16(b + v * N);
@@ -416,8 +419,25 @@ __global__ __launch_bounds__(SAL_NT) void k_saliency_approx(int n, int D, const 
     if (threadIdx.x == 0) {
       const float s = dot / (fmaxf(sqrtf(na), 1e-8f) * fmaxf(sqrtf(nb), 1e-8f));
       if (cos_out) cos_out[r] = s;
-      flag_out[r] = (s < tau) ? 1 : 0;
+      flag_out[j] = (s < tau) ? 1 : 0;
     }
+  }
+}
+
+// The tokens at positions [lo, L) of every sequence as an index list (a response-only step's rows).
+__global__ __launch_bounds__(256) void k_make_window(int B, int L, int lo, int32_t *idx, int32_t *off) {
+  const int w = L - lo, n = B * w;
+  for (int j = blockIdx.x * 256 + threadIdx.x; j < n; j += gridDim.x * 256) idx[j] = (j / w) * L + lo + j % w;
+  if (blockIdx.x == 0)
+    for (int b = threadIdx.x; b <= B; b += 256) off[b] = b * w;
+}
+
+// flag[r] = 1 for the tokens r of a list at positions >= lo of their sequence
+__global__ __launch_bounds__(256) void k_mark_flags(Rows rows, int L, int lo, uint8_t *flag) {
+  const int n = row_count(rows);
+  for (int j = blockIdx.x * 256 + threadIdx.x; j < n; j += gridDim.x * 256) {
+    const int r = rows.idx[j];
+    if (r % L >= lo) flag[r] = 1;
   }
 }
 
@@ -426,16 +446,26 @@ void launch_mark_rows(Rows rows, int32_t *pos, hipStream_t s) {
   k_mark_rows<<<(rows.cap + 255) / 256, 256, 0, s>>>(rows, pos);
 }
 
-void launch_saliency_approx(DType t, int T, int D, const void *c_sal, const void *dc, const int32_t *pos,
+void launch_saliency_approx(DType t, Rows win, int D, const void *c_sal, const void *dc, const int32_t *pos,
                             void *c_cache, float tau, float *cos_out, uint8_t *flag_out, hipStream_t s) {
-  if (T <= 0) return;
-  const int grid = T > 65536 ? 65536 : T;
+  if (win.cap <= 0) return;
+  const int grid = win.cap > 65536 ? 65536 : win.cap;
   if (t == F32)
-    k_saliency_approx<float><<<grid, SAL_NT, 0, s>>>(T, D, (const float *)c_sal, (const float *)dc, pos,
+    k_saliency_approx<float><<<grid, SAL_NT, 0, s>>>(win, D, (const float *)c_sal, (const float *)dc, pos,
                                                     (float *)c_cache, tau, cos_out, flag_out);
   else
-    k_saliency_approx<bf16_t><<<grid, SAL_NT, 0, s>>>(T, D, (const bf16_t *)c_sal, (const bf16_t *)dc, pos,
+    k_saliency_approx<bf16_t><<<grid, SAL_NT, 0, s>>>(win, D, (const bf16_t *)c_sal, (const bf16_t *)dc, pos,
                                                      (bf16_t *)c_cache, tau, cos_out, flag_out);
+}
+
+void launch_make_window(int B, int L, int lo, int32_t *idx, int32_t *off, hipStream_t s) {
+  const int n = B * (L - lo);
+  k_make_window<<<n > 0 ? (n + 255) / 256 : 1, 256, 0, s>>>(B, L, lo, idx, off);
+}
+
+void launch_mark_flags(Rows rows, int L, int lo, uint8_t *flag, hipStream_t s) {
+  if (rows.cap <= 0) return;
+  k_mark_flags<<<(rows.cap + 255) / 256, 256, 0, s>>>(rows, L, lo, flag);
 }
 
 void launch_clear_rows(DType t, Rows rows, int32_t *pos, void *dv, int dkv, hipStream_t s) {

@@ -96,11 +96,12 @@ class Layer:
         return out
 
     def layer_step_approx(self, x_dev: torch.Tensor, idx_in: B_.IndexList, tau: float,
-                          idx_out: Optional[B_.IndexList] = None, cos_out: Optional[torch.Tensor] = None):
+                          idx_out: Optional[B_.IndexList] = None, cos_out: Optional[torch.Tensor] = None,
+                          row_lo: int = 0):
         """Sparse step with the approximate update of the other tokens; the context must cover B*L rows.
-        cos_out: [B*L] fp32 (by token) or None."""
+        cos_out: [B*L] fp32 (by token) or None; row_lo > 0: response-only step."""
         out = self.idx_out if idx_out is None else idx_out
-        self.ctx.layer_step_approx(self.w, self.cache, x_dev, idx_in, self.B, self.L, tau, out, cos_out)
+        self.ctx.layer_step_approx(self.w, self.cache, x_dev, idx_in, self.B, self.L, tau, out, cos_out, row_lo)
         return out
 
     def read_list(self, il: B_.IndexList) -> Tuple[np.ndarray, np.ndarray]:
@@ -140,6 +141,19 @@ class Stack:
         self.ctx.stack_step([l.w for l in self.layers], [l.cache for l in self.layers], x_dev, idx_in,
                             self.B, self.L, tau, self.idx_outs, cos)
         return self.idx_outs
+
+    def stack_step_approx(self, x_dev: torch.Tensor, idx_in: B_.IndexList, tau: float, row_lo: int = 0,
+                          cos_out: Optional[torch.Tensor] = None):
+        """cos_out: [n_layers, B*L] fp32 (by token) or None."""
+        self.ctx.stack_step_approx([l.w for l in self.layers], [l.cache for l in self.layers], x_dev, idx_in,
+                                   self.B, self.L, tau, self.idx_outs, cos_out, row_lo)
+        return self.idx_outs
+
+    def denoise_step(self, sched: B_.Schedule, t: int, x_dev: torch.Tensor, decoded, carry, cand: B_.IndexList):
+        """One iteration of the generation loop; returns (step kind, the list to carry or None)."""
+        kind = self.ctx.denoise_step(sched, t, [l.w for l in self.layers], [l.cache for l in self.layers],
+                                     x_dev, decoded, carry, self.B, self.L, cand, self.idx_outs)
+        return kind, (None if kind == B_.STEP_DENSE else self.idx_outs[-1])
 
     def close(self):
         self.ctx.close()
