@@ -190,3 +190,81 @@ def test_generation_loop_steps_against_oracle(dtype, approx):
         x = _round(x, dtype).reshape(B, L, -1)
     assert kinds == [Bd.STEP_DENSE] * 2 + [Bd.STEP_RESPONSE] * 2 + [Bd.STEP_FULL] + [Bd.STEP_RESPONSE] * 3 + [Bd.STEP_FULL]
     st.close()
+
+
+@pytest.mark.parametrize("approx", [False, True])
+def test_stack_step_replays_from_a_captured_graph(approx):
+    """The layer loop is one enqueue of kernels with no allocation, copy or wait in it, so a caller may
+    capture it once and replay it with new inputs in the same buffers.  Every replay (with eager work
+    and synchronisations in between) must give what the eager call gives on the same inputs."""
+    _say("graph replay", "approx" if approx else "exact")
+    dtype = "bf16"
+    s = small_shape(dtype, gqa=True)
+    B, L, NL, CAP = 2, 96, 3, 40
+    T = B * L
+    cfg, ws, st = _stack_refs(s, NL, B, L, 111)
+    x0 = _round(W.philox(112, "x").standard_normal((B, L, s.hidden), dtype=np.float32), dtype)
+    st.full_step(st.upload(x0))
+    torch.cuda.synchronize()
+    snap = [{k: getattr(one, k).clone() for k in ("k", "v", "c", "out")} for one in st.layers]
+
+    def restore():
+        for one, sn in zip(st.layers, snap):
+            for k, v in sn.items():
+                getattr(one, k).copy_(v)
+
+    def run(xd, il):
+        if approx:
+            st.stack_step_approx(xd, il, 0.9)
+        else:
+            st.stack_step(xd, il, 0.99, want_cos=False)
+
+    def state():
+        torch.cuda.synchronize()
+        lists = [tuple(a.copy() for a in st.layers[0].read_list(o)) for o in st.idx_outs]
+        return [one.get_caches() for one in st.layers], lists
+
+    # three inputs with different candidate counts, all within one list capacity
+    cases = []
+    for k, counts in enumerate(([20, 15], [3, 0], [11, 29])):
+        idx, off = rand_rows(113 + k, B, L, counts)
+        x = x0.copy().reshape(T, -1)
+        x[idx] = W.perturbed_rows(x[idx], np.full(idx.size, 1.0), 120 + k)
+        cases.append((_round(x, dtype).reshape(B, L, -1), idx, off))
+    eager = []
+    for x, idx, off in cases:
+        restore()
+        run(st.upload(x), st.make_list(idx, off, cap=CAP))
+        eager.append(state())
+    # persistent input buffers for the captured call
+    xd = st.upload(cases[0][0]).clone()
+    il = st.make_list(cases[0][1], cases[0][2], cap=CAP)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        restore()
+        run(xd, il)  # warm-up on the capture stream (one-time function attributes are set here)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run(xd, il)
+    torch.cuda.synchronize()
+    for rep in range(2):
+        for k, (x, idx, off) in enumerate(cases):
+            restore()
+            xd.copy_(st.upload(x))
+            buf = np.zeros(CAP, np.int32)
+            buf[:idx.size] = idx
+            il.idx.copy_(torch.from_numpy(buf).cuda())
+            il.offsets.copy_(torch.from_numpy(off.astype(np.int32)).cuda())
+            torch.cuda.synchronize()
+            graph.replay()
+            got_c, got_l = state()
+            want_c, want_l = eager[k]
+            for l in range(NL):
+                assert np.array_equal(got_l[l][0], want_l[l][0]) and np.array_equal(got_l[l][1], want_l[l][1]), (rep, k, l)
+                for name in ("k", "v", "c", "out"):
+                    assert np.array_equal(got_c[l][name], want_c[l][name]), (rep, k, l, name)
+    assert st.ctx.poll_status() == 0
+    st.close()
