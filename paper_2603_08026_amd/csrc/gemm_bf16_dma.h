@@ -24,6 +24,7 @@
 // workgroup walks the existing tiles in a grouped order, remapped so that neighbouring tiles run on
 // one XCD (workgroup i is dispatched to XCD i % 8) and share A / weight tiles in its L2.
 #pragma once
+#include <type_traits>
 #include "gemm_epilogues.h"
 #include "kernels.h"
 
@@ -59,11 +60,13 @@ template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, bool DUAL_, int NS_, int
   static constexpr int A_BYTES = BM * ROWB, W_BYTES = NMAT * BN * ROWB;
   static constexpr int STAGE_BYTES = A_BYTES + W_BYTES;
   static constexpr size_t LDS_BYTES = (size_t)NSA * A_BYTES + (size_t)NS * W_BYTES;
+  // shapes with three or more stages (weight streaming) run the loop pipelined over slices
+  static constexpr bool PIPE = !ROLES && NS >= 3;
   static_assert(NW == 4 || NW == 8, "four or eight waves per workgroup");
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile is made of 32x32 blocks");
   static_assert(BM % (8 * NWC) == 0 && BN % (8 * NWC) == 0, "tile rows are copied in blocks of 8 per wave");
-  static_assert(NS >= 2 && NSA >= 2 && (ROLES ? NS <= 16 : NS <= 4), "LDS stages");
-  static_assert((NS - 2) * (ROLES ? NMAT * B_LD : LPS) < 64 && (NSA - 2) * A_LD < 64, "vmcnt immediate");
+  static_assert(NS >= 2 && NSA >= 2 && (ROLES ? NS <= 16 : NS <= 8), "LDS stages");
+  static_assert((NS - 1) * (ROLES ? NMAT * B_LD : LPS) < 64 && (NSA - 2) * A_LD < 64, "vmcnt immediate");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS of one CU");
 };
 
@@ -170,6 +173,66 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
     };
 
     __syncthreads();  // LDS free: the previous tile of this workgroup is fully consumed
+    if constexpr (SH::PIPE) {
+      // Weight-streaming shapes: one wave per SIMD and few products per slice, so nothing hides the
+      // chain wait -> barrier -> operand reads -> products of a slice.  The loop is therefore
+      // pipelined over slices: the operands of slice kt+1 are read (into a second register set)
+      // while the products of slice kt run, and because a wave holds slice kt in registers when it
+      // reaches the barrier of iteration kt, that stage is refilled at once: NS slices are in flight
+      // instead of NS-1.
+      constexpr int KS = BK / 16, RD = MB + NMAT * NB, MM = NMAT * MB * NB;
+      bf16x8 af[2][KS][MB], bfr[2][KS][NMAT][NB];
+      auto read_slice = [&](bf16x8 (&a)[KS][MB], bf16x8 (&b)[KS][NMAT][NB], int kt) {
+        const unsigned char *sa = smem_raw + (size_t)(kt % NS) * SH::A_BYTES + (wm0 + l32) * ROWB;
+        const unsigned char *sb = smem_raw + (size_t)NS * SH::A_BYTES + (size_t)(kt % NS) * SH::W_BYTES +
+                                  (wn0 + l32) * ROWB;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+#pragma unroll
+          for (int i = 0; i < MB; ++i) a[kk][i] = *reinterpret_cast<const bf16x8 *>(sa + i * 32 * ROWB + rd_off[kk]);
+#pragma unroll
+          for (int t = 0; t < NMAT; ++t)
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+              b[kk][t][j] = *reinterpret_cast<const bf16x8 *>(sb + (t * BN + j * 32) * ROWB + rd_off[kk]);
+        }
+      };
+      auto slice = [&](int kt, auto cur_c) {
+        constexpr int CUR = decltype(cur_c)::value;
+        // slice kt+1 has landed: the copies issued after it may still be on their way
+        if (kt + NS - 1 < KT) wait_vmcnt<(NS - 2) * SH::LPS>();
+        else wait_vmcnt<0>();
+        wait_lgkmcnt0();  // the operands of slice kt are in registers: its stage is free
+        __syncthreads();
+        if (kt + NS < KT) { issue_a(kt + NS); issue_w(kt + NS); }
+        read_slice(af[CUR ^ 1], bfr[CUR ^ 1], kt + 1 < KT ? kt + 1 : kt);  // (past the end: a harmless re-read)
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk)
+#pragma unroll
+          for (int t = 0; t < NMAT; ++t)
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+              for (int j = 0; j < NB; ++j)
+                acc[t][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[CUR][kk][i], bfr[CUR][kk][t][j], acc[t][i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, KS * RD, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, KS * MM, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      };
+#pragma unroll
+      for (int s = 0; s < NS; ++s)
+        if (s < KT) { issue_a(s); issue_w(s); }
+      if (NS - 1 < KT) wait_vmcnt<(NS - 1) * SH::LPS>();  // slice 0 has landed
+      else wait_vmcnt<0>();
+      __syncthreads();
+      read_slice(af[0], bfr[0], 0);
+      int kt = 0;
+      for (; kt + 1 < KT; kt += 2) {
+        slice(kt, std::integral_constant<int, 0>{});
+        slice(kt + 1, std::integral_constant<int, 1>{});
+      }
+      if (kt < KT) slice(kt, std::integral_constant<int, 0>{});
+    } else {
     // slice by slice (a wave that copies both operands counts whole slices in its waits)
 #pragma unroll
     for (int s = 0; s < (NS > NSA ? NS : NSA) - 1; ++s) {
@@ -274,6 +337,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
         }
         __builtin_amdgcn_sched_group_barrier(0x008, MM, 0);
       }
+    }
     }
 
     // epilogue
