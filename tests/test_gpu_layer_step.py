@@ -278,3 +278,36 @@ def test_full_batch_at_bench_size_on_sampled_sequences(name, seqs):
         for cname in ("k", "v", "c", "out"):
             assert_close(got[cname][b], ref[cname][0], TOL["bf16"], "%s sequence %d cache %s" % (wl.name, b, cname))
     lay.close()
+
+
+@pytest.mark.parametrize("dh,hkv", [(64, 8), (128, 4)])
+def test_wide_batch_with_bias_in_the_large_tile_regime(dh, hkv):
+    """8192 rows x 1536 q|k|v columns with q/k/v bias: the 256x256-tile plan of the large regime with
+    both head sizes.  Dense step against the oracle, then the sparse step over all rows (index list
+    instead of the identity) against the dense step."""
+    _say("wide batch with bias", dh, hkv)
+    nh = 512 // dh
+    s = W.LayerShape(hidden=512, n_heads=nh, n_kv_heads=hkv, head_dim=dh, ffn=384, dtype="bf16")
+    cfg = oracle_cfg(s)
+    B, L = 16, 512
+    T = B * L
+    w = rand_weights(s, 131, bias=True, std=0.08)
+    lay = Layer.from_shape(s, B, L)
+    lay.set_weights(w)
+    x0 = W.round_bf16(W.philox(132, "x").standard_normal((B, L, s.hidden), dtype=np.float32))
+    x1 = W.round_bf16(W.philox(133, "x").standard_normal((B, L, s.hidden), dtype=np.float32))
+    ref = O.new_caches(B, L, cfg)
+    O.full_step(x0, w, cfg, ref)
+    lay.full_step(lay.upload(x0))
+    _compare_caches(lay, ref, TOL["bf16"], "wide dense")
+    allrows = lay.make_list(np.arange(T, dtype=np.int32), np.arange(B + 1, dtype=np.int32) * L)
+    out = lay.layer_step(lay.upload(x1), allrows, 1.5)
+    idx_g, _ = lay.read_list(out)
+    assert np.array_equal(idx_g, np.arange(T))
+    sparse = {k: getattr(lay, k).clone() for k in ("k", "v", "c", "out")}
+    lay.full_step(lay.upload(x1))
+    for k in sparse:
+        assert torch.equal(getattr(lay, k), sparse[k]), k
+    O.full_step(x1, w, cfg, ref)
+    _compare_caches(lay, ref, TOL["bf16"], "wide dense, second input")
+    lay.close()

@@ -27,11 +27,15 @@ def _round(a, dtype):
 
 
 def _compare_layers(stk, refs, tol, what):
+    """One call runs all layers, so layer l is compared after l layers of the GPU's own rounding went
+    into its input: its bound is the one-layer bound times sqrt(l + 1) (independent errors of equal
+    size add in quadrature)."""
     worst = 0.0
     for l, (lay, ref) in enumerate(zip(stk.layers, refs)):
         got = lay.get_caches()
         for name in ("k", "v", "c", "out"):
-            worst = max(worst, assert_close(got[name], ref[name], tol, "%s layer %d cache %s" % (what, l, name)))
+            worst = max(worst, assert_close(got[name], ref[name], tol * np.sqrt(l + 1.0),
+                                            "%s layer %d cache %s" % (what, l, name)))
     return worst
 
 
