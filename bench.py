@@ -136,6 +136,8 @@ def main():
     ap.add_argument("--frac", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dense-iters", type=int, default=3)
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the graph-replay, approximate-step and stand-alone-kernel legs (profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on exactly one GPU (the path shards along the batch with no "
@@ -239,6 +241,8 @@ def main():
     # reads of x -- are copied into those buffers, inside the timed region.
     graph_info = None
     try:
+        if args.no_extras:
+            raise RuntimeError("skipped (--no-extras)")
         for one, sn in zip(layers, snap):
             for k_, v_ in sn.items():
                 getattr(one, k_).copy_(v_)
@@ -276,7 +280,7 @@ def main():
     # single layer: the same K steps once more with the approximate update of all other tokens
     # (Sec. 3.3, Alg. 4) in place of leaving their contexts untouched
     approx = None
-    if NL == 1:
+    if NL == 1 and not args.no_extras:
         def restore():
             for k_, v_ in snap[0].items():
                 getattr(lay, k_).copy_(v_)
@@ -364,7 +368,8 @@ def main():
     if approx is not None:
         approx["speedup_vs_dense"] = t_dense * 1e3 / approx["ms_per_step"]
         out["approx_step"] = approx
-    out["standalone"] = standalone_kernels(s, torch)
+    if not args.no_extras:
+        out["standalone"] = standalone_kernels(s, torch)
     if NL > 1:
         # stack only: generated tokens per second of the paper's kind over the layer stack alone
         # (no embedding, logits or sampling): B * L_R over T_full dense and the remaining sparse steps
