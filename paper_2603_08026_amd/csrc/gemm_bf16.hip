@@ -1,4 +1,5 @@
 // bf16 salient-row GEMMs: tile-shape choice per regime and the four fused launchers.
+#include <algorithm>
 #include "gemm_bf16_dma.h"
 
 namespace dy {
@@ -42,12 +43,28 @@ int cu_count() {
   return n;
 }
 
-// 256-row tiles with n_l (large) or n_x (xlarge, twice as wide) column tiles: one workgroup per CU and
-// round; an xlarge tile takes about 1.63 times as long as a large one (measured at many rounds).
+// Rounds of the chip (one workgroup per CU at a time) that `cap` rows in 256-row tiles take with
+// ncol column tiles and sk K-splits.  The tiles of a last row tile with fewer than 256 rows cost a
+// fraction f of a full tile (their weight copies at least, plus the products of the busiest wave's
+// 32-row blocks); they run at the end of every XCD's schedule and first fill the slots the last
+// round of full tiles leaves idle.
+double tile_rounds(int cap, long ncol, int sk) {
+  const long cu = cu_count(), rows_full = cap / 256;
+  const int tail = cap % 256;
+  const long full_tiles = rows_full * ncol * sk;
+  const long full_rounds = (full_tiles + cu - 1) / cu;
+  if (!tail) return (double)full_rounds;
+  const double f = std::max(0.2, (double)((tail + 31) / 32) / 8.0);
+  const long slack = full_rounds * cu - full_tiles;
+  long rest = ncol * sk - slack * (long)(1.0 / f);
+  if (rest < 0) rest = 0;
+  return (double)full_rounds + (double)((rest + cu - 1) / cu) * f;
+}
+
+// 256-row tiles with n_l (large) or n_x (xlarge, twice as wide) column tiles: an xlarge tile takes
+// about 1.63 times as long as a large one (measured at many rounds).
 bool prefer_xlarge(int cap, int n_l, int n_x) {
-  const long rows = (cap + 255) / 256, cu = cu_count();
-  const long rounds_l = (rows * n_l + cu - 1) / cu, rounds_x = (rows * n_x + cu - 1) / cu;
-  return 1.63 * (double)rounds_x < (double)rounds_l;
+  return 1.63 * tile_rounds(cap, n_x, 1) < tile_rounds(cap, n_l, 1);
 }
 
 template <typename SH, typename Epi>
@@ -55,9 +72,15 @@ void run_tiles(GemmA A, Rows rows, int K, int N, WSeg seg, const void *w2, Epi e
                float *part, hipStream_t s) {
   set_lds_once<SH, Epi>();
   const int tiles = ((rows.cap + SH::BM - 1) / SH::BM) * (N / SH::BN);
-  int gx = tiles < 1 ? 1 : tiles;
+  // one workgroup per tile up to 2048, as the kernel numbers them when the list is full: per XCD its
+  // share of the full row tiles' tiles and its share of a partial last row tile's, each rounded up
+  // (a shorter list leaves workgroups without a tile, or in rare splits gives a few a second one)
+  const int ncol = N / SH::BN;
+  const int n_full = (rows.cap / SH::BM) * ncol, n_part = (rows.cap % SH::BM) ? ncol : 0;
+  int gx = ((n_full + N_XCD - 1) / N_XCD + (n_part + N_XCD - 1) / N_XCD) * N_XCD;
+  if (gx < N_XCD) gx = N_XCD;
   if (gx > 2048) gx = 2048;
-  gx = (gx + N_XCD - 1) / N_XCD * N_XCD;  // multiple of the XCD count: p % 8 is then the XCD of p
+  (void)tiles;
   SplitStore sp{part, (size_t)rows.cap * N, N};
   dim3 grid(gx, splitk);
   k_gemm_bf16<SH, Epi><<<grid, SH::NT, SH::LDS_BYTES, s>>>(
@@ -90,16 +113,15 @@ template <typename SH> inline long tiles_of(int cap, int N) { return (long)((cap
 // writing and re-reading the fp32 partials of a split (dear when N is wide and K short).
 struct LargePlan { bool xlarge; int splitk; };
 inline LargePlan plan_large(int cap, int N, int K, size_t part_elems, bool x_ok) {
-  const long cu = cu_count(), rows = (cap + 255) / 256;
   LargePlan best{false, 1};
   double best_cost = 1e30;
   for (int x = 0; x <= (x_ok ? 1 : 0); ++x) {
-    const long tiles = rows * (N / (x ? XLargeS::BN : LargeS::BN));
+    const long ncol = N / (x ? XLargeS::BN : LargeS::BN);
     const double tile_cost = x ? 1.63 : 1.0;
     for (int sk = 1; sk <= 8; ++sk) {
       if ((K / BK) % sk != 0 || K / BK / sk < 8) continue;
       if (sk > 1 && (size_t)sk * cap * N > part_elems) continue;
-      const long rounds = (tiles * sk + cu - 1) / cu;
+      const double rounds = tile_rounds(cap, ncol, sk);
       // partials: sk * cap * N floats written and read again (~4 TB/s) against a round of tiles
       // (256 tiles x 2*256*128*K flop at ~1 PFLOP/s)
       const double partials = sk > 1 ? 1.2e-4 * sk * (double)cap * N / K + 0.02 : 0.0;

@@ -111,16 +111,35 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
 #pragma unroll
   for (int kk = 0; kk < BK / 16; ++kk) rd_off[kk] = (((2 * kk + lhi) ^ ((l32 >> 1) & 7)) * 16);
 
-  const int per_xcd = (total + N_XCD - 1) / N_XCD;
-  const int total_pad = per_xcd * N_XCD;
+  // Tile order.  Workgroup p runs on XCD p % 8, and an XCD takes its workgroups in the order of p.
+  // Each XCD gets a contiguous run of the FULL row tiles' tiles (walked in groups of group_m row tiles,
+  // so that the tiles it runs at one time share operands in its L2) and, after those, its share of
+  // the tiles of a last row tile that holds fewer than BM rows: those cost a fraction of a full tile
+  // (see the partial loop below) and fill the end of every XCD's schedule instead of one XCD's.
+  const int has_tail = (tiles_m > 0 && M % BM != 0) ? 1 : 0;
+  const int rows_full = tiles_m - has_tail;
+  const int n_full = rows_full * tiles_n, n_part = has_tail * tiles_n;
+  const int fx = (n_full + N_XCD - 1) / N_XCD, px = (n_part + N_XCD - 1) / N_XCD;
+  const int total_pad = (fx + px) * N_XCD;
+  (void)total;
 
   for (int p = blockIdx.x; p < total_pad; p += gridDim.x) {
-    const int logical = (p % N_XCD) * per_xcd + p / N_XCD;
-    if (logical >= total) continue;  // uniform for the workgroup
-    const int gsz = group_m * tiles_n;
-    const int g = logical / gsz, r = logical % gsz;
-    const int gm = min(group_m, tiles_m - g * group_m);
-    const int tm = g * group_m + r % gm, tn = r / gm;
+    const int xcd = p % N_XCD, q = p / N_XCD;
+    int tm, tn;
+    if (q < fx) {
+      const int logical = xcd * fx + q;
+      if (logical >= n_full) continue;  // uniform for the workgroup
+      const int gsz = group_m * tiles_n;
+      const int g = logical / gsz, r = logical % gsz;
+      const int gm = min(group_m, rows_full - g * group_m);
+      tm = g * group_m + r % gm;
+      tn = r / gm;
+    } else {
+      const int lp = xcd * px + (q - fx);
+      if (lp >= n_part) continue;
+      tm = tiles_m - 1;
+      tn = lp;
+    }
     const int m0 = tm * BM, n0 = tn * BN;
 
     // per-lane global sources of the copies it issues every slice
@@ -232,6 +251,53 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
         slice(kt + 1, std::integral_constant<int, 1>{});
       }
       if (kt < KT) slice(kt, std::integral_constant<int, 0>{});
+    } else if (!ROLES && NS == 2 && m0 + BM > M) {
+      // A row tile that holds fewer than BM rows: copies of 8-row blocks past the end are left out,
+      // and a wave multiplies only its 32-row blocks that hold rows (none at all for many waves), so
+      // that the tile costs about what its weight copies cost.  Same barriers as the full loop.
+      const int mbv_raw = (M - (m0 + wm0) + 31) / 32;
+      const int mbv = mbv_raw < 0 ? 0 : (mbv_raw > MB ? MB : mbv_raw);  // wave-uniform
+      auto issue_a_part = [&](int kt) {
+        const uint32_t sb = lds0 + (uint32_t)(kt % NSA) * SH::A_BYTES + (uint32_t)wavec * 1024u;
+        const int ko = kt * BK;
+#pragma unroll
+        for (int i = 0; i < SH::A_LD; ++i)
+          if (m0 + (i * NWC + wavec) * 8 < M) dma16(ap[i] + ko, sb + i * (NWC * 1024u));
+      };
+      issue_a_part(0);
+      issue_w(0);
+      for (int kt = 0; kt < KT; ++kt) {
+        wait_vmcnt<0>();
+        __syncthreads();
+        if (kt + 1 < KT) {
+          issue_a_part(kt + 1);
+          issue_w(kt + 1);
+        }
+        if (mbv == 0) continue;  // wave-uniform; the barriers above are all this wave owes the tile
+        const unsigned char *sa = smem_raw + (size_t)(kt % NSA) * SH::A_BYTES + (wm0 + l32) * ROWB;
+        const unsigned char *sb = smem_raw + (size_t)NSA * SH::A_BYTES + (size_t)(kt % NS) * SH::W_BYTES +
+                                  (wn0 + l32) * ROWB;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+          bf16x8 bfr[NMAT][NB];
+#pragma unroll
+          for (int t = 0; t < NMAT; ++t)
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+              bfr[t][j] = *reinterpret_cast<const bf16x8 *>(sb + (t * BN + j * 32) * ROWB + rd_off[kk]);
+#pragma unroll
+          for (int i = 0; i < MB; ++i) {
+            if (i < mbv) {
+              const bf16x8 af = *reinterpret_cast<const bf16x8 *>(sa + i * 32 * ROWB + rd_off[kk]);
+#pragma unroll
+              for (int t = 0; t < NMAT; ++t)
+#pragma unroll
+                for (int j = 0; j < NB; ++j)
+                  acc[t][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr[t][j], acc[t][i][j], 0, 0, 0);
+            }
+          }
+        }
+      }
     } else {
     // slice by slice (a wave that copies both operands counts whole slices in its waits)
 #pragma unroll

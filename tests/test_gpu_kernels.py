@@ -262,6 +262,50 @@ def test_salient_ffn(dtype):
     lay.close()
 
 
+@pytest.mark.parametrize("M,cap", [(520, 520), (520, 820), (700, 701), (1024, 1024), (397, 900), (769, 1600)])
+def test_large_tile_regime_with_ragged_row_counts(M, cap):
+    """More than 384 list entries: 256-row GEMM tiles.  A last row tile with few rows runs the
+    shortened loop and is numbered after the full tiles on every XCD; a list shorter than its capacity
+    moves that split away from what the host sized the grid for."""
+    _say("large tiles, ragged", M, cap)
+    dtype = "bf16"
+    s = small_shape(dtype)
+    cfg = oracle_cfg(s)
+    B, L = 4, 400
+    T = B * L
+    lay = Layer.from_shape(s, B, L)
+    w = rand_weights(s, 141, bias=True)
+    lay.set_weights(w)
+    per = [M // B + (1 if b < M % B else 0) for b in range(B)]
+    idx, off = rand_rows(142, B, L, per)
+    rows = lay.make_list(idx, off, cap=cap)
+    tol = TOL[dtype]
+    # q/k/v refresh (raw GEMM + row kernel)
+    x = _vals(143, (B, L, s.hidden), dtype)
+    q_out = torch.zeros(cap, s.dq, dtype=lay.k.dtype, device="cuda")
+    lay.ctx.qkv_refresh(lay.w, lay.upload(x), rows, B, L, lay.cache, q_out)
+    torch.cuda.synchronize()
+    n = O.rmsnorm(x.reshape(T, -1)[idx], w["g_attn"], cfg.rms_eps)
+    q, k, v = O.project_qkv(n, idx % L, w, cfg)
+    assert_close(to_host(q_out)[:M], q.reshape(M, -1), tol, "q")
+    assert_close(to_host(lay.k).reshape(T, -1)[idx], k.reshape(M, -1), tol, "k rows")
+    assert_close(to_host(lay.v).reshape(T, -1)[idx], v.reshape(M, -1), tol, "v rows")
+    assert np.all(to_host(q_out)[M:] == 0)
+    # out-projection + FFN (raw GEMM, fused SwiGLU and residual epilogues)
+    c = _vals(144, (T, s.dq), dtype)
+    out0 = _vals(145, (T, s.hidden), dtype)
+    ref = out0.astype(np.float64)
+    O.salient_ffn(x.reshape(T, -1), c, idx, w, cfg, ref)
+    d_out = to_device(out0, dtype)
+    lay.ctx.salient_ffn(lay.w, lay.upload(x), to_device(c, dtype), rows, B, L, d_out)
+    torch.cuda.synchronize()
+    got = to_host(d_out)
+    assert_close(got[idx], ref[idx], tol, "ffn rows")
+    others = np.setdiff1d(np.arange(T), idx)
+    assert np.array_equal(got[others], out0[others].astype(np.float64))
+    lay.close()
+
+
 def test_error_paths_do_not_launch():
     _say("error paths")
     s = small_shape("f32")
