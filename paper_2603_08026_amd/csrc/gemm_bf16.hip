@@ -71,7 +71,6 @@ template <typename SH, typename Epi>
 void run_tiles(GemmA A, Rows rows, int K, int N, WSeg seg, const void *w2, Epi epi, int splitk,
                float *part, hipStream_t s) {
   set_lds_once<SH, Epi>();
-  const int tiles = ((rows.cap + SH::BM - 1) / SH::BM) * (N / SH::BN);
   // one workgroup per tile up to 2048, as the kernel numbers them when the list is full: per XCD its
   // share of the full row tiles' tiles and its share of a partial last row tile's, each rounded up
   // (a shorter list leaves workgroups without a tile, or in rare splits gives a few a second one)
@@ -80,7 +79,6 @@ void run_tiles(GemmA A, Rows rows, int K, int N, WSeg seg, const void *w2, Epi e
   int gx = ((n_full + N_XCD - 1) / N_XCD + (n_part + N_XCD - 1) / N_XCD) * N_XCD;
   if (gx < N_XCD) gx = N_XCD;
   if (gx > 2048) gx = 2048;
-  (void)tiles;
   SplitStore sp{part, (size_t)rows.cap * N, N};
   dim3 grid(gx, splitk);
   k_gemm_bf16<SH, Epi><<<grid, SH::NT, SH::LDS_BYTES, s>>>(

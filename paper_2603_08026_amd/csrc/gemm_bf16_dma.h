@@ -38,35 +38,29 @@ constexpr int BK = 64;    // K slice (elements)
 constexpr int ROWB = 128; // bytes per tile row and slice
 constexpr int N_XCD = 8;
 
-// NSA_ > 0 selects separate copy roles for the weight-streaming regime: the first half of the waves
-// copies only weight rows, NS_ stages deep, the second half only A rows, NSA_ stages deep.  A wave's
-// copies complete in order, so one wave cannot keep a deep queue of weight slices (HBM, long latency,
-// the bytes that matter) next to a shallow one of A slices (L2): the split lets the weight queue be as
-// deep as the LDS allows.
-template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, bool DUAL_, int NS_, int NSA_ = 0> struct Shape {
+// Tile shape: BM x BN output tile, WAVES_M x WAVES_N waves, DUAL = two weight matrices per tile (fused
+// gate/up), NS LDS stages of one K slice each.
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, bool DUAL_, int NS_> struct Shape {
   static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, NS = NS_;
   static constexpr bool DUAL = DUAL_;
-  static constexpr bool ROLES = NSA_ > 0;
-  static constexpr int NSA = ROLES ? NSA_ : NS_;  // stages of the A tile
   static constexpr int NMAT = DUAL ? 2 : 1;
   static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   static constexpr int MB = WM / 32, NB = WN / 32;
   static constexpr int NW = WAVES_M * WAVES_N;  // waves per workgroup (4 or 8)
   static constexpr int NT = NW * 64;
-  static constexpr int NWC = ROLES ? NW / 2 : NW;  // waves that copy one operand
-  static constexpr int A_LD = BM / (8 * NWC);  // copy instructions per copying wave and slice (8 rows each)
-  static constexpr int B_LD = BN / (8 * NWC);
-  static constexpr int LPS = A_LD + NMAT * B_LD;  // copies per wave and slice when every wave copies both
+  static constexpr int A_LD = BM / (8 * NW);  // copy instructions per wave and slice (8 rows each)
+  static constexpr int B_LD = BN / (8 * NW);
+  static constexpr int LPS = A_LD + NMAT * B_LD;  // copies per wave and slice
   static constexpr int A_BYTES = BM * ROWB, W_BYTES = NMAT * BN * ROWB;
-  static constexpr int STAGE_BYTES = A_BYTES + W_BYTES;
-  static constexpr size_t LDS_BYTES = (size_t)NSA * A_BYTES + (size_t)NS * W_BYTES;
+  static constexpr size_t LDS_BYTES = (size_t)NS * (A_BYTES + W_BYTES);
   // shapes with three or more stages (weight streaming) run the loop pipelined over slices
-  static constexpr bool PIPE = !ROLES && NS >= 3;
+  static constexpr bool PIPE = NS >= 3;
   static_assert(NW == 4 || NW == 8, "four or eight waves per workgroup");
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile is made of 32x32 blocks");
-  static_assert(BM % (8 * NWC) == 0 && BN % (8 * NWC) == 0, "tile rows are copied in blocks of 8 per wave");
-  static_assert(NS >= 2 && NSA >= 2 && (ROLES ? NS <= 16 : NS <= 8), "LDS stages");
-  static_assert((NS - 1) * (ROLES ? NMAT * B_LD : LPS) < 64 && (NSA - 2) * A_LD < 64, "vmcnt immediate");
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows are copied in blocks of 8 per wave");
+  static_assert(NS >= 2 && NS <= 8, "LDS stages");
+  static_assert((NS - 1) * LPS < 64, "vmcnt immediate");
+  static_assert(PIPE || MB * NB * NMAT > 2, "two-stage shapes interleave operand reads with enough products");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS of one CU");
 };
 
@@ -83,13 +77,10 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
                                                    const bf16_t *__restrict__ W2, int ldw, int kchunk,
                                                    int group_m, Epi epi, SplitStore split) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
-  constexpr int BM = SH::BM, BN = SH::BN, MB = SH::MB, NB = SH::NB, NMAT = SH::NMAT, NS = SH::NS,
-                NSA = SH::NSA, NWC = SH::NWC;
-  constexpr bool ROLES = SH::ROLES;
+  constexpr int BM = SH::BM, BN = SH::BN, MB = SH::MB, NB = SH::NB, NMAT = SH::NMAT, NS = SH::NS, NW = SH::NW;
 
   const int M = rows.count ? min(*rows.count, rows.cap) : rows.cap;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
-  const int total = tiles_m * tiles_n;
   const int tid = threadIdx.x, lane = tid % WAVE;
   const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);  // wave-uniform, kept scalar
   const int wm0 = (wave / SH::WAVES_N) * SH::WM, wn0 = (wave % SH::WAVES_N) * SH::WN;
@@ -99,13 +90,10 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
   const int KT = kchunk / BK;
   const uint32_t lds0 = lds_offset_of(smem_raw);
 
-  // copy roles: every wave copies both operands, or (ROLES) waves [0, NWC) the weights and the rest A
-  const bool copies_w = !ROLES || wave < NWC, copies_a = !ROLES || wave >= NWC;  // wave-uniform
-  const int wavec = ROLES ? wave % NWC : wave;  // index among the waves that copy the same operand
   // copy mapping of this lane inside an 8-row block: tile row r8, chunk position p, source chunk c
   const int r8 = lane / 8, cpos = lane % 8;
-  // tile row of this lane in copy i is (i*NWC + wavec)*8 + r8, so (row/2) % 8 = ((wavec & 1) * 4 + r8 / 2)
-  const int csrc = cpos ^ (((wavec & 1) << 2) | (r8 >> 1));
+  // tile row of this lane in copy i is (i*NW + wave)*8 + r8, so (row/2) % 8 = ((wave & 1) * 4 + r8 / 2)
+  const int csrc = cpos ^ (((wave & 1) << 2) | (r8 >> 1));
   // operand-read swizzle of this lane: chunk position of logical chunk (2*kk + lhi)
   int rd_off[BK / 16];
 #pragma unroll
@@ -121,7 +109,6 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
   const int n_full = rows_full * tiles_n, n_part = has_tail * tiles_n;
   const int fx = (n_full + N_XCD - 1) / N_XCD, px = (n_part + N_XCD - 1) / N_XCD;
   const int total_pad = (fx + px) * N_XCD;
-  (void)total;
 
   for (int p = blockIdx.x; p < total_pad; p += gridDim.x) {
     const int xcd = p % N_XCD, q = p / N_XCD;
@@ -146,7 +133,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
     const bf16_t *ap[SH::A_LD];
 #pragma unroll
     for (int i = 0; i < SH::A_LD; ++i) {
-      int j = m0 + (i * NWC + wavec) * 8 + r8;
+      int j = m0 + (i * NW + wave) * 8 + r8;
       j = j < M ? j : M - 1;  // rows past the end are clamped; their results are never stored
       const int src = gather ? gather[j] : j;
       ap[i] = A + (size_t)src * lda + kbeg + csrc * 8;
@@ -155,7 +142,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
     const bf16_t *wp[NMAT][SH::B_LD];
 #pragma unroll
     for (int i = 0; i < SH::B_LD; ++i) {
-      const int nrow = (i * NWC + wavec) * 8 + r8;
+      const int nrow = (i * NW + wave) * 8 + r8;
       const int n = n0 + nrow;
       const bool in1 = n >= seg.n_end[0], in2 = n >= seg.n_end[1];
       const bf16_t *wbase = (const bf16_t *)(in2 ? seg.w[2] : in1 ? seg.w[1] : seg.w[0]);
@@ -174,21 +161,21 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
 #pragma unroll
           for (int e = 0; e < 16; ++e) acc[t][i][j][e] = 0.f;
 
-    // LDS: NSA stages of the A tile, then NS stages of the weight tile(s)
-    auto issue_a = [&](int kt) {  // A rows of slice kt -> A stage kt % NSA
-      const uint32_t sb = lds0 + (uint32_t)(kt % NSA) * SH::A_BYTES + (uint32_t)wavec * 1024u;
+    // LDS: NS stages of the A tile, then NS stages of the weight tile(s)
+    auto issue_a = [&](int kt) {  // A rows of slice kt -> A stage kt % NS
+      const uint32_t sb = lds0 + (uint32_t)(kt % NS) * SH::A_BYTES + (uint32_t)wave * 1024u;
       const int ko = kt * BK;
 #pragma unroll
-      for (int i = 0; i < SH::A_LD; ++i) dma16(ap[i] + ko, sb + i * (NWC * 1024u));
+      for (int i = 0; i < SH::A_LD; ++i) dma16(ap[i] + ko, sb + i * (NW * 1024u));
     };
     auto issue_w = [&](int kt) {  // weight rows of slice kt -> weight stage kt % NS
-      const uint32_t sb = lds0 + (uint32_t)(NSA * SH::A_BYTES) + (uint32_t)(kt % NS) * SH::W_BYTES +
-                          (uint32_t)wavec * 1024u;
+      const uint32_t sb = lds0 + (uint32_t)(NS * SH::A_BYTES) + (uint32_t)(kt % NS) * SH::W_BYTES +
+                          (uint32_t)wave * 1024u;
       const int ko = kt * BK;
 #pragma unroll
       for (int t = 0; t < NMAT; ++t)
 #pragma unroll
-        for (int i = 0; i < SH::B_LD; ++i) dma16(wp[t][i] + ko, sb + (uint32_t)(t * BN) * ROWB + i * (NWC * 1024u));
+        for (int i = 0; i < SH::B_LD; ++i) dma16(wp[t][i] + ko, sb + (uint32_t)(t * BN) * ROWB + i * (NW * 1024u));
     };
 
     __syncthreads();  // LDS free: the previous tile of this workgroup is fully consumed
@@ -251,18 +238,18 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
         slice(kt + 1, std::integral_constant<int, 1>{});
       }
       if (kt < KT) slice(kt, std::integral_constant<int, 0>{});
-    } else if (!ROLES && NS == 2 && m0 + BM > M) {
+    } else if (NS == 2 && m0 + BM > M) {
       // A row tile that holds fewer than BM rows: copies of 8-row blocks past the end are left out,
       // and a wave multiplies only its 32-row blocks that hold rows (none at all for many waves), so
       // that the tile costs about what its weight copies cost.  Same barriers as the full loop.
       const int mbv_raw = (M - (m0 + wm0) + 31) / 32;
       const int mbv = mbv_raw < 0 ? 0 : (mbv_raw > MB ? MB : mbv_raw);  // wave-uniform
       auto issue_a_part = [&](int kt) {
-        const uint32_t sb = lds0 + (uint32_t)(kt % NSA) * SH::A_BYTES + (uint32_t)wavec * 1024u;
+        const uint32_t sb = lds0 + (uint32_t)(kt % NS) * SH::A_BYTES + (uint32_t)wave * 1024u;
         const int ko = kt * BK;
 #pragma unroll
         for (int i = 0; i < SH::A_LD; ++i)
-          if (m0 + (i * NWC + wavec) * 8 < M) dma16(ap[i] + ko, sb + i * (NWC * 1024u));
+          if (m0 + (i * NW + wave) * 8 < M) dma16(ap[i] + ko, sb + i * (NW * 1024u));
       };
       issue_a_part(0);
       issue_w(0);
@@ -274,8 +261,8 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
           issue_w(kt + 1);
         }
         if (mbv == 0) continue;  // wave-uniform; the barriers above are all this wave owes the tile
-        const unsigned char *sa = smem_raw + (size_t)(kt % NSA) * SH::A_BYTES + (wm0 + l32) * ROWB;
-        const unsigned char *sb = smem_raw + (size_t)NSA * SH::A_BYTES + (size_t)(kt % NS) * SH::W_BYTES +
+        const unsigned char *sa = smem_raw + (size_t)(kt % NS) * SH::A_BYTES + (wm0 + l32) * ROWB;
+        const unsigned char *sb = smem_raw + (size_t)NS * SH::A_BYTES + (size_t)(kt % NS) * SH::W_BYTES +
                                   (wn0 + l32) * ROWB;
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
@@ -299,63 +286,21 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
         }
       }
     } else {
-    // slice by slice (a wave that copies both operands counts whole slices in its waits)
+    // slice by slice
 #pragma unroll
-    for (int s = 0; s < (NS > NSA ? NS : NSA) - 1; ++s) {
-      if (copies_a && s < NSA - 1 && s < KT) issue_a(s);
-      if (copies_w && s < NS - 1 && s < KT) issue_w(s);
-    }
+    for (int s = 0; s < NS - 1; ++s)
+      if (s < KT) { issue_a(s); issue_w(s); }
 
     for (int kt = 0; kt < KT; ++kt) {
       // slice kt has landed (this wave's part); a wave's copies complete in issue order
-      if (!ROLES) {
-        if (kt + NS - 2 < KT) wait_vmcnt<(NS - 2) * SH::LPS>();
-        else wait_vmcnt<0>();
-      } else if (copies_w) {
-        if (kt + NS - 2 < KT) wait_vmcnt<(NS - 2) * NMAT * SH::B_LD>();
-        else wait_vmcnt<0>();
-      } else {
-        if (kt + NSA - 2 < KT) wait_vmcnt<(NSA - 2) * SH::A_LD>();
-        else wait_vmcnt<0>();
-      }
+      if (kt + NS - 2 < KT) wait_vmcnt<(NS - 2) * SH::LPS>();
+      else wait_vmcnt<0>();
       __syncthreads();  // ... all waves' parts; and everyone is done with slice kt-1
-      if (copies_a && kt + NSA - 1 < KT) issue_a(kt + NSA - 1);  // into the stages slice kt-1 occupied
-      if (copies_w && kt + NS - 1 < KT) issue_w(kt + NS - 1);
+      if (kt + NS - 1 < KT) { issue_a(kt + NS - 1); issue_w(kt + NS - 1); }  // into the stage slice kt-1 left
 
-      const unsigned char *sa = smem_raw + (size_t)(kt % NSA) * SH::A_BYTES + (wm0 + l32) * ROWB;
-      const unsigned char *sb = smem_raw + (size_t)NSA * SH::A_BYTES + (size_t)(kt % NS) * SH::W_BYTES +
+      const unsigned char *sa = smem_raw + (size_t)(kt % NS) * SH::A_BYTES + (wm0 + l32) * ROWB;
+      const unsigned char *sb = smem_raw + (size_t)NS * SH::A_BYTES + (size_t)(kt % NS) * SH::W_BYTES +
                                 (wn0 + l32) * ROWB;
-      if (SH::MB * SH::NB * NMAT <= 2) {
-        // Few matrix products per wave and step (weight-streaming shapes): a single product cannot
-        // cover the LDS latency of the next step's operands, so all operands of the slice are
-        // fetched first and the products follow.
-        constexpr int KS = BK / 16;
-        bf16x8 af[KS][MB], bfr[KS][NMAT][NB];
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk) {
-#pragma unroll
-          for (int i = 0; i < MB; ++i)
-            af[kk][i] = *reinterpret_cast<const bf16x8 *>(sa + i * 32 * ROWB + rd_off[kk]);
-#pragma unroll
-          for (int t = 0; t < NMAT; ++t)
-#pragma unroll
-            for (int jn = 0; jn < NB; ++jn)
-              bfr[kk][t][jn] = *reinterpret_cast<const bf16x8 *>(sb + (t * BN + jn * 32) * ROWB + rd_off[kk]);
-        }
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk)
-#pragma unroll
-          for (int t = 0; t < NMAT; ++t)
-#pragma unroll
-            for (int i = 0; i < MB; ++i)
-#pragma unroll
-              for (int jn = 0; jn < NB; ++jn)
-                acc[t][i][jn] =
-                    __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk][i], bfr[kk][t][jn], acc[t][i][jn], 0, 0, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, KS * (MB + NMAT * NB), 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, KS * NMAT * MB * NB, 0);
-        continue;
-      }
       // operand fragments of slice step kk+1 are fetched while the MFMAs of step kk run
       bf16x8 af[2][MB], bfr[2][NMAT][NB];
 #pragma unroll
