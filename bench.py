@@ -305,6 +305,23 @@ def main():
             lay.layer_step_approx(steps[i][0], steps[i][1], -2.0)
         torch.cuda.synchronize()
         approx["ms_per_step_nothing_selected"] = (time.perf_counter() - t0) / K * 1e3
+        # ... and as a response-only step (Sec. 3.5): the step's tokens are the last resp_len positions
+        # of every sequence, the candidates are cut down to them, keys and values span the sequence
+        row_lo = wl.seq - wl.resp_len
+        if 0 < row_lo < wl.seq:
+            resp_lists = []
+            for i in range(Wu, Wu + K):
+                cut = lay.make_list(np.zeros(0, np.int32), np.zeros(wl.batch + 1, np.int32), cap=steps[i][2])
+                lay.ctx.merge_lists(steps[i][1], None, wl.batch, wl.seq, row_lo, cut)
+                resp_lists.append(cut)
+            restore()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(Wu, Wu + K):
+                lay.layer_step_approx(steps[i][0], resp_lists[i - Wu], -2.0, row_lo=row_lo)
+            torch.cuda.synchronize()
+            approx["ms_per_step_response_only_nothing_selected"] = (time.perf_counter() - t0) / K * 1e3
+            approx["response_rows"] = wl.batch * wl.resp_len
     del snap
 
     # dense step of the same shape on the same GPU
