@@ -29,7 +29,7 @@ typedef Shape<128, 64, 4, 2, false, 4> SkinnyS;
 typedef Shape<128, 96, 4, 1, false, 4> SkinnyW96;
 typedef Shape<128, 128, 4, 2, false, 4> SkinnyW128;
 
-constexpr int MID_MAX_ROWS = 384;
+constexpr int MID_MAX_ROWS = 320;  // above, 256-row tiles with a cheap partial second row tile do better
 constexpr int SKINNY_MAX_ROWS = 128;
 
 int cu_count() {

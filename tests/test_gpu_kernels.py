@@ -264,7 +264,7 @@ def test_salient_ffn(dtype):
 
 @pytest.mark.parametrize("M,cap", [(520, 520), (520, 820), (700, 701), (1024, 1024), (397, 900), (769, 1600)])
 def test_large_tile_regime_with_ragged_row_counts(M, cap):
-    """More than 384 list entries: 256-row GEMM tiles.  A last row tile with few rows runs the
+    """More than 320 list entries: 256-row GEMM tiles.  A last row tile with few rows runs the
     shortened loop and is numbered after the full tiles on every XCD; a list shorter than its capacity
     moves that split away from what the host sized the grid for."""
     _say("large tiles, ragged", M, cap)
