@@ -357,8 +357,8 @@ int enqueue_merge(dyllm_ctx *ctx, const dyllm_index_list *a, const dyllm_index_l
                   int pos_lo, dyllm_index_list *out, hipStream_t s) {
   const int T = B * L;
   launch_fill_i32((int32_t *)ctx->flag, 0, (T + 3) / 4, s);
-  if (a) launch_mark_flags(rows_of(a, B), L, pos_lo, ctx->flag, s);
-  if (b) launch_mark_flags(rows_of(b, B), L, pos_lo, ctx->flag, s);
+  if (a) launch_mark_flags(rows_of(a, B), T, L, pos_lo, ctx->flag, s);
+  if (b) launch_mark_flags(rows_of(b, B), T, L, pos_lo, ctx->flag, s);
   launch_compact(ctx->flag, Rows{nullptr, nullptr, T}, B, L, out->idx, out->offsets, out->cap, ctx->status, s);
   return check_launch(ctx, "list merge");
 }

@@ -123,8 +123,8 @@ void launch_saliency_approx(DType t, Rows win, int D, const void *c_sal, const v
                             void *c_cache, float tau, float *cos_out, uint8_t *flag_out, hipStream_t s);
 // idx/off := the tokens at positions [lo, L) of each of the B sequences, as an index list
 void launch_make_window(int B, int L, int lo, int32_t *idx, int32_t *off, hipStream_t s);
-// flag[r] = 1 for every token r of the list whose position in its sequence is >= lo
-void launch_mark_flags(Rows rows, int L, int lo, uint8_t *flag, hipStream_t s);
+// flag[r] = 1 for every token r < T of the list whose position in its sequence is >= lo
+void launch_mark_flags(Rows rows, int T, int L, int lo, uint8_t *flag, hipStream_t s);
 // pos[row_j] = 0 and dv[row_j, :] = 0 for the rows of the list
 void launch_clear_rows(DType t, Rows rows, int32_t *pos, void *dv, int dkv, hipStream_t s);
 

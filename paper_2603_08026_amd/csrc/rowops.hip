@@ -432,12 +432,13 @@ __global__ __launch_bounds__(256) void k_make_window(int B, int L, int lo, int32
     for (int b = threadIdx.x; b <= B; b += 256) off[b] = b * w;
 }
 
-// flag[r] = 1 for the tokens r of a list at positions >= lo of their sequence
-__global__ __launch_bounds__(256) void k_mark_flags(Rows rows, int L, int lo, uint8_t *flag) {
+// flag[r] = 1 for the tokens r of a list at positions >= lo of their sequence (an id outside [0, T)
+// is ignored rather than written through)
+__global__ __launch_bounds__(256) void k_mark_flags(Rows rows, int T, int L, int lo, uint8_t *flag) {
   const int n = row_count(rows);
   for (int j = blockIdx.x * 256 + threadIdx.x; j < n; j += gridDim.x * 256) {
     const int r = rows.idx[j];
-    if (r % L >= lo) flag[r] = 1;
+    if ((unsigned)r < (unsigned)T && r % L >= lo) flag[r] = 1;
   }
 }
 
@@ -463,9 +464,9 @@ void launch_make_window(int B, int L, int lo, int32_t *idx, int32_t *off, hipStr
   k_make_window<<<n > 0 ? (n + 255) / 256 : 1, 256, 0, s>>>(B, L, lo, idx, off);
 }
 
-void launch_mark_flags(Rows rows, int L, int lo, uint8_t *flag, hipStream_t s) {
+void launch_mark_flags(Rows rows, int T, int L, int lo, uint8_t *flag, hipStream_t s) {
   if (rows.cap <= 0) return;
-  k_mark_flags<<<(rows.cap + 255) / 256, 256, 0, s>>>(rows, L, lo, flag);
+  k_mark_flags<<<(rows.cap + 255) / 256, 256, 0, s>>>(rows, T, L, lo, flag);
 }
 
 void launch_clear_rows(DType t, Rows rows, int32_t *pos, void *dv, int dkv, hipStream_t s) {
