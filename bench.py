@@ -131,11 +131,14 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default 40; 6 for c5)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default 5; 2 for c5)")
-    ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c6"])
     ap.add_argument("--layers", type=int, default=None, help="stack depth override for c5")
     ap.add_argument("--frac", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dense-iters", type=int, default=3)
+    ap.add_argument("--variant", default="sparse", choices=["sparse", "salient-ablation"],
+                    help="salient-ablation: every token is a candidate (exact attention and the cosine test "
+                         "over all rows), out-projection and FFN for the selected ones only (Table 1, 'Salient')")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the graph-replay, approximate-step and stand-alone-kernel legs (profiling runs)")
     args = ap.parse_args()
@@ -200,6 +203,9 @@ def main():
         xd = lay.upload(st.x)
         if st.dense:
             dense_x.append(xd)
+        elif args.variant == "salient-ablation":
+            all_idx = np.arange(wl.tokens, dtype=np.int32)
+            steps.append((xd, lay.make_list(all_idx, np.arange(wl.batch + 1, dtype=np.int32) * wl.seq), wl.tokens))
         else:
             steps.append((xd, lay.make_list(st.idx, st.offsets), int(st.idx.size)))
     # cache warm-up: T_full dense steps (Sec. 3.2)
@@ -335,7 +341,8 @@ def main():
     t_dense = (time.perf_counter() - t0) / args.dense_iters
 
     m_in = float(np.mean([m for _, _, m in steps[Wu:Wu + K]]))
-    work = stage_work(s, wl.batch, wl.seq, m_in, m_in, esz)  # every candidate passes the test here
+    # (sparse variant: every candidate passes the test on this workload; ablation: the last step's count)
+    work = stage_work(s, wl.batch, wl.seq, m_in, m_in if args.variant == "sparse" else float(m_out_last), esz)
     # every stage time runs from one stream event to the next; the cost of the event itself is
     # measured by the stage that has no kernel and taken off the others
     ev = stage_ms.get("marker_overhead", 0.0)
@@ -372,7 +379,7 @@ def main():
         "value": wl.tokens * NL / t_step, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wu,
         "ms_per_step": t_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": s.dtype, "data": "synthetic",
-        "config": {"workload": wl.name, "batch": wl.batch, "seq_len": wl.seq, "salient_frac": wl.frac,
+        "config": {"workload": wl.name + ("" if args.variant == "sparse" else "+" + args.variant), "batch": wl.batch, "seq_len": wl.seq, "salient_frac": wl.frac,
                    "salient_rows_mean": m_in, "salient_rows_out_last": m_out_last, "tau": wl.tau,
                    "hidden": s.hidden, "n_heads": s.n_heads, "n_kv_heads": s.n_kv_heads, "ffn": s.ffn,
                    "layers": NL},

@@ -89,6 +89,8 @@ class Workload:
     tau: float = 0.99
     n_layers: int = 1
     drift_std: float = 1e-3
+    resp_share: Optional[float] = None  # share of the redrawn rows taken from the response (None: uniform over L)
+    unmask: Optional[int] = None        # tokens unmasked per step and sequence (None: resp_len // steps)
 
     @property
     def seq(self) -> int:
@@ -100,7 +102,7 @@ class Workload:
 
     @property
     def n_unmask(self) -> int:
-        return max(1, self.resp_len // self.steps)
+        return max(1, self.resp_len // self.steps) if self.unmask is None else self.unmask
 
 
 TINY = LayerShape(hidden=256, n_heads=4, n_kv_heads=4, head_dim=64, ffn=768, dtype="f32")
@@ -119,6 +121,10 @@ CONFIGS: Dict[str, Workload] = {
     # 32-layer LLaDA-shaped stack, batch 16, 1536 + 512
     "c5": Workload("c5-llada8b-stack32-b16-l2048", LLADA, 16, 1536, 512, 128, 0.10,
                    ragged=True, tau=0.99, n_layers=32),
+    # second workload: salient tokens concentrated in the response (Sec. 3.5; App. D.1: context
+    # updates cluster around the latest unmasked tokens), two tokens unmasked per step (Sec. 4.2.4)
+    "c6": Workload("c6-llada8b-b16-l1280-resp", LLADA, 16, 1024, 256, 128, 0.05, ragged=True, tau=0.99,
+                   resp_share=0.9, unmask=2),
 }
 
 
@@ -186,7 +192,14 @@ def step_rows(w: Workload, t: int, seed: int = SEED_X) -> Tuple[np.ndarray, np.n
     nu = w.n_unmask
     for b in range(w.batch):
         n = _count_for(w, t, b, seed)
-        red = philox(seed, "redraw", t, b).choice(w.seq, size=n, replace=False)
+        g = philox(seed, "redraw", t, b)
+        if w.resp_share is None:
+            red = g.choice(w.seq, size=n, replace=False)
+        else:  # n_r of the n rows from the response positions, the others from the prompt
+            n_r = min(w.resp_len, int(round(w.resp_share * n)))
+            n_p = min(w.prompt_len, n - n_r)
+            red = np.concatenate([w.prompt_len + g.choice(w.resp_len, size=n_r, replace=False),
+                                  g.choice(w.prompt_len, size=n_p, replace=False)])
         order = unmask_order(w, b, seed)
         lo = ((t - 1) * nu) % max(1, w.resp_len)
         newly = order[lo:lo + nu]

@@ -192,7 +192,7 @@ def _slice_batch(wl: W.Workload, nb: int) -> W.Workload:
     return replace(wl, batch=nb, name=wl.name + "-first%d" % nb)
 
 
-@pytest.mark.parametrize("name,nb,steps", [("c2", 1, 7), ("c3", 2, 6), ("c4", 2, 6)])
+@pytest.mark.parametrize("name,nb,steps", [("c2", 1, 7), ("c3", 2, 6), ("c4", 2, 6), ("c6", 2, 5)])
 def test_8b_shapes_teacher_forced(name, nb, steps):
     """1..4 dense warm-up steps then sparse steps at the real layer shape (first nb sequences)."""
     wl = _slice_batch(W.CONFIGS[name], nb)
@@ -310,4 +310,47 @@ def test_wide_batch_with_bias_in_the_large_tile_regime(dh, hkv):
         assert torch.equal(getattr(lay, k), sparse[k]), k
     O.full_step(x1, w, cfg, ref)
     _compare_caches(lay, ref, TOL["bf16"], "wide dense, second input")
+    lay.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_salient_ablation_variant(dtype):
+    """Table 1's 'Salient' variant: every token is a candidate (exact attention and the cosine test
+    over all rows), out-projection and FFN only for the tokens the test selects."""
+    _say("salient ablation", dtype)
+    s = small_shape(dtype, gqa=True)
+    cfg = oracle_cfg(s)
+    B, L = 2, 96
+    T = B * L
+    w = rand_weights(s, 151, std=0.08)
+    lay = Layer.from_shape(s, B, L)
+    lay.set_weights(w)
+    x0 = W.philox(152, "x0").standard_normal((B, L, s.hidden), dtype=np.float32)
+    x0 = W.round_bf16(x0) if dtype == "bf16" else x0
+    ref = O.new_caches(B, L, cfg)
+    O.full_step(x0, w, cfg, ref)
+    start = {k: (W.round_bf16(v.astype(np.float32)) if dtype == "bf16" else v.astype(np.float32)) for k, v in ref.items()}
+    lay.set_caches(start)
+    ref = {k: v.astype(np.float64) for k, v in start.items()}
+    # every row moves by its own amount, so that the cosines spread and the median threshold splits them
+    sig = 10.0 ** W.philox(153, "sig").uniform(-3, 0, T)
+    x1 = W.perturbed_rows(x0.reshape(T, -1), sig, 154)
+    x1 = (W.round_bf16(x1) if dtype == "bf16" else x1).reshape(B, L, -1)
+    allrows = np.arange(T, dtype=np.int32)
+    probe = O.layer_step(x1, allrows, w, cfg, {k: v.copy() for k, v in ref.items()}, 0.5)[2]
+    tau = float(np.median(probe))
+    before_out = ref["out"].copy()
+    idx_ref, off_ref, cos_ref = O.layer_step(x1, allrows, w, cfg, ref, tau)
+    assert 0 < idx_ref.size < T
+    out = lay.layer_step(lay.upload(x1), lay.make_list(allrows, np.arange(B + 1, dtype=np.int32) * L), tau)
+    idx_g, off_g = lay.read_list(out)
+    assert_index_sets_match(idx_g, idx_ref, allrows, cos_ref, tau, "ablation")
+    got = lay.get_caches()
+    for name in ("k", "v", "c"):
+        assert_close(got[name], ref[name], TOL[dtype], "ablation %s" % name)
+    both = np.intersect1d(idx_g, idx_ref)
+    assert_close(got["out"].reshape(T, -1)[both], ref["out"].reshape(T, -1)[both], TOL[dtype], "ablation out rows")
+    kept = np.setdiff1d(allrows, np.union1d(idx_g, idx_ref))
+    assert kept.size > 0
+    assert np.array_equal(got["out"].reshape(T, -1)[kept], before_out.reshape(T, -1)[kept])  # cached rows reused
     lay.close()

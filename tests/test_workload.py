@@ -84,3 +84,18 @@ def test_weights_shapes_and_bf16_rounding():
     wb = W.make_weights(small)
     assert wb["wk"].shape == (32, 64)
     assert all(np.all((v.view(np.uint32) & 0xFFFF) == 0) for v in wb.values())
+
+
+def test_second_workload_concentrates_the_redraw_in_the_response():
+    w = W.CONFIGS["c6"]
+    assert w.n_unmask == 2
+    for t in (1, 7, 40):
+        idx, off = W.step_rows(w, t)
+        assert np.all(np.diff(idx) > 0) and off[-1] == idx.size
+        pos = idx % w.seq
+        share = np.mean(pos >= w.prompt_len)
+        assert 0.85 <= share <= 0.95
+        for b in range(w.batch):
+            rows = idx[off[b]:off[b + 1]]
+            assert np.all(rows // w.seq == b)
+            assert 0.5 * 0.05 * w.seq - 2 <= rows.size <= 1.5 * 0.05 * w.seq + 2 + w.n_unmask
