@@ -18,6 +18,9 @@ What each function follows:
   approx_attention ................ App. C.4, Alg. 4 (approximate attention): the
                                     salient columns of the full softmax times the
                                     value residual of the salient tokens  [Eq. 3]
+  approx_attention_cached ......... variant of Alg. 4 with the softmax normalisers reused from each
+                                    query's last exact evaluation (Sec. 3.3: cost O(N |A| d),
+                                    "attention weights are reused"); not the printed algorithm
   layer_step_approx ............... Alg. 3 layer body with both attention paths
                                     (exact rows for the salient set, approximate
                                     context update for all other rows)
@@ -158,6 +161,20 @@ def attention_rows(q: np.ndarray, k: np.ndarray, v: np.ndarray) -> np.ndarray:
     return out.reshape(m, H * dh)
 
 
+def attention_lse(q: np.ndarray, k: np.ndarray) -> np.ndarray:
+    """Log of the softmax normaliser of every (query, head): log sum_j exp(q.k_j / sqrt(dh)) over all
+    keys of the sequence.  q: [m, H, dh], k: [L, Hkv, dh]; returns [m, H]."""
+    q, k = _f64(q), _f64(k)
+    m, H, dh = q.shape
+    g = H // k.shape[1]
+    out = np.empty((m, H), dtype=F64)
+    for h in range(H):
+        z = (q[:, h, :] @ k[:, h // g, :].T) / np.sqrt(dh)
+        top = z.max(axis=1)
+        out[:, h] = top + np.log(np.exp(z - top[:, None]).sum(axis=1))
+    return out
+
+
 def cosine_rows(a: np.ndarray, b: np.ndarray) -> np.ndarray:
     """s = <a,b> / (max(|a|, floor) * max(|b|, floor)) per row.  [Sec. 3.1]"""
     a, b = _f64(a), _f64(b)
@@ -228,6 +245,17 @@ def partial_attention(q_sal: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarra
         sel = np.nonzero((rows >= b * L) & (rows < (b + 1) * L))[0]
         if sel.size:
             out[sel] = attention_rows(q_sal[sel], k_cache[b], v_cache[b])
+    return out
+
+
+def partial_lse(q_sal: np.ndarray, k_cache: np.ndarray, rows: np.ndarray, B: int, L: int) -> np.ndarray:
+    """attention_lse for the tokens in rows (flat ids), each against its own sequence's keys: [M, H]."""
+    rows = np.asarray(rows, dtype=np.int64)
+    out = np.empty((q_sal.shape[0], q_sal.shape[1]), dtype=F64)
+    for b in range(B):
+        sel = np.nonzero((rows >= b * L) & (rows < (b + 1) * L))[0]
+        if sel.size:
+            out[sel] = attention_lse(q_sal[sel], k_cache[b])
     return out
 
 
@@ -309,6 +337,8 @@ def full_step(x: np.ndarray, w: Dict[str, np.ndarray], cfg: LayerCfg,
         gate = f @ wg.T
         y = hcur + ((gate / (1.0 + np.exp(-gate))) * (f @ wu.T)) @ wd.T
         caches["k"][b], caches["v"][b], caches["c"][b], caches["out"][b] = K, V, C, y
+        if "lse" in caches:  # optional fifth cache: log-normalisers of the exact rows (cached-normaliser variant)
+            caches["lse"][b] = attention_lse(Q, K)
 
 
 def layer_step(x: np.ndarray, idx_in: np.ndarray, w: Dict[str, np.ndarray], cfg: LayerCfg,
@@ -348,6 +378,8 @@ def layer_step(x: np.ndarray, idx_in: np.ndarray, w: Dict[str, np.ndarray], cfg:
     vc[idx_in] = v
     # (3) exact rows
     c_new = partial_attention(q, caches["k"], caches["v"], idx_in, B, L)
+    if "lse" in caches:
+        caches["lse"].reshape(B * L, -1)[idx_in] = partial_lse(q, caches["k"], idx_in, B, L)
     # (4) cosine against the cached context, selection
     cos = cosine_rows(c_new, cc[idx_in])
     flag = salient_mask(cos, tau)
@@ -387,9 +419,41 @@ def approx_attention(q_all: np.ndarray, k_cache: np.ndarray, dv: np.ndarray, idx
     return out
 
 
+def approx_attention_cached(q_all: np.ndarray, k_cache: np.ndarray, dv: np.ndarray, idx_sal: np.ndarray,
+                            lse: np.ndarray, B: int, L: int) -> np.ndarray:
+    """Approximate attention with REUSED normalisers: the weight of salient key j for query i is
+    exp(q_i.k_j / sqrt(dh) - lse_i), with lse_i the log-normaliser cached at query i's last exact
+    evaluation, so that only the salient columns are ever scored -- the O(N |A| d) cost that
+    Sec. 3.3 states and its remark that attention weights are reused.  This is a variant of Alg. 4,
+    which renormalises over all keys; the two agree whenever lse is the current log-normaliser.
+
+    q_all: [T, H, dh]; k_cache: [B, L, Hkv, dh] (merged); dv: [M, Hkv, dh]; idx_sal: [M] flat ids;
+    lse: [T, H].  Returns dC [T, H*dh].
+    """
+    q_all, k_cache, dv, lse = _f64(q_all), _f64(k_cache), _f64(dv), _f64(lse)
+    idx_sal = np.asarray(idx_sal, dtype=np.int64)
+    T, H, dh = q_all.shape
+    g = H // k_cache.shape[2]
+    out = np.zeros((T, H, dh), dtype=F64)
+    for b in range(B):
+        sel = np.nonzero((idx_sal >= b * L) & (idx_sal < (b + 1) * L))[0]
+        if sel.size == 0:
+            continue
+        cols = idx_sal[sel] - b * L
+        for h in range(H):
+            z = (q_all[b * L:(b + 1) * L, h, :] @ k_cache[b, cols, h // g, :].T) / np.sqrt(dh)  # [L, |A_b|]
+            wgt = np.exp(z - lse[b * L:(b + 1) * L, h][:, None])
+            out[b * L:(b + 1) * L, h, :] = wgt @ dv[sel, h // g, :]
+    return out.reshape(T, H * dh)
+
+
 def layer_step_approx(x: np.ndarray, idx_in: np.ndarray, w: Dict[str, np.ndarray], cfg: LayerCfg,
-                      caches: Dict[str, np.ndarray], tau: float, row_lo: int = 0):
+                      caches: Dict[str, np.ndarray], tau: float, row_lo: int = 0, cached_norm: bool = False):
     """One layer of SparseStep with both attention paths.  [Alg. 3 layer body; Sec. 3.3]
+
+    cached_norm: the residual of the non-salient tokens comes from approx_attention_cached with the
+    log-normalisers in caches["lse"] ([B, L, H], kept by full_step and by every exact row) instead of
+    Alg. 4's full softmax.
 
     As layer_step, plus: queries are projected for ALL tokens of the step; the value residual dV of
     the idx_in tokens is taken before their V rows are merged; every other token of the step gets
@@ -426,7 +490,14 @@ def layer_step_approx(x: np.ndarray, idx_in: np.ndarray, w: Dict[str, np.ndarray
         kc[idx_in] = k
         vc[idx_in] = v
         c_sal = partial_attention(q_all[idx_in], caches["k"], caches["v"], idx_in, B, L)
-        dc = approx_attention(q_all, caches["k"], dv, idx_in, B, L)
+        if cached_norm:
+            lse = caches["lse"].reshape(T, cfg.n_heads)
+            dc = approx_attention_cached(q_all, caches["k"], dv, idx_in, lse, B, L)  # stale lse of the others
+            lse[idx_in] = partial_lse(q_all[idx_in], caches["k"], idx_in, B, L)
+        else:
+            dc = approx_attention(q_all, caches["k"], dv, idx_in, B, L)
+            if "lse" in caches:
+                caches["lse"].reshape(T, cfg.n_heads)[idx_in] = partial_lse(q_all[idx_in], caches["k"], idx_in, B, L)
         others = np.setdiff1d(step_rows, idx_in)
         c_new[others] = cc[others] + dc[others]
         c_new[idx_in] = c_sal
@@ -466,12 +537,12 @@ def stack_full_step(x: np.ndarray, ws, cfg: LayerCfg, caches) -> None:
 
 
 def stack_step_approx(x: np.ndarray, idx_in: np.ndarray, ws, cfg: LayerCfg, caches, tau: float,
-                      row_lo: int = 0):
+                      row_lo: int = 0, cached_norm: bool = False):
     """SparseStep over a stack of layers with both attention paths.  [Alg. 3, loop over l]"""
     h, idx = x, idx_in
     per_layer = []
     for w, c in zip(ws, caches):
-        idx, off, cos = layer_step_approx(h, idx, w, cfg, c, tau, row_lo)
+        idx, off, cos = layer_step_approx(h, idx, w, cfg, c, tau, row_lo, cached_norm)
         per_layer.append((idx, off, cos))
         h = c["out"]
     return per_layer

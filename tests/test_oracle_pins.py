@@ -722,3 +722,94 @@ def test_denoise_step_composes_the_schedule(approx):
         for ca, cb in zip(c5, c6):
             for k in ca:
                 assert np.array_equal(ca[k], cb[k])
+
+
+# ---- approximate attention with reused normalisers (variant of Alg. 4; Sec. 3.3 cost claim) -------
+
+def test_attention_lse_is_the_log_of_the_softmax_normaliser():
+    from scipy.special import logsumexp
+    r = _rng(51)
+    q, k = r.normal(size=(7, 4, 8)), r.normal(size=(13, 2, 8))
+    got = O.attention_lse(q, k)
+    for i in range(7):
+        for h in range(4):
+            z = np.array([q[i, h] @ k[j, h // 2] for j in range(13)]) / math.sqrt(8)
+            assert abs(got[i, h] - logsumexp(z)) < 1e-12
+    # one key: the normaliser is that key's score
+    assert np.allclose(O.attention_lse(q, k[:1]), np.einsum("ihd,hd->ih", q, k[0].repeat(2, axis=0)) / math.sqrt(8))
+
+
+def test_cached_normaliser_variant_equals_alg4_with_fresh_normalisers():
+    r = _rng(53)
+    B, L, H, Hkv, dh = 2, 9, 4, 2, 8
+    T = B * L
+    q = r.normal(size=(T, H, dh))
+    k = r.normal(size=(B, L, Hkv, dh))
+    idx = np.array([1, 4, 8, 10, 16])
+    dv = r.normal(size=(idx.size, Hkv, dh))
+    lse = np.concatenate([O.attention_lse(q[b * L:(b + 1) * L], k[b]) for b in range(B)])
+    a = O.approx_attention(q, k, dv, idx, B, L)
+    c = O.approx_attention_cached(q, k, dv, idx, lse, B, L)
+    assert np.allclose(a, c, rtol=1e-12, atol=1e-13)
+    # scalar-loop definition with an arbitrary (stale) normaliser
+    stale = lse + r.normal(size=lse.shape) * 0.3
+    c2 = O.approx_attention_cached(q, k, dv, idx, stale, B, L).reshape(T, H, dh)
+    for i in (0, 7, 12):
+        b = i // L
+        for h in range(H):
+            want = np.zeros(dh)
+            for n, j in enumerate(idx):
+                if j // L == b:
+                    want += math.exp(q[i, h] @ k[b, j % L, h // 2] / math.sqrt(dh) - stale[i, h]) * dv[n, h // 2]
+            assert np.allclose(c2[i, h], want, atol=1e-12)
+    # no salient token in a sequence: no residual there
+    only0 = O.approx_attention_cached(q, k, dv[:3], idx[:3], lse, B, L).reshape(B, L, -1)
+    assert np.all(only0[1] == 0)
+
+
+def test_layer_step_with_reused_normalisers():
+    """The fifth cache is filled by the dense step and refreshed for the exact rows; with unchanged
+    keys the variant reproduces the literal step, with changed keys the two differ only in the
+    contexts of the non-salient tokens."""
+    r, cfg, w, x0, caches = _setup(seed=55)
+    B, L, T = 2, 10, 20
+    caches["lse"] = np.zeros((B, L, cfg.n_heads))
+    O.full_step(x0, w, cfg, caches)
+    q_all = O.rope((O.rmsnorm(x0.reshape(T, -1), w["g_attn"], cfg.rms_eps) @ w["wq"].T).reshape(T, cfg.n_heads, cfg.head_dim),
+                   np.arange(T) % L, cfg.rope_theta)
+    fresh = np.concatenate([O.attention_lse(q_all[b * L:(b + 1) * L], caches["k"][b]) for b in range(B)])
+    assert np.allclose(caches["lse"].reshape(T, -1), fresh, atol=1e-12)
+    # (i) keys that cannot change (a zero key projection): the reused normalisers are the current ones
+    idx = np.array([3, 6, 15])
+    w0 = dict(w)
+    w0["wk"] = np.zeros_like(w["wk"])
+    c0 = O.new_caches(B, L, cfg)
+    c0["lse"] = np.zeros((B, L, cfg.n_heads))
+    O.full_step(x0, w0, cfg, c0)
+    x1 = x0.copy()
+    x1.reshape(T, -1)[idx] = r.normal(size=(idx.size, x0.shape[-1]))
+    a, b_ = _copy(c0), _copy(c0)
+    oa = O.layer_step_approx(x1, idx, w0, cfg, a, 0.999)
+    ob = O.layer_step_approx(x1, idx, w0, cfg, b_, 0.999, cached_norm=True)
+    assert np.array_equal(oa[0], ob[0])
+    for k_ in ("k", "v", "c", "out", "lse"):
+        assert np.allclose(a[k_], b_[k_], rtol=1e-10, atol=1e-12), k_
+    # (ii) keys change: exact rows, K, V and the refreshed normalisers agree; the other contexts differ
+    a, b_ = _copy(caches), _copy(caches)
+    O.layer_step_approx(x1, idx, w, cfg, a, -2.0)
+    O.layer_step_approx(x1, idx, w, cfg, b_, -2.0, cached_norm=True)
+    others = np.setdiff1d(np.arange(T), idx)
+    for k_ in ("k", "v"):
+        assert np.array_equal(a[k_], b_[k_])
+    assert np.allclose(a["c"].reshape(T, -1)[idx], b_["c"].reshape(T, -1)[idx], atol=1e-13)
+    assert np.allclose(a["lse"].reshape(T, -1)[idx], b_["lse"].reshape(T, -1)[idx], atol=1e-13)
+    assert np.array_equal(b_["lse"].reshape(T, -1)[others], caches["lse"].reshape(T, -1)[others])
+    assert not np.allclose(a["c"].reshape(T, -1)[others], b_["c"].reshape(T, -1)[others], atol=1e-9)
+    # ... by exactly the ratio of stale to fresh normalisers, head by head
+    qn = O.rope((O.rmsnorm(x1.reshape(T, -1), w["g_attn"], cfg.rms_eps) @ w["wq"].T).reshape(T, cfg.n_heads, cfg.head_dim),
+                np.arange(T) % L, cfg.rope_theta)
+    fresh = np.concatenate([O.attention_lse(qn[b * L:(b + 1) * L], a["k"][b]) for b in range(B)])
+    ratio = np.exp(fresh - caches["lse"].reshape(T, -1))  # [T, H]
+    da = (a["c"] - caches["c"]).reshape(T, cfg.n_heads, -1)
+    db = (b_["c"] - caches["c"]).reshape(T, cfg.n_heads, -1)
+    assert np.allclose(db[others], da[others] * ratio[others][:, :, None], rtol=1e-9, atol=1e-12)
