@@ -328,6 +328,28 @@ def main():
             torch.cuda.synchronize()
             approx["ms_per_step_response_only_nothing_selected"] = (time.perf_counter() - t0) / K * 1e3
             approx["response_rows"] = wl.batch * wl.resp_len
+        # the variant with reused softmax normalisers (only the candidates' keys are scored): a second
+        # layer object with the fifth cache, same weights, warmed by the same dense steps
+        lay2 = Layer.from_shape(s, wl.batch, wl.seq, keep_lse=True)
+        lay2.set_device_weights(lay.wt)
+        for xd_ in dense_x:
+            lay2.full_step(xd_)
+        lay2.layer_step_approx(steps[Wu][0], steps[Wu][1], -2.0, cached_norm=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(Wu, Wu + K):
+            lay2.layer_step_approx(steps[i][0], steps[i][1], -2.0, cached_norm=True)
+        torch.cuda.synchronize()
+        approx["ms_per_step_reused_normalisers_nothing_selected"] = (time.perf_counter() - t0) / K * 1e3
+        if 0 < row_lo < wl.seq:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(Wu, Wu + K):
+                lay2.layer_step_approx(steps[i][0], resp_lists[i - Wu], -2.0, row_lo=row_lo, cached_norm=True)
+            torch.cuda.synchronize()
+            approx["ms_per_step_reused_normalisers_response_only_nothing_selected"] = (time.perf_counter() - t0) / K * 1e3
+        lay2.close()
+        del lay2
     del snap
 
     # dense step of the same shape on the same GPU

@@ -83,13 +83,15 @@ typedef struct {
   const void *g_ffn;  /* [d] RMSNorm gain before the FFN */
 } dyllm_layer_weights;
 
-/* The four per-layer caches [Alg. 1 initialisation; Alg. 2 / Alg. 3 cache lines].
- * Updated in place. */
+/* The four per-layer caches [Alg. 1 initialisation; Alg. 2 / Alg. 3 cache lines], updated in place,
+ * and an optional fifth one for the reused-normaliser form of the approximate update. */
 typedef struct {
   void *k;   /* [B, L, Hkv, dh]  keys, stored AFTER the rotary embedding */
   void *v;   /* [B, L, Hkv, dh] */
   void *c;   /* [B, L, H*dh]     attention context, before the output projection */
   void *out; /* [B, L, d]        layer output hidden state ("FFN output cache") */
+  float *lse; /* NULL, or [B, L, H] fp32: log(sum_j exp(q.k_j/sqrt(dh))) of every token's last EXACT
+                 attention row; written by the dense step and for the exact rows of every sparse step */
 } dyllm_layer_cache;
 
 /* A set of tokens: ascending, unique token ids, grouped by sequence. */
@@ -190,21 +192,26 @@ int dyllm_layer_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_c
  *   it may hold tokens outside idx_in, so idx_out->cap should be B*(L-row_lo) (overflow sets
  *   DYLLM_ERR_CAPACITY in the status word as for dyllm_compact).  Out-projection and FFN run for
  *   idx_out only.
+ * cached_norm != 0 selects a variant that is NOT the printed Alg. 4: the weight of candidate key j for
+ *   query i is exp(q_i.k_j/sqrt(dh) - cache->lse[i]), i.e. the softmax normaliser is the one cached at
+ *   token i's last exact evaluation instead of a sum over all keys now, so that only the candidates'
+ *   keys are scored -- the O(N |A| d) cost that Sec. 3.3 states.  It equals Alg. 4 whenever the
+ *   cached normalisers are current; needs cache->lse.
  * cos_out: [B*L] indexed by token (entries of tokens outside the step are not written) or NULL.
  * Needs a context with max_rows covering B*L.  An empty idx_in leaves every cached value unchanged
  * and yields an empty idx_out. */
 int dyllm_layer_step_approx(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
                             const void *x, const dyllm_index_list *idx_in, int32_t B, int32_t L,
-                            int32_t row_lo, float tau, dyllm_index_list *idx_out, float *cos_out,
-                            void *stream);
+                            int32_t row_lo, float tau, int32_t cached_norm, dyllm_index_list *idx_out,
+                            float *cos_out, void *stream);
 
 /* dyllm_layer_step_approx through a stack of n_layers layers, chained like dyllm_stack_step.  [Alg. 3,
  * loop over l]  The selections may grow from layer to layer: every idx_out[l] should have capacity
  * B*(L-row_lo).  cos_out: NULL or [n_layers, B*L]. */
 int dyllm_stack_step_approx(dyllm_ctx *ctx, int32_t n_layers, const dyllm_layer_weights *w,
                             dyllm_layer_cache *caches, const void *x, const dyllm_index_list *idx_in,
-                            int32_t B, int32_t L, int32_t row_lo, float tau, dyllm_index_list *idx_out,
-                            float *cos_out, void *stream);
+                            int32_t B, int32_t L, int32_t row_lo, float tau, int32_t cached_norm,
+                            dyllm_index_list *idx_out, float *cos_out, void *stream);
 
 /* out = the ascending, duplicate-free union of the token lists a and b (either may be NULL), kept to
  * the tokens at positions >= pos_lo of their sequence, with per-sequence offsets.  Serves the carry
@@ -221,7 +228,8 @@ typedef struct {
   int32_t full_period; /* a later step t takes the whole sequence when t % full_period == 0 (the paper
                           uses 4), the response only otherwise; <= 1: always the whole sequence */
   int32_t prompt_len;  /* L_P: positions [0, L_P) of every sequence are the prompt */
-  int32_t approx;      /* non-zero: approximate update of the non-salient tokens (Sec. 3.3) */
+  int32_t approx;      /* 0: exact rows only; 1: approximate update of the non-salient tokens (Sec. 3.3,
+                          Alg. 4); 2: the same with reused normalisers (see dyllm_layer_step_approx) */
   float tau;
 } dyllm_schedule;
 #define DYLLM_STEP_DENSE 0

@@ -556,6 +556,7 @@ class Schedule:
     prompt_len: int    # ... every other one only the positions [prompt_len, L) of each sequence
     approx: bool       # approximate update of the non-salient tokens (Sec. 3.3) on or off
     tau: float
+    cached_norm: bool = False  # with approx: reuse the cached softmax normalisers (approx_attention_cached)
 
 
 def step_kind(t: int, sched: Schedule) -> str:
@@ -591,7 +592,7 @@ def denoise_step(t: int, sched: Schedule, x: np.ndarray, decoded: np.ndarray, ca
     row_lo = 0 if kind == "full" else sched.prompt_len
     idx = merge_lists(carry, decoded, L, row_lo)
     if sched.approx:
-        per_layer = stack_step_approx(x, idx, ws, cfg, caches, sched.tau, row_lo)
+        per_layer = stack_step_approx(x, idx, ws, cfg, caches, sched.tau, row_lo, sched.cached_norm)
     else:
         per_layer = stack_step(x, idx, ws, cfg, caches, sched.tau)
     return per_layer[-1][0]

@@ -51,7 +51,7 @@ class LayerWeights(C.Structure):
 
 
 class LayerCache(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("k", "v", "c", "out")]
+    _fields_ = [(n, C.c_void_p) for n in ("k", "v", "c", "out", "lse")]
 
 
 class IndexListC(C.Structure):
@@ -96,9 +96,9 @@ def load_library() -> C.CDLL:
     lib.dyllm_layer_step.argtypes = [vp, P(LayerWeights), P(LayerCache), vp, P(IndexListC), i32, i32, f32,
                                      P(IndexListC), vp, vp]
     lib.dyllm_layer_step_approx.argtypes = [vp, P(LayerWeights), P(LayerCache), vp, P(IndexListC), i32, i32, i32,
-                                            f32, P(IndexListC), vp, vp]
+                                            f32, i32, P(IndexListC), vp, vp]
     lib.dyllm_stack_step_approx.argtypes = [vp, i32, P(LayerWeights), P(LayerCache), vp, P(IndexListC), i32, i32,
-                                            i32, f32, P(IndexListC), vp, vp]
+                                            i32, f32, i32, P(IndexListC), vp, vp]
     lib.dyllm_merge_lists.argtypes = [vp, P(IndexListC), P(IndexListC), i32, i32, i32, P(IndexListC), vp]
     lib.dyllm_step_kind.argtypes = [P(Schedule), i32]
     lib.dyllm_denoise_step.argtypes = [vp, P(Schedule), i32, i32, P(LayerWeights), P(LayerCache), vp,
@@ -160,8 +160,10 @@ def make_weights(tensors: dict) -> LayerWeights:
     return w
 
 
-def make_cache(k, v, c, out) -> LayerCache:
-    return LayerCache(k.data_ptr(), v.data_ptr(), c.data_ptr(), out.data_ptr())
+def make_cache(k, v, c, out, lse=None) -> LayerCache:
+    """lse: fp32 [B, L, H] tensor for the log-normaliser cache, or None."""
+    return LayerCache(k.data_ptr(), v.data_ptr(), c.data_ptr(), out.data_ptr(),
+                      lse.data_ptr() if lse is not None else None)
 
 
 def workspace_bytes(cfg: LayerCfg) -> int:
@@ -250,19 +252,21 @@ class Context:
                                               B, L, tau, C.byref(o), _ptr(cos_out), _stream()))
 
     def layer_step_approx(self, w: LayerWeights, cache: LayerCache, x, idx_in: IndexList, B, L, tau,
-                          idx_out: IndexList, cos_out=None, row_lo=0):
+                          idx_out: IndexList, cos_out=None, row_lo=0, cached_norm=False):
         i, o = idx_in.c(), idx_out.c()
         self._check(self.lib.dyllm_layer_step_approx(self.h, C.byref(w), C.byref(cache), _ptr(x), C.byref(i),
-                                                     B, L, row_lo, tau, C.byref(o), _ptr(cos_out), _stream()))
+                                                     B, L, row_lo, tau, int(cached_norm), C.byref(o),
+                                                     _ptr(cos_out), _stream()))
 
-    def stack_step_approx(self, ws, caches, x, idx_in: IndexList, B, L, tau, idx_outs, cos_out=None, row_lo=0):
+    def stack_step_approx(self, ws, caches, x, idx_in: IndexList, B, L, tau, idx_outs, cos_out=None, row_lo=0,
+                          cached_norm=False):
         n = len(ws)
         wa = (LayerWeights * n)(*ws)
         ca = (LayerCache * n)(*caches)
         oa = (IndexListC * n)(*[o.c() for o in idx_outs])
         i = idx_in.c()
         self._check(self.lib.dyllm_stack_step_approx(self.h, n, wa, ca, _ptr(x), C.byref(i), B, L, row_lo, tau,
-                                                     oa, _ptr(cos_out), _stream()))
+                                                     int(cached_norm), oa, _ptr(cos_out), _stream()))
 
     def merge_lists(self, a, b, B, L, pos_lo, out: IndexList):
         """a, b: IndexList or None."""

@@ -32,6 +32,7 @@ struct dyllm_ctx {
   void *csal;      // [R, dq] exact context rows of the salient tokens (approximate path)
   int32_t *pos;    // [R] position+1 of a token in the salient list; all zero between calls
   int32_t *win_idx, *win_off;  // [R], [max_batch+1]: the tokens of a response-only step as a list
+  void *ksal;      // [R, dkv] compact copy of the candidates' new key rows (reused-normaliser variant)
   float *cosb;     // [R]
   uint8_t *flag;   // [R]
   float *hs;       // [R, d]        x + Wo c (fp32)
@@ -49,7 +50,7 @@ struct dyllm_ctx {
 namespace {
 
 struct Layout {
-  size_t ns, qkv, qs, part_o, part_ml, cosb, flag, hs, fs, act, status, rope, dv_full, dc, csal, pos, win_idx, win_off, total;
+  size_t ns, qkv, qs, part_o, part_ml, cosb, flag, hs, fs, act, status, rope, dv_full, dc, csal, pos, win_idx, win_off, ksal, total;
   size_t part_elems;
 };
 
@@ -86,6 +87,7 @@ Layout make_layout(const dyllm_layer_cfg &c) {
   l.pos = take(R * 4);
   l.win_idx = take(R * 4);
   l.win_off = take(((size_t)c.max_batch + 1) * 4);
+  l.ksal = take(R * dkv * e);
   l.total = off;
   return l;
 }
@@ -176,7 +178,7 @@ int enqueue_qkv(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x, Row
   prof_mark(ctx, ST_GEMM_QKV, s);
   launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)rows.cap * seg.n_end[2], ctx->rope, rows, L,
                       c.n_heads, c.n_kv_heads, c.head_dim, w->bq, w->bk, w->bv, q_out, cache->k,
-                      cache->v, nullptr, 0, s);
+                      cache->v, nullptr, 0, nullptr, 0, s);
   prof_mark(ctx, ST_ROPE_SCATTER, s);
   return check_launch(ctx, "qkv refresh");
 }
@@ -186,6 +188,7 @@ AttnArgs attn_args(dyllm_ctx *ctx, const void *q, const void *k, const void *v, 
   const dyllm_layer_cfg &c = ctx->cfg;
   AttnArgs a;
   a.q = q; a.q_by_token = 0; a.k = k; a.v = v; a.rows = rows; a.offsets = offsets;
+  a.key_offsets = nullptr; a.lse_out = nullptr;
   a.B = B; a.L = L; a.H = c.n_heads; a.Hkv = c.n_kv_heads; a.dh = c.head_dim;
   const int rows_per_seq = offsets ? (rows.cap + B - 1) / B : L;
   attention_plan(dt(ctx), B, L, c.n_heads, c.head_dim, rows.cap, rows_per_seq, ctx->part_elems, &a);
@@ -268,7 +271,8 @@ int enqueue_sparse_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
   if ((rc = enqueue_qkv(ctx, w, x, rin, L, cache, ctx->qs, s))) return rc;
   {
     // attention leaves per-split partials; their merge is fused with the cosine test and the commit
-    const AttnArgs a = attn_args(ctx, ctx->qs, cache->k, cache->v, rin, idx_in->offsets, B, L, nullptr, 1);
+    AttnArgs a = attn_args(ctx, ctx->qs, cache->k, cache->v, rin, idx_in->offsets, B, L, nullptr, 1);
+    a.lse_out = (float *)cache->lse;  // optional fifth cache: log-normalisers of the exact rows
     launch_attention(dt(ctx), a, s);
     prof_mark(ctx, ST_ATTENTION, s);
     // ... and the last workgroup of that kernel compacts the flags into idx_out
@@ -299,7 +303,7 @@ Window make_window(dyllm_ctx *ctx, int B, int L, int row_lo, hipStream_t s) {
 // [Alg. 3 layer body; Sec. 3.3: exact rows for the salient tokens, approximate update for the others]
 int enqueue_approx_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
                          const void *x, const dyllm_index_list *idx_in, int B, int L, Window win, float tau,
-                         dyllm_index_list *idx_out, float *cos_out, hipStream_t s) {
+                         int cached_norm, dyllm_index_list *idx_out, float *cos_out, hipStream_t s) {
   const dyllm_layer_cfg &c = ctx->cfg;
   const Rows all = win.rows;
   const Rows rin = rows_of(idx_in, B);
@@ -314,7 +318,7 @@ int enqueue_approx_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
                                        wseg_one(w->wq, ctx->dq), ctx->part_o, ctx->part_elems, s);
     launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)all.cap * ctx->dq, ctx->rope, all, L, c.n_heads,
                         0, c.head_dim, w->bq, nullptr, nullptr, ctx->qs, nullptr, nullptr, nullptr, by_token,
-                        s);
+                        nullptr, 0, s);
   }
   // k, v of the salient tokens: norm, projection, rotation, value residual, merge into the caches
   launch_gather_rmsnorm(dt(ctx), x, w->g_attn, rin, c.hidden, c.rms_eps, ctx->fs, s);
@@ -324,29 +328,55 @@ int enqueue_approx_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
     seg.n_end[0] = ctx->dkv; seg.n_end[1] = 2 * ctx->dkv; seg.n_end[2] = 2 * ctx->dkv;
     const int splits = launch_gemm_raw(dt(ctx), GemmA{ctx->fs, nullptr, c.hidden}, rin, c.hidden, seg,
                                        ctx->part_o, ctx->part_elems, s);
+    // value residual: by token into the zero-padded [T, dkv] buffer (Alg. 4 as printed), or by list
+    // entry next to a compact copy of the new keys (reused normalisers: only candidates are scored)
     launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)rin.cap * 2 * ctx->dkv, ctx->rope, rin, L, 0,
                         c.n_kv_heads, c.head_dim, nullptr, w->bk, w->bv, nullptr, cache->k, cache->v,
-                        ctx->dv_full, 0, s);
+                        cached_norm ? ctx->dc : ctx->dv_full, 0, cached_norm ? ctx->ksal : nullptr,
+                        cached_norm, s);
   }
   if ((rc = check_launch(ctx, "approx: projections"))) return rc;
-  // exact rows of the salient tokens  [Alg. 3: C_sal]; q is stored by token here
+  // exact rows of the salient tokens  [Alg. 3: C_sal]; q is stored by token here.  With a cache of
+  // log-normalisers the rows go through the merge kernel, which stores theirs.
   {
-    AttnArgs a = attn_args(ctx, ctx->qs, cache->k, cache->v, rin, idx_in->offsets, B, L, ctx->csal, 0);
+    const int keep_lse = cache->lse != nullptr;
+    AttnArgs a = attn_args(ctx, ctx->qs, cache->k, cache->v, rin, idx_in->offsets, B, L, ctx->csal, keep_lse);
     a.q_by_token = 1;
+    a.lse_out = (float *)cache->lse;
     launch_attention(dt(ctx), a, s);
+    if (keep_lse) launch_attn_combine(dt(ctx), a, s);
   }
-  // approximate residual of every token of the step: the full softmax against the merged keys times
-  // the value residual, which is zero outside the salient rows  [Alg. 4]
-  {
+  launch_mark_rows(rin, ctx->pos, s);
+  if (!cached_norm) {
+    // approximate residual of every token of the step: the full softmax against the merged keys times
+    // the value residual, which is zero outside the salient rows  [Alg. 4]
     AttnArgs a = attn_args(ctx, ctx->qs, cache->k, ctx->dv_full, all, win.offsets, B, L, ctx->dc, 0);
     a.q_by_token = by_token;
     launch_attention(dt(ctx), a, s);
+    if ((rc = check_launch(ctx, "approx: attention"))) return rc;
+    // new contexts of the step's tokens, cosine test, commit; then the scratch maps go back to zero
+    launch_saliency_approx(dt(ctx), all, ctx->dq, ctx->csal, ctx->dc, ctx->pos, cache->c, tau, cos_out, ctx->flag,
+                           nullptr, nullptr, L, s);
+    launch_clear_rows(dt(ctx), rin, ctx->pos, ctx->dv_full, ctx->dkv, s);
+  } else {
+    // Reused normalisers (Sec. 3.3's O(N |A| d) form): every token of the step is scored against the
+    // candidates' keys only -- compact rows, sequence b's at [offsets[b], offsets[b+1]) -- and the
+    // un-normalised partial sums are scaled by the log-normaliser cached at the token's last exact
+    // evaluation instead of a softmax over all keys.
+    int lk_max = rin.cap < L ? rin.cap : L;
+    if (lk_max < 1) lk_max = 1;
+    AttnArgs a = attn_args(ctx, ctx->qs, ctx->ksal, ctx->dc, all, win.offsets, B, L, nullptr, 1);
+    // key splits over the longest possible candidate run; the query side still walks sequences of L
+    attention_plan(dt(ctx), B, lk_max, c.n_heads, c.head_dim, all.cap, win.offsets ? (all.cap + B - 1) / B : L,
+                   ctx->part_elems, &a);
+    a.q_by_token = by_token;
+    a.key_offsets = idx_in->offsets;
+    launch_attention(dt(ctx), a, s);
+    if ((rc = check_launch(ctx, "approx: attention"))) return rc;
+    launch_saliency_approx(dt(ctx), all, ctx->dq, ctx->csal, nullptr, ctx->pos, cache->c, tau, cos_out, ctx->flag,
+                           &a, (const float *)cache->lse, L, s);
+    launch_clear_rows(dt(ctx), rin, ctx->pos, nullptr, ctx->dkv, s);
   }
-  if ((rc = check_launch(ctx, "approx: attention"))) return rc;
-  // new contexts of the step's tokens, cosine test, commit; then the scratch maps go back to zero
-  launch_mark_rows(rin, ctx->pos, s);
-  launch_saliency_approx(dt(ctx), all, ctx->dq, ctx->csal, ctx->dc, ctx->pos, cache->c, tau, cos_out, ctx->flag, s);
-  launch_clear_rows(dt(ctx), rin, ctx->pos, ctx->dv_full, ctx->dkv, s);
   launch_compact(ctx->flag, all, B, L, idx_out->idx, idx_out->offsets, idx_out->cap, ctx->status, s);
   if ((rc = check_launch(ctx, "approx: saliency / compact"))) return rc;
   return enqueue_ffn(ctx, w, x, cache->c, rows_of(idx_out, B), cache->out, s);
@@ -371,7 +401,16 @@ int enqueue_dense_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_laye
   prof_begin_call(ctx, s);
   if ((rc = enqueue_qkv(ctx, w, x, all, L, cache, ctx->qs, s))) return rc;
   // every row is a query: the context cache is written directly
-  if ((rc = enqueue_attention(ctx, ctx->qs, cache->k, cache->v, all, nullptr, B, L, cache->c, s))) return rc;
+  if (cache->lse) {  // ... through the merge kernel when the log-normalisers are kept as well
+    AttnArgs a = attn_args(ctx, ctx->qs, cache->k, cache->v, all, nullptr, B, L, cache->c, 1);
+    a.lse_out = (float *)cache->lse;
+    launch_attention(dt(ctx), a, s);
+    launch_attn_combine(dt(ctx), a, s);
+    prof_mark(ctx, ST_ATTENTION, s);
+    if ((rc = check_launch(ctx, "attention"))) return rc;
+  } else if ((rc = enqueue_attention(ctx, ctx->qs, cache->k, cache->v, all, nullptr, B, L, cache->c, s))) {
+    return rc;
+  }
   prof_mark(ctx, ST_SALIENCY, s);
   prof_mark(ctx, ST_COMPACT, s);
   rc = enqueue_ffn(ctx, w, x, cache->c, all, cache->out, s);
@@ -435,6 +474,7 @@ int dyllm_create(const dyllm_layer_cfg *cfg, dyllm_ctx **out) {
   ctx->status = (int32_t *)(b + l.status); ctx->rope = (float *)(b + l.rope);
   ctx->dv_full = b + l.dv_full; ctx->dc = b + l.dc; ctx->csal = b + l.csal; ctx->pos = (int32_t *)(b + l.pos);
   ctx->win_idx = (int32_t *)(b + l.win_idx); ctx->win_off = (int32_t *)(b + l.win_off);
+  ctx->ksal = b + l.ksal;
 
   // rotary table in double precision on the host, cleared status word
   const int half = cfg->head_dim / 2;
@@ -617,23 +657,31 @@ int check_window(dyllm_ctx *ctx, int B, int L, int row_lo) {
   return DYLLM_OK;
 }
 
+int check_cached_norm(dyllm_ctx *ctx, int cached_norm, const dyllm_layer_cache *cache) {
+  if (cached_norm && !cache->lse)
+    return fail(ctx, DYLLM_ERR_INVALID_ARG, "reused normalisers need cache->lse");
+  return DYLLM_OK;
+}
+
 int dyllm_layer_step_approx(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,
                             const void *x, const dyllm_index_list *idx_in, int32_t B, int32_t L,
-                            int32_t row_lo, float tau, dyllm_index_list *idx_out, float *cos_out,
-                            void *stream) {
+                            int32_t row_lo, float tau, int32_t cached_norm, dyllm_index_list *idx_out,
+                            float *cos_out, void *stream) {
   if (!ctx) return DYLLM_ERR_INVALID_ARG;
   int rc;
   if ((rc = check_bl(ctx, B, L))) return rc;
   if ((rc = check_window(ctx, B, L, row_lo))) return rc;
   if ((rc = check_sparse_layer(ctx, w, cache, x, idx_in, idx_out))) return rc;
+  if ((rc = check_cached_norm(ctx, cached_norm, cache))) return rc;
   const Window win = make_window(ctx, B, L, row_lo, (hipStream_t)stream);
-  return enqueue_approx_layer(ctx, w, cache, x, idx_in, B, L, win, tau, idx_out, cos_out, (hipStream_t)stream);
+  return enqueue_approx_layer(ctx, w, cache, x, idx_in, B, L, win, tau, cached_norm != 0, idx_out, cos_out,
+                              (hipStream_t)stream);
 }
 
 int dyllm_stack_step_approx(dyllm_ctx *ctx, int32_t n_layers, const dyllm_layer_weights *w,
                             dyllm_layer_cache *caches, const void *x, const dyllm_index_list *idx_in,
-                            int32_t B, int32_t L, int32_t row_lo, float tau, dyllm_index_list *idx_out,
-                            float *cos_out, void *stream) {
+                            int32_t B, int32_t L, int32_t row_lo, float tau, int32_t cached_norm,
+                            dyllm_index_list *idx_out, float *cos_out, void *stream) {
   if (!ctx) return DYLLM_ERR_INVALID_ARG;
   if (n_layers <= 0 || !w || !caches || !idx_out) return fail(ctx, DYLLM_ERR_INVALID_ARG, "empty stack or NULL array");
   int rc;
@@ -643,13 +691,14 @@ int dyllm_stack_step_approx(dyllm_ctx *ctx, int32_t n_layers, const dyllm_layer_
     const void *xl = l ? caches[l - 1].out : x;
     const dyllm_index_list *in = l ? &idx_out[l - 1] : idx_in;
     if ((rc = check_sparse_layer(ctx, &w[l], &caches[l], xl, in, &idx_out[l]))) return rc;
+    if ((rc = check_cached_norm(ctx, cached_norm, &caches[l]))) return rc;
   }
   const Window win = make_window(ctx, B, L, row_lo, (hipStream_t)stream);
   const dyllm_index_list *in = idx_in;
   for (int l = 0; l < n_layers; ++l) {
     float *cos_l = cos_out ? cos_out + (size_t)l * B * L : nullptr;
     if ((rc = enqueue_approx_layer(ctx, &w[l], &caches[l], l ? caches[l - 1].out : x, in, B, L, win, tau,
-                                   &idx_out[l], cos_l, (hipStream_t)stream)))
+                                   cached_norm != 0, &idx_out[l], cos_l, (hipStream_t)stream)))
       return rc;
     in = &idx_out[l];
   }
@@ -692,8 +741,8 @@ int dyllm_denoise_step(dyllm_ctx *ctx, const dyllm_schedule *sched, int32_t t, i
   int rc;
   if ((rc = dyllm_merge_lists(ctx, carry, decoded, B, L, row_lo, cand, stream))) return rc;
   if (sched->approx)
-    return dyllm_stack_step_approx(ctx, n_layers, w, caches, x, cand, B, L, row_lo, sched->tau, idx_out,
-                                   nullptr, stream);
+    return dyllm_stack_step_approx(ctx, n_layers, w, caches, x, cand, B, L, row_lo, sched->tau,
+                                   sched->approx == 2, idx_out, nullptr, stream);
   return dyllm_stack_step(ctx, n_layers, w, caches, x, cand, B, L, sched->tau, idx_out, nullptr, stream);
 }
 

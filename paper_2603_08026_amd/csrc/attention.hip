@@ -9,8 +9,10 @@ namespace {
 // One workgroup per query row, a thread per 16 bytes of the row in the storage type (V = 4 or 8
 // neighbouring columns, all of one head).  For every head: M = max_s m_s, l = sum_s l_s e^{m_s - M},
 // out = sum_s o_s e^{m_s - M} / l  (the usual merge of online-softmax partials).
+// lse (optional) receives log(sum_keys exp(score)) of the row's head: M + log l.
 template <int V>
-__device__ __forceinline__ void merge_splits(const AttnArgs &a, int j, int c, int D, float (&out)[V]) {
+__device__ __forceinline__ void merge_splits(const AttnArgs &a, int j, int c, int D, float (&out)[V],
+                                             float *lse = nullptr) {
   const int h = c / a.dh;
   float M = -INFINITY;
   for (int s = 0; s < a.splits; ++s) M = fmaxf(M, a.part_ml[(((size_t)s * a.rows.cap + j) * a.H + h) * 2]);
@@ -31,6 +33,7 @@ __device__ __forceinline__ void merge_splits(const AttnArgs &a, int j, int c, in
   const float inv = 1.0f / l;
 #pragma unroll
   for (int e = 0; e < V; ++e) out[e] *= inv;
+  if (lse) *lse = M + __logf(l);
 }
 
 constexpr int FIN_NT = 512;  // threads of the merge kernels
@@ -42,9 +45,11 @@ __global__ __launch_bounds__(FIN_NT) void k_attn_combine(AttnArgs a) {
   const int D = a.H * a.dh;
   for (int j = blockIdx.x; j < n; j += gridDim.x) {
     T *orow = (T *)a.out + (size_t)j * D;
+    const int r = a.rows.idx ? a.rows.idx[j] : j;
     for (int c = threadIdx.x * V; c < D; c += FIN_NT * V) {
-      float o[V];
-      merge_splits<V>(a, j, c, D, o);
+      float o[V], lse;
+      merge_splits<V>(a, j, c, D, o, &lse);
+      if (a.lse_out && c % a.dh == 0) a.lse_out[(size_t)r * a.H + c / a.dh] = lse;
       Vec16<T> v;
 #pragma unroll
       for (int e = 0; e < V; ++e) v.set(e, o[e]);
@@ -79,8 +84,9 @@ __global__ __launch_bounds__(FIN_NT) void k_attn_finalize(AttnArgs a, T *c_cache
     T *crow = c_cache + (size_t)r * D;
     float dot = 0.f, na = 0.f, nb = 0.f;
     for (int c = threadIdx.x * V; c < D; c += FIN_NT * V) {
-      float o[V];
-      merge_splits<V>(a, j, c, D, o);
+      float o[V], lse;
+      merge_splits<V>(a, j, c, D, o, &lse);
+      if (a.lse_out && c % a.dh == 0) a.lse_out[(size_t)r * a.H + c / a.dh] = lse;
       const Vec16<T> old = ld16(crow + c);
       Vec16<T> nw;
 #pragma unroll

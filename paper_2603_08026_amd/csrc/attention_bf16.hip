@@ -127,12 +127,14 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
   if (b < 0) return;  // uniform: no such tile
   const int j0 = tile_info[1], nq = tile_info[2];
   const int h = blockIdx.y, kvh = h / (a.H / a.Hkv), split = blockIdx.z;
-  const int k_lo = split * a.chunk, k_hi = min(a.L, k_lo + a.chunk);
+  const int kbase = a.key_offsets ? a.key_offsets[b] : b * a.L;
+  const int Lk = a.key_offsets ? a.key_offsets[b + 1] - kbase : a.L;
+  const int k_lo = split * a.chunk, k_hi = min(Lk, k_lo + a.chunk);
   if (k_lo >= k_hi) return;  // uniform
 
   const size_t kv_stride = (size_t)a.Hkv * DH;
-  const bf16_t *kc = (const bf16_t *)a.k + ((size_t)b * a.L * a.Hkv + kvh) * DH;
-  const bf16_t *vc = (const bf16_t *)a.v + ((size_t)b * a.L * a.Hkv + kvh) * DH;
+  const bf16_t *kc = (const bf16_t *)a.k + ((size_t)kbase * a.Hkv + kvh) * DH;
+  const bf16_t *vc = (const bf16_t *)a.v + ((size_t)kbase * a.Hkv + kvh) * DH;
 
   // query operands: QB blocks of 32 queries per wave, kept in registers for the whole key sweep
   bf16x8 qf[QB][KK];
@@ -384,12 +386,14 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a) 
   if (b < 0) return;  // uniform: no such tile
   const int j0 = tile_info[1], nq = tile_info[2];
   const int h = blockIdx.y, kvh = h / (a.H / a.Hkv), split = blockIdx.z;
-  const int k_lo = split * a.chunk, k_hi = min(a.L, k_lo + a.chunk);
+  const int kbase = a.key_offsets ? a.key_offsets[b] : b * a.L;
+  const int Lk = a.key_offsets ? a.key_offsets[b + 1] - kbase : a.L;
+  const int k_lo = split * a.chunk, k_hi = min(Lk, k_lo + a.chunk);
   if (k_lo >= k_hi) return;  // uniform
 
   const size_t kv_stride = (size_t)a.Hkv * DH;
-  const bf16_t *kc = (const bf16_t *)a.k + ((size_t)b * a.L * a.Hkv + kvh) * DH;
-  const bf16_t *vc = (const bf16_t *)a.v + ((size_t)b * a.L * a.Hkv + kvh) * DH;
+  const bf16_t *kc = (const bf16_t *)a.k + ((size_t)kbase * a.Hkv + kvh) * DH;
+  const bf16_t *vc = (const bf16_t *)a.v + ((size_t)kbase * a.Hkv + kvh) * DH;
 
   // query operand: the wave's 32 queries, in registers for the whole key sweep
   bf16x8 qf[KK];

@@ -34,12 +34,14 @@ __global__ __launch_bounds__(256) void k_attn_f32(AttnArgs a) {
   if (b < 0) return;  // uniform: no such tile
   const int j0 = tile_info[1], nq = tile_info[2];
   const int h = blockIdx.y, kvh = h / (a.H / a.Hkv), split = blockIdx.z;
-  const int k_lo = split * a.chunk, k_hi = min(a.L, k_lo + a.chunk);
+  const int kbase = a.key_offsets ? a.key_offsets[b] : b * a.L;
+  const int Lk = a.key_offsets ? a.key_offsets[b + 1] - kbase : a.L;
+  const int k_lo = split * a.chunk, k_hi = min(Lk, k_lo + a.chunk);
   if (k_lo >= k_hi) return;  // uniform
 
   const T *q = (const T *)a.q;
-  const T *kc = (const T *)a.k + ((size_t)b * a.L * a.Hkv + kvh) * DH;
-  const T *vc = (const T *)a.v + ((size_t)b * a.L * a.Hkv + kvh) * DH;
+  const T *kc = (const T *)a.k + ((size_t)kbase * a.Hkv + kvh) * DH;
+  const T *vc = (const T *)a.v + ((size_t)kbase * a.Hkv + kvh) * DH;
   const size_t kv_stride = (size_t)a.Hkv * DH;
   const float scale = 1.0f / sqrtf((float)DH);
 

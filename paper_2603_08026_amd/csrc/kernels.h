@@ -24,13 +24,15 @@ void launch_gather_rmsnorm(DType t, const void *x, const void *gain, Rows rows, 
 //
 // q/k/v: sum of splits + bias, rotary embedding of q and k by the table entry of position
 // (row mod L), q_out[j] (T-typed [cap,dq]; q_out[row_j] when q_by_token), k and v rows scattered into
-// the caches at row_j; dv_out (may be nullptr) takes v - v_cache of those rows before the merge.
+// the caches at row_j; dv_out (may be nullptr) takes v - v_cache of those rows before the merge, at
+// row_j or (dv_by_entry) at j; ksal_out (may be nullptr) takes a copy of the rotated k rows at j.
 // rope_tab: [max_seq, dh/2, 2] fp32 (cos, sin).  dh is 64 or 128.
 // dv_out (optional, [T, Hkv*dh] T-typed): value residual new - cached of the rows, taken before the merge
 void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_stride,
                          const float *rope_tab, Rows rows, int L, int H, int Hkv, int dh,
                          const void *bq, const void *bk, const void *bv, void *q_out, void *k_cache,
-                         void *v_cache, void *dv_out, int q_by_token, hipStream_t s);
+                         void *v_cache, void *dv_out, int q_by_token, void *ksal_out, int dv_by_entry,
+                         hipStream_t s);
 // out-projection: h[j] = x[row_j] + sum of splits (fp32 [cap,d]); f[j] = RMSNorm(h[j]) * gain (T-typed)
 void launch_oproj_finalize(DType t, const float *part, int splits, size_t split_stride, const void *x,
                            const void *gain, Rows rows, int d, float eps, float *h, void *f,
@@ -53,7 +55,10 @@ void launch_compact(const uint8_t *flag, Rows rows, int B, int L, int32_t *out_i
 struct AttnArgs {
   const void *q;        // [cap, H, dh] T-typed; with q_by_token: [T, H, dh], row of query j = rows.idx[j]
   int q_by_token;
-  const void *k, *v;    // [B, L, Hkv, dh] T-typed
+  const void *k, *v;    // [B, L, Hkv, dh] T-typed; with key_offsets: compact rows [*, Hkv, dh]
+  const int32_t *key_offsets;  // nullptr, or [B+1]: the keys of sequence b are rows [key_offsets[b],
+                               // key_offsets[b+1]) of k / v (a split past a sequence's last key writes nothing)
+  float *lse_out;       // nullptr, or [T, H]: the merge kernels store log(sum exp) of every merged row here
   Rows rows;            // token ids of the query rows (idx may be nullptr = identity)
   const int32_t *offsets;  // [B+1] per-sequence offsets into rows, or nullptr = every sequence has L rows
   int B, L, H, Hkv, dh;
@@ -67,6 +72,8 @@ struct AttnArgs {
 };
 // attention rows; merges the splits into a.out unless a.partial is set
 void launch_attention(DType t, const AttnArgs &a, hipStream_t s);
+// merge of the attention partials of a call that left them (a.partial) into a.out (and a.lse_out)
+void launch_attn_combine(DType t, const AttnArgs &a, hipStream_t s);
 // merge of the attention partials fused with the saliency test and the context commit:
 // new = merged row (rounded to T), cos against c_cache[row_j], flag = cos < tau, c_cache[row_j] = new.
 // The workgroup that finishes last also compacts the flags into (out_idx, out_offsets) like
@@ -117,15 +124,18 @@ void launch_fill_i32(int32_t *p, int32_t v, int n, hipStream_t s);
 // pos[row_j] = j + 1 for the rows of the list (pos is zero elsewhere, before and after a step)
 void launch_mark_rows(Rows rows, int32_t *pos, hipStream_t s);
 // For every entry j of the window `win` (token r = win.idx[j], or j): new context = c_sal[pos[r]-1]
-// where pos[r] != 0, else c_cache[r] + dc[j] (rounded to T); cosine against the cached row, commit;
-// cos_out[r] (may be nullptr), flag_out[j] = cos < tau.
+// where pos[r] != 0, else c_cache[r] + residual (rounded to T); cosine against the cached row, commit;
+// cos_out[r] (may be nullptr), flag_out[j] = cos < tau.  The residual is dc[j], or (cached != nullptr)
+// sum over the key splits s of part_o[s][j] * exp(m_s - lse[r, h]) from the partials of an attention
+// pass over the compact candidate keys (cached->key_offsets) -- the normalisers are NOT recomputed.
 void launch_saliency_approx(DType t, Rows win, int D, const void *c_sal, const void *dc, const int32_t *pos,
-                            void *c_cache, float tau, float *cos_out, uint8_t *flag_out, hipStream_t s);
+                            void *c_cache, float tau, float *cos_out, uint8_t *flag_out,
+                            const AttnArgs *cached, const float *lse, int L, hipStream_t s);
 // idx/off := the tokens at positions [lo, L) of each of the B sequences, as an index list
 void launch_make_window(int B, int L, int lo, int32_t *idx, int32_t *off, hipStream_t s);
 // flag[r] = 1 for every token r < T of the list whose position in its sequence is >= lo
 void launch_mark_flags(Rows rows, int T, int L, int lo, uint8_t *flag, hipStream_t s);
-// pos[row_j] = 0 and dv[row_j, :] = 0 for the rows of the list
+// pos[row_j] = 0 and (dv != nullptr) dv[row_j, :] = 0 for the rows of the list
 void launch_clear_rows(DType t, Rows rows, int32_t *pos, void *dv, int dkv, hipStream_t s);
 
 }  // namespace dy

@@ -163,7 +163,8 @@ __global__ __launch_bounds__(RB) void k_qkv_finalize(const float *__restrict__ p
                                                       const T *__restrict__ bq, const T *__restrict__ bk,
                                                       const T *__restrict__ bv, T *__restrict__ q_out,
                                                       T *__restrict__ kc, T *__restrict__ vc,
-                                                      T *__restrict__ dv_out, int q_by_token) {
+                                                      T *__restrict__ dv_out, int q_by_token,
+                                                      T *__restrict__ ksal_out, int dv_by_entry) {
   const int n = row_count(rows);
   const int half = dh / 2, dq = H * dh, dkv = Hkv * dh, ld = dq + 2 * dkv;
   const int per_head = half / 4;  // items of 4 pairs per head
@@ -197,14 +198,21 @@ __global__ __launch_bounds__(RB) void k_qkv_finalize(const float *__restrict__ p
         const float4 t0 = *reinterpret_cast<const float4 *>(t + 2 * p4);      // cos0 sin0 cos1 sin1
         const float4 t1 = *reinterpret_cast<const float4 *>(t + 2 * p4 + 4);  // cos2 sin2 cos3 sin3
         T *dst = isq ? q_out + (size_t)(q_by_token ? r : j) * dq : kc + (size_t)r * dkv;
-        dst[c0 + 0] = from_f<T>(x1.x * t0.x - x2.x * t0.y);
-        dst[c0 + 1] = from_f<T>(x1.y * t0.z - x2.y * t0.w);
-        dst[c0 + 2] = from_f<T>(x1.z * t1.x - x2.z * t1.y);
-        dst[c0 + 3] = from_f<T>(x1.w * t1.z - x2.w * t1.w);
-        dst[c0 + half + 0] = from_f<T>(x2.x * t0.x + x1.x * t0.y);
-        dst[c0 + half + 1] = from_f<T>(x2.y * t0.z + x1.y * t0.w);
-        dst[c0 + half + 2] = from_f<T>(x2.z * t1.x + x1.z * t1.y);
-        dst[c0 + half + 3] = from_f<T>(x2.w * t1.z + x1.w * t1.w);
+        const T lo4[4] = {from_f<T>(x1.x * t0.x - x2.x * t0.y), from_f<T>(x1.y * t0.z - x2.y * t0.w),
+                          from_f<T>(x1.z * t1.x - x2.z * t1.y), from_f<T>(x1.w * t1.z - x2.w * t1.w)};
+        const T hi4[4] = {from_f<T>(x2.x * t0.x + x1.x * t0.y), from_f<T>(x2.y * t0.z + x1.y * t0.w),
+                          from_f<T>(x2.z * t1.x + x1.z * t1.y), from_f<T>(x2.w * t1.z + x1.w * t1.w)};
+        // (the new key row also goes to a compact copy when the approximate pass scores candidates only)
+        T *ks = (!isq && ksal_out) ? ksal_out + (size_t)j * dkv : nullptr;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          dst[c0 + u] = lo4[u];
+          dst[c0 + half + u] = hi4[u];
+          if (ks) {
+            ks[c0 + u] = lo4[u];
+            ks[c0 + half + u] = hi4[u];
+          }
+        }
       } else {
         const int c0 = (it - qk_items) * 4;
         float4 x = *reinterpret_cast<const float4 *>(src + dq + dkv + c0);
@@ -218,7 +226,7 @@ __global__ __launch_bounds__(RB) void k_qkv_finalize(const float *__restrict__ p
         T *vrow = vc + (size_t)r * dkv + c0;
         const T n0 = from_f<T>(x.x), n1 = from_f<T>(x.y), n2 = from_f<T>(x.z), n3 = from_f<T>(x.w);
         if (dv_out) {  // residual of the stored values, before the merge overwrites the cached row
-          T *d = dv_out + (size_t)r * dkv + c0;
+          T *d = dv_out + (size_t)(dv_by_entry ? j : r) * dkv + c0;
           d[0] = from_f<T>(to_f<T>(n0) - to_f<T>(vrow[0])); d[1] = from_f<T>(to_f<T>(n1) - to_f<T>(vrow[1]));
           d[2] = from_f<T>(to_f<T>(n2) - to_f<T>(vrow[2])); d[3] = from_f<T>(to_f<T>(n3) - to_f<T>(vrow[3]));
         }
@@ -331,16 +339,19 @@ void launch_swiglu_finalize(DType t, const float *part, int splits, size_t split
 void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_stride,
                          const float *rope_tab, Rows rows, int L, int H, int Hkv, int dh,
                          const void *bq, const void *bk, const void *bv, void *q_out, void *k_cache,
-                         void *v_cache, void *dv_out, int q_by_token, hipStream_t s) {
+                         void *v_cache, void *dv_out, int q_by_token, void *ksal_out, int dv_by_entry,
+                         hipStream_t s) {
   if (rows.cap <= 0) return;
   if (t == F32)
     k_qkv_finalize<float><<<row_grid(rows.cap), RB, 0, s>>>(
         part, splits, split_stride, rope_tab, rows, L, H, Hkv, dh, (const float *)bq, (const float *)bk,
-        (const float *)bv, (float *)q_out, (float *)k_cache, (float *)v_cache, (float *)dv_out, q_by_token);
+        (const float *)bv, (float *)q_out, (float *)k_cache, (float *)v_cache, (float *)dv_out, q_by_token,
+        (float *)ksal_out, dv_by_entry);
   else
     k_qkv_finalize<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>(
         part, splits, split_stride, rope_tab, rows, L, H, Hkv, dh, (const bf16_t *)bq, (const bf16_t *)bk,
-        (const bf16_t *)bv, (bf16_t *)q_out, (bf16_t *)k_cache, (bf16_t *)v_cache, (bf16_t *)dv_out, q_by_token);
+        (const bf16_t *)bv, (bf16_t *)q_out, (bf16_t *)k_cache, (bf16_t *)v_cache, (bf16_t *)dv_out, q_by_token,
+        (bf16_t *)ksal_out, dv_by_entry);
 }
 
 inline int sal_grid(int cap) { return cap < 1 ? 1 : (cap > 65536 ? 65536 : cap); }
@@ -377,20 +388,31 @@ __global__ __launch_bounds__(256) void k_clear_rows(Rows rows, int32_t *pos, T *
   for (int j = blockIdx.x; j < n; j += gridDim.x) {
     const int r = rows.idx ? rows.idx[j] : j;
     if (threadIdx.x == 0) pos[r] = 0;
-    for (int v = threadIdx.x; v < dkv / N; v += 256) st16(dv + (size_t)r * dkv + v * N, zero);
+    if (dv)
+      for (int v = threadIdx.x; v < dkv / N; v += 256) st16(dv + (size_t)r * dkv + v * N, zero);
   }
 }
 
 // One workgroup per token of the step (entry j of `win`, token r).  Salient tokens (pos[r] != 0) take
-// their exact row, all others the cached row plus the approximate residual dc[j]; the cosine is taken
-// over the stored (rounded) values against the cached row, which is read before it is overwritten.
+// their exact row, all others the cached row plus the approximate residual; the cosine is taken over
+// the stored (rounded) values against the cached row, which is read before it is overwritten.
 // cos_out is indexed by token, flag_out by window entry.
-template <typename T>
+// Residual: dc[j] (CACHED = false), or rebuilt from the partials of an attention pass over the compact
+// candidate keys with the token's CACHED log-normaliser: sum over the key splits that hold keys of
+// the token's sequence of part_o[s][j] * exp(m_s - lse[r, h])  (part_o is relative to the split's own
+// running maximum m_s; nothing is renormalised).
+struct CachedNorm {
+  const float *part_o, *part_ml, *lse;
+  const int32_t *key_offsets;
+  int cap, H, dh, chunk, splits, L;
+};
+
+template <typename T, bool CACHED>
 __global__ __launch_bounds__(SAL_NT) void k_saliency_approx(Rows win, int D, const T *__restrict__ c_sal,
                                                              const T *__restrict__ dc,
                                                              const int32_t *__restrict__ pos, T *c_cache,
                                                              float tau, float *__restrict__ cos_out,
-                                                             uint8_t *__restrict__ flag_out) {
+                                                             uint8_t *__restrict__ flag_out, CachedNorm cn) {
   __shared__ float red[3 * SAL_NT / WAVE];
   constexpr int N = Vec16<T>::N;
   const int nv = D / N;
@@ -400,15 +422,44 @@ __global__ __launch_bounds__(SAL_NT) void k_saliency_approx(Rows win, int D, con
     const int p = pos[r];
     T *b = c_cache + (size_t)r * D;
     const T *src = p ? c_sal + (size_t)(p - 1) * D : dc + (size_t)j * D;
+    int ns = 0;  // key splits that hold candidate keys of this token's sequence
+    if (CACHED && !p) {
+      const int sq = r / cn.L;
+      const int lk = cn.key_offsets[sq + 1] - cn.key_offsets[sq];
+      ns = (lk + cn.chunk - 1) / cn.chunk;
+      ns = ns < cn.splits ? ns : cn.splits;
+    }
     float dot = 0.f, na = 0.f, nb = 0.f;
     for (int v = threadIdx.x; v < nv; v += SAL_NT) {
-      const Vec16<T> vs = ld16(src + v * N), vb = ld16(b + v * N);
+      const Vec16<T> vb = ld16(b + v * N);
       Vec16<T> vn;
+      if (CACHED && !p) {
+        const int c = v * N, h = c / cn.dh;
+        const float ref = cn.lse[(size_t)r * cn.H + h];
+        float res[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) res[i] = 0.f;
+        for (int sp = 0; sp < ns; ++sp) {
+          const size_t row = (size_t)sp * cn.cap + j;
+          const float wgt = __expf(cn.part_ml[(row * cn.H + h) * 2] - ref);
+          const float4 *po = reinterpret_cast<const float4 *>(cn.part_o + row * D + c);
+#pragma unroll
+          for (int q4 = 0; q4 < N / 4; ++q4) {
+            const float4 o = po[q4];
+            res[4 * q4] += o.x * wgt; res[4 * q4 + 1] += o.y * wgt;
+            res[4 * q4 + 2] += o.z * wgt; res[4 * q4 + 3] += o.w * wgt;
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < N; ++i) vn.set(i, vb.get(i) + res[i]);
+      } else {
+        const Vec16<T> vs = ld16(src + v * N);
+#pragma unroll
+        for (int i = 0; i < N; ++i) vn.set(i, p ? vs.get(i) : vb.get(i) + vs.get(i));
+      }
 #pragma unroll
       for (int i = 0; i < N; ++i) {
-        const float fb = vb.get(i);
-        vn.set(i, p ? vs.get(i) : fb + vs.get(i));
-        const float fa = vn.get(i);
+        const float fa = vn.get(i), fb = vb.get(i);
         dot += fa * fb;
         na += fa * fa;
         nb += fb * fb;
@@ -448,15 +499,25 @@ void launch_mark_rows(Rows rows, int32_t *pos, hipStream_t s) {
 }
 
 void launch_saliency_approx(DType t, Rows win, int D, const void *c_sal, const void *dc, const int32_t *pos,
-                            void *c_cache, float tau, float *cos_out, uint8_t *flag_out, hipStream_t s) {
+                            void *c_cache, float tau, float *cos_out, uint8_t *flag_out,
+                            const AttnArgs *cached, const float *lse, int L, hipStream_t s) {
   if (win.cap <= 0) return;
   const int grid = win.cap > 65536 ? 65536 : win.cap;
-  if (t == F32)
-    k_saliency_approx<float><<<grid, SAL_NT, 0, s>>>(win, D, (const float *)c_sal, (const float *)dc, pos,
-                                                    (float *)c_cache, tau, cos_out, flag_out);
-  else
-    k_saliency_approx<bf16_t><<<grid, SAL_NT, 0, s>>>(win, D, (const bf16_t *)c_sal, (const bf16_t *)dc, pos,
-                                                     (bf16_t *)c_cache, tau, cos_out, flag_out);
+  CachedNorm cn{};
+  if (cached)
+    cn = CachedNorm{cached->part_o, cached->part_ml, lse, cached->key_offsets, cached->rows.cap,
+                    cached->H, cached->dh, cached->chunk, cached->splits, L};
+#define DY_SAL_APPROX(TT, C)                                                                        \
+  k_saliency_approx<TT, C><<<grid, SAL_NT, 0, s>>>(win, D, (const TT *)c_sal, (const TT *)dc, pos, \
+                                                   (TT *)c_cache, tau, cos_out, flag_out, cn)
+  if (t == F32) {
+    if (cached) DY_SAL_APPROX(float, true);
+    else DY_SAL_APPROX(float, false);
+  } else {
+    if (cached) DY_SAL_APPROX(bf16_t, true);
+    else DY_SAL_APPROX(bf16_t, false);
+  }
+#undef DY_SAL_APPROX
 }
 
 void launch_make_window(int B, int L, int lo, int32_t *idx, int32_t *off, hipStream_t s) {

@@ -30,7 +30,8 @@ def to_host(t: torch.Tensor) -> np.ndarray:
 
 class Layer:
     def __init__(self, hidden, n_heads, n_kv_heads, head_dim, ffn, dtype: str, batch: int, seq: int,
-                 max_rows: int = 0, rms_eps: float = 1e-5, rope_theta: float = 10000.0, ctx=None):
+                 max_rows: int = 0, rms_eps: float = 1e-5, rope_theta: float = 10000.0, ctx=None,
+                 keep_lse: bool = False):
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the dyllm library only runs on a HIP device")
         self.dtype = dtype
@@ -46,7 +47,10 @@ class Layer:
         self.v = torch.zeros_like(self.k)
         self.c = torch.zeros(batch, seq, self.dq, dtype=td, device="cuda")
         self.out = torch.zeros(batch, seq, hidden, dtype=td, device="cuda")
-        self.cache = B_.make_cache(self.k, self.v, self.c, self.out)
+        # optional fifth cache: log-normalisers of every token's last exact attention row (needed by the
+        # reused-normaliser variant of the approximate update; the dense step then runs its merge kernel)
+        self.lse = torch.zeros(batch, seq, n_heads, dtype=torch.float32, device="cuda") if keep_lse else None
+        self.cache = B_.make_cache(self.k, self.v, self.c, self.out, self.lse)
         self.rows_cap = max_rows if max_rows > 0 else T
         self.idx_out = B_.IndexList.empty(self.rows_cap, batch)
         self.cos = torch.zeros(self.rows_cap, dtype=torch.float32, device="cuda")
@@ -54,9 +58,9 @@ class Layer:
         self.w = None
 
     @classmethod
-    def from_shape(cls, shape, batch, seq, max_rows=0, ctx=None):
+    def from_shape(cls, shape, batch, seq, max_rows=0, ctx=None, keep_lse=False):
         return cls(shape.hidden, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.ffn, shape.dtype,
-                   batch, seq, max_rows, shape.rms_eps, shape.rope_theta, ctx)
+                   batch, seq, max_rows, shape.rms_eps, shape.rope_theta, ctx, keep_lse)
 
     def set_weights(self, w: Dict[str, np.ndarray]):
         self.wt = {k: to_device(v, self.dtype) for k, v in w.items() if v is not None}
@@ -70,6 +74,8 @@ class Layer:
     def set_caches(self, caches: Dict[str, np.ndarray]):
         for name in ("k", "v", "c", "out"):
             getattr(self, name).copy_(to_device(caches[name].astype(np.float32), self.dtype))
+        if "lse" in caches and self.lse is not None:
+            self.lse.copy_(torch.from_numpy(np.ascontiguousarray(caches["lse"], dtype=np.float32)).cuda())
 
     def get_caches(self) -> Dict[str, np.ndarray]:
         return {n: to_host(getattr(self, n)) for n in ("k", "v", "c", "out")}
@@ -97,11 +103,13 @@ class Layer:
 
     def layer_step_approx(self, x_dev: torch.Tensor, idx_in: B_.IndexList, tau: float,
                           idx_out: Optional[B_.IndexList] = None, cos_out: Optional[torch.Tensor] = None,
-                          row_lo: int = 0):
+                          row_lo: int = 0, cached_norm: bool = False):
         """Sparse step with the approximate update of the other tokens; the context must cover B*L rows.
-        cos_out: [B*L] fp32 (by token) or None; row_lo > 0: response-only step."""
+        cos_out: [B*L] fp32 (by token) or None; row_lo > 0: response-only step; cached_norm: reuse the
+        cached softmax normalisers instead of Alg. 4's sum over all keys."""
         out = self.idx_out if idx_out is None else idx_out
-        self.ctx.layer_step_approx(self.w, self.cache, x_dev, idx_in, self.B, self.L, tau, out, cos_out, row_lo)
+        self.ctx.layer_step_approx(self.w, self.cache, x_dev, idx_in, self.B, self.L, tau, out, cos_out, row_lo,
+                                   cached_norm)
         return out
 
     def read_list(self, il: B_.IndexList) -> Tuple[np.ndarray, np.ndarray]:
@@ -116,9 +124,9 @@ class Layer:
 class Stack:
     """n_layers layers sharing one library context; layer l reads layer l-1's output cache."""
 
-    def __init__(self, shape, n_layers: int, batch: int, seq: int, max_rows: int = 0):
-        first = Layer.from_shape(shape, batch, seq, max_rows)
-        self.layers = [first] + [Layer.from_shape(shape, batch, seq, max_rows, ctx=first.ctx)
+    def __init__(self, shape, n_layers: int, batch: int, seq: int, max_rows: int = 0, keep_lse: bool = False):
+        first = Layer.from_shape(shape, batch, seq, max_rows, keep_lse=keep_lse)
+        self.layers = [first] + [Layer.from_shape(shape, batch, seq, max_rows, ctx=first.ctx, keep_lse=keep_lse)
                                  for _ in range(n_layers - 1)]
         self.ctx, self.B, self.L, self.dtype = first.ctx, batch, seq, first.dtype
         cap = first.rows_cap
@@ -143,10 +151,10 @@ class Stack:
         return self.idx_outs
 
     def stack_step_approx(self, x_dev: torch.Tensor, idx_in: B_.IndexList, tau: float, row_lo: int = 0,
-                          cos_out: Optional[torch.Tensor] = None):
+                          cos_out: Optional[torch.Tensor] = None, cached_norm: bool = False):
         """cos_out: [n_layers, B*L] fp32 (by token) or None."""
         self.ctx.stack_step_approx([l.w for l in self.layers], [l.cache for l in self.layers], x_dev, idx_in,
-                                   self.B, self.L, tau, self.idx_outs, cos_out, row_lo)
+                                   self.B, self.L, tau, self.idx_outs, cos_out, row_lo, cached_norm)
         return self.idx_outs
 
     def denoise_step(self, sched: B_.Schedule, t: int, x_dev: torch.Tensor, decoded, carry, cand: B_.IndexList):

@@ -182,3 +182,78 @@ def test_c2_shape_one_step():
     st = steps[1]
     _check_step(lay, ref, w, cfg, st.x, st.idx, st.offsets, wl.tau, "c2 approx")
     lay.close()
+
+
+# ---- approximate update with reused softmax normalisers (variant of Alg. 4) -----------------------
+
+def _lse_close(lay, ref, rows, dtype, what):
+    got = lay.lse.cpu().numpy().reshape(lay.B * lay.L, -1)[rows]
+    want = ref["lse"].reshape(lay.B * lay.L, -1)[rows]
+    assert np.max(np.abs(got - want)) < (1e-4 if dtype == "f32" else 3e-2), what
+
+
+@pytest.mark.parametrize("dtype,gqa,dh,row_lo", [("f32", True, 64, 0), ("bf16", True, 128, 0), ("bf16", False, 64, 0),
+                                                 ("f32", False, 64, 60), ("bf16", True, 128, 72)])
+def test_reused_normalisers_against_oracle(dtype, gqa, dh, row_lo):
+    """Dense step (fills the log-normaliser cache), then two sparse steps of the variant: the first
+    with normalisers that are stale only through the candidates' new keys, the second with the
+    normalisers the first step left (refreshed for its candidates only).  One sequence gets no
+    candidate in step 2, and candidate counts span several key tiles / splits."""
+    _say("reused normalisers", dtype, "gqa" if gqa else "mha", dh, "row_lo", row_lo)
+    s = small_shape(dtype, gqa=gqa, dh=dh)
+    cfg = oracle_cfg(s)
+    B, L = 3, 200
+    T = B * L
+    w = rand_weights(s, 161, bias=gqa, std=0.08)
+    lay = Layer.from_shape(s, B, L, keep_lse=True)
+    lay.set_weights(w)
+    x0 = _round(W.philox(162, "x0").standard_normal((B, L, s.hidden), dtype=np.float32), dtype)
+    ref = O.new_caches(B, L, cfg)
+    ref["lse"] = np.zeros((B, L, cfg.n_heads))
+    O.full_step(x0, w, cfg, ref)
+    lay.full_step(lay.upload(x0))
+    assert_close(lay.get_caches()["c"], ref["c"], TOL[dtype], "dense context through the merge kernel")
+    _lse_close(lay, ref, np.arange(T), dtype, "dense lse")
+    tol = TOL[dtype]
+    full = Bd.IndexList.empty(T, B)
+    x = x0
+    for step, counts in enumerate(([70, 9, 33], [40, 0, 5])):
+        start = {k: (_round(v, dtype) if k != "lse" else v.astype(np.float32)) for k, v in ref.items()}
+        lay.set_caches(start)
+        ref = {k: v.astype(np.float64) for k, v in start.items()}
+        counts = [min(c, L - row_lo) for c in counts]
+        idx = np.concatenate([row_lo + np.sort(W.philox(163 + step, "r", b).choice(L - row_lo, size=n, replace=False)) + b * L
+                              for b, n in enumerate(counts)]).astype(np.int32)
+        off = np.searchsorted(idx, np.arange(B + 1) * L).astype(np.int32)
+        x1 = x.copy().reshape(T, -1)
+        x1[idx] = W.perturbed_rows(x1[idx], np.full(idx.size, 0.5), 170 + step)
+        x1 = _round(x1, dtype).reshape(B, L, -1)
+        step_rows = np.flatnonzero(np.arange(T) % L >= row_lo)
+        probe = O.layer_step_approx(x1, idx, w, cfg, {k: v.copy() for k, v in ref.items()}, 0.5, row_lo, True)[2]
+        others = np.setdiff1d(step_rows, idx)
+        tau = float(np.quantile(probe[others], 0.3))
+        idx_ref, off_ref, cos_ref = O.layer_step_approx(x1, idx, w, cfg, ref, tau, row_lo, True)
+        cos = torch.ones(T, dtype=torch.float32, device="cuda")
+        out = lay.layer_step_approx(lay.upload(x1), lay.make_list(idx, off), tau, full, cos, row_lo=row_lo,
+                                    cached_norm=True)
+        assert lay.ctx.poll_status() == 0
+        idx_g, off_g = lay.read_list(out)
+        what = "step %d" % step
+        assert np.max(np.abs(cos.cpu().numpy() - cos_ref)) < (5e-5 if dtype == "f32" else 2e-2), what
+        assert_index_sets_match(idx_g, idx_ref, step_rows, cos_ref[step_rows], tau, what)
+        got = lay.get_caches()
+        for name in ("k", "v", "c"):
+            assert_close(got[name].reshape(T, -1), ref[name].reshape(T, -1), tol, "%s: %s cache" % (what, name))
+        both = np.intersect1d(idx_g, idx_ref)
+        assert_close(got["out"].reshape(T, -1)[both], ref["out"].reshape(T, -1)[both], tol, what + ": out rows")
+        _lse_close(lay, ref, idx, dtype, what + ": lse of the exact rows")
+        rest = np.setdiff1d(np.arange(T), idx)
+        assert np.array_equal(lay.lse.cpu().numpy().reshape(T, -1)[rest], start["lse"].reshape(T, -1)[rest])
+        x = x1
+    # the variant needs the fifth cache
+    plain = Layer.from_shape(s, B, L)
+    plain.set_weights(w)
+    with pytest.raises(Bd.DyllmError):
+        plain.layer_step_approx(plain.upload(x0), plain.make_list(idx, off), 0.9, full, None, cached_norm=True)
+    plain.close()
+    lay.close()
