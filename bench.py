@@ -331,7 +331,7 @@ def main():
         # the variant with reused softmax normalisers (only the candidates' keys are scored): a second
         # layer object with the fifth cache, same weights, warmed by the same dense steps
         lay2 = Layer.from_shape(s, wl.batch, wl.seq, keep_lse=True)
-        lay2.set_device_weights(lay.wt)
+        lay2.set_device_weights(lay.wt, packed=True)
         for xd_ in dense_x:
             lay2.full_step(xd_)
         lay2.layer_step_approx(steps[Wu][0], steps[Wu][1], -2.0, cached_norm=True)

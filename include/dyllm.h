@@ -13,7 +13,8 @@
  *  - Every tensor pointer is DEVICE memory owned by the caller (allocated and
  *    freed by the caller); the library owns only the scratch workspace of its
  *    context.  Pointers named host_* are host memory.
- *  - Tensors are dense row-major.  A "token id" is b*L + i for position i of
+ *  - Tensors are dense row-major (the weight matrices of bf16 contexts excepted:
+ *    see dyllm_layer_weights).  A "token id" is b*L + i for position i of
  *    sequence b; T = B*L.  Element type is the context's dtype (fp32 or bf16)
  *    unless a parameter says otherwise.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -67,7 +68,11 @@ typedef struct {
   float rope_theta;   /* rotary base */
 } dyllm_layer_cfg;
 
-/* Weights of one layer, [out, in] row-major: y = W x (+ b). */
+/* Weights of one layer, y = W x (+ b); the shapes below are [out, in].
+ * DYLLM_F32 contexts read every matrix row-major.  DYLLM_BF16 contexts read every matrix in the
+ * panel layout written by dyllm_pack_weight (the GEMM kernels stream each tile's share of a matrix
+ * as contiguous 4 KB runs instead of one 128-byte piece per row); biases and gains are plain
+ * vectors in both. */
 typedef struct {
   const void *wq;     /* [H*dh, d] */
   const void *wk;     /* [Hkv*dh, d] */
@@ -101,6 +106,15 @@ typedef struct {
   int32_t *offsets; /* [B+1] offsets[b]..offsets[b+1] = entries of sequence b; offsets[B] = count */
   int32_t cap;      /* capacity of idx (host value); the count on the device must not exceed it */
 } dyllm_index_list;
+
+/* Re-lays a row-major bf16 matrix src [n_out, n_in] (device) into dst (device, same number of
+ * bytes, must not overlap src) in the layout the bf16 GEMMs of Alg. 3's projection and FFN lines
+ * read: panels of 32 output rows, each panel stored K-slice-major,
+ *   dst[((n/32) * (n_in/64) + k/64) * 2048 + (n%32) * 64 + k%64] = src[n * n_in + k].
+ * Call once per matrix when the weights are loaded; the row-major copy is not needed afterwards.
+ * Only enqueues on `stream`.  Errors: INVALID_ARG (NULL, src == dst, sizes <= 0), UNSUPPORTED
+ * (n_out not a multiple of 32 or n_in not a multiple of 64), HIP. */
+int dyllm_pack_weight(const void *src, int32_t n_out, int32_t n_in, void *dst, void *stream);
 
 /* Bytes of device scratch a context with this configuration allocates. */
 int dyllm_workspace_bytes(const dyllm_layer_cfg *cfg, size_t *host_bytes);

@@ -25,7 +25,7 @@ SYMBOLS = [
     "dyllm_poll_status", "dyllm_saliency", "dyllm_compact", "dyllm_qkv_refresh",
     "dyllm_partial_attention", "dyllm_salient_ffn", "dyllm_layer_step", "dyllm_layer_step_approx",
     "dyllm_stack_step_approx", "dyllm_merge_lists", "dyllm_step_kind", "dyllm_denoise_step", "dyllm_full_step",
-    "dyllm_stack_step", "dyllm_stack_full_step",
+    "dyllm_stack_step", "dyllm_stack_full_step", "dyllm_pack_weight",
     "dyllm_profile_begin", "dyllm_profile_end", "dyllm_stage_count", "dyllm_stage_name",
 ]
 
@@ -164,6 +164,16 @@ def make_cache(k, v, c, out, lse=None) -> LayerCache:
     """lse: fp32 [B, L, H] tensor for the log-normaliser cache, or None."""
     return LayerCache(k.data_ptr(), v.data_ptr(), c.data_ptr(), out.data_ptr(),
                       lse.data_ptr() if lse is not None else None)
+
+
+def pack_weight(src: torch.Tensor, dst: torch.Tensor) -> None:
+    """Row-major bf16 [n_out, n_in] device matrix -> the panel layout bf16 contexts read (dst: same size)."""
+    if src.dim() != 2 or src.dtype != torch.bfloat16 or dst.dtype != torch.bfloat16 or dst.numel() != src.numel():
+        raise ValueError("pack_weight takes a 2-D bf16 matrix and a bf16 destination of the same size")
+    lib = load_library()
+    rc = lib.dyllm_pack_weight(_ptr(src), C.c_int32(src.shape[0]), C.c_int32(src.shape[1]), _ptr(dst), _stream())
+    if rc:
+        raise DyllmError(rc, lib.dyllm_strerror(rc).decode())
 
 
 def workspace_bytes(cfg: LayerCfg) -> int:

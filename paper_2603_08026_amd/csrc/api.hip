@@ -720,6 +720,14 @@ int dyllm_merge_lists(dyllm_ctx *ctx, const dyllm_index_list *a, const dyllm_ind
   return enqueue_merge(ctx, a, b, B, L, pos_lo, out, (hipStream_t)stream);
 }
 
+int dyllm_pack_weight(const void *src, int32_t n_out, int32_t n_in, void *dst, void *stream) {
+  if (!src || !dst || src == dst) return DYLLM_ERR_INVALID_ARG;
+  if (n_out <= 0 || n_in <= 0) return DYLLM_ERR_INVALID_ARG;
+  if (n_out % 32 || n_in % 64) return DYLLM_ERR_UNSUPPORTED;
+  launch_pack_weight(src, n_out, n_in, dst, (hipStream_t)stream);
+  return hipGetLastError() == hipSuccess ? DYLLM_OK : DYLLM_ERR_HIP;
+}
+
 int dyllm_step_kind(const dyllm_schedule *sched, int32_t t) {
   if (!sched || t < 0) return DYLLM_ERR_INVALID_ARG;
   if (t < sched->t_full) return DYLLM_STEP_DENSE;

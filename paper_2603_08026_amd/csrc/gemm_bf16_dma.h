@@ -1,6 +1,15 @@
 // bf16 salient-row GEMM for the gfx950 matrix cores with asynchronous global -> LDS copies.
 //   C[j,n] = sum_k A[row_j,k] * W[n,k]      (both operands K-contiguous)
 //
+// Weight layout.  W is stored in panels of 32 output rows, each panel K-slice-major:
+//   W[n][k] lives at ((n/32) * (K/64) + k/64) * 2048 + (n%32) * 64 + k%64   (elements).
+// The 128 bytes a tile row needs per K slice are then contiguous with those of the 31 other rows of
+// its panel (4 KB), and a panel is read front to back while K advances: a workgroup that streams
+// weights from HBM reads whole DRAM pages in order instead of one 128-byte piece per 8 KB row
+// (measured at 106 rows on a 32-layer stack, whose weights always come from HBM: q/k/v GEMM 25.6 ->
+// 23.7 us, gate|up 49.4 -> 46.2 us per layer against the row-major layout; a copy loop without
+// products streams 6.0 TB/s from contiguous runs and 4.9-5.3 TB/s from 128-byte pieces).
+//
 // Data path.  K is cut into slices of 64 elements (128 bytes per tile row).  A slice of the
 // (BM + BN) tile rows is copied straight from global memory into LDS by global_load_lds_dwordx4:
 // every lane names its own 16-byte global source, the hardware writes lane i's data to
@@ -37,6 +46,7 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 constexpr int BK = 64;    // K slice (elements)
 constexpr int ROWB = 128; // bytes per tile row and slice
 constexpr int N_XCD = 8;
+constexpr int WPANEL = 32;  // output rows per weight panel
 
 // Tile shape: BM x BN output tile, WAVES_M x WAVES_N waves, DUAL = two weight matrices per tile (fused
 // gate/up), NS LDS stages of one K slice each.
@@ -147,8 +157,12 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
       const bool in1 = n >= seg.n_end[0], in2 = n >= seg.n_end[1];
       const bf16_t *wbase = (const bf16_t *)(in2 ? seg.w[2] : in1 ? seg.w[1] : seg.w[0]);
       const int wstart = in2 ? seg.n_end[1] : in1 ? seg.n_end[0] : 0;
-      wp[0][i] = wbase + (size_t)(n - wstart) * ldw + kbeg + csrc * 8;
-      if (SH::DUAL) wp[NMAT - 1][i] = W2 + (size_t)n * ldw + kbeg + csrc * 8;
+      // panel layout: slice kt of this row sits kt * (WPANEL * BK) elements further on
+      const int nl = n - wstart;
+      const size_t woff = ((size_t)(nl / WPANEL) * (ldw / BK) + kbeg / BK) * (WPANEL * BK) + (nl % WPANEL) * BK + csrc * 8;
+      wp[0][i] = wbase + woff;
+      if (SH::DUAL)
+        wp[NMAT - 1][i] = W2 + ((size_t)(n / WPANEL) * (ldw / BK) + kbeg / BK) * (WPANEL * BK) + (n % WPANEL) * BK + csrc * 8;
     }
 
     floatx16 acc[NMAT][MB][NB];
@@ -171,7 +185,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
     auto issue_w = [&](int kt) {  // weight rows of slice kt -> weight stage kt % NS
       const uint32_t sb = lds0 + (uint32_t)(NS * SH::A_BYTES) + (uint32_t)(kt % NS) * SH::W_BYTES +
                           (uint32_t)wave * 1024u;
-      const int ko = kt * BK;
+      const int ko = kt * (WPANEL * BK);
 #pragma unroll
       for (int t = 0; t < NMAT; ++t)
 #pragma unroll

@@ -118,6 +118,8 @@ void launch_gemm_swiglu(DType t, GemmA A, Rows rows, int K, int N, const void *w
 void launch_gemm_down(DType t, GemmA A, Rows rows, int K, int N, const void *w_down, const float *h,
                       void *out_cache, float *scratch, size_t scratch_elems, hipStream_t s);
 
+// row-major [n_out, n_in] (2-byte elements; n_out % 32 == 0, n_in % 64 == 0) -> weight panels of the bf16 GEMMs
+void launch_pack_weight(const void *src, int n_out, int n_in, void *dst, hipStream_t s);
 void launch_fill_i32(int32_t *p, int32_t v, int n, hipStream_t s);
 
 // ---- approximate (column-sparse) context update of the non-salient rows  [Sec. 3.3; Alg. 3, Alg. 4]

@@ -536,6 +536,27 @@ void launch_clear_rows(DType t, Rows rows, int32_t *pos, void *dv, int dkv, hipS
   else k_clear_rows<bf16_t><<<row_grid(rows.cap), 256, 0, s>>>(rows, pos, (bf16_t *)dv, dkv);
 }
 
+// Row-major [n_out, n_in] matrix of 2-byte elements -> the panel layout the bf16 GEMMs read
+// (panels of 32 rows, K-slice-major inside a panel): thread u moves the 16 bytes of destination unit u.
+__global__ __launch_bounds__(256) void k_pack_weight(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
+                                                     int n_in, size_t units) {
+  const int kslices = n_in / 64;
+  for (size_t u = (size_t)blockIdx.x * 256 + threadIdx.x; u < units; u += (size_t)gridDim.x * 256) {
+    const int c8 = (int)(u % 8), r = (int)((u / 8) % 32);
+    const size_t pk = u / 256;  // panel * kslices + slice
+    const int kt = (int)(pk % kslices);
+    const size_t row = (pk / kslices) * 32 + r;
+    dst[u] = src[(row * (size_t)n_in + (size_t)kt * 64) / 8 + c8];
+  }
+}
+
+void launch_pack_weight(const void *src, int n_out, int n_in, void *dst, hipStream_t s) {
+  const size_t units = (size_t)n_out * n_in / 8;
+  if (units == 0) return;
+  const size_t want = (units + 255) / 256;
+  k_pack_weight<<<(unsigned)(want < 65536 ? want : 65536), 256, 0, s>>>((const uint4 *)src, (uint4 *)dst, n_in, units);
+}
+
 void launch_fill_i32(int32_t *p, int32_t v, int n, hipStream_t s) {
   if (n <= 0) return;
   k_fill_i32<<<(n + 255) / 256, 256, 0, s>>>(p, v, n);

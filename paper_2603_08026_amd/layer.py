@@ -28,6 +28,9 @@ def to_host(t: torch.Tensor) -> np.ndarray:
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
+MATRICES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+
+
 class Layer:
     def __init__(self, hidden, n_heads, n_kv_heads, head_dim, ffn, dtype: str, batch: int, seq: int,
                  max_rows: int = 0, rms_eps: float = 1e-5, rope_theta: float = 10000.0, ctx=None,
@@ -62,14 +65,26 @@ class Layer:
         return cls(shape.hidden, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.ffn, shape.dtype,
                    batch, seq, max_rows, shape.rms_eps, shape.rope_theta, ctx, keep_lse)
 
-    def set_weights(self, w: Dict[str, np.ndarray]):
-        self.wt = {k: to_device(v, self.dtype) for k, v in w.items() if v is not None}
+    def pack(self, t: torch.Tensor) -> torch.Tensor:
+        """Row-major bf16 matrix -> a new tensor in the panel layout the bf16 kernels read (library call)."""
+        out = torch.empty_like(t)
+        B_.pack_weight(t, out)
+        return out
+
+    def _install(self, wt: Dict[str, torch.Tensor], packed: bool):
+        if self.dtype != "f32" and not packed:
+            wt = {n: (self.pack(t) if n in MATRICES else t) for n, t in wt.items()}
+        self.wt = dict(wt)  # what the library reads (bf16: packed matrices)
         self.w = B_.make_weights(self.wt)
 
-    def set_device_weights(self, wt: Dict[str, torch.Tensor]):
-        """Weights that already live on the device in the storage type (large synthetic stacks)."""
-        self.wt = dict(wt)
-        self.w = B_.make_weights(self.wt)
+    def set_weights(self, w: Dict[str, np.ndarray]):
+        """Row-major host weights [out, in]; bf16 layers re-lay the matrices on the device."""
+        self._install({k: to_device(v, self.dtype) for k, v in w.items() if v is not None}, False)
+
+    def set_device_weights(self, wt: Dict[str, torch.Tensor], packed: bool = False):
+        """Weights that already live on the device in the storage type (large synthetic stacks);
+        packed: the bf16 matrices are already in the panel layout (e.g. another layer's `wt`)."""
+        self._install(wt, packed)
 
     def set_caches(self, caches: Dict[str, np.ndarray]):
         for name in ("k", "v", "c", "out"):

@@ -327,3 +327,39 @@ def test_error_paths_do_not_launch():
     assert e.value.code == -2
     torch.cuda.synchronize()
     lay.close()
+
+
+# ------------------------------------------------------------------ weight re-layout
+
+@pytest.mark.parametrize("n_out,n_in", [(32, 64), (96, 192), (4096 + 512, 4096), (384, 12288)])
+def test_pack_weight_bit_exact(n_out, n_in):
+    """dyllm_pack_weight against the layout its declaration states, written as a numpy re-shape:
+    panels of 32 rows, slices of 64 columns, slice-major inside a panel."""
+    _say("pack weight", n_out, n_in)
+    bits = W.philox(41, "packbits", n_out, n_in).integers(0, 1 << 16, size=(n_out, n_in), dtype=np.uint16)
+    src = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    dst = torch.full_like(src, float("nan"))
+    Bd.pack_weight(src, dst)
+    torch.cuda.synchronize()
+    got = dst.view(torch.int16).cpu().numpy().view(np.uint16).ravel()
+    want = bits.reshape(n_out // 32, 32, n_in // 64, 64).transpose(0, 2, 1, 3).ravel()
+    assert np.array_equal(got, want)
+    # one element by the stated formula
+    n, k = n_out - 3, n_in - 5
+    assert got[((n // 32) * (n_in // 64) + k // 64) * 2048 + (n % 32) * 64 + k % 64] == bits[n, k]
+
+
+def test_pack_weight_rejects_bad_sizes():
+    _say("pack weight errors")
+    a = torch.zeros(48, 64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(Bd.DyllmError) as e:
+        Bd.pack_weight(a, torch.empty_like(a))  # 48 rows: not a multiple of 32
+    assert e.value.code == -3
+    b = torch.zeros(32, 96, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(Bd.DyllmError) as e:
+        Bd.pack_weight(b, torch.empty_like(b))  # 96 columns: not a multiple of 64
+    assert e.value.code == -3
+    c = torch.zeros(32, 64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(Bd.DyllmError) as e:
+        Bd.pack_weight(c, c)  # in place
+    assert e.value.code == -1

@@ -223,10 +223,12 @@ def test_weights_between_poisoned_guard_bands(dtype, dh):
         guard = 70000
         buf = torch.full((a.size + 2 * guard,), float("nan"), dtype=td, device="cuda")
         view = buf[guard:guard + a.size].view(*a.shape)
-        view.copy_(torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(td))
+        val = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(td)
+        # the guarded buffer must hold what the kernels read: for bf16 the re-laid matrix
+        view.copy_(lay.pack(val) if dtype == "bf16" and a.ndim == 2 else val)
         held.append(buf)
         wt[name] = view
-    lay.set_device_weights(wt)
+    lay.set_device_weights(wt, packed=True)
     x0 = W.philox(98, "x").standard_normal((B, L, s.hidden), dtype=np.float32)
     x1 = W.philox(99, "x").standard_normal((B, L, s.hidden), dtype=np.float32)
     if dtype == "bf16":
