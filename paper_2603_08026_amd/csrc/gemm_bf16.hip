@@ -162,7 +162,13 @@ void gemm_bf16_swiglu(GemmA A, Rows rows, int K, int N, const void *wg, const vo
                       float *part, size_t part_elems, hipStream_t s) {
   if (rows.cap <= 0) return;
   EpiSwiGLU<bf16_t> e{(bf16_t *)act, N};
-  if (rows.cap <= SKINNY_MAX_ROWS && (size_t)rows.cap * 2 * N <= part_elems) {
+  if (rows.cap <= SKINNY_MAX_ROWS && N % EpiSwiGLUHalves<bf16_t>::INTERLEAVE == 0) {
+    // 96-column tiles of 48 gate + 48 up columns: SwiGLU in registers, no raw result
+    WSeg seg;
+    seg.w[0] = wg; seg.w[1] = wu; seg.w[2] = wu;
+    seg.n_end[0] = N; seg.n_end[1] = 2 * N; seg.n_end[2] = 2 * N;
+    run_tiles<SkinnyW96>(A, rows, K, 2 * N, seg, nullptr, EpiSwiGLUHalves<bf16_t>{(bf16_t *)act, N}, 1, nullptr, s);
+  } else if (rows.cap <= SKINNY_MAX_ROWS && (size_t)rows.cap * 2 * N <= part_elems) {
     WSeg seg;
     seg.w[0] = wg; seg.w[1] = wu; seg.w[2] = wu;
     seg.n_end[0] = N; seg.n_end[1] = 2 * N; seg.n_end[2] = 2 * N;

@@ -154,11 +154,21 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
     for (int i = 0; i < SH::B_LD; ++i) {
       const int nrow = (i * NW + wave) * 8 + r8;
       const int n = n0 + nrow;
-      const bool in1 = n >= seg.n_end[0], in2 = n >= seg.n_end[1];
-      const bf16_t *wbase = (const bf16_t *)(in2 ? seg.w[2] : in1 ? seg.w[1] : seg.w[0]);
-      const int wstart = in2 ? seg.n_end[1] : in1 ? seg.n_end[0] : 0;
+      const bf16_t *wbase;
+      int nl;  // row inside its matrix
+      if constexpr (Epi::INTERLEAVE > 0) {
+        // tile tn = HALF rows of matrix 0 followed by the same HALF rows of matrix 1
+        constexpr int HALF = Epi::INTERLEAVE;
+        static_assert(BN == 2 * HALF, "one half tile per matrix");
+        const bool second = nrow >= HALF;
+        wbase = (const bf16_t *)(second ? seg.w[1] : seg.w[0]);
+        nl = tn * HALF + (second ? nrow - HALF : nrow);
+      } else {
+        const bool in1 = n >= seg.n_end[0], in2 = n >= seg.n_end[1];
+        wbase = (const bf16_t *)(in2 ? seg.w[2] : in1 ? seg.w[1] : seg.w[0]);
+        nl = n - (in2 ? seg.n_end[1] : in1 ? seg.n_end[0] : 0);
+      }
       // panel layout: slice kt of this row sits kt * (WPANEL * BK) elements further on
-      const int nl = n - wstart;
       const size_t woff = ((size_t)(nl / WPANEL) * (ldw / BK) + kbeg / BK) * (WPANEL * BK) + (nl % WPANEL) * BK + csrc * 8;
       wp[0][i] = wbase + woff;
       if (SH::DUAL)
@@ -366,6 +376,25 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
     }
 
     // epilogue
+    if constexpr (Epi::INTERLEAVE > 0) {
+      // 32 x 96 wave tile = columns [0,48) of matrix 0 (gate) and [48,96) of matrix 1 (up): gate
+      // column c pairs with tile column c + 48, which lane (c%32) ^ 16 holds one or two blocks on
+      static_assert(NB == 3 && SH::WAVES_N == 1 && NMAT == 1, "half-interleaved tiles are 96 columns of one wave");
+      const bool hi16 = (l32 & 16) != 0;
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
+          const float a0 = acc[0][i][0][e], a1 = acc[0][i][1][e], a2 = acc[0][i][2][e];
+          const float up0 = __shfl_xor(hi16 ? a1 : a2, 16, WAVE);  // up value of gate column l32
+          const float up1 = __shfl_xor(a2, 16, WAVE);              // lanes 0..15: up value of gate column 32 + l32
+          if (j < M) {
+            epi.store(j, tn * Epi::INTERLEAVE + l32, a0, up0);
+            if (!hi16) epi.store(j, tn * Epi::INTERLEAVE + 32 + l32, a1, up1);
+          }
+        }
+    } else
 #pragma unroll
     for (int i = 0; i < MB; ++i)
 #pragma unroll

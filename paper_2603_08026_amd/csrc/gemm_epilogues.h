@@ -3,6 +3,11 @@
 //   EpiStoreF32 ... plain fp32 store (raw result; a finalize row kernel follows)
 //   EpiSwiGLU ..... act = silu(acc_gate) * acc_up           [Alg. 3: FFN, first half]
 //   EpiDown ....... out_cache[row_j] = h + acc              [Alg. 3: FFN second half + cache commit]
+//   EpiSwiGLUHalves  the same SwiGLU for the weight-streaming regime: a column tile holds HALF gate
+//                   columns followed by the HALF up columns of the same outputs (the kernel looks the
+//                   weight rows up that way), so one matrix serves per tile and the product never
+//                   leaves the registers
+// INTERLEAVE = that HALF (0: the tile's columns are consecutive rows of the stacked matrices).
 #pragma once
 #include "common.h"
 #include "kernels.h"
@@ -11,6 +16,7 @@ namespace dy {
 
 struct EpiStoreF32 {
   static constexpr bool DUAL = false;
+  static constexpr int INTERLEAVE = 0;
   float *out;
   int ldo;
   __device__ __forceinline__ void operator()(int j, int row, int n, float acc, float) const {
@@ -21,6 +27,7 @@ struct EpiStoreF32 {
 
 template <typename T> struct EpiSwiGLU {
   static constexpr bool DUAL = true;
+  static constexpr int INTERLEAVE = 0;
   T *act;  // [cap, N]
   int N;
   __device__ __forceinline__ void operator()(int j, int row, int n, float gate, float up) const {
@@ -32,12 +39,26 @@ template <typename T> struct EpiSwiGLU {
 
 template <typename T> struct EpiDown {
   static constexpr bool DUAL = false;
+  static constexpr int INTERLEAVE = 0;
   const float *h;  // [cap, N]
   T *out;          // [T, N]
   int N;
   __device__ __forceinline__ void operator()(int j, int row, int n, float acc, float) const {
     out[(size_t)row * N + n] = from_f<T>(h[(size_t)j * N + n] + acc);
   }
+};
+
+template <typename T> struct EpiSwiGLUHalves {
+  static constexpr bool DUAL = false;
+  static constexpr int INTERLEAVE = 48;
+  T *act;  // [cap, F]
+  int F;
+  // f = output column of the FFN's hidden layer
+  __device__ __forceinline__ void store(int j, int f, float gate, float up) const {
+    const float s = gate / (1.0f + __expf(-gate));
+    act[(size_t)j * F + f] = from_f<T>(s * up);
+  }
+  __device__ __forceinline__ void operator()(int, int, int, float, float) const {}
 };
 
 }  // namespace dy
