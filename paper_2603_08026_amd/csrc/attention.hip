@@ -154,9 +154,13 @@ void attention_plan(DType t, int B, int L, int H, int dh, int cap, int rows_per_
   const int BK = (t == F32) ? 64 : 128;
   const int n_opt = (t == F32) ? 1 : 2;
   const int bq_opt[2] = {(t == F32) ? 16 : 128, 64};
-  const long target = 256;  // workgroups that cover the 256 CUs once
-  // 128-row query tiles when sequences bring that many rows, else 64-row tiles
-  const int best_bq = (n_opt == 1) ? bq_opt[0] : (rows_per_seq > 80 ? 128 : 64);
+  // Few rows: the kernel is latency-bound and every extra key split costs the merge kernel a read of
+  // one more partial result, so half the CUs' worth of workgroups is the aim (measured at 106 rows of
+  // one sequence, 32 heads: 64-row tiles x 2 splits 13.2 + 6.0 us for attention + merge, 128-row
+  // tiles x 8 splits 13.9 + 8.9 us), and 128-row tiles are taken only when they alone reach it.
+  const long target = 128;
+  const long tiles128 = (long)((rows_per_seq + 127) / 128) * B * H;
+  const int best_bq = (n_opt == 1) ? bq_opt[0] : (rows_per_seq > 80 && tiles128 >= target ? 128 : 64);
   long tiles = (long)((rows_per_seq + best_bq - 1) / best_bq) * B * H;
   if (tiles < 1) tiles = 1;  // empty list
   const int best_s = (int)((target + tiles - 1) / tiles);
