@@ -70,8 +70,6 @@ Layout make_layout(const dyllm_layer_cfg &c) {
   const size_t prow = R < 2048 ? R : 2048;
   const size_t widest = dq + 2 * dkv > d ? dq + 2 * dkv : d;
   l.part_elems = 16 * prow * dq > R * widest ? 16 * prow * dq : R * widest;
-  const size_t skinny_ffn = (R < 128 ? R : 128) * 2 * (size_t)c.ffn_dim;  // raw gate|up of the skinny regime
-  if (l.part_elems < skinny_ffn) l.part_elems = skinny_ffn;
   l.part_o = take(l.part_elems * 4);
   l.part_ml = take(l.part_elems / c.head_dim * 2 * 4);
   l.cosb = take(R * 4);

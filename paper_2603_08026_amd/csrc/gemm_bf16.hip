@@ -24,10 +24,10 @@ typedef Shape<256, 64, 4, 2, true, 2> LargeD;
 typedef Shape<128, 128, 2, 2, false, 2> MidS;
 typedef Shape<128, 64, 2, 2, true, 2> MidD;
 typedef Shape<128, 64, 4, 2, false, 4> SkinnyS;
-// gate|up in the skinny regime: one raw GEMM over both weight matrices (wide column tiles keep the
-// re-reads of the activation tile down), SwiGLU applied by a row kernel
+// skinny regime, wide column tiles (fewer re-reads of the activation tile): q|k|v raw result, and
+// gate|up with half-interleaved tiles (48 + 48 or 64 + 64 columns) and SwiGLU in registers
 typedef Shape<128, 96, 4, 1, false, 4> SkinnyW96;
-typedef Shape<128, 128, 4, 2, false, 4> SkinnyW128;
+typedef Shape<128, 128, 4, 1, false, 4> SkinnyH128;
 
 constexpr int MID_MAX_ROWS = 320;  // above, 256-row tiles with a cheap partial second row tile do better
 constexpr int SKINNY_MAX_ROWS = 128;
@@ -159,23 +159,19 @@ int gemm_bf16_raw(GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_
 }
 
 void gemm_bf16_swiglu(GemmA A, Rows rows, int K, int N, const void *wg, const void *wu, void *act,
-                      float *part, size_t part_elems, hipStream_t s) {
+                      float *, size_t, hipStream_t s) {
   if (rows.cap <= 0) return;
   EpiSwiGLU<bf16_t> e{(bf16_t *)act, N};
-  if (rows.cap <= SKINNY_MAX_ROWS && N % EpiSwiGLUHalves<bf16_t>::INTERLEAVE == 0) {
-    // 96-column tiles of 48 gate + 48 up columns: SwiGLU in registers, no raw result
+  if (rows.cap <= SKINNY_MAX_ROWS && (N % 48 == 0 || N % 64 == 0)) {
+    // weight streaming: tiles of HALF gate + HALF up columns, SwiGLU in registers, no raw result
+    // (N is a multiple of 64 for every bf16 configuration the library accepts)
     WSeg seg;
     seg.w[0] = wg; seg.w[1] = wu; seg.w[2] = wu;
     seg.n_end[0] = N; seg.n_end[1] = 2 * N; seg.n_end[2] = 2 * N;
-    run_tiles<SkinnyW96>(A, rows, K, 2 * N, seg, nullptr, EpiSwiGLUHalves<bf16_t>{(bf16_t *)act, N}, 1, nullptr, s);
-  } else if (rows.cap <= SKINNY_MAX_ROWS && (size_t)rows.cap * 2 * N <= part_elems) {
-    WSeg seg;
-    seg.w[0] = wg; seg.w[1] = wu; seg.w[2] = wu;
-    seg.n_end[0] = N; seg.n_end[1] = 2 * N; seg.n_end[2] = 2 * N;
-    EpiStoreF32 raw{part, 2 * N};
-    if (N % 96 == 0) run_tiles<SkinnyW96>(A, rows, K, 2 * N, seg, nullptr, raw, 1, part, s);
-    else run_tiles<SkinnyW128>(A, rows, K, 2 * N, seg, nullptr, raw, 1, part, s);
-    launch_swiglu_finalize(BF16, part, 1, (size_t)rows.cap * 2 * N, rows, N, act, s);
+    if (N % 48 == 0)
+      run_tiles<SkinnyW96>(A, rows, K, 2 * N, seg, nullptr, EpiSwiGLUHalves<bf16_t, 48>{(bf16_t *)act, N}, 1, nullptr, s);
+    else
+      run_tiles<SkinnyH128>(A, rows, K, 2 * N, seg, nullptr, EpiSwiGLUHalves<bf16_t, 64>{(bf16_t *)act, N}, 1, nullptr, s);
   } else if (rows.cap <= MID_MAX_ROWS) run_tiles<MidD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
   else if (N % XLargeD::BN == 0 && prefer_xlarge(rows.cap, N / LargeD::BN, N / XLargeD::BN))
     run_tiles<XLargeD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);

@@ -376,7 +376,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
     }
 
     // epilogue
-    if constexpr (Epi::INTERLEAVE > 0) {
+    if constexpr (Epi::INTERLEAVE == 48) {
       // 32 x 96 wave tile = columns [0,48) of matrix 0 (gate) and [48,96) of matrix 1 (up): gate
       // column c pairs with tile column c + 48, which lane (c%32) ^ 16 holds one or two blocks on
       static_assert(NB == 3 && SH::WAVES_N == 1 && NMAT == 1, "half-interleaved tiles are 96 columns of one wave");
@@ -390,8 +390,22 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
           const float up0 = __shfl_xor(hi16 ? a1 : a2, 16, WAVE);  // up value of gate column l32
           const float up1 = __shfl_xor(a2, 16, WAVE);              // lanes 0..15: up value of gate column 32 + l32
           if (j < M) {
-            epi.store(j, tn * Epi::INTERLEAVE + l32, a0, up0);
-            if (!hi16) epi.store(j, tn * Epi::INTERLEAVE + 32 + l32, a1, up1);
+            epi.store(j, tn * 48 + l32, a0, up0);
+            if (!hi16) epi.store(j, tn * 48 + 32 + l32, a1, up1);
+          }
+        }
+    } else if constexpr (Epi::INTERLEAVE == 64) {
+      // 32 x 128 wave tile = 64 gate + 64 up columns: the partner of a gate column is two blocks on
+      // in the same lane
+      static_assert(NB == 4 && SH::WAVES_N == 1 && NMAT == 1, "half-interleaved tiles are 128 columns of one wave");
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
+          if (j < M) {
+            epi.store(j, tn * 64 + l32, acc[0][i][0][e], acc[0][i][2][e]);
+            epi.store(j, tn * 64 + 32 + l32, acc[0][i][1][e], acc[0][i][3][e]);
           }
         }
     } else

@@ -48,9 +48,9 @@ template <typename T> struct EpiDown {
   }
 };
 
-template <typename T> struct EpiSwiGLUHalves {
+template <typename T, int HALF> struct EpiSwiGLUHalves {
   static constexpr bool DUAL = false;
-  static constexpr int INTERLEAVE = 48;
+  static constexpr int INTERLEAVE = HALF;  // 48 (96-column tiles) or 64 (128-column tiles)
   T *act;  // [cap, F]
   int F;
   // f = output column of the FFN's hidden layer

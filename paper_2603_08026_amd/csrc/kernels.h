@@ -37,10 +37,6 @@ void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_st
 void launch_oproj_finalize(DType t, const float *part, int splits, size_t split_stride, const void *x,
                            const void *gain, Rows rows, int d, float eps, float *h, void *f,
                            hipStream_t s);
-// gate|up: act[j] = silu(sum of splits of the gate columns) * (sum of splits of the up columns);
-// part rows are [2F] wide, gate columns first
-void launch_swiglu_finalize(DType t, const float *part, int splits, size_t split_stride, Rows rows,
-                            int F, void *act, hipStream_t s);
 // down projection after a K split: out_cache[row_j] = h[j] + sum of splits
 void launch_down_finalize(DType t, const float *part, int splits, size_t split_stride, const float *h,
                           Rows rows, int d, void *out_cache, hipStream_t s);

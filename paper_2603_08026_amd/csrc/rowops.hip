@@ -125,33 +125,6 @@ __global__ __launch_bounds__(RB) void k_down_finalize(const float *__restrict__ 
   }
 }
 
-// ---- SwiGLU after a raw gate|up GEMM: act = silu(gate) * up  [Alg. 3: FFN, first half] ------------
-// part: [splits][cap][2F] fp32 with the gate columns first, then the up columns.
-template <typename T>
-__global__ __launch_bounds__(256) void k_swiglu_finalize(const float *__restrict__ part, int splits,
-                                                          size_t split_stride, Rows rows, int F,
-                                                          T *__restrict__ act) {
-  const int n = row_count(rows), nv = F / 4;
-  const size_t total = (size_t)n * nv;
-  for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
-    const int j = (int)(e / nv), v = (int)(e % nv);
-    const float *src = part + (size_t)j * 2 * F + v * 4;
-    float4 g = *reinterpret_cast<const float4 *>(src);
-    float4 u = *reinterpret_cast<const float4 *>(src + F);
-    for (int z = 1; z < splits; ++z) {
-      const float4 g2 = *reinterpret_cast<const float4 *>(src + z * split_stride);
-      const float4 u2 = *reinterpret_cast<const float4 *>(src + z * split_stride + F);
-      g.x += g2.x; g.y += g2.y; g.z += g2.z; g.w += g2.w;
-      u.x += u2.x; u.y += u2.y; u.z += u2.z; u.w += u2.w;
-    }
-    T *dst = act + (size_t)j * F + v * 4;
-    dst[0] = from_f<T>(g.x / (1.0f + __expf(-g.x)) * u.x);
-    dst[1] = from_f<T>(g.y / (1.0f + __expf(-g.y)) * u.y);
-    dst[2] = from_f<T>(g.z / (1.0f + __expf(-g.z)) * u.z);
-    dst[3] = from_f<T>(g.w / (1.0f + __expf(-g.w)) * u.w);
-  }
-}
-
 // ---- q/k/v tail: bias + rotary embedding + K/V merge  [Alg. 3: K[idx] <- k_proj(x[idx]), same V] --
 // Half-split pairing: element p of a head couples with element p + dh/2, rotated by the angle
 // pos * theta^(-2p/dh); the table holds (cos, sin) per (pos, p).  A thread handles 4 neighbouring
@@ -324,16 +297,6 @@ void launch_down_finalize(DType t, const float *part, int splits, size_t split_s
   else
     k_down_finalize<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>(part, splits, split_stride, h, rows, d,
                                                               (bf16_t *)out_cache);
-}
-
-void launch_swiglu_finalize(DType t, const float *part, int splits, size_t split_stride, Rows rows,
-                            int F, void *act, hipStream_t s) {
-  if (rows.cap <= 0) return;
-  size_t total = (size_t)rows.cap * (F / 4);
-  int grid = (int)((total + 255) / 256);
-  if (grid > 4096) grid = 4096;
-  if (t == F32) k_swiglu_finalize<float><<<grid, 256, 0, s>>>(part, splits, split_stride, rows, F, (float *)act);
-  else k_swiglu_finalize<bf16_t><<<grid, 256, 0, s>>>(part, splits, split_stride, rows, F, (bf16_t *)act);
 }
 
 void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_stride,

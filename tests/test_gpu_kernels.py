@@ -329,6 +329,34 @@ def test_error_paths_do_not_launch():
     lay.close()
 
 
+@pytest.mark.parametrize("ffn,rows", [(640, [70, 40]), (384, [101, 9]), (1024, [5, 0])])
+def test_salient_ffn_weight_streaming_tiles(ffn, rows):
+    """bf16, at most 128 rows: gate|up tiles hold 48 + 48 (F a multiple of 48) or 64 + 64 columns and
+    SwiGLU is applied inside the GEMM; the widths here reach both forms and several column tiles."""
+    _say("salient_ffn streaming tiles", ffn, rows)
+    s = W.LayerShape(hidden=256, n_heads=4, n_kv_heads=4, head_dim=64, ffn=ffn, dtype="bf16", rope_theta=10000.0)
+    cfg = oracle_cfg(s)
+    B, L = 2, 150
+    lay = Layer.from_shape(s, B, L)
+    w = rand_weights(s, 61)
+    lay.set_weights(w)
+    x = _vals(62, (B * L, s.hidden), "bf16")
+    c = _vals(63, (B * L, s.dq), "bf16")
+    out0 = _vals(64, (B * L, s.hidden), "bf16")
+    idx, off = rand_rows(65, B, L, rows)
+    ref = out0.astype(np.float64)
+    O.salient_ffn(x, c, idx, w, cfg, ref)
+    d_out = to_device(out0, "bf16")
+    lay.ctx.salient_ffn(lay.w, to_device(x, "bf16"), to_device(c, "bf16"), lay.make_list(idx, off, cap=idx.size + 1),
+                        B, L, d_out)
+    torch.cuda.synchronize()
+    got = to_host(d_out)
+    assert_close(got[idx], ref[idx], TOL["bf16"], "ffn rows")
+    others = np.setdiff1d(np.arange(B * L), idx)
+    assert np.array_equal(got[others], out0[others].astype(np.float64))
+    lay.close()
+
+
 # ------------------------------------------------------------------ weight re-layout
 
 @pytest.mark.parametrize("n_out,n_in", [(32, 64), (96, 192), (4096 + 512, 4096), (384, 12288)])
