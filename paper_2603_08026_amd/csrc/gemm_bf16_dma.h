@@ -210,6 +210,19 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
       // while the products of slice kt run, and because a wave holds slice kt in registers when it
       // reaches the barrier of iteration kt, that stage is refilled at once: NS slices are in flight
       // instead of NS-1.
+      // Few rows: only the first ALD of a wave's A_LD copies per slice hold rows below M (copy i of
+      // wave w fills rows (i*NW + w)*8 ...), the others are left out -- with at most 64 (32) rows that
+      // halves (quarters) the activation traffic from L2, which competes with the weight stream.
+      // Tile rows that are never filled only feed results that are never stored.
+      auto pipe_loop = [&](auto ald_c) {
+      constexpr int ALD = decltype(ald_c)::value;
+      constexpr int LPS = ALD + NMAT * SH::B_LD;  // copies per wave and slice
+      auto issue_a_n = [&](int kt) {
+        const uint32_t sb = lds0 + (uint32_t)(kt % NS) * SH::A_BYTES + (uint32_t)wave * 1024u;
+        const int ko = kt * BK;
+#pragma unroll
+        for (int i = 0; i < ALD; ++i) dma16(ap[i] + ko, sb + i * (NW * 1024u));
+      };
       constexpr int KS = BK / 16, RD = MB + NMAT * NB, MM = NMAT * MB * NB;
       bf16x8 af[2][KS][MB], bfr[2][KS][NMAT][NB];
       auto read_slice = [&](bf16x8 (&a)[KS][MB], bf16x8 (&b)[KS][NMAT][NB], int kt) {
@@ -230,11 +243,11 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
       auto slice = [&](int kt, auto cur_c) {
         constexpr int CUR = decltype(cur_c)::value;
         // slice kt+1 has landed: the copies issued after it may still be on their way
-        if (kt + NS - 1 < KT) wait_vmcnt<(NS - 2) * SH::LPS>();
+        if (kt + NS - 1 < KT) wait_vmcnt<(NS - 2) * LPS>();
         else wait_vmcnt<0>();
         wait_lgkmcnt0();  // the operands of slice kt are in registers: its stage is free
         __syncthreads();
-        if (kt + NS < KT) { issue_a(kt + NS); issue_w(kt + NS); }
+        if (kt + NS < KT) { issue_a_n(kt + NS); issue_w(kt + NS); }
         read_slice(af[CUR ^ 1], bfr[CUR ^ 1], kt + 1 < KT ? kt + 1 : kt);  // (past the end: a harmless re-read)
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk)
@@ -251,8 +264,8 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
       };
 #pragma unroll
       for (int s = 0; s < NS; ++s)
-        if (s < KT) { issue_a(s); issue_w(s); }
-      if (NS - 1 < KT) wait_vmcnt<(NS - 1) * SH::LPS>();  // slice 0 has landed
+        if (s < KT) { issue_a_n(s); issue_w(s); }
+      if (NS - 1 < KT) wait_vmcnt<(NS - 1) * LPS>();  // slice 0 has landed
       else wait_vmcnt<0>();
       __syncthreads();
       read_slice(af[0], bfr[0], 0);
@@ -262,6 +275,11 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
         slice(kt + 1, std::integral_constant<int, 1>{});
       }
       if (kt < KT) slice(kt, std::integral_constant<int, 0>{});
+      };
+      const int a_need = (M - m0 + 8 * NW - 1) / (8 * NW);  // copies per wave that hold rows
+      if (SH::A_LD >= 4 && a_need <= 1) pipe_loop(std::integral_constant<int, 1>{});
+      else if (SH::A_LD >= 2 && a_need <= SH::A_LD / 2) pipe_loop(std::integral_constant<int, (SH::A_LD >= 2 ? SH::A_LD / 2 : 1)>{});
+      else pipe_loop(std::integral_constant<int, SH::A_LD>{});
     } else if (NS == 2 && m0 + BM > M) {
       // A row tile that holds fewer than BM rows: copies of 8-row blocks past the end are left out,
       // and a wave multiplies only its 32-row blocks that hold rows (none at all for many waves), so
