@@ -17,11 +17,13 @@ __device__ __forceinline__ int row_count(const Rows &rows) {
 }
 
 // ---- gather + RMSNorm  [Alg. 3: layernorm(x) restricted to the salient rows] -------------------
-template <typename T>
-__global__ __launch_bounds__(RB) void k_gather_rmsnorm(const T *__restrict__ x,
+// NT threads per row: 256 when the row fits KEEP vectors per thread (more rows in flight per CU and a
+// four-wave reduction), else RB.
+template <typename T, int NT>
+__global__ __launch_bounds__(NT) void k_gather_rmsnorm(const T *__restrict__ x,
                                                         const T *__restrict__ gain, Rows rows, int d,
                                                         float eps, T *__restrict__ out) {
-  __shared__ float red[RB / WAVE];
+  __shared__ float red[NT / WAVE];
   constexpr int N = Vec16<T>::N;
   const int n = row_count(rows), nv = d / N;
   for (int j = blockIdx.x; j < n; j += gridDim.x) {
@@ -31,19 +33,19 @@ __global__ __launch_bounds__(RB) void k_gather_rmsnorm(const T *__restrict__ x,
     Vec16<T> keep[KEEP];
 #pragma unroll
     for (int it = 0; it < KEEP; ++it) {
-      const int v = threadIdx.x + it * RB;
+      const int v = threadIdx.x + it * NT;
       if (v < nv) {
         keep[it] = ld16(xr + v * N);
 #pragma unroll
         for (int i = 0; i < N; ++i) ss += keep[it].get(i) * keep[it].get(i);
       }
     }
-    ss = block_sum<RB>(ss, red);
+    ss = block_sum<NT>(ss, red);
     const float sc = 1.0f / sqrtf(ss / (float)d + eps);
     T *orow = out + (size_t)j * d;
 #pragma unroll
     for (int it = 0; it < KEEP; ++it) {
-      const int v = threadIdx.x + it * RB;
+      const int v = threadIdx.x + it * NT;
       if (v < nv) {
         Vec16<T> g = ld16(gain + v * N), o;
 #pragma unroll
@@ -267,12 +269,18 @@ inline int row_grid(int cap) { return cap < 1 ? 1 : (cap > 8192 ? 8192 : cap); }
 void launch_gather_rmsnorm(DType t, const void *x, const void *gain, Rows rows, int d, float eps,
                            void *out, hipStream_t s) {
   if (rows.cap <= 0) return;
-  if (t == F32)
-    k_gather_rmsnorm<float><<<row_grid(rows.cap), RB, 0, s>>>((const float *)x, (const float *)gain,
-                                                              rows, d, eps, (float *)out);
-  else
-    k_gather_rmsnorm<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>((const bf16_t *)x, (const bf16_t *)gain,
-                                                               rows, d, eps, (bf16_t *)out);
+  const int grid = rows.cap < 1 ? 1 : (rows.cap > 32768 ? 32768 : rows.cap);
+  if (t == F32) {
+    if (d / 4 <= 256 * KEEP)
+      k_gather_rmsnorm<float, 256><<<grid, 256, 0, s>>>((const float *)x, (const float *)gain, rows, d, eps, (float *)out);
+    else
+      k_gather_rmsnorm<float, RB><<<row_grid(rows.cap), RB, 0, s>>>((const float *)x, (const float *)gain, rows, d, eps, (float *)out);
+  } else {
+    if (d / 8 <= 256 * KEEP)
+      k_gather_rmsnorm<bf16_t, 256><<<grid, 256, 0, s>>>((const bf16_t *)x, (const bf16_t *)gain, rows, d, eps, (bf16_t *)out);
+    else
+      k_gather_rmsnorm<bf16_t, RB><<<row_grid(rows.cap), RB, 0, s>>>((const bf16_t *)x, (const bf16_t *)gain, rows, d, eps, (bf16_t *)out);
+  }
 }
 
 void launch_oproj_finalize(DType t, const float *part, int splits, size_t split_stride, const void *x,
