@@ -82,13 +82,14 @@ void launch_attn_finalize(DType t, const AttnArgs &a, void *c_cache, float tau, 
 void attention_plan(DType t, int B, int L, int H, int dh, int cap, int rows_per_seq, size_t part_elems,
                     AttnArgs *a);
 
-// ---- GEMMs  C[m,n] = sum_k A[m,k] * W[n,k]  (W is [N,K] row-major) -----------------------------
+// ---- GEMMs  C[m,n] = sum_k A[m,k] * W[n,k]  (W [N,K]: row-major for fp32, 32-row panels for bf16) --
 struct GemmA {
   const void *a;        // T-typed, row stride lda
   const int32_t *gather;  // nullptr, or row j of the GEMM reads a[gather[j], :]
   int lda;
 };
-// Up to three weight matrices stacked along N (q | k | v); a tile never straddles two of them.
+// Up to three weight matrices stacked along N (q | k | v); the bf16 kernels look the matrix up per
+// tile row, so a column tile may span two of them.
 struct WSeg {
   const void *w[3];
   int n_end[3];  // exclusive end column of each segment; N = n_end[2]
