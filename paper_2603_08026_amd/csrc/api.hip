@@ -176,7 +176,7 @@ int enqueue_qkv(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x, Row
   prof_mark(ctx, ST_GEMM_QKV, s);
   launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)rows.cap * seg.n_end[2], ctx->rope, rows, L,
                       c.n_heads, c.n_kv_heads, c.head_dim, w->bq, w->bk, w->bv, q_out, cache->k,
-                      cache->v, nullptr, 0, nullptr, 0, s);
+                      cache->v, nullptr, 0, nullptr, 0, nullptr, s);
   prof_mark(ctx, ST_ROPE_SCATTER, s);
   return check_launch(ctx, "qkv refresh");
 }
@@ -316,7 +316,7 @@ int enqueue_approx_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
                                        wseg_one(w->wq, ctx->dq), ctx->part_o, ctx->part_elems, s);
     launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)all.cap * ctx->dq, ctx->rope, all, L, c.n_heads,
                         0, c.head_dim, w->bq, nullptr, nullptr, ctx->qs, nullptr, nullptr, nullptr, by_token,
-                        nullptr, 0, s);
+                        nullptr, 0, nullptr, s);
   }
   // k, v of the salient tokens: norm, projection, rotation, value residual, merge into the caches
   launch_gather_rmsnorm(dt(ctx), x, w->g_attn, rin, c.hidden, c.rms_eps, ctx->fs, s);
@@ -331,7 +331,7 @@ int enqueue_approx_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
     launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)rin.cap * 2 * ctx->dkv, ctx->rope, rin, L, 0,
                         c.n_kv_heads, c.head_dim, nullptr, w->bk, w->bv, nullptr, cache->k, cache->v,
                         cached_norm ? ctx->dc : ctx->dv_full, 0, cached_norm ? ctx->ksal : nullptr,
-                        cached_norm, s);
+                        cached_norm, ctx->pos, s);  // also marks the candidates in the token -> entry map
   }
   if ((rc = check_launch(ctx, "approx: projections"))) return rc;
   // exact rows of the salient tokens  [Alg. 3: C_sal]; q is stored by token here.  With a cache of
@@ -344,7 +344,6 @@ int enqueue_approx_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
     launch_attention(dt(ctx), a, s);
     if (keep_lse) launch_attn_combine(dt(ctx), a, s);
   }
-  launch_mark_rows(rin, ctx->pos, s);
   if (!cached_norm) {
     // approximate residual of every token of the step: the full softmax against the merged keys times
     // the value residual, which is zero outside the salient rows  [Alg. 4]

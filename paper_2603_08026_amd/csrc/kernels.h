@@ -28,11 +28,12 @@ void launch_gather_rmsnorm(DType t, const void *x, const void *gain, Rows rows, 
 // row_j or (dv_by_entry) at j; ksal_out (may be nullptr) takes a copy of the rotated k rows at j.
 // rope_tab: [max_seq, dh/2, 2] fp32 (cos, sin).  dh is 64 or 128.
 // dv_out (optional, [T, Hkv*dh] T-typed): value residual new - cached of the rows, taken before the merge
+// entry_of (optional, [T] int32): entry_of[row_j] = j + 1, the map from a token to its list entry
 void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_stride,
                          const float *rope_tab, Rows rows, int L, int H, int Hkv, int dh,
                          const void *bq, const void *bk, const void *bv, void *q_out, void *k_cache,
                          void *v_cache, void *dv_out, int q_by_token, void *ksal_out, int dv_by_entry,
-                         hipStream_t s);
+                         int32_t *entry_of, hipStream_t s);
 // out-projection: h[j] = x[row_j] + sum of splits (fp32 [cap,d]); f[j] = RMSNorm(h[j]) * gain (T-typed)
 void launch_oproj_finalize(DType t, const float *part, int splits, size_t split_stride, const void *x,
                            const void *gain, Rows rows, int d, float eps, float *h, void *f,
@@ -120,8 +121,8 @@ void launch_pack_weight(const void *src, int n_out, int n_in, void *dst, hipStre
 void launch_fill_i32(int32_t *p, int32_t v, int n, hipStream_t s);
 
 // ---- approximate (column-sparse) context update of the non-salient rows  [Sec. 3.3; Alg. 3, Alg. 4]
-// pos[row_j] = j + 1 for the rows of the list (pos is zero elsewhere, before and after a step)
-void launch_mark_rows(Rows rows, int32_t *pos, hipStream_t s);
+// pos[row_j] = j + 1 for the candidates (written by the k|v finalize kernel of the step through its
+// entry_of argument; pos is zero elsewhere, before and after a step)
 // For every entry j of the window `win` (token r = win.idx[j], or j): new context = c_sal[pos[r]-1]
 // where pos[r] != 0, else c_cache[r] + residual (rounded to T); cosine against the cached row, commit;
 // cos_out[r] (may be nullptr), flag_out[j] = cos < tau.  The residual is dc[j], or (cached != nullptr)

@@ -139,13 +139,15 @@ __global__ __launch_bounds__(RB) void k_qkv_finalize(const float *__restrict__ p
                                                       const T *__restrict__ bv, T *__restrict__ q_out,
                                                       T *__restrict__ kc, T *__restrict__ vc,
                                                       T *__restrict__ dv_out, int q_by_token,
-                                                      T *__restrict__ ksal_out, int dv_by_entry) {
+                                                      T *__restrict__ ksal_out, int dv_by_entry,
+                                                      int32_t *__restrict__ entry_of) {
   const int n = row_count(rows);
   const int half = dh / 2, dq = H * dh, dkv = Hkv * dh, ld = dq + 2 * dkv;
   const int per_head = half / 4;  // items of 4 pairs per head
   const int qk_items = (H + Hkv) * per_head, v_items = dkv / 4;
   for (int j = blockIdx.x; j < n; j += gridDim.x) {
     const int r = rows.idx ? rows.idx[j] : j;
+    if (entry_of && threadIdx.x == 0) entry_of[r] = j + 1;  // token -> its list entry (0 = not in the list)
     const int pos = r % L;
     const float *src = part + (size_t)j * ld;
     const float *t = tab + (size_t)pos * half * 2;
@@ -311,18 +313,18 @@ void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_st
                          const float *rope_tab, Rows rows, int L, int H, int Hkv, int dh,
                          const void *bq, const void *bk, const void *bv, void *q_out, void *k_cache,
                          void *v_cache, void *dv_out, int q_by_token, void *ksal_out, int dv_by_entry,
-                         hipStream_t s) {
+                         int32_t *entry_of, hipStream_t s) {
   if (rows.cap <= 0) return;
   if (t == F32)
     k_qkv_finalize<float><<<row_grid(rows.cap), RB, 0, s>>>(
         part, splits, split_stride, rope_tab, rows, L, H, Hkv, dh, (const float *)bq, (const float *)bk,
         (const float *)bv, (float *)q_out, (float *)k_cache, (float *)v_cache, (float *)dv_out, q_by_token,
-        (float *)ksal_out, dv_by_entry);
+        (float *)ksal_out, dv_by_entry, entry_of);
   else
     k_qkv_finalize<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>(
         part, splits, split_stride, rope_tab, rows, L, H, Hkv, dh, (const bf16_t *)bq, (const bf16_t *)bk,
         (const bf16_t *)bv, (bf16_t *)q_out, (bf16_t *)k_cache, (bf16_t *)v_cache, (bf16_t *)dv_out, q_by_token,
-        (bf16_t *)ksal_out, dv_by_entry);
+        (bf16_t *)ksal_out, dv_by_entry, entry_of);
 }
 
 inline int sal_grid(int cap) { return cap < 1 ? 1 : (cap > 65536 ? 65536 : cap); }
@@ -344,11 +346,6 @@ void launch_compact(const uint8_t *flag, Rows rows, int B, int L, int32_t *out_i
 }
 
 // ---- approximate context update of the non-salient rows  [Sec. 3.3; Alg. 3 lines C <- ..., cosine] --
-__global__ __launch_bounds__(256) void k_mark_rows(Rows rows, int32_t *pos) {
-  const int n = row_count(rows);
-  for (int j = blockIdx.x * 256 + threadIdx.x; j < n; j += gridDim.x * 256) pos[rows.idx ? rows.idx[j] : j] = j + 1;
-}
-
 template <typename T>
 __global__ __launch_bounds__(256) void k_clear_rows(Rows rows, int32_t *pos, T *dv, int dkv) {
   const int n = row_count(rows);
@@ -462,11 +459,6 @@ __global__ __launch_bounds__(256) void k_mark_flags(Rows rows, int T, int L, int
     const int r = rows.idx[j];
     if ((unsigned)r < (unsigned)T && r % L >= lo) flag[r] = 1;
   }
-}
-
-void launch_mark_rows(Rows rows, int32_t *pos, hipStream_t s) {
-  if (rows.cap <= 0) return;
-  k_mark_rows<<<(rows.cap + 255) / 256, 256, 0, s>>>(rows, pos);
 }
 
 void launch_saliency_approx(DType t, Rows win, int D, const void *c_sal, const void *dc, const int32_t *pos,
