@@ -176,7 +176,7 @@ int enqueue_qkv(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x, Row
   prof_mark(ctx, ST_GEMM_QKV, s);
   launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)rows.cap * seg.n_end[2], ctx->rope, rows, L,
                       c.n_heads, c.n_kv_heads, c.head_dim, w->bq, w->bk, w->bv, q_out, cache->k,
-                      cache->v, nullptr, 0, nullptr, 0, nullptr, s);
+                      cache->v, nullptr, 0, nullptr, 0, nullptr, 0, s);
   prof_mark(ctx, ST_ROPE_SCATTER, s);
   return check_launch(ctx, "qkv refresh");
 }
@@ -290,11 +290,11 @@ int enqueue_sparse_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
 
 // The tokens of a step: all B*L (row_lo = 0) or the positions [row_lo, L) of every sequence, as a list
 // in the context's workspace  [Sec. 3.5: response-only steps]
-struct Window { Rows rows; const int32_t *offsets; };
+struct Window { Rows rows; const int32_t *offsets; int lo; };
 Window make_window(dyllm_ctx *ctx, int B, int L, int row_lo, hipStream_t s) {
-  if (row_lo <= 0) return Window{Rows{nullptr, nullptr, B * L}, nullptr};
+  if (row_lo <= 0) return Window{Rows{nullptr, nullptr, B * L}, nullptr, 0};
   launch_make_window(B, L, row_lo, ctx->win_idx, ctx->win_off, s);
-  return Window{Rows{ctx->win_idx, nullptr, B * (L - row_lo)}, ctx->win_off};
+  return Window{Rows{ctx->win_idx, nullptr, B * (L - row_lo)}, ctx->win_off, row_lo};
 }
 
 // one layer of the sparse step with both attention paths, arguments already checked
@@ -316,7 +316,7 @@ int enqueue_approx_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
                                        wseg_one(w->wq, ctx->dq), ctx->part_o, ctx->part_elems, s);
     launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)all.cap * ctx->dq, ctx->rope, all, L, c.n_heads,
                         0, c.head_dim, w->bq, nullptr, nullptr, ctx->qs, nullptr, nullptr, nullptr, by_token,
-                        nullptr, 0, nullptr, s);
+                        nullptr, 0, nullptr, 0, s);
   }
   // k, v of the salient tokens: norm, projection, rotation, value residual, merge into the caches
   launch_gather_rmsnorm(dt(ctx), x, w->g_attn, rin, c.hidden, c.rms_eps, ctx->fs, s);
@@ -331,7 +331,7 @@ int enqueue_approx_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
     launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)rin.cap * 2 * ctx->dkv, ctx->rope, rin, L, 0,
                         c.n_kv_heads, c.head_dim, nullptr, w->bk, w->bv, nullptr, cache->k, cache->v,
                         cached_norm ? ctx->dc : ctx->dv_full, 0, cached_norm ? ctx->ksal : nullptr,
-                        cached_norm, ctx->pos, s);  // also marks the candidates in the token -> entry map
+                        cached_norm, ctx->pos, win.lo, s);  // also marks the step's candidates in the token -> entry map
   }
   if ((rc = check_launch(ctx, "approx: projections"))) return rc;
   // exact rows of the salient tokens  [Alg. 3: C_sal]; q is stored by token here.  With a cache of
@@ -354,7 +354,7 @@ int enqueue_approx_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
     // new contexts of the step's tokens, cosine test, commit; then the scratch maps go back to zero
     launch_saliency_approx(dt(ctx), all, ctx->dq, ctx->csal, ctx->dc, ctx->pos, cache->c, tau, cos_out, ctx->flag,
                            nullptr, nullptr, L, s);
-    launch_clear_rows(dt(ctx), rin, ctx->pos, ctx->dv_full, ctx->dkv, s);
+    launch_clear_rows(dt(ctx), rin, ctx->dv_full, ctx->dkv, s);  // the residual buffer goes back to zero
   } else {
     // Reused normalisers (Sec. 3.3's O(N |A| d) form): every token of the step is scored against the
     // candidates' keys only -- compact rows, sequence b's at [offsets[b], offsets[b+1]) -- and the
@@ -372,7 +372,6 @@ int enqueue_approx_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
     if ((rc = check_launch(ctx, "approx: attention"))) return rc;
     launch_saliency_approx(dt(ctx), all, ctx->dq, ctx->csal, nullptr, ctx->pos, cache->c, tau, cos_out, ctx->flag,
                            &a, (const float *)cache->lse, L, s);
-    launch_clear_rows(dt(ctx), rin, ctx->pos, nullptr, ctx->dkv, s);
   }
   launch_compact(ctx->flag, all, B, L, idx_out->idx, idx_out->offsets, idx_out->cap, ctx->status, s);
   if ((rc = check_launch(ctx, "approx: saliency / compact"))) return rc;

@@ -28,12 +28,13 @@ void launch_gather_rmsnorm(DType t, const void *x, const void *gain, Rows rows, 
 // row_j or (dv_by_entry) at j; ksal_out (may be nullptr) takes a copy of the rotated k rows at j.
 // rope_tab: [max_seq, dh/2, 2] fp32 (cos, sin).  dh is 64 or 128.
 // dv_out (optional, [T, Hkv*dh] T-typed): value residual new - cached of the rows, taken before the merge
-// entry_of (optional, [T] int32): entry_of[row_j] = j + 1, the map from a token to its list entry
+// entry_of (optional, [T] int32): entry_of[row_j] = j + 1, the map from a token to its list entry, written
+// for the rows at positions >= entry_lo of their sequence only
 void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_stride,
                          const float *rope_tab, Rows rows, int L, int H, int Hkv, int dh,
                          const void *bq, const void *bk, const void *bv, void *q_out, void *k_cache,
                          void *v_cache, void *dv_out, int q_by_token, void *ksal_out, int dv_by_entry,
-                         int32_t *entry_of, hipStream_t s);
+                         int32_t *entry_of, int entry_lo, hipStream_t s);
 // out-projection: h[j] = x[row_j] + sum of splits (fp32 [cap,d]); f[j] = RMSNorm(h[j]) * gain (T-typed)
 void launch_oproj_finalize(DType t, const float *part, int splits, size_t split_stride, const void *x,
                            const void *gain, Rows rows, int d, float eps, float *h, void *f,
@@ -121,21 +122,23 @@ void launch_pack_weight(const void *src, int n_out, int n_in, void *dst, hipStre
 void launch_fill_i32(int32_t *p, int32_t v, int n, hipStream_t s);
 
 // ---- approximate (column-sparse) context update of the non-salient rows  [Sec. 3.3; Alg. 3, Alg. 4]
-// pos[row_j] = j + 1 for the candidates (written by the k|v finalize kernel of the step through its
-// entry_of argument; pos is zero elsewhere, before and after a step)
+// pos[row_j] = j + 1 for the candidates among the step's tokens (written by the k|v finalize kernel of
+// the step through its entry_of argument, consumed and zeroed by launch_saliency_approx; pos is zero
+// elsewhere, before and after a step)
 // For every entry j of the window `win` (token r = win.idx[j], or j): new context = c_sal[pos[r]-1]
 // where pos[r] != 0, else c_cache[r] + residual (rounded to T); cosine against the cached row, commit;
 // cos_out[r] (may be nullptr), flag_out[j] = cos < tau.  The residual is dc[j], or (cached != nullptr)
 // sum over the key splits s of part_o[s][j] * exp(m_s - lse[r, h]) from the partials of an attention
 // pass over the compact candidate keys (cached->key_offsets) -- the normalisers are NOT recomputed.
-void launch_saliency_approx(DType t, Rows win, int D, const void *c_sal, const void *dc, const int32_t *pos,
+// Every pos entry that is read non-zero is set back to zero.
+void launch_saliency_approx(DType t, Rows win, int D, const void *c_sal, const void *dc, int32_t *pos,
                             void *c_cache, float tau, float *cos_out, uint8_t *flag_out,
                             const AttnArgs *cached, const float *lse, int L, hipStream_t s);
 // idx/off := the tokens at positions [lo, L) of each of the B sequences, as an index list
 void launch_make_window(int B, int L, int lo, int32_t *idx, int32_t *off, hipStream_t s);
 // flag[r] = 1 for every token r < T of the list whose position in its sequence is >= lo
 void launch_mark_flags(Rows rows, int T, int L, int lo, uint8_t *flag, hipStream_t s);
-// pos[row_j] = 0 and (dv != nullptr) dv[row_j, :] = 0 for the rows of the list
-void launch_clear_rows(DType t, Rows rows, int32_t *pos, void *dv, int dkv, hipStream_t s);
+// dv[row_j, :] = 0 for the rows of the list
+void launch_clear_rows(DType t, Rows rows, void *dv, int dkv, hipStream_t s);
 
 }  // namespace dy

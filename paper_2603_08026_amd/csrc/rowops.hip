@@ -140,15 +140,16 @@ __global__ __launch_bounds__(RB) void k_qkv_finalize(const float *__restrict__ p
                                                       T *__restrict__ kc, T *__restrict__ vc,
                                                       T *__restrict__ dv_out, int q_by_token,
                                                       T *__restrict__ ksal_out, int dv_by_entry,
-                                                      int32_t *__restrict__ entry_of) {
+                                                      int32_t *__restrict__ entry_of, int entry_lo) {
   const int n = row_count(rows);
   const int half = dh / 2, dq = H * dh, dkv = Hkv * dh, ld = dq + 2 * dkv;
   const int per_head = half / 4;  // items of 4 pairs per head
   const int qk_items = (H + Hkv) * per_head, v_items = dkv / 4;
   for (int j = blockIdx.x; j < n; j += gridDim.x) {
     const int r = rows.idx ? rows.idx[j] : j;
-    if (entry_of && threadIdx.x == 0) entry_of[r] = j + 1;  // token -> its list entry (0 = not in the list)
     const int pos = r % L;
+    // token -> its list entry (0 = not in the list), for the tokens at positions >= entry_lo only
+    if (entry_of && threadIdx.x == 0 && pos >= entry_lo) entry_of[r] = j + 1;
     const float *src = part + (size_t)j * ld;
     const float *t = tab + (size_t)pos * half * 2;
     for (int it = threadIdx.x; it < qk_items + v_items; it += RB) {
@@ -313,18 +314,18 @@ void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_st
                          const float *rope_tab, Rows rows, int L, int H, int Hkv, int dh,
                          const void *bq, const void *bk, const void *bv, void *q_out, void *k_cache,
                          void *v_cache, void *dv_out, int q_by_token, void *ksal_out, int dv_by_entry,
-                         int32_t *entry_of, hipStream_t s) {
+                         int32_t *entry_of, int entry_lo, hipStream_t s) {
   if (rows.cap <= 0) return;
   if (t == F32)
     k_qkv_finalize<float><<<row_grid(rows.cap), RB, 0, s>>>(
         part, splits, split_stride, rope_tab, rows, L, H, Hkv, dh, (const float *)bq, (const float *)bk,
         (const float *)bv, (float *)q_out, (float *)k_cache, (float *)v_cache, (float *)dv_out, q_by_token,
-        (float *)ksal_out, dv_by_entry, entry_of);
+        (float *)ksal_out, dv_by_entry, entry_of, entry_lo);
   else
     k_qkv_finalize<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>(
         part, splits, split_stride, rope_tab, rows, L, H, Hkv, dh, (const bf16_t *)bq, (const bf16_t *)bk,
         (const bf16_t *)bv, (bf16_t *)q_out, (bf16_t *)k_cache, (bf16_t *)v_cache, (bf16_t *)dv_out, q_by_token,
-        (bf16_t *)ksal_out, dv_by_entry, entry_of);
+        (bf16_t *)ksal_out, dv_by_entry, entry_of, entry_lo);
 }
 
 inline int sal_grid(int cap) { return cap < 1 ? 1 : (cap > 65536 ? 65536 : cap); }
@@ -347,7 +348,7 @@ void launch_compact(const uint8_t *flag, Rows rows, int B, int L, int32_t *out_i
 
 // ---- approximate context update of the non-salient rows  [Sec. 3.3; Alg. 3 lines C <- ..., cosine] --
 template <typename T>
-__global__ __launch_bounds__(256) void k_clear_rows(Rows rows, int32_t *pos, T *dv, int dkv) {
+__global__ __launch_bounds__(256) void k_clear_rows(Rows rows, T *dv, int dkv) {
   const int n = row_count(rows);
   constexpr int N = Vec16<T>::N;
   Vec16<T> zero;
@@ -355,9 +356,7 @@ __global__ __launch_bounds__(256) void k_clear_rows(Rows rows, int32_t *pos, T *
   for (int e = 0; e < N; ++e) zero.set(e, 0.f);
   for (int j = blockIdx.x; j < n; j += gridDim.x) {
     const int r = rows.idx ? rows.idx[j] : j;
-    if (threadIdx.x == 0) pos[r] = 0;
-    if (dv)
-      for (int v = threadIdx.x; v < dkv / N; v += 256) st16(dv + (size_t)r * dkv + v * N, zero);
+    for (int v = threadIdx.x; v < dkv / N; v += 256) st16(dv + (size_t)r * dkv + v * N, zero);
   }
 }
 
@@ -378,7 +377,7 @@ struct CachedNorm {
 template <typename T, bool CACHED>
 __global__ __launch_bounds__(SAL_NT) void k_saliency_approx(Rows win, int D, const T *__restrict__ c_sal,
                                                              const T *__restrict__ dc,
-                                                             const int32_t *__restrict__ pos, T *c_cache,
+                                                             int32_t *__restrict__ pos, T *c_cache,
                                                              float tau, float *__restrict__ cos_out,
                                                              uint8_t *__restrict__ flag_out, CachedNorm cn) {
   __shared__ float red[3 * SAL_NT / WAVE];
@@ -439,6 +438,9 @@ __global__ __launch_bounds__(SAL_NT) void k_saliency_approx(Rows win, int D, con
       const float s = dot / (fmaxf(sqrtf(na), 1e-8f) * fmaxf(sqrtf(nb), 1e-8f));
       if (cos_out) cos_out[r] = s;
       flag_out[j] = (s < tau) ? 1 : 0;
+      // The map goes back to zero as it is consumed: every marked token is a token of the step, this
+      // workgroup alone reads its entry, and all its threads did so before the barriers of the sum.
+      if (p) pos[r] = 0;
     }
   }
 }
@@ -461,7 +463,7 @@ __global__ __launch_bounds__(256) void k_mark_flags(Rows rows, int T, int L, int
   }
 }
 
-void launch_saliency_approx(DType t, Rows win, int D, const void *c_sal, const void *dc, const int32_t *pos,
+void launch_saliency_approx(DType t, Rows win, int D, const void *c_sal, const void *dc, int32_t *pos,
                             void *c_cache, float tau, float *cos_out, uint8_t *flag_out,
                             const AttnArgs *cached, const float *lse, int L, hipStream_t s) {
   if (win.cap <= 0) return;
@@ -493,10 +495,10 @@ void launch_mark_flags(Rows rows, int T, int L, int lo, uint8_t *flag, hipStream
   k_mark_flags<<<(rows.cap + 255) / 256, 256, 0, s>>>(rows, T, L, lo, flag);
 }
 
-void launch_clear_rows(DType t, Rows rows, int32_t *pos, void *dv, int dkv, hipStream_t s) {
+void launch_clear_rows(DType t, Rows rows, void *dv, int dkv, hipStream_t s) {
   if (rows.cap <= 0) return;
-  if (t == F32) k_clear_rows<float><<<row_grid(rows.cap), 256, 0, s>>>(rows, pos, (float *)dv, dkv);
-  else k_clear_rows<bf16_t><<<row_grid(rows.cap), 256, 0, s>>>(rows, pos, (bf16_t *)dv, dkv);
+  if (t == F32) k_clear_rows<float><<<row_grid(rows.cap), 256, 0, s>>>(rows, (float *)dv, dkv);
+  else k_clear_rows<bf16_t><<<row_grid(rows.cap), 256, 0, s>>>(rows, (bf16_t *)dv, dkv);
 }
 
 // Row-major [n_out, n_in] matrix of 2-byte elements -> the panel layout the bf16 GEMMs read
