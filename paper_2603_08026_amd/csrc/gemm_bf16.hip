@@ -45,16 +45,16 @@ int cu_count() {
 
 // Rounds of the chip (one workgroup per CU at a time) that `cap` rows in 256-row tiles take with
 // ncol column tiles and sk K-splits.  The tiles of a last row tile with fewer than 256 rows cost a
-// fraction f of a full tile (their weight copies at least, plus the products of the busiest wave's
-// 32-row blocks); they run at the end of every XCD's schedule and first fill the slots the last
-// round of full tiles leaves idle.
+// fraction f of a full tile (they still walk all of K with their weight copies: measured at 0.55-0.6 of
+// a full tile for a few rows; more with the products of the busiest wave's 32-row blocks); they run
+// at the end of every XCD's schedule and first fill the slots the last round of full tiles leaves idle.
 double tile_rounds(int cap, long ncol, int sk) {
   const long cu = cu_count(), rows_full = cap / 256;
   const int tail = cap % 256;
   const long full_tiles = rows_full * ncol * sk;
   const long full_rounds = (full_tiles + cu - 1) / cu;
   if (!tail) return (double)full_rounds;
-  const double f = std::max(0.2, (double)((tail + 31) / 32) / 8.0);
+  const double f = std::max(0.55, (double)((tail + 31) / 32) / 8.0);
   const long slack = full_rounds * cu - full_tiles;
   long rest = ncol * sk - slack * (long)(1.0 / f);
   if (rest < 0) rest = 0;
