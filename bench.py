@@ -143,8 +143,8 @@ def main():
                     help="skip the graph-replay, approximate-step and stand-alone-kernel legs (profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.stderr.write("bench.py: this build runs on exactly one GPU (the path shards along the batch with no "
-                         "exchange; see DESIGN.md); --gpus %d is not supported\n" % args.gpus)
+        sys.stderr.write("bench.py: this build runs on exactly one GPU (sequences are independent, so the path "
+                         "would shard along the batch with no exchange); --gpus %d is not supported\n" % args.gpus)
         sys.exit(2)
 
     import numpy as np
