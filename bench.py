@@ -7,7 +7,13 @@ over one batch of synthetic input that is already resident in HBM; for the 32-la
 (c5) a step is one dyllm_stack_step, i.e. 32 such layer steps chained through the output caches and
 the salient sets.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2|c3|c4|c5] [--frac 0.10]
+The headline workload is c3 at a salient fraction of 10 % (LLaDA-8B-shaped layer, 16 sequences of
+1280 tokens: the regime where the gathered GEMMs are bound by the matrix pipes); the same line
+carries a "sweep" over the other 8B-shaped configurations (c2, c3 at 5 % and 25 %, c4, c5).  The
+dense step is timed twice, as the library's own dyllm_full_step and as a plain torch layer
+(library GEMMs + SDPA, harness only), and the speed-up is quoted against the faster of the two.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2|c3|c4|c5] [--frac 0.10] [--no-sweep]
 """
 import argparse
 import json
@@ -126,12 +132,230 @@ def cpu_baseline(wl, budget_s=20.0):
     }
 
 
+def torch_dense_layer_ms(s, B, L, torch, iters=3, seed=5):
+    """A dense layer step of the same shape written with torch's library calls (F.linear, SDPA,
+    elementwise ops): the comparator the library's own dense step is checked against.  It is
+    harness code, outside the product path, and produces the same four outputs (K after rotation,
+    V, attention context, layer output).  Returns milliseconds per layer step."""
+    import torch.nn.functional as Fn
+    td = torch.float32 if s.dtype == "f32" else torch.bfloat16
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    d, dq, dkv, F, H, Hkv, dh = s.hidden, s.dq, s.dkv, s.ffn, s.n_heads, s.n_kv_heads, s.head_dim
+
+    def mat(n, k):
+        return (torch.randn(n, k, generator=g, device="cuda") * 0.02).to(td)
+
+    wqkv, wo, wgu, wd = mat(dq + 2 * dkv, d), mat(d, dq), mat(2 * F, d), mat(d, F)
+    ga = torch.ones(d, dtype=td, device="cuda")
+    gf = torch.ones(d, dtype=td, device="cuda")
+    x = torch.randn(B, L, d, generator=g, device="cuda").to(td)
+    half = dh // 2
+    ang = torch.arange(L, device="cuda", dtype=torch.float32)[:, None] * \
+        (s.rope_theta ** (-2.0 * torch.arange(half, device="cuda", dtype=torch.float32) / dh))[None, :]
+    cs, sn = ang.cos().to(td)[None, :, None, :], ang.sin().to(td)[None, :, None, :]
+
+    def rot(t):  # [B, L, heads, dh], half-split pairing
+        a, b = t[..., :half], t[..., half:]
+        return torch.cat([a * cs - b * sn, a * sn + b * cs], dim=-1)
+
+    def layer():
+        n = Fn.rms_norm(x, (d,), ga, s.rms_eps)
+        qkv = Fn.linear(n, wqkv)
+        q = rot(qkv[..., :dq].view(B, L, H, dh))
+        k = rot(qkv[..., dq:dq + dkv].view(B, L, Hkv, dh))
+        v = qkv[..., dq + dkv:].view(B, L, Hkv, dh)
+        c = Fn.scaled_dot_product_attention(q.transpose(1, 2), k.transpose(1, 2), v.transpose(1, 2),
+                                            enable_gqa=(H != Hkv)).transpose(1, 2).reshape(B, L, dq)
+        h = x + Fn.linear(c, wo)
+        f = Fn.rms_norm(h, (d,), gf, s.rms_eps)
+        gu = Fn.linear(f, wgu)
+        y = h + Fn.linear(Fn.silu(gu[..., :F]) * gu[..., F:], wd)
+        return k, v, c, y
+
+    with torch.no_grad():
+        layer()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            layer()
+        torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / iters * 1e3
+
+
+def roofline_of(stage_ms, work, dtype):
+    """The stage with the largest time against the roof that bounds it."""
+    dom = max((n for n in stage_ms if n != "marker_overhead"), key=lambda n: stage_ms[n])
+    fl, by = work[dom]
+    ms = stage_ms[dom]
+    is_gemm_or_attn = dom.startswith("gemm") or dom == "partial_attention"
+    if dtype == "bf16" and is_gemm_or_attn and fl / by >= RIDGE:
+        roof = {"bound": "mfma", "achieved": fl / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    elif dtype == "f32" and is_gemm_or_attn and fl / by >= FP32_VALU_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS:
+        roof = {"bound": "alu", "achieved": fl / (ms * 1e-3) / 1e12, "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "hbm", "achieved": by / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["kernel"] = dom
+    roof["launch_ms"] = ms
+    return roof
+
+
+class Bench:
+    """One workload on the device: layers (or the stack), its inputs, and the timed legs."""
+
+    def __init__(self, wl, variant, torch, np, host_inputs, n_sparse):
+        from paper_2603_08026_amd.layer import Layer, Stack
+        from synth import workload as W
+        self.wl, self.torch, self.np, self.variant = wl, torch, np, variant
+        s = wl.shape
+        self.NL = NL = wl.n_layers
+        td = torch.float32 if s.dtype == "f32" else torch.bfloat16
+        if NL == 1 and host_inputs:
+            lay = Layer.from_shape(s, wl.batch, wl.seq)
+            lay.set_weights(W.make_weights(s))
+            self.layers = [lay]
+        else:
+            # weights drawn on the device (same distribution as the host generator: N(0, 0.02^2)
+            # matrices, gains 1 + 0.1 N(0,1)); a stack's 14 GB would take minutes on the host
+            lay = Stack(s, NL, wl.batch, wl.seq) if NL > 1 else Layer.from_shape(s, wl.batch, wl.seq)
+            self.layers = lay.layers if NL > 1 else [lay]
+            shapes = {"wq": (s.dq, s.hidden), "wk": (s.dkv, s.hidden), "wv": (s.dkv, s.hidden),
+                      "wo": (s.hidden, s.dq), "w_gate": (s.ffn, s.hidden), "w_up": (s.ffn, s.hidden),
+                      "w_down": (s.hidden, s.ffn)}
+            for l, one in enumerate(self.layers):
+                g = torch.Generator(device="cuda")
+                g.manual_seed(W.SEED_W + l)
+                wt = {n: (torch.randn(*sh, generator=g, device="cuda") * 0.02).to(td) for n, sh in shapes.items()}
+                for n in ("g_attn", "g_ffn"):
+                    wt[n] = (1 + 0.1 * torch.randn(s.hidden, generator=g, device="cuda")).to(td)
+                one.set_device_weights(wt)
+        self.lay, self.last = lay, self.layers[-1]
+        if NL == 1:
+            self.full = lay.full_step
+            self.sparse = lambda xd, il: lay.layer_step(xd, il, wl.tau, want_cos=False)
+        else:
+            self.full = lay.full_step
+            self.sparse = lambda xd, il: lay.stack_step(xd, il, wl.tau, want_cos=False)
+        self.dense_x, self.steps = [], []
+        all_idx = np.arange(wl.tokens, dtype=np.int32)
+        all_off = np.arange(wl.batch + 1, dtype=np.int32) * wl.seq
+        if host_inputs:
+            # the seeded host generator the parity tests use
+            for st in W.step_stream(wl, wl.t_full + n_sparse):
+                xd = lay.upload(st.x)
+                if st.dense:
+                    self.dense_x.append(xd)
+                elif variant == "salient-ablation":
+                    self.steps.append((xd, lay.make_list(all_idx, all_off), wl.tokens))
+                else:
+                    self.steps.append((xd, lay.make_list(st.idx, st.offsets), int(st.idx.size)))
+        else:
+            # same candidate lists as the host generator (W.step_rows), hidden states drawn on the
+            # device: N(0,1) start, candidates redrawn N(0,1) per step.  (A sparse step reads only
+            # the candidates' rows of x, so the tiny drift of the other rows is left out here.)
+            g = torch.Generator(device="cuda")
+            g.manual_seed(W.SEED_X)
+            x = torch.randn(wl.batch, wl.seq, s.hidden, generator=g, device="cuda").to(td)
+            self.dense_x.append(x)
+            for t in range(1, n_sparse + 1):
+                idx, off = W.step_rows(wl, t)
+                x = x.clone()
+                sel = torch.from_numpy(idx.astype(np.int64)).cuda()
+                x.view(wl.tokens, -1)[sel] = torch.randn(idx.size, s.hidden, generator=g, device="cuda").to(td)
+                self.steps.append((x, lay.make_list(idx, off), int(idx.size)))
+
+    def warm_caches(self):
+        for xd in self.dense_x:  # dense warm-up steps (Sec. 3.2)
+            self.full(xd)
+        self.torch.cuda.synchronize()
+
+    def run(self, range_):
+        for i in range_:
+            xd, il, _ = self.steps[i]
+            self.sparse(xd, il)
+
+    def snapshot(self):
+        return [{k: getattr(one, k).clone() for k in ("k", "v", "c", "out")} for one in self.layers]
+
+    def restore(self, snap):
+        for one, sn in zip(self.layers, snap):
+            for k_, v_ in sn.items():
+                getattr(one, k_).copy_(v_)
+        self.torch.cuda.synchronize()
+
+    def time_sparse(self, Wu, K):
+        torch = self.torch
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        self.run(range(Wu, Wu + K))
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / K
+
+    def time_stages(self, Wu, K):
+        """The same K steps with one HIP event after every stage, recorded on the launch stream."""
+        self.lay.ctx.profile_begin(K * self.NL)
+        t0 = time.perf_counter()
+        self.run(range(Wu, Wu + K))
+        self.torch.cuda.synchronize()
+        t = (time.perf_counter() - t0) / K
+        stage_ms, calls = self.lay.ctx.profile_end()
+        # every stage time runs from one stream event to the next; the cost of the event itself is
+        # measured by the stage that has no kernel and taken off the others
+        ev = stage_ms.get("marker_overhead", 0.0)
+        stage_ms = {n: (max(ms - ev, 1e-6) if n != "marker_overhead" else ms) for n, ms in stage_ms.items()}
+        return t, stage_ms, calls
+
+    def time_dense(self, iters):
+        torch = self.torch
+        xd = self.dense_x[-1]
+        self.full(xd)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            self.full(xd)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / iters
+
+    def close(self):
+        self.lay.close()
+
+
+def sweep_entry(wl, torch, np, K, Wu, dense_iters):
+    """One line of the sweep: sparse step, both dense steps, dominant stage and its roofline fraction."""
+    s = wl.shape
+    esz = 4 if s.dtype == "f32" else 2
+    b = Bench(wl, "sparse", torch, np, host_inputs=False, n_sparse=Wu + K)
+    b.warm_caches()
+    b.run(range(Wu))
+    snap = b.snapshot() if wl.n_layers == 1 else None
+    t_step = b.time_sparse(Wu, K)
+    if snap is not None:
+        b.restore(snap)
+    _, stage_ms, _ = b.time_stages(Wu, K)
+    t_dense = b.time_dense(dense_iters)
+    m_in = float(np.mean([m for _, _, m in b.steps[Wu:Wu + K]]))
+    b.close()
+    del b, snap
+    torch.cuda.empty_cache()
+    t_torch = torch_dense_layer_ms(s, wl.batch, wl.seq, torch, iters=dense_iters) * wl.n_layers * 1e-3
+    roof = roofline_of(stage_ms, stage_work(s, wl.batch, wl.seq, m_in, m_in, esz), s.dtype)
+    torch.cuda.empty_cache()
+    return {"workload": wl.name, "frac": wl.frac, "layers": wl.n_layers, "salient_rows_mean": m_in,
+            "ms_per_step": t_step * 1e3, "tokens_per_s": wl.tokens * wl.n_layers / t_step,
+            "dense_ms": t_dense * 1e3, "dense_torch_ms": t_torch * 1e3,
+            "speedup": min(t_dense, t_torch) / t_step,
+            "dominant": roof["kernel"], "bound": roof["bound"], "achieved": round(roof["achieved"], 1),
+            "unit": roof["unit"], "frac_of_peak": round(roof["frac"], 4),
+            "stage_ms": {n: round(ms, 5) for n, ms in stage_ms.items()}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None, help="timed steps (default 40; 6 for c5)")
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default 20; 6 for c5)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default 5; 2 for c5)")
-    ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "c6"])
+    ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c4", "c5", "c6"])
     ap.add_argument("--layers", type=int, default=None, help="stack depth override for c5")
     ap.add_argument("--frac", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -141,6 +365,10 @@ def main():
                          "over all rows), out-projection and FFN for the selected ones only (Table 1, 'Salient')")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the graph-replay, approximate-step and stand-alone-kernel legs (profiling runs)")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the sweep over the other configurations")
+    ap.add_argument("--device-inputs", action="store_true",
+                    help="draw weights and hidden states on the device (as the sweep entries do) instead of "
+                         "taking them from the seeded host generator")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on exactly one GPU (sequences are independent, so the path "
@@ -150,7 +378,7 @@ def main():
     import numpy as np
     import torch
     from dataclasses import replace
-    from paper_2603_08026_amd.layer import Layer, Stack
+    from paper_2603_08026_amd.layer import Layer
     from synth import workload as W
 
     if not torch.cuda.is_available():
@@ -165,7 +393,7 @@ def main():
     s = wl.shape
     esz = 4 if s.dtype == "f32" else 2
     NL = wl.n_layers
-    K = args.steps if args.steps is not None else (40 if NL == 1 else 6)
+    K = args.steps if args.steps is not None else (20 if NL == 1 else 6)
     Wu = args.warmup if args.warmup is not None else (5 if NL == 1 else 2)
 
     # traffic calibration dispatch: one plain device copy of a known size, larger than every cache
@@ -176,82 +404,30 @@ def main():
     torch.cuda.synchronize()
     del calib_src, calib_dst
 
-    if NL == 1:
-        lay = Layer.from_shape(s, wl.batch, wl.seq)
-        lay.set_weights(W.make_weights(s))
-        layers, last = [lay], lay
-        full, sparse = lay.full_step, (lambda xd, il: lay.layer_step(xd, il, wl.tau, want_cos=False))
-    else:
-        # the stack's 14 GB of weights are drawn on the device (same distribution as the host
-        # generator of the single-layer configurations: N(0, 0.02^2) matrices, gains 1 + 0.1 N(0,1))
-        lay = Stack(s, NL, wl.batch, wl.seq)
-        td = torch.float32 if s.dtype == "f32" else torch.bfloat16
-        shapes = {"wq": (s.dq, s.hidden), "wk": (s.dkv, s.hidden), "wv": (s.dkv, s.hidden),
-                  "wo": (s.hidden, s.dq), "w_gate": (s.ffn, s.hidden), "w_up": (s.ffn, s.hidden),
-                  "w_down": (s.hidden, s.ffn)}
-        for l, one in enumerate(lay.layers):
-            g = torch.Generator(device="cuda")
-            g.manual_seed(W.SEED_W + l)
-            wt = {n: (torch.randn(*sh, generator=g, device="cuda") * 0.02).to(td) for n, sh in shapes.items()}
-            for n in ("g_attn", "g_ffn"):
-                wt[n] = (1 + 0.1 * torch.randn(s.hidden, generator=g, device="cuda")).to(td)
-            one.set_device_weights(wt)
-        layers, last = lay.layers, lay.layers[-1]
-        full, sparse = lay.full_step, (lambda xd, il: lay.stack_step(xd, il, wl.tau, want_cos=False))
-    dense_x, steps = [], []
-    for st in W.step_stream(wl, wl.t_full + Wu + K):
-        xd = lay.upload(st.x)
-        if st.dense:
-            dense_x.append(xd)
-        elif args.variant == "salient-ablation":
-            all_idx = np.arange(wl.tokens, dtype=np.int32)
-            steps.append((xd, lay.make_list(all_idx, np.arange(wl.batch + 1, dtype=np.int32) * wl.seq), wl.tokens))
-        else:
-            steps.append((xd, lay.make_list(st.idx, st.offsets), int(st.idx.size)))
-    # cache warm-up: T_full dense steps (Sec. 3.2)
-    for xd in dense_x:
-        full(xd)
+    host_inputs = (NL == 1) and not args.device_inputs
+    bn = Bench(wl, args.variant, torch, np, host_inputs, Wu + K)
+    lay, layers, last, steps, sparse, dense_x = bn.lay, bn.layers, bn.last, bn.steps, bn.sparse, bn.dense_x
+    bn.warm_caches()
+    bn.run(range(Wu))
     torch.cuda.synchronize()
-
-    def run(range_):
-        for i in range_:
-            xd, il, _ = steps[i]
-            sparse(xd, il)
-
-    run(range(Wu))
-    torch.cuda.synchronize()
-    snap = [{k: getattr(one, k).clone() for k in ("k", "v", "c", "out")} for one in layers]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run(range(Wu, Wu + K))
-    torch.cuda.synchronize()
-    t_step = (time.perf_counter() - t0) / K
+    snap = bn.snapshot()
+    t_step = bn.time_sparse(Wu, K)
     m_out_last = int(last.idx_out.offsets[-1].item())
 
     # the same K steps again, from the same cache state, with one HIP event after every stage
-    # (recorded on the stream of the launches)
-    for one, sn in zip(layers, snap):
-        for k_, v_ in sn.items():
-            getattr(one, k_).copy_(v_)
-    torch.cuda.synchronize()
-    lay.ctx.profile_begin(K * NL)
-    t0 = time.perf_counter()
-    run(range(Wu, Wu + K))
-    torch.cuda.synchronize()
-    t_step_instr = (time.perf_counter() - t0) / K
-    stage_ms, calls = lay.ctx.profile_end()
+    bn.restore(snap)
+    t_step_instr, stage_ms, calls = bn.time_stages(Wu, K)
 
     # The same K steps from a HIP graph: one sparse step is captured once on persistent input buffers
-    # (the step path only enqueues kernels, so a caller may capture it) and replayed K times; before
-    # every replay the step's candidate list and the candidates' input rows -- all that a sparse step
-    # reads of x -- are copied into those buffers, inside the timed region.
+    # (the step path only enqueues kernels, so a caller may capture it) and replayed K times.  Two
+    # timings: the replays alone (inputs of the first timed step stay in the buffers), and replays
+    # with the step's candidate list and the candidates' input rows -- all that a sparse step reads of
+    # x -- copied into those buffers before each one.
     graph_info = None
     try:
         if args.no_extras:
             raise RuntimeError("skipped (--no-extras)")
-        for one, sn in zip(layers, snap):
-            for k_, v_ in sn.items():
-                getattr(one, k_).copy_(v_)
+        bn.restore(snap)
         T_, cap = wl.tokens, max(m for _, _, m in steps[Wu:Wu + K])
         feeds = []
         for i in range(Wu, Wu + K):
@@ -260,6 +436,8 @@ def main():
             feeds.append((sel, xd_i.view(T_, -1)[sel].clone(), il_i.idx[:m_i], il_i.offsets))
         xg = steps[Wu][0].clone()
         ilg = lay.make_list(np.zeros(0, np.int32), np.zeros(wl.batch + 1, np.int32), cap=cap)
+        ilg.idx[:feeds[0][2].numel()].copy_(feeds[0][2])
+        ilg.offsets.copy_(feeds[0][3])
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
@@ -270,6 +448,13 @@ def main():
         with torch.cuda.graph(graph, stream=side):
             sparse(xg, ilg)
         torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            graph.replay()
+        torch.cuda.synchronize()
+        t_replay_only = (time.perf_counter() - t0) / K
         t0 = time.perf_counter()
         for sel, rows_i, idx_i, off_i in feeds:
             xg.view(T_, -1).index_copy_(0, sel, rows_i)
@@ -278,6 +463,7 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         graph_info = {"ms_per_step": (time.perf_counter() - t0) / K * 1e3, "replays": K,
+                      "ms_per_replay_alone": t_replay_only * 1e3,
                       "salient_rows_out_last": int(last.idx_out.offsets[-1].item())}
         del graph, feeds, xg
     except Exception as e:  # reported, never hidden: the figure is an extra, not the metric
@@ -352,46 +538,36 @@ def main():
         del lay2
     del snap
 
-    # dense step of the same shape on the same GPU
-    xd = dense_x[-1] if dense_x else steps[0][0]
-    full(xd)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.dense_iters):
-        full(xd)
-    torch.cuda.synchronize()
-    t_dense = (time.perf_counter() - t0) / args.dense_iters
+    # dense step of the same shape on the same GPU: the library's own, and the torch comparator
+    t_dense = bn.time_dense(args.dense_iters)
+    try:
+        t_dense_torch = torch_dense_layer_ms(s, wl.batch, wl.seq, torch, iters=args.dense_iters) * NL * 1e-3
+        torch.cuda.empty_cache()
+    except Exception as e:
+        sys.stderr.write("bench.py: torch dense comparator failed: %r\n" % (e,))
+        t_dense_torch = None
+    t_dense_best = t_dense if t_dense_torch is None else min(t_dense, t_dense_torch)
 
     m_in = float(np.mean([m for _, _, m in steps[Wu:Wu + K]]))
     # (sparse variant: every candidate passes the test on this workload; ablation: the last step's count)
     work = stage_work(s, wl.batch, wl.seq, m_in, m_in if args.variant == "sparse" else float(m_out_last), esz)
-    # every stage time runs from one stream event to the next; the cost of the event itself is
-    # measured by the stage that has no kernel and taken off the others
-    ev = stage_ms.get("marker_overhead", 0.0)
-    stage_ms = {n: (max(ms - ev, 1e-6) if n != "marker_overhead" else ms) for n, ms in stage_ms.items()}
     stages = {}
     for name, ms in stage_ms.items():
         fl, by = work[name]
         stages[name] = {"ms": round(ms, 5), "gbps": round(by / (ms * 1e-3) / 1e9, 1) if by else None,
                         "tflops": round(fl / (ms * 1e-3) / 1e12, 2) if fl else None}
-    dom = max((n for n in stage_ms if n != "marker_overhead"), key=lambda n: stage_ms[n])
-    fl, by = work[dom]
-    ms = stage_ms[dom]
-    is_gemm_or_attn = dom.startswith("gemm") or dom == "partial_attention"
-    if s.dtype == "bf16" and is_gemm_or_attn and fl / by >= RIDGE:
-        roof = {"bound": "mfma", "achieved": fl / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
-    elif s.dtype == "f32" and is_gemm_or_attn and fl / by >= FP32_VALU_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS:
-        roof = {"bound": "alu", "achieved": fl / (ms * 1e-3) / 1e12, "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s"}
-    else:
-        roof = {"bound": "hbm", "achieved": by / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["kernel"] = dom
-    roof["launch_ms"] = ms
+    roof = roofline_of(stage_ms, work, s.dtype)
+    dom = roof["kernel"]
+    # HBM bytes of the dominant stage's kernels: from a separate counter run of this command (two
+    # rocprofv3 --pmc passes), kept as a file; it is NOT measured in this run
     roof["traffic"] = None
-    tr = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.config)
+    tag = args.config + ("" if args.frac is None else "_%g" % args.frac)
+    tr = os.path.join(ROOT, "profiles", "traffic_%s.json" % tag)
     if os.path.exists(tr):
         try:
             roof["traffic"] = json.load(open(tr)).get(dom)
+            roof["traffic_source"] = "static: profiles/traffic_%s.json (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE " \
+                                     "runs of this command, not measured in this run)" % tag
         except Exception:
             roof["traffic"] = None
 
@@ -405,17 +581,20 @@ def main():
                    "salient_rows_mean": m_in, "salient_rows_out_last": m_out_last, "tau": wl.tau,
                    "hidden": s.hidden, "n_heads": s.n_heads, "n_kv_heads": s.n_kv_heads, "ffn": s.ffn,
                    "layers": NL},
-        "dense_ms_per_step": t_dense * 1e3, "speedup_vs_dense": t_dense / t_step,
+        "dense_ms_per_step": t_dense * 1e3,
+        "dense_torch_ms_per_step": None if t_dense_torch is None else t_dense_torch * 1e3,
+        # against the faster of the two dense steps
+        "speedup_vs_dense": t_dense_best / t_step,
+        "speedup_vs_own_dense": t_dense / t_step,
+        "speedup_vs_torch_dense": None if t_dense_torch is None else t_dense_torch / t_step,
         "salient_rows_per_s": m_in / t_step,
         "ms_per_step_with_stage_events": t_step_instr * 1e3, "stage_calls": calls, "stages": stages,
         "roofline": roof,
     }
     out["graph_replay"] = graph_info
     if approx is not None:
-        approx["speedup_vs_dense"] = t_dense * 1e3 / approx["ms_per_step"]
+        approx["speedup_vs_dense"] = t_dense_best * 1e3 / approx["ms_per_step"]
         out["approx_step"] = approx
-    if not args.no_extras:
-        out["standalone"] = standalone_kernels(s, torch)
     if NL > 1:
         # stack only: generated tokens per second of the paper's kind over the layer stack alone
         # (no embedding, logits or sampling): B * L_R over T_full dense and the remaining sparse steps
@@ -424,9 +603,29 @@ def main():
         out["stack_generated_tokens_per_s"] = wl.batch * wl.resp_len / total
         out["stack_generated_tokens_per_s_dense_only"] = wl.batch * wl.resp_len / (wl.steps * t_dense)
         out["data"] = "synthetic (weights drawn on the device)"
+    elif not host_inputs:
+        out["data"] = "synthetic (weights and hidden states drawn on the device)"
+    bn.close()
+    del bn, lay, layers, last, steps, sparse, dense_x
+    torch.cuda.empty_cache()
+    if not args.no_extras:
+        out["standalone"] = standalone_kernels(s, torch)
+        torch.cuda.empty_cache()
+    if not args.no_sweep:
+        # the other 8B-shaped configurations, with fewer steps each; inputs drawn on the device
+        sweep = []
+        for name, frac in (("c2", None), ("c3", 0.05), ("c3", 0.10), ("c3", 0.25), ("c4", None), ("c5", None)):
+            w2 = W.CONFIGS[name] if frac is None else W.with_frac(W.CONFIGS[name], frac)
+            deep = w2.n_layers > 1
+            try:
+                sweep.append(sweep_entry(w2, torch, np, K=(min(K, 4) if deep else min(K, 10)),
+                                         Wu=(1 if deep else 2), dense_iters=(1 if deep else 2)))
+            except Exception as e:
+                sweep.append({"workload": w2.name, "frac": w2.frac, "error": repr(e)})
+            torch.cuda.empty_cache()
+        out["sweep"] = sweep
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
-    lay.close()
     print(json.dumps(out), flush=True)
 
 

@@ -246,12 +246,14 @@ def test_weights_between_poisoned_guard_bands(dtype, dh):
     lay.close()
 
 
-@pytest.mark.parametrize("name,seqs", [("c3", (5, 15)), ("c4", (0, 9))])
-def test_full_batch_at_bench_size_on_sampled_sequences(name, seqs):
-    """The launch configuration bench.py times (all 16 sequences, about 2000 salient rows: the
-    256-row GEMM tiles with gathered rows, unsplit attention) checked on sampled sequences:
-    sequences are independent, so the oracle runs the same two steps on each sampled one alone."""
-    wl = replace(W.CONFIGS[name], t_full=1)
+@pytest.mark.parametrize("name,frac,seqs", [("c3", 0.10, (5, 15)), ("c4", 0.10, (0, 9)),
+                                            ("c3", 0.05, (7,)), ("c3", 0.25, (2,))])
+def test_full_batch_at_bench_size_on_sampled_sequences(name, frac, seqs):
+    """The launch configurations bench.py times (all 16 sequences; about 1000, 2000 and 5000 salient
+    rows at the three salient fractions of the sweep, which take different GEMM tile plans and
+    attention splits) checked on sampled sequences: sequences are independent, so the oracle runs
+    the same two steps on each sampled one alone."""
+    wl = replace(W.with_frac(W.CONFIGS[name], frac), t_full=1)
     s = wl.shape
     cfg = oracle_cfg(s)
     w = W.make_weights(s)

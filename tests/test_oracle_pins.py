@@ -675,6 +675,64 @@ def test_response_only_step_of_the_approximate_path():
         O.layer_step_approx(x1, np.array([1, 5]), w, cfg, _copy(caches), 0.9, row_lo=lo)
 
 
+@pytest.mark.parametrize("row_lo", [0, 4])
+@pytest.mark.parametrize("cached_norm", [False, True])
+def test_stack_step_approx_is_the_hand_composed_layer_loop(row_lo, cached_norm):
+    """The layer loop of the approximate path against layer_step_approx applied by hand, layer after
+    layer: layer l reads the output cache layer l-1 holds after its update and the list layer l-1
+    selected, with the same response window and normaliser choice in every layer.  [Alg. 3, loop over l]
+    A wrong hand-through of row_lo / cached_norm, a broken list chain or a layer reading the step's
+    input instead of the previous output cache each change a cache or a set here."""
+    r, cfg, ws, x0, caches = _stack_setup(n_layers=3, seed=47)
+    B, L, T = 2, 10, 20
+    if cached_norm:
+        for c in caches:
+            c["lse"] = np.zeros((B, L, cfg.n_heads))
+        O.stack_full_step(x0, ws, cfg, caches)  # fills the normalisers
+    idx = np.array([5, 8, 14, 19])
+    x1 = x0.copy()
+    x1.reshape(T, -1)[idx] += 0.3 * r.normal(size=(idx.size, 16))
+    x1.reshape(T, -1)[[1, 12]] += 3.0   # prompt rows move too: only a whole-sequence step may see them
+    tau = 0.99
+    loop = [_copy(c) for c in caches]
+    per_layer = O.stack_step_approx(x1, idx, ws, cfg, loop, tau, row_lo, cached_norm)
+    hand = [_copy(c) for c in caches]
+    h, cur = x1, idx
+    sets = []
+    for l, w in enumerate(ws):
+        cur, off, cos = O.layer_step_approx(h, cur, w, cfg, hand[l], tau, row_lo=row_lo, cached_norm=cached_norm)
+        assert np.array_equal(per_layer[l][0], cur) and np.array_equal(per_layer[l][1], off)
+        assert np.array_equal(per_layer[l][2], cos)
+        sets.append(cur)
+        h = hand[l]["out"]
+    for a, b_ in zip(loop, hand):
+        assert a.keys() == b_.keys()
+        for k in a:
+            assert np.array_equal(a[k], b_[k]), k
+    # the case is not degenerate: sets differ between layers, tokens outside the candidates get
+    # selected, and the switches matter (each alternative gives another result)
+    assert len({tuple(s_.tolist()) for s_ in sets}) > 1
+    assert any(set(s_.tolist()) - set(idx.tolist()) for s_ in sets)
+    pos = np.arange(T) % L
+    for l in range(3):
+        assert np.all(sets[l] % L >= row_lo)
+        for k in ("k", "v", "c", "out"):
+            assert np.array_equal(loop[l][k].reshape(T, -1)[pos < row_lo], caches[l][k].reshape(T, -1)[pos < row_lo])
+    other = [_copy(c) for c in caches]
+    alt = O.stack_step_approx(x1, idx, ws, cfg, other, tau, 4 - row_lo, cached_norm)
+    assert not all(np.array_equal(a["c"], b_["c"]) for a, b_ in zip(loop, other))
+    if "lse" in caches[0]:
+        other = [_copy(c) for c in caches]
+        O.stack_step_approx(x1, idx, ws, cfg, other, tau, row_lo, not cached_norm)
+        assert not all(np.allclose(a["c"], b_["c"], atol=1e-9) for a, b_ in zip(loop, other))
+    # a layer that read the step's input x instead of the output cache above it would differ
+    wrong = [_copy(c) for c in caches]
+    cur = idx
+    for l, w in enumerate(ws):
+        cur, _, _ = O.layer_step_approx(x1, cur, w, cfg, wrong[l], tau, row_lo=row_lo, cached_norm=cached_norm)
+    assert not np.allclose(wrong[1]["out"], loop[1]["out"], atol=1e-9)
+
+
 @pytest.mark.parametrize("approx", [False, True])
 def test_denoise_step_composes_the_schedule(approx):
     r, cfg, ws, x, caches = _stack_setup(n_layers=2, seed=45)
