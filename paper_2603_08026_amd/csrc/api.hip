@@ -22,7 +22,6 @@ struct dyllm_ctx {
   size_t ws_bytes;
   // carved buffers
   void *ns;        // [R, d]        normalised salient rows
-  float *qkv;      // [R, dq+2dkv]  fp32 projections before rotation
   void *qs;        // [R, dq]       rotated queries
   float *part_o;   // fp32 scratch shared by consecutive stages: raw GEMM results / attention partials
   float *part_ml;
@@ -39,6 +38,7 @@ struct dyllm_ctx {
   void *fs;        // [R, d]        RMSNorm(h)
   void *act;       // [R, F]        silu(gate)*up
   int32_t *status; // device status word
+  int32_t *scan;   // words of the chained compaction kernel; all zero between calls
   float *rope;     // [max_seq, dh/2, 2]
   // optional per-stage timing (dyllm_profile_begin / _end)
   std::vector<hipEvent_t> *prof_events;
@@ -50,7 +50,7 @@ struct dyllm_ctx {
 namespace {
 
 struct Layout {
-  size_t ns, qkv, qs, part_o, part_ml, cosb, flag, hs, fs, act, status, rope, dv_full, dc, csal, pos, win_idx, win_off, ksal, total;
+  size_t ns, qs, part_o, part_ml, cosb, flag, hs, fs, act, status, rope, dv_full, dc, csal, pos, win_idx, win_off, ksal, scan, total;
   size_t part_elems;
 };
 
@@ -64,7 +64,6 @@ Layout make_layout(const dyllm_layer_cfg &c) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   l.ns = take(R * d * e);
-  l.qkv = take(R * (dq + 2 * dkv) * 4);
   l.qs = take(R * dq * e);
   // fp32 scratch: 16 attention splits of up to 2048 rows, or one raw GEMM result of R rows
   const size_t prow = R < 2048 ? R : 2048;
@@ -86,6 +85,7 @@ Layout make_layout(const dyllm_layer_cfg &c) {
   l.win_idx = take(R * 4);
   l.win_off = take(((size_t)c.max_batch + 1) * 4);
   l.ksal = take(R * dkv * e);
+  l.scan = take((size_t)compact_scan_words() * 4);
   l.total = off;
   return l;
 }
@@ -373,7 +373,7 @@ int enqueue_approx_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
     launch_saliency_approx(dt(ctx), all, ctx->dq, ctx->csal, nullptr, ctx->pos, cache->c, tau, cos_out, ctx->flag,
                            &a, (const float *)cache->lse, L, s);
   }
-  launch_compact(ctx->flag, all, B, L, idx_out->idx, idx_out->offsets, idx_out->cap, ctx->status, s);
+  launch_compact(ctx->flag, all, B, L, idx_out->idx, idx_out->offsets, idx_out->cap, ctx->status, ctx->scan, s);
   if ((rc = check_launch(ctx, "approx: saliency / compact"))) return rc;
   return enqueue_ffn(ctx, w, x, cache->c, rows_of(idx_out, B), cache->out, s);
 }
@@ -385,7 +385,7 @@ int enqueue_merge(dyllm_ctx *ctx, const dyllm_index_list *a, const dyllm_index_l
   launch_fill_i32((int32_t *)ctx->flag, 0, (T + 3) / 4, s);
   if (a) launch_mark_flags(rows_of(a, B), T, L, pos_lo, ctx->flag, s);
   if (b) launch_mark_flags(rows_of(b, B), T, L, pos_lo, ctx->flag, s);
-  launch_compact(ctx->flag, Rows{nullptr, nullptr, T}, B, L, out->idx, out->offsets, out->cap, ctx->status, s);
+  launch_compact(ctx->flag, Rows{nullptr, nullptr, T}, B, L, out->idx, out->offsets, out->cap, ctx->status, ctx->scan, s);
   return check_launch(ctx, "list merge");
 }
 
@@ -462,7 +462,7 @@ int dyllm_create(const dyllm_layer_cfg *cfg, dyllm_ctx **out) {
     return DYLLM_ERR_NO_MEM;
   }
   char *b = ctx->ws;
-  ctx->ns = b + l.ns; ctx->qkv = (float *)(b + l.qkv); ctx->qs = b + l.qs;
+  ctx->ns = b + l.ns; ctx->qs = b + l.qs;
   ctx->part_o = (float *)(b + l.part_o); ctx->part_ml = (float *)(b + l.part_ml);
   ctx->part_elems = l.part_elems;
   ctx->cosb = (float *)(b + l.cosb); ctx->flag = (uint8_t *)(b + l.flag);
@@ -470,7 +470,7 @@ int dyllm_create(const dyllm_layer_cfg *cfg, dyllm_ctx **out) {
   ctx->status = (int32_t *)(b + l.status); ctx->rope = (float *)(b + l.rope);
   ctx->dv_full = b + l.dv_full; ctx->dc = b + l.dc; ctx->csal = b + l.csal; ctx->pos = (int32_t *)(b + l.pos);
   ctx->win_idx = (int32_t *)(b + l.win_idx); ctx->win_off = (int32_t *)(b + l.win_off);
-  ctx->ksal = b + l.ksal;
+  ctx->ksal = b + l.ksal; ctx->scan = (int32_t *)(b + l.scan);
 
   // rotary table in double precision on the host, cleared status word
   const int half = cfg->head_dim / 2;
@@ -485,6 +485,7 @@ int dyllm_create(const dyllm_layer_cfg *cfg, dyllm_ctx **out) {
   if (e == hipSuccess) e = hipMemset(ctx->status, 0, 256);
   if (e == hipSuccess) e = hipMemset(ctx->dv_full, 0, l.dc - l.dv_full);
   if (e == hipSuccess) e = hipMemset(ctx->pos, 0, l.win_idx - l.pos);
+  if (e == hipSuccess) e = hipMemset(ctx->scan, 0, (size_t)compact_scan_words() * 4);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     (void)hipFree(ctx->ws);
@@ -596,7 +597,7 @@ int dyllm_compact(dyllm_ctx *ctx, const uint8_t *flag, const dyllm_index_list *r
   } else {
     r = Rows{nullptr, nullptr, B * L};
   }
-  launch_compact(flag, r, B, L, out->idx, out->offsets, out->cap, ctx->status, (hipStream_t)stream);
+  launch_compact(flag, r, B, L, out->idx, out->offsets, out->cap, ctx->status, ctx->scan, (hipStream_t)stream);
   return check_launch(ctx, "compact");
 }
 

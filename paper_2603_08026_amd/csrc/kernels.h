@@ -45,9 +45,12 @@ void launch_down_finalize(DType t, const float *part, int splits, size_t split_s
 // cosine of c_new[j] vs c_cache[row_j], flag = cos < tau, optional commit of the new row.
 void launch_saliency(DType t, const void *c_new, void *c_cache, Rows rows, int D, float tau,
                      float *cos_out, uint8_t *flag_out, int commit, hipStream_t s);
-// stable compaction (single workgroup); out_offsets[b] = #selected tokens with id < b*L.
+// stable compaction over up to 1024 chained workgroups; out_offsets[b] = #selected tokens with id < b*L.
+// scan: compact_scan_words() device ints, all zero before the launch; the kernel leaves them zero.
+// Launches that share `scan` must not overlap.
 void launch_compact(const uint8_t *flag, Rows rows, int B, int L, int32_t *out_idx,
-                    int32_t *out_offsets, int out_cap, int32_t *status, hipStream_t s);
+                    int32_t *out_offsets, int out_cap, int32_t *status, int32_t *scan, hipStream_t s);
+int compact_scan_words();
 
 // ---- attention ---------------------------------------------------------------------------------
 struct AttnArgs {

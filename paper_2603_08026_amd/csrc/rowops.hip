@@ -251,13 +251,68 @@ __global__ __launch_bounds__(SAL_NT) void k_saliency(const T *__restrict__ c_new
   }
 }
 
-// ---- stream compaction as a kernel of its own (one workgroup) -------------------------------------
-__global__ __launch_bounds__(CB) void k_compact(const uint8_t *__restrict__ flag, Rows rows, int B,
-                                                 int L, int32_t *out_idx, int32_t *out_off,
-                                                 int out_cap, int32_t *status, int overflow_code) {
+// ---- stream compaction as a kernel of its own ------------------------------------------------------
+// Workgroup i takes entries [i*chunk, (i+1)*chunk) of the list.  It counts its flagged entries,
+// publishes the count, adds up the counts of the chunks before it, and then places its own entries.
+// scan (CSCAN_WORDS ints, all zero before and after a launch): [0] a ticket counter that numbers the
+// workgroups in the order they start, [1] finished workgroups, [2 + i] 1 + count of chunk i once
+// published.  Every workgroup publishes BEFORE it waits, and it only waits for tickets lower than its
+// own, whose workgroups are already running: every wait ends.  The workgroup that finishes last puts
+// the words back to zero for the next launch.  Launches that share `scan` must not overlap.
+__global__ __launch_bounds__(CB) void k_compact(const uint8_t *__restrict__ flag, Rows rows, int B, int L,
+                                                 int chunk, int32_t *out_idx, int32_t *out_off, int out_cap,
+                                                 int32_t *status, int overflow_code, int32_t *scan) {
   __shared__ int wave_cnt[CB / WAVE];
-  compact_block<CB>(flag, rows, row_count(rows), B, L, out_idx, out_off, out_cap, status, overflow_code,
-                false, wave_cnt);
+  __shared__ int s_bid, s_last;
+  const int tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
+  const int n = row_count(rows);
+  const int G = gridDim.x;
+  if (tid == 0) s_bid = __hip_atomic_fetch_add(scan, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  const int bid = s_bid;
+  const int lo = min(n, bid * chunk), hi = min(n, lo + chunk);
+  int mine = 0;  // wave-uniform
+  for (int start = lo; start < hi; start += CB) {
+    const int j = start + tid;
+    mine += __popcll(__ballot(j < hi && flag[j] != 0));
+  }
+  if (lane == 0) wave_cnt[w] = mine;
+  __syncthreads();
+  int own = 0;
+#pragma unroll
+  for (int i = 0; i < CB / WAVE; ++i) own += wave_cnt[i];
+  if (tid == 0) __hip_atomic_store(scan + 2 + bid, own + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  int before = 0;
+  if (lo < hi) {  // a chunk past the end places nothing and waits for nobody
+    for (int i = tid; i < bid; i += CB) {
+      int v;
+      do {
+        v = __hip_atomic_load(scan + 2 + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      } while (v == 0);
+      before += v - 1;
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) before += __shfl_xor(before, o, WAVE);
+  __syncthreads();
+  if (lane == 0) wave_cnt[w] = before;
+  __syncthreads();
+  before = 0;
+#pragma unroll
+  for (int i = 0; i < CB / WAVE; ++i) before += wave_cnt[i];
+  __syncthreads();
+  const int total = compact_range<CB>(flag, rows, lo, hi, before, B, L, out_idx, out_off, out_cap, false, wave_cnt);
+  // the workgroup that holds the end of the list (workgroup 0 of an empty one) writes the tail
+  if ((lo < hi && hi == n) || (n == 0 && bid == 0))
+    compact_tail<CB>(rows, n, total, B, L, out_off, out_cap, status, overflow_code);
+  __syncthreads();
+  if (tid == 0)
+    s_last = __hip_atomic_fetch_add(scan + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == G - 1;
+  __syncthreads();
+  if (s_last) {
+    for (int i = tid; i < G + 2; i += CB)
+      __hip_atomic_store(scan + i, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
 }
 
 __global__ void k_fill_i32(int32_t *p, int32_t v, int n) {
@@ -341,9 +396,17 @@ void launch_saliency(DType t, const void *c_new, void *c_cache, Rows rows, int D
                                                          rows, D, tau, cos_out, flag_out, commit);
 }
 
+int compact_scan_words() { return CSCAN_WORDS; }
+
 void launch_compact(const uint8_t *flag, Rows rows, int B, int L, int32_t *out_idx,
-                    int32_t *out_offsets, int out_cap, int32_t *status, hipStream_t s) {
-  k_compact<<<1, CB, 0, s>>>(flag, rows, B, L, out_idx, out_offsets, out_cap, status, -6);
+                    int32_t *out_offsets, int out_cap, int32_t *status, int32_t *scan, hipStream_t s) {
+  const int cap = rows.cap < 0 ? 0 : rows.cap;
+  int G = (cap + CB - 1) / CB;
+  G = G < 1 ? 1 : (G > CMAXG ? CMAXG : G);
+  int chunk = (cap + G - 1) / G;
+  chunk = ((chunk + CB - 1) / CB) * CB;
+  if (chunk < CB) chunk = CB;
+  k_compact<<<G, CB, 0, s>>>(flag, rows, B, L, chunk, out_idx, out_offsets, out_cap, status, -6, scan);
 }
 
 // ---- approximate context update of the non-salient rows  [Sec. 3.3; Alg. 3 lines C <- ..., cosine] --
