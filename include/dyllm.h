@@ -152,6 +152,21 @@ int dyllm_saliency(dyllm_ctx *ctx, const void *c_new, void *c_cache, const dyllm
 int dyllm_compact(dyllm_ctx *ctx, const uint8_t *flag, const dyllm_index_list *rows, int32_t B,
                   int32_t L, dyllm_index_list *out, void *stream);
 
+/* dyllm_compact for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  It takes no context (dyllm_create allocates one)
+ * and calls no allocating routine; the few counter and partial-count words its kernel needs live in a
+ * fixed array inside the library's code object (4352 bytes per GPU, held until the process ends).
+ * Same inputs, outputs and results as dyllm_compact.  B*L (rows == NULL) or rows->cap may be at most
+ * DYLLM_COMPACT_STATIC_MAX_ROWS; a larger request returns DYLLM_ERR_CAPACITY and launches nothing.
+ * status: NULL, or a device word that receives DYLLM_ERR_CAPACITY when more than out->cap tokens are
+ * flagged (the excess is dropped); it is not written otherwise.
+ * Every call on one GPU shares that GPU's array: calls that may overlap on one GPU (different
+ * streams without an ordering between them) race; calls on one stream are safe.  The first call on
+ * a device looks the array's address up once (no allocation), so make it outside stream capture. */
+#define DYLLM_COMPACT_STATIC_MAX_ROWS (1 << 20)
+int dyllm_compact_static(const uint8_t *flag, const dyllm_index_list *rows, int32_t B, int32_t L,
+                         dyllm_index_list *out, int32_t *status, void *stream);
+
 /* K/V refresh of the salient rows.  [Alg. 3: norm, q_proj, k_proj / v_proj merge lines]
  * For every token r in rows: n = RMSNorm(x[r]; g_attn); q, k, v = W n (+ b); q and k rotated by the
  * rotary embedding at position r mod L; cache->k[r] = k, cache->v[r] = v (other rows untouched);

@@ -22,7 +22,7 @@ OK, ERR_INVALID_ARG, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_NO_MEM, ERR_HIP, ERR_CA
 
 SYMBOLS = [
     "dyllm_workspace_bytes", "dyllm_create", "dyllm_destroy", "dyllm_strerror", "dyllm_last_error",
-    "dyllm_poll_status", "dyllm_saliency", "dyllm_compact", "dyllm_qkv_refresh",
+    "dyllm_poll_status", "dyllm_saliency", "dyllm_compact", "dyllm_compact_static", "dyllm_qkv_refresh",
     "dyllm_partial_attention", "dyllm_salient_ffn", "dyllm_layer_step", "dyllm_layer_step_approx",
     "dyllm_stack_step_approx", "dyllm_merge_lists", "dyllm_step_kind", "dyllm_denoise_step", "dyllm_full_step",
     "dyllm_stack_step", "dyllm_stack_full_step", "dyllm_pack_weight",
@@ -90,6 +90,7 @@ def load_library() -> C.CDLL:
     lib.dyllm_poll_status.argtypes = [vp, P(i32), vp]
     lib.dyllm_saliency.argtypes = [vp, vp, vp, P(IndexListC), i32, i32, f32, vp, vp, C.c_int, vp]
     lib.dyllm_compact.argtypes = [vp, vp, P(IndexListC), i32, i32, P(IndexListC), vp]
+    lib.dyllm_compact_static.argtypes = [vp, P(IndexListC), i32, i32, P(IndexListC), vp, vp]
     lib.dyllm_qkv_refresh.argtypes = [vp, P(LayerWeights), vp, P(IndexListC), i32, i32, P(LayerCache), vp, vp]
     lib.dyllm_partial_attention.argtypes = [vp, vp, vp, vp, P(IndexListC), i32, i32, vp, vp]
     lib.dyllm_salient_ffn.argtypes = [vp, P(LayerWeights), vp, vp, P(IndexListC), i32, i32, vp, vp]
@@ -172,6 +173,21 @@ def pack_weight(src: torch.Tensor, dst: torch.Tensor) -> None:
         raise ValueError("pack_weight takes a 2-D bf16 matrix and a bf16 destination of the same size")
     lib = load_library()
     rc = lib.dyllm_pack_weight(_ptr(src), C.c_int32(src.shape[0]), C.c_int32(src.shape[1]), _ptr(dst), _stream())
+    if rc:
+        raise DyllmError(rc, lib.dyllm_strerror(rc).decode())
+
+
+COMPACT_STATIC_MAX_ROWS = 1 << 20
+
+
+def compact_static(flag: torch.Tensor, rows: Optional["IndexList"], B: int, L: int, out: "IndexList",
+                   status: Optional[torch.Tensor] = None) -> None:
+    """dyllm_compact without a context: no device memory is allocated by the call."""
+    lib = load_library()
+    r = rows.c() if rows is not None else None
+    o = out.c()
+    rc = lib.dyllm_compact_static(_ptr(flag), C.byref(r) if r is not None else None, C.c_int32(B), C.c_int32(L),
+                                  C.byref(o), _ptr(status), _stream())
     if rc:
         raise DyllmError(rc, lib.dyllm_strerror(rc).decode())
 

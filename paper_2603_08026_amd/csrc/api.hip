@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -88,6 +89,33 @@ Layout make_layout(const dyllm_layer_cfg &c) {
   l.scan = take((size_t)compact_scan_words() * 4);
   l.total = off;
   return l;
+}
+
+// Device words of dyllm_compact_static, the entry point that allocates nothing.  In host code the
+// array's name is only a handle for the symbol lookup: kernels get the address that
+// hipGetSymbolAddress returns for the current device (every GPU holds its own copy).
+constexpr int kScratchWords = 1088;  // COMPACT_SCAN_WORDS + the spare status word, padded to 4352 bytes
+static_assert(kScratchWords > COMPACT_SCAN_WORDS, "room for the spare status word");
+static __device__ __align__(256) int32_t scratch[kScratchWords];
+constexpr int kMaxDevices = 64;
+int32_t *g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mu;
+
+// address of `scratch` on the current device, looked up once per device
+int static_scratch(int32_t **words) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DYLLM_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return DYLLM_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = (int32_t *)p;
+  }
+  *words = g_scratch_ptr[dev];
+  return DYLLM_OK;
 }
 
 int check_cfg(const dyllm_layer_cfg *c) {
@@ -599,6 +627,29 @@ int dyllm_compact(dyllm_ctx *ctx, const uint8_t *flag, const dyllm_index_list *r
   }
   launch_compact(flag, r, B, L, out->idx, out->offsets, out->cap, ctx->status, ctx->scan, (hipStream_t)stream);
   return check_launch(ctx, "compact");
+}
+
+int dyllm_compact_static(const uint8_t *flag, const dyllm_index_list *rows, int32_t B, int32_t L,
+                         dyllm_index_list *out, int32_t *status, void *stream) {
+  if (!flag || !out || !out->offsets || out->cap < 0 || (!out->idx && out->cap > 0)) return DYLLM_ERR_INVALID_ARG;
+  if (B <= 0 || L <= 0) return DYLLM_ERR_INVALID_ARG;
+  if ((long)B * L > (1l << 30)) return DYLLM_ERR_UNSUPPORTED;
+  Rows r;
+  if (rows) {
+    if (!rows->offsets || rows->cap < 0 || (!rows->idx && rows->cap > 0)) return DYLLM_ERR_INVALID_ARG;
+    r = rows_of(rows, B);
+  } else {
+    r = Rows{nullptr, nullptr, B * L};
+  }
+  if (r.cap > DYLLM_COMPACT_STATIC_MAX_ROWS) return DYLLM_ERR_CAPACITY;
+  int32_t *words = nullptr;
+  const int rc = static_scratch(&words);
+  if (rc) return rc;
+  // words [0, COMPACT_SCAN_WORDS): the kernel's scan words, zero between calls (the kernel clears
+  // them itself); the word behind them takes the overflow code when the caller gives no status word
+  launch_compact(flag, r, B, L, out->idx, out->offsets, out->cap, status ? status : words + COMPACT_SCAN_WORDS,
+                 words, (hipStream_t)stream);
+  return hipGetLastError() == hipSuccess ? DYLLM_OK : DYLLM_ERR_HIP;
 }
 
 int dyllm_qkv_refresh(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x,

@@ -10,7 +10,7 @@ namespace dy {
 
 constexpr int CB = 256;       // threads of a workgroup of the stand-alone compaction kernel
 constexpr int CMAXG = 1024;   // most workgroups of one stand-alone launch
-constexpr int CSCAN_WORDS = 2 + CMAXG;  // device words the chained kernel needs (all zero between launches)
+static_assert(COMPACT_SCAN_WORDS == 2 + CMAXG, "scan words: ticket, finished count, one word per workgroup");
 
 // sequence of a token id, never past the last sequence (an id outside [0, B*L) must not index past
 // offsets[B])

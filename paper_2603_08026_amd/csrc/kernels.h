@@ -50,7 +50,8 @@ void launch_saliency(DType t, const void *c_new, void *c_cache, Rows rows, int D
 // Launches that share `scan` must not overlap.
 void launch_compact(const uint8_t *flag, Rows rows, int B, int L, int32_t *out_idx,
                     int32_t *out_offsets, int out_cap, int32_t *status, int32_t *scan, hipStream_t s);
-int compact_scan_words();
+constexpr int COMPACT_SCAN_WORDS = 2 + 1024;
+inline int compact_scan_words() { return COMPACT_SCAN_WORDS; }
 
 // ---- attention ---------------------------------------------------------------------------------
 struct AttnArgs {

@@ -254,7 +254,7 @@ __global__ __launch_bounds__(SAL_NT) void k_saliency(const T *__restrict__ c_new
 // ---- stream compaction as a kernel of its own ------------------------------------------------------
 // Workgroup i takes entries [i*chunk, (i+1)*chunk) of the list.  It counts its flagged entries,
 // publishes the count, adds up the counts of the chunks before it, and then places its own entries.
-// scan (CSCAN_WORDS ints, all zero before and after a launch): [0] a ticket counter that numbers the
+// scan (COMPACT_SCAN_WORDS ints, all zero before and after a launch): [0] a ticket counter that numbers the
 // workgroups in the order they start, [1] finished workgroups, [2 + i] 1 + count of chunk i once
 // published.  Every workgroup publishes BEFORE it waits, and it only waits for tickets lower than its
 // own, whose workgroups are already running: every wait ends.  The workgroup that finishes last puts
@@ -395,8 +395,6 @@ void launch_saliency(DType t, const void *c_new, void *c_cache, Rows rows, int D
     k_saliency<bf16_t><<<sal_grid(rows.cap), SAL_NT, 0, s>>>((const bf16_t *)c_new, (bf16_t *)c_cache,
                                                          rows, D, tau, cos_out, flag_out, commit);
 }
-
-int compact_scan_words() { return CSCAN_WORDS; }
 
 void launch_compact(const uint8_t *flag, Rows rows, int B, int L, int32_t *out_idx,
                     int32_t *out_offsets, int out_cap, int32_t *status, int32_t *scan, hipStream_t s) {
