@@ -14,6 +14,18 @@ template <int V>
 __device__ __forceinline__ void merge_splits(const AttnArgs &a, int j, int c, int D, float (&out)[V],
                                              float *lse = nullptr) {
   const int h = c / a.dh;
+  if (a.splits == 1) {  // one partial: nothing to weigh, and one dependent load less
+    const float2 ml = *reinterpret_cast<const float2 *>(a.part_ml + ((size_t)j * a.H + h) * 2);
+    const float4 *po = reinterpret_cast<const float4 *>(a.part_o + (size_t)j * D + c);
+    const float inv = 1.0f / ml.y;
+#pragma unroll
+    for (int q = 0; q < V / 4; ++q) {
+      const float4 o = po[q];
+      out[4 * q] = o.x * inv; out[4 * q + 1] = o.y * inv; out[4 * q + 2] = o.z * inv; out[4 * q + 3] = o.w * inv;
+    }
+    if (lse) *lse = ml.x + __logf(ml.y);
+    return;
+  }
   float M = -INFINITY;
   for (int s = 0; s < a.splits; ++s) M = fmaxf(M, a.part_ml[(((size_t)s * a.rows.cap + j) * a.H + h) * 2]);
   float l = 0.f;
@@ -158,9 +170,13 @@ void attention_plan(DType t, int B, int L, int H, int dh, int cap, int rows_per_
   // one more partial result, so half the CUs' worth of workgroups is the aim (measured at 106 rows of
   // one sequence, 32 heads: 64-row tiles x 2 splits 13.2 + 6.0 us for attention + merge, 128-row
   // tiles x 8 splits 13.9 + 8.9 us), and 128-row tiles are taken only when they alone reach it.
+  // Once 128-row tiles alone fill the chip (two workgroups per CU) they are taken at any row count:
+  // waves without a query skip the products, and the 64-row kernel holds one workgroup per CU only
+  // (measured at about 66 rows in each of 16 sequences, 32 heads: 72 us against 116 us).
   const long target = 128;
   const long tiles128 = (long)((rows_per_seq + 127) / 128) * B * H;
-  const int best_bq = (n_opt == 1) ? bq_opt[0] : (rows_per_seq > 80 && tiles128 >= target ? 128 : 64);
+  const int best_bq = (n_opt == 1) ? bq_opt[0]
+                                   : ((rows_per_seq > 80 && tiles128 >= target) || tiles128 >= 2 * 256 ? 128 : 64);
   long tiles = (long)((rows_per_seq + best_bq - 1) / best_bq) * B * H;
   if (tiles < 1) tiles = 1;  // empty list
   const int best_s = (int)((target + tiles - 1) / tiles);

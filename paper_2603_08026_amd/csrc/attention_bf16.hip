@@ -111,7 +111,7 @@ __device__ __forceinline__ void store_kv_tile(const uint4 (&rk)[KCH], const uint
 }
 
 template <int DH, int WQ, int NW, int QB>
-__global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
+__global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a, int q_tiles) {
   using T = ATile<DH, WQ, NW, QB>;
   constexpr int WK = T::WK, BQ = T::BQ, TK = T::TK, KSTR = T::KSTR, VSTR = T::VSTR, DB = T::DB, KK = T::KK;
   extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -121,12 +121,14 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
   const int tid = threadIdx.x, lane = tid % WAVE, wave = tid / WAVE;
   const int l32 = lane % 32, lhi = lane / 32;
   const int wq = wave / WK, wk = wave % WK;
-  if (tid == 0) find_tile(a, BQ, blockIdx.x, tile_info);
+  int tile, h, split;
+  if (!attn_work_item(a, q_tiles, &tile, &h, &split)) return;  // uniform
+  if (tid == 0) find_tile(a, BQ, tile, tile_info);
   __syncthreads();
   const int b = tile_info[0];
   if (b < 0) return;  // uniform: no such tile
   const int j0 = tile_info[1], nq = tile_info[2];
-  const int h = blockIdx.y, kvh = h / (a.H / a.Hkv), split = blockIdx.z;
+  const int kvh = h / (a.H / a.Hkv);
   const int kbase = a.key_offsets ? a.key_offsets[b] : b * a.L;
   const int Lk = a.key_offsets ? a.key_offsets[b + 1] - kbase : a.L;
   const int k_lo = split * a.chunk, k_hi = min(Lk, k_lo + a.chunk);
@@ -349,6 +351,12 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
 //     of the operand in the key order the P^T registers have.  The 32-byte pair p of row r sits at
 //     pair position p ^ (r % 8): the 4 rows x 64 bytes that 32 lanes read hit every bank once.
 typedef short shortx4 __attribute__((ext_vector_type(4)));
+#ifdef DY_ATTN_PROBE
+__device__ long long g_attn_probe[8];
+#define DY_PROBE_T(x) const long long x = __builtin_readcyclecounter()
+#else
+#define DY_PROBE_T(x)
+#endif
 
 template <int WQ, int WK_> struct DTile {
   static constexpr int DH = 128, WK = WK_;  // wave columns over the keys of a tile
@@ -369,7 +377,7 @@ template <int WQ, int WK_> struct DTile {
 };
 
 template <int WQ, int WK_>
-__global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a) {  // two waves per SIMD: 256 registers, no AGPR shuffling
+__global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, int q_tiles) {  // two waves per SIMD: 256 registers, no AGPR shuffling
   using T = DTile<WQ, WK_>;
   constexpr int DH = T::DH, NW = T::NW, WK = T::WK, BQ = T::BQ, TK = T::TK, ROWB = T::ROWB, NS = T::NS,
                 DB = T::DB, KK = T::KK, LPW = T::LPW;
@@ -380,12 +388,14 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a) 
   const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
   const int l32 = lane % 32, lhi = lane / 32;
   const int wq = wave / WK, wk = wave % WK;
-  if (tid == 0) find_tile(a, BQ, blockIdx.x, tile_info);
+  int tile, h, split;
+  if (!attn_work_item(a, q_tiles, &tile, &h, &split)) return;  // uniform
+  if (tid == 0) find_tile(a, BQ, tile, tile_info);
   __syncthreads();
   const int b = tile_info[0];
   if (b < 0) return;  // uniform: no such tile
   const int j0 = tile_info[1], nq = tile_info[2];
-  const int h = blockIdx.y, kvh = h / (a.H / a.Hkv), split = blockIdx.z;
+  const int kvh = h / (a.H / a.Hkv);
   const int kbase = a.key_offsets ? a.key_offsets[b] : b * a.L;
   const int Lk = a.key_offsets ? a.key_offsets[b + 1] - kbase : a.L;
   const int k_lo = split * a.chunk, k_hi = min(Lk, k_lo + a.chunk);
@@ -443,6 +453,21 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a) 
   for (int s = 0; s < NS - 1; ++s)
     if (s < n_tiles) issue(s);
 
+  // A wave whose 32 query rows all lie past the tile's last row (ragged row counts: a sequence with
+  // 70 candidates leaves two of the four waves of a 128-row tile without a query) takes no part in the
+  // products: it keeps its share of the copies and meets the same barriers, in a loop of its own so
+  // that the schedule of the working waves' loop is untouched.
+  if (wq * 32 >= nq) {  // wave-uniform
+    if (NS - 2 < n_tiles) wait_vmcnt<(NS - 2) * LPW>();
+    else wait_vmcnt<0>();
+    __syncthreads();
+    for (int t = 0; t < n_tiles; ++t) {
+      if (t + NS - 2 < n_tiles) wait_vmcnt<(NS - 3) * LPW>();
+      else wait_vmcnt<0>();
+      __syncthreads();
+      if (t + NS - 1 < n_tiles) issue(t + NS - 1);
+    }
+  } else {
   // Software pipeline: the score block of tile t+1 is issued to the matrix pipe before the softmax
   // arithmetic of tile t, so that the vector ALU work of a wave runs under its own matrix products
   // (the waves of a workgroup move in step, tile by tile, and would otherwise all queue for the same
@@ -462,12 +487,18 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a) 
     }
   }
 
+#ifdef DY_ATTN_PROBE
+  long long pr_wait = 0, pr_soft = 0, pr_pv = 0;
+  const long long pr_begin = __builtin_readcyclecounter();
+#endif
   for (int t = 0; t < n_tiles; ++t) {
+    DY_PROBE_T(p0);
     // tile t+1 (K for the next scores) has landed; tiles up to t+NS-2 are in flight
     if (t + NS - 2 < n_tiles) wait_vmcnt<(NS - 3) * LPW>();
     else wait_vmcnt<0>();
     __syncthreads();  // ... all waves' parts; and everyone is done with K of tile t and V of tile t-1
     if (t + NS - 1 < n_tiles) issue(t + NS - 1);  // into the stage tile t-1 occupied
+    DY_PROBE_T(p1);
     const unsigned char *st = smem_raw + (size_t)(t % NS) * T::STAGE_BYTES;
     const unsigned char *st_next = smem_raw + (size_t)((t + 1) % NS) * T::STAGE_BYTES;
     const int k0 = k_lo + t * TK;
@@ -536,6 +567,11 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a) 
       __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);  // rounding and sum of an earlier pair
     }
 
+#ifdef DY_ATTN_PROBE
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#endif
+    DY_PROBE_T(p2);
     // O^T += V^T P^T over the wave's 32 keys of tile t
     const unsigned char *svp = st + T::REGION + vrow * ROWB + 8 * (lane % 4);
 #pragma unroll
@@ -552,6 +588,18 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a) 
         acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ks], acc_o[db], 0, 0, 0);
       }
     s_cur = s_next;
+#ifdef DY_ATTN_PROBE
+    __builtin_amdgcn_sched_barrier(0);
+    DY_PROBE_T(p3);
+    pr_wait += p1 - p0; pr_soft += p2 - p1; pr_pv += p3 - p2;
+#endif
+  }
+#ifdef DY_ATTN_PROBE
+  if (blockIdx.x == 64 && tid == 0) {
+    g_attn_probe[0] = pr_wait; g_attn_probe[1] = pr_soft; g_attn_probe[2] = pr_pv; g_attn_probe[3] = n_tiles;
+    g_attn_probe[4] = __builtin_readcyclecounter() - pr_begin;
+  }
+#endif
   }
   __syncthreads();  // every wave is done with the last tile: the stages become merge scratch
 
@@ -634,8 +682,8 @@ template <int WQ, int WK> void launch_dma(const AttnArgs &a, hipStream_t s) {
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::LDS_BYTES);
     done = true;
   }
-  dim3 grid(max_q_tiles(a, T::BQ), a.H, a.splits);
-  k_attn_bf16_dma<WQ, WK><<<grid, T::NT, T::LDS_BYTES, s>>>(a);
+  const int q_tiles = max_q_tiles(a, T::BQ);
+  k_attn_bf16_dma<WQ, WK><<<attn_grid(a, q_tiles), T::NT, T::LDS_BYTES, s>>>(a, q_tiles);
 }
 
 template <int DH, int WQ, int NW, int QB> void launch_cfg(const AttnArgs &a, hipStream_t s) {
@@ -646,8 +694,8 @@ template <int DH, int WQ, int NW, int QB> void launch_cfg(const AttnArgs &a, hip
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::LDS_BYTES);
     done = true;
   }
-  dim3 grid(max_q_tiles(a, T::BQ), a.H, a.splits);
-  k_attn_bf16<DH, WQ, NW, QB><<<grid, T::NT, T::LDS_BYTES, s>>>(a);
+  const int q_tiles = max_q_tiles(a, T::BQ);
+  k_attn_bf16<DH, WQ, NW, QB><<<attn_grid(a, q_tiles), T::NT, T::LDS_BYTES, s>>>(a, q_tiles);
 }
 
 }  // namespace

@@ -51,6 +51,33 @@ __device__ inline void find_tile(const AttnArgs &a, int BQ, int tile, int *info)
   }
 }
 
+// Work item of a workgroup of a 1-D launch over (key split, KV head, query tile, query head of the
+// group).  Workgroup p runs on XCD p % 8, and an XCD takes its workgroups in the order of p: every
+// XCD gets one contiguous range of the items in the order above, so all query tiles and all query
+// heads that read the keys and values of one (sequence, KV head) run on ONE XCD, next to each other
+// in time, and that K/V stream crosses the fabric once instead of once per tile and head.
+constexpr int ATTN_XCD = 8;
+inline int attn_grid(const AttnArgs &a, int q_tiles) {
+  const long items = (long)q_tiles * a.H * a.splits;
+  return (int)((items + ATTN_XCD - 1) / ATTN_XCD) * ATTN_XCD;
+}
+// returns false when the workgroup has no item
+__device__ __forceinline__ bool attn_work_item(const AttnArgs &a, int q_tiles, int *tile, int *h, int *split) {
+  const int items = q_tiles * a.H * a.splits;
+  const int per_xcd = (items + ATTN_XCD - 1) / ATTN_XCD;
+  const int p = blockIdx.x;
+  const int w = (p % ATTN_XCD) * per_xcd + p / ATTN_XCD;
+  if (p / ATTN_XCD >= per_xcd || w >= items) return false;
+  const int g = a.H / a.Hkv;
+  const int gi = w % g;
+  int rest = w / g;
+  *tile = rest % q_tiles;
+  rest /= q_tiles;
+  *h = (rest % a.Hkv) * g + gi;
+  *split = rest / a.Hkv;
+  return true;
+}
+
 void launch_attention_f32(DType t, const AttnArgs &a, hipStream_t s);
 void launch_attention_bf16(const AttnArgs &a, hipStream_t s);
 void launch_attn_combine(DType t, const AttnArgs &a, hipStream_t s);
