@@ -214,7 +214,7 @@ AttnArgs attn_args(dyllm_ctx *ctx, const void *q, const void *k, const void *v, 
   const dyllm_layer_cfg &c = ctx->cfg;
   AttnArgs a;
   a.q = q; a.q_by_token = 0; a.k = k; a.v = v; a.rows = rows; a.offsets = offsets;
-  a.key_offsets = nullptr; a.lse_out = nullptr;
+  a.key_offsets = nullptr; a.lse_out = nullptr; a.c_commit = nullptr; a.cos_part = nullptr;
   a.B = B; a.L = L; a.H = c.n_heads; a.Hkv = c.n_kv_heads; a.dh = c.head_dim;
   const int rows_per_seq = offsets ? (rows.cap + B - 1) / B : L;
   attention_plan(dt(ctx), B, L, c.n_heads, c.head_dim, rows.cap, rows_per_seq, ctx->part_elems, &a);
@@ -296,14 +296,26 @@ int enqueue_sparse_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
   prof_begin_call(ctx, s);
   if ((rc = enqueue_qkv(ctx, w, x, rin, L, cache, ctx->qs, s))) return rc;
   {
-    // attention leaves per-split partials; their merge is fused with the cosine test and the commit
     AttnArgs a = attn_args(ctx, ctx->qs, cache->k, cache->v, rin, idx_in->offsets, B, L, nullptr, 1);
     a.lse_out = (float *)cache->lse;  // optional fifth cache: log-normalisers of the exact rows
-    launch_attention(dt(ctx), a, s);
-    prof_mark(ctx, ST_ATTENTION, s);
-    // ... and the last workgroup of that kernel compacts the flags into idx_out
-    launch_attn_finalize(dt(ctx), a, cache->c, tau, cos_out ? cos_out : ctx->cosb, ctx->flag,
-                         idx_out->idx, idx_out->offsets, idx_out->cap, ctx->status, ctx->status + 1, s);
+    if (dt(ctx) == BF16 && ctx->cfg.head_dim == 128 && a.splits == 1) {
+      // one key split: the attention kernel commits its rows itself and leaves per-head sums for the
+      // cosine (no fp32 partial result, no second pass over the rows); the cosine test of a row then
+      // rides on the compaction kernel
+      a.c_commit = cache->c;
+      a.cos_part = ctx->part_o;
+      launch_attention(dt(ctx), a, s);
+      prof_mark(ctx, ST_ATTENTION, s);
+      launch_cos_compact(ctx->part_o, ctx->cfg.n_heads, tau, cos_out ? cos_out : ctx->cosb, ctx->flag, rin, B, L,
+                         idx_out->idx, idx_out->offsets, idx_out->cap, ctx->status, ctx->scan, s);
+    } else {
+      // attention leaves per-split partials; their merge is fused with the cosine test and the commit
+      launch_attention(dt(ctx), a, s);
+      prof_mark(ctx, ST_ATTENTION, s);
+      // ... and the last workgroup of that kernel compacts the flags into idx_out
+      launch_attn_finalize(dt(ctx), a, cache->c, tau, cos_out ? cos_out : ctx->cosb, ctx->flag,
+                           idx_out->idx, idx_out->offsets, idx_out->cap, ctx->status, ctx->status + 1, s);
+    }
     prof_mark(ctx, ST_SALIENCY, s);
     prof_mark(ctx, ST_COMPACT, s);
   }

@@ -643,6 +643,50 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
   }
 
   const int r = wq * 32 + l32;
+  if (a.c_commit) {
+    // Fused commit  [Alg. 3: cosine line and cache commit]: the row is normalised and rounded to the
+    // storage type; this lane holds 64 of the head's 128 columns of its query.  It reads the same
+    // columns of the cached context of the query's token, adds up <new, old>, |new|^2, |old|^2 over the
+    // stored values, overwrites the cached columns, and the two lanes of a query leave the head's sums.
+    float dot = 0.f, na = 0.f, nb = 0.f;
+    const bool live = r < nq;  // (lanes past the tile's last row take part in the shuffle only)
+    const int j = j0 + (live ? r : 0);
+    if (live) {
+      const size_t tok = a.rows.idx ? (size_t)a.rows.idx[j] : (size_t)j;
+      bf16_t *crow = (bf16_t *)a.c_commit + (tok * a.H + h) * DH + 4 * lhi;
+      const float inv = 1.0f / l_run;
+      uint2 old[DB][4];
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) old[db][g] = *reinterpret_cast<const uint2 *>(crow + db * 32 + 8 * g);
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          uint2 w;
+          w.x = pack_bf16(acc_o[db][4 * g] * inv, acc_o[db][4 * g + 1] * inv);
+          w.y = pack_bf16(acc_o[db][4 * g + 2] * inv, acc_o[db][4 * g + 3] * inv);
+          const uint32_t nw[2] = {w.x, w.y}, ow[2] = {old[db][g].x, old[db][g].y};
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            const float f0 = __uint_as_float(nw[q] << 16), f1 = __uint_as_float(nw[q] & 0xffff0000u);
+            const float b0 = __uint_as_float(ow[q] << 16), b1 = __uint_as_float(ow[q] & 0xffff0000u);
+            dot += f0 * b0 + f1 * b1;
+            na += f0 * f0 + f1 * f1;
+            nb += b0 * b0 + b1 * b1;
+          }
+          *reinterpret_cast<uint2 *>(crow + db * 32 + 8 * g) = w;
+        }
+      if (a.lse_out && lhi == 0) a.lse_out[tok * a.H + h] = m_run * LN2 + __logf(l_run);
+    }
+    dot += __shfl_xor(dot, 32, WAVE);
+    na += __shfl_xor(na, 32, WAVE);
+    nb += __shfl_xor(nb, 32, WAVE);
+    if (live && lhi == 0)
+      *reinterpret_cast<float4 *>(a.cos_part + ((size_t)j * a.H + h) * 4) = float4{dot, na, nb, 0.f};
+    return;
+  }
   if (r >= nq) return;
   const int j = j0 + r;
   if (a.splits == 1 && !a.partial) {

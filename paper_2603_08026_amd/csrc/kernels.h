@@ -53,6 +53,14 @@ void launch_compact(const uint8_t *flag, Rows rows, int B, int L, int32_t *out_i
 constexpr int COMPACT_SCAN_WORDS = 2 + 1024;
 inline int compact_scan_words() { return COMPACT_SCAN_WORDS; }
 
+// The cosine test from per-head sums, then the same compaction: entry j of `rows` has
+// cos = sum_h p[j][h][0] / (max(sqrt(sum_h p[j][h][1]), 1e-8) * max(sqrt(sum_h p[j][h][2]), 1e-8)),
+// flag = cos < tau; cos_out[j] and flag_out[j] are written, the flagged tokens compacted as by
+// launch_compact.  cos_part: [cap, H, 4] fp32.
+void launch_cos_compact(const float *cos_part, int H, float tau, float *cos_out, uint8_t *flag_out, Rows rows,
+                        int B, int L, int32_t *out_idx, int32_t *out_offsets, int out_cap, int32_t *status,
+                        int32_t *scan, hipStream_t s);
+
 // ---- attention ---------------------------------------------------------------------------------
 struct AttnArgs {
   const void *q;        // [cap, H, dh] T-typed; with q_by_token: [T, H, dh], row of query j = rows.idx[j]
@@ -71,6 +79,13 @@ struct AttnArgs {
   float *part_o;        // [splits, cap, H*dh] fp32 un-normalised partial outputs
   float *part_ml;       // [splits, cap, H, 2] fp32 (running max in natural-log units, running sum)
   void *out;            // [cap, H*dh] T-typed (unused when partials are left)
+  // Fused commit (bf16, head_dim 128, one key split; null otherwise): the attention kernel itself
+  // normalises its rows, rounds them to the storage type, reads the cached context row of the query's
+  // token (rows.idx, or the identity), overwrites it with the new one, and leaves the three sums the
+  // cosine needs -- <new, old>, |new|^2, |old|^2 over the head's dh columns -- in cos_part[j][h][0..2]
+  // (fp32, [cap, H, 4]); no partial output is written.
+  void *c_commit;       // [T, H*dh] T-typed context cache
+  float *cos_part;
 };
 // attention rows; merges the splits into a.out unless a.partial is set
 void launch_attention(DType t, const AttnArgs &a, hipStream_t s);

@@ -259,9 +259,21 @@ __global__ __launch_bounds__(SAL_NT) void k_saliency(const T *__restrict__ c_new
 // published.  Every workgroup publishes BEFORE it waits, and it only waits for tickets lower than its
 // own, whose workgroups are already running: every wait ends.  The workgroup that finishes last puts
 // the words back to zero for the next launch.  Launches that share `scan` must not overlap.
+// FROM_PARTS: the flags do not exist yet; a thread first takes the cosine of each of its entries from
+// the per-head sums the attention kernel left (cos_part [n, H, 4]: <new, old>, |new|^2, |old|^2), writes
+// cos_out and the flag, and then counts and places the flags it wrote itself.
+struct CosParts {
+  const float *part;
+  float *cos_out;
+  uint8_t *flag_out;
+  int H;
+  float tau;
+};
+
+template <bool FROM_PARTS>
 __global__ __launch_bounds__(CB) void k_compact(const uint8_t *__restrict__ flag, Rows rows, int B, int L,
                                                  int chunk, int32_t *out_idx, int32_t *out_off, int out_cap,
-                                                 int32_t *status, int overflow_code, int32_t *scan) {
+                                                 int32_t *status, int overflow_code, int32_t *scan, CosParts cp) {
   __shared__ int wave_cnt[CB / WAVE];
   __shared__ int s_bid, s_last;
   const int tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
@@ -274,7 +286,24 @@ __global__ __launch_bounds__(CB) void k_compact(const uint8_t *__restrict__ flag
   int mine = 0;  // wave-uniform
   for (int start = lo; start < hi; start += CB) {
     const int j = start + tid;
-    mine += __popcll(__ballot(j < hi && flag[j] != 0));
+    bool f = false;
+    if (j < hi) {
+      if constexpr (FROM_PARTS) {
+        const float4 *p = reinterpret_cast<const float4 *>(cp.part) + (size_t)j * cp.H;
+        float dot = 0.f, na = 0.f, nb = 0.f;
+        for (int h = 0; h < cp.H; ++h) {
+          const float4 v = p[h];
+          dot += v.x; na += v.y; nb += v.z;
+        }
+        const float c = dot / (fmaxf(sqrtf(na), 1e-8f) * fmaxf(sqrtf(nb), 1e-8f));
+        f = c < cp.tau;
+        if (cp.cos_out) cp.cos_out[j] = c;
+        cp.flag_out[j] = f ? 1 : 0;  // read back in the placement pass (device-scope load, after the store is acknowledged)
+      } else {
+        f = flag[j] != 0;
+      }
+    }
+    mine += __popcll(__ballot(f));
   }
   if (lane == 0) wave_cnt[w] = mine;
   __syncthreads();
@@ -301,7 +330,9 @@ __global__ __launch_bounds__(CB) void k_compact(const uint8_t *__restrict__ flag
 #pragma unroll
   for (int i = 0; i < CB / WAVE; ++i) before += wave_cnt[i];
   __syncthreads();
-  const int total = compact_range<CB>(flag, rows, lo, hi, before, B, L, out_idx, out_off, out_cap, false, wave_cnt);
+  if constexpr (FROM_PARTS) wait_vmcnt<0>();  // this thread's flag stores have reached the L2
+  const int total = compact_range<CB>(FROM_PARTS ? cp.flag_out : flag, rows, lo, hi, before, B, L, out_idx, out_off,
+                                      out_cap, FROM_PARTS, wave_cnt);
   // the workgroup that holds the end of the list (workgroup 0 of an empty one) writes the tail
   if ((lo < hi && hi == n) || (n == 0 && bid == 0))
     compact_tail<CB>(rows, n, total, B, L, out_off, out_cap, status, overflow_code);
@@ -404,7 +435,20 @@ void launch_compact(const uint8_t *flag, Rows rows, int B, int L, int32_t *out_i
   int chunk = (cap + G - 1) / G;
   chunk = ((chunk + CB - 1) / CB) * CB;
   if (chunk < CB) chunk = CB;
-  k_compact<<<G, CB, 0, s>>>(flag, rows, B, L, chunk, out_idx, out_offsets, out_cap, status, -6, scan);
+  k_compact<false><<<G, CB, 0, s>>>(flag, rows, B, L, chunk, out_idx, out_offsets, out_cap, status, -6, scan, CosParts{});
+}
+
+void launch_cos_compact(const float *cos_part, int H, float tau, float *cos_out, uint8_t *flag_out, Rows rows,
+                        int B, int L, int32_t *out_idx, int32_t *out_offsets, int out_cap, int32_t *status,
+                        int32_t *scan, hipStream_t s) {
+  const int cap = rows.cap < 0 ? 0 : rows.cap;
+  int G = (cap + CB - 1) / CB;
+  G = G < 1 ? 1 : (G > CMAXG ? CMAXG : G);
+  int chunk = (cap + G - 1) / G;
+  chunk = ((chunk + CB - 1) / CB) * CB;
+  if (chunk < CB) chunk = CB;
+  k_compact<true><<<G, CB, 0, s>>>(flag_out, rows, B, L, chunk, out_idx, out_offsets, out_cap, status, -6, scan,
+                                   CosParts{cos_part, cos_out, flag_out, H, tau});
 }
 
 // ---- approximate context update of the non-salient rows  [Sec. 3.3; Alg. 3 lines C <- ..., cosine] --
