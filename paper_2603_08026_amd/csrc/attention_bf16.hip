@@ -351,12 +351,6 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a, int q_tiles) 
 //     of the operand in the key order the P^T registers have.  The 32-byte pair p of row r sits at
 //     pair position p ^ (r % 8): the 4 rows x 64 bytes that 32 lanes read hit every bank once.
 typedef short shortx4 __attribute__((ext_vector_type(4)));
-#ifdef DY_ATTN_PROBE
-__device__ long long g_attn_probe[8];
-#define DY_PROBE_T(x) const long long x = __builtin_readcyclecounter()
-#else
-#define DY_PROBE_T(x)
-#endif
 
 template <int WQ, int WK_> struct DTile {
   static constexpr int DH = 128, WK = WK_;  // wave columns over the keys of a tile
@@ -487,18 +481,12 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
     }
   }
 
-#ifdef DY_ATTN_PROBE
-  long long pr_wait = 0, pr_soft = 0, pr_pv = 0;
-  const long long pr_begin = __builtin_readcyclecounter();
-#endif
   for (int t = 0; t < n_tiles; ++t) {
-    DY_PROBE_T(p0);
     // tile t+1 (K for the next scores) has landed; tiles up to t+NS-2 are in flight
     if (t + NS - 2 < n_tiles) wait_vmcnt<(NS - 3) * LPW>();
     else wait_vmcnt<0>();
     __syncthreads();  // ... all waves' parts; and everyone is done with K of tile t and V of tile t-1
     if (t + NS - 1 < n_tiles) issue(t + NS - 1);  // into the stage tile t-1 occupied
-    DY_PROBE_T(p1);
     const unsigned char *st = smem_raw + (size_t)(t % NS) * T::STAGE_BYTES;
     const unsigned char *st_next = smem_raw + (size_t)((t + 1) % NS) * T::STAGE_BYTES;
     const int k0 = k_lo + t * TK;
@@ -567,11 +555,6 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
       __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);  // rounding and sum of an earlier pair
     }
 
-#ifdef DY_ATTN_PROBE
-    __builtin_amdgcn_sched_barrier(0);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#endif
-    DY_PROBE_T(p2);
     // O^T += V^T P^T over the wave's 32 keys of tile t
     const unsigned char *svp = st + T::REGION + vrow * ROWB + 8 * (lane % 4);
 #pragma unroll
@@ -588,18 +571,7 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
         acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ks], acc_o[db], 0, 0, 0);
       }
     s_cur = s_next;
-#ifdef DY_ATTN_PROBE
-    __builtin_amdgcn_sched_barrier(0);
-    DY_PROBE_T(p3);
-    pr_wait += p1 - p0; pr_soft += p2 - p1; pr_pv += p3 - p2;
-#endif
   }
-#ifdef DY_ATTN_PROBE
-  if (blockIdx.x == 64 && tid == 0) {
-    g_attn_probe[0] = pr_wait; g_attn_probe[1] = pr_soft; g_attn_probe[2] = pr_pv; g_attn_probe[3] = n_tiles;
-    g_attn_probe[4] = __builtin_readcyclecounter() - pr_begin;
-  }
-#endif
   }
   __syncthreads();  // every wave is done with the last tile: the stages become merge scratch
 
