@@ -23,6 +23,7 @@
 // The key range of a sequence can additionally be split over workgroups (few query rows): then
 // un-normalised partials go to global memory and k_attn_combine merges them.
 #include "attention_common.h"
+#include <type_traits>
 
 namespace dy {
 
@@ -350,6 +351,18 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a, int q_tiles) 
 //     dh0 + i of the rows key0 .. key0+3 -- four consecutive keys of one dh, which is exactly one half
 //     of the operand in the key order the P^T registers have.  The 32-byte pair p of row r sits at
 //     pair position p ^ (r % 8): the 4 rows x 64 bytes that 32 lanes read hit every bank once.
+
+// value of the lane 32 away combined with this lane's (v_permlane32_swap: no LDS round trip)
+__device__ __forceinline__ float xhalf_max(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float xhalf_sum(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 
 template <int WQ, int WK_> struct DTile {
@@ -437,6 +450,31 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
     }
   };
 
+  // full tiles: a scalar base per tile and loop-invariant lane offsets (no vector arithmetic per copy)
+  uint32_t off_k[LPW / 2], off_v[LPW / 2];
+#pragma unroll
+  for (int i = 0; i < LPW / 2; ++i) {
+    const int ii = i * NW + wave, row = ii * 4 + r4;
+    off_k[i] = (uint32_t)(((size_t)row * kv_stride + (cpos ^ (row & 15)) * 8) * 2);
+    off_v[i] = (uint32_t)(((size_t)row * kv_stride + (((((cpos >> 1) ^ (row & 7)) << 1) | (cpos & 1)) * 8)) * 2);
+  }
+  auto uniform_ptr = [](const void *p) {
+    const uint64_t u = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+    return (const unsigned char *)(((uint64_t)hi << 32) | lo);
+  };
+  const unsigned char *kc_u = uniform_ptr(kc + (size_t)k_lo * kv_stride), *vc_u = uniform_ptr(vc + (size_t)k_lo * kv_stride);
+  auto issue_full = [&](int t) {  // tile t, all of whose keys exist, -> stage t % NS
+    const uint32_t sb = lds0 + (uint32_t)(t % NS) * T::STAGE_BYTES;
+    const size_t adv = (size_t)t * TK * kv_stride * 2;
+#pragma unroll
+    for (int i = 0; i < LPW / 2; ++i) {
+      const int ii = i * NW + wave;
+      dma16_s(kc_u + adv, off_k[i], sb + (uint32_t)ii * 1024u);
+      dma16_s(vc_u + adv, off_v[i], sb + (uint32_t)T::REGION + (uint32_t)ii * 1024u);
+    }
+  };
+
   // per-lane constants of the operand reads
   const int krow = wk * 32 + l32, ksw = l32 & 15;
   const int vq = (lane % 16) / 4;                       // row of this lane inside a 4-key group
@@ -462,10 +500,10 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
       if (t + NS - 1 < n_tiles) issue(t + NS - 1);
     }
   } else {
-  // Software pipeline: the score block of tile t+1 is issued to the matrix pipe before the softmax
-  // arithmetic of tile t, so that the vector ALU work of a wave runs under its own matrix products
-  // (the waves of a workgroup move in step, tile by tile, and would otherwise all queue for the same
-  // pipe at the same time).
+  // Software pipeline over three tiles: while the vector ALU takes the exponentials of tile t, the
+  // matrix pipe works through the P V product of tile t-1 and the score block of tile t+1, so a
+  // wave's vector work runs under its own matrix products (the waves of a workgroup move in step,
+  // tile by tile, and would otherwise all queue for the same pipe at the same time).
   floatx16 s_cur;
   {
     if (NS - 2 < n_tiles) wait_vmcnt<(NS - 2) * LPW>();  // tile 0 has landed (this wave's part)
@@ -481,29 +519,71 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
     }
   }
 
-  for (int t = 0; t < n_tiles; ++t) {
-    // tile t+1 (K for the next scores) has landed; tiles up to t+NS-2 are in flight
-    if (t + NS - 2 < n_tiles) wait_vmcnt<(NS - 3) * LPW>();
-    else wait_vmcnt<0>();
-    __syncthreads();  // ... all waves' parts; and everyone is done with K of tile t and V of tile t-1
-    if (t + NS - 1 < n_tiles) issue(t + NS - 1);  // into the stage tile t-1 occupied
+  // Loop state carried from one tile to the next: the V^T fragments and the rounded probabilities
+  // of the tile whose P V product is still to be issued (zero before the first tile).
+  typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
+  typedef short shortx8 __attribute__((ext_vector_type(8)));
+  bf16x8 vf[2][DB], pf[2];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pf[ks][e] = (__bf16)0.f;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) vf[ks][db] = pf[ks];
+  }
+  auto pv = [&]() {  // O^T += V^T P^T of the tile held in vf / pf
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks][db], pf[ks], acc_o[db], 0, 0, 0);
+  };
+  // One tile.  Order: (1) the first K fragments of tile t+1 are requested from LDS and the maximum
+  // of tile t's scores is taken (and, rarely, the reference moved); (2) sixteen matrix instructions
+  // follow -- the P V product of tile t-1, then the score product of tile t+1 -- each with its share
+  // of tile t's exponentials behind it; the other K fragments are requested in between and the V
+  // fragments of tile t at the end, into registers the products have released.  No product waits
+  // for an LDS read issued right before it, and the vector ALU works while the matrix pipe does.
+  // STEADY: the tile fetched in this iteration is a full one and no key of tile t lies past the end.
+  auto body = [&](int t, auto steady_c) {
+    constexpr bool STEADY = decltype(steady_c)::value;
+    if (STEADY) {
+      wait_vmcnt<(NS - 3) * LPW>();
+    } else {
+      if (t + NS - 2 < n_tiles) wait_vmcnt<(NS - 3) * LPW>();
+      else wait_vmcnt<0>();
+    }
+    __syncthreads();  // tile t+1 is in LDS (all waves' parts); everyone is done with tile t-1's stage
+    if (STEADY) issue_full(t + NS - 1);
+    else if (t + NS - 1 < n_tiles) issue(t + NS - 1);
     const unsigned char *st = smem_raw + (size_t)(t % NS) * T::STAGE_BYTES;
     const unsigned char *st_next = smem_raw + (size_t)((t + 1) % NS) * T::STAGE_BYTES;
     const int k0 = k_lo + t * TK;
 
-    // running maximum of tile t (lazily moved reference)
-    const int key_base = k0 + key_lane;
-    if (k0 + TK > k_hi) {  // wave-uniform: only the last tile can hold keys past the end
+    bf16x8 kf[KK];
+    {
+      const unsigned char *skp = st_next + krow * ROWB;
 #pragma unroll
-      for (int e = 0; e < 16; ++e)
-        if (key_base + 8 * (e / 4) + (e % 4) >= k_hi) s_cur[e] = -INFINITY;
+      for (int kk = 0; kk < KK / 2; ++kk)
+        kf[kk] = *reinterpret_cast<const bf16x8 *>(skp + (((2 * kk + lhi) ^ ksw) * 16));
     }
+    if (!STEADY) {
+      const int key_base = k0 + key_lane;
+      if (k0 + TK > k_hi) {  // wave-uniform: only the last tile can hold keys past the end
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (key_base + 8 * (e / 4) + (e % 4) >= k_hi) s_cur[e] = -INFINITY;
+      }
+    }
+    // running maximum of tile t (lazily moved reference)
     float mx = s_cur[0];
 #pragma unroll
     for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s_cur[e]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE)) * sc;
+    mx = xhalf_max(mx) * sc;
     const bool need = mx > m_run + 8.0f;
     if (__any(need)) {
+      // (rare after the first tiles) the accumulator changes its reference; the pending probabilities
+      // of tile t-1 belong to the old one and are scaled with it (by 2^-8 at most, or by exactly 1)
       const float corr = need ? __builtin_amdgcn_exp2f(m_run - mx) : 1.0f;
       m_run = need ? mx : m_run;
       l_run *= corr;
@@ -511,67 +591,94 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc_o[db][e] *= corr;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const uint4 w = __builtin_bit_cast(uint4, pf[ks]);
+        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+        uint32_t o[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          o[q] = pack_bf16(__uint_as_float(ww[q] << 16) * corr, __uint_as_float(ww[q] & 0xffff0000u) * corr);
+        pf[ks] = __builtin_bit_cast(bf16x8, uint4{o[0], o[1], o[2], o[3]});
+      }
     }
     const float neg_ref = (m_run == -INFINITY) ? 0.f : -m_run;
 
-    // scores of tile t+1 (matrix pipe) under the exponentials of tile t (vector ALU)
-    // (after the last tile this reads a stage that holds no tile: the result is dropped)
-    floatx16 s_next;
+    // Sixteen matrix instructions -- P V of tile t-1, then the scores of tile t+1 -- each followed by
+    // its share of tile t's exponentials; the V fragments of tile t are requested in between, into
+    // the registers the first eight have released.
+    // (after the last tile the score product reads a stage that holds no tile: the result is dropped)
+    float arg[16], pe[16];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) s_next[e] = 0.f;
+    for (int e = 0; e < 16; ++e) arg[e] = fmaf(s_cur[e], sc, neg_ref);
+    pv();
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pe[e] = __builtin_amdgcn_exp2f(arg[e]);
     {
       const unsigned char *skp = st_next + krow * ROWB;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(skp + (((2 * kk + lhi) ^ ksw) * 16));
-        s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s_next, 0, 0, 0);
-      }
+      for (int kk = KK / 2; kk < KK; ++kk)
+        kf[kk] = *reinterpret_cast<const bf16x8 *>(skp + (((2 * kk + lhi) ^ ksw) * 16));
     }
+    floatx16 s_next;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s_next[e] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+      s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s_next, 0, 0, 0);
+#pragma unroll
+    for (int e = 8; e < 16; ++e) pe[e] = __builtin_amdgcn_exp2f(arg[e]);
     float ps = 0.f;
     uint32_t pw[8];
 #pragma unroll
     for (int e = 0; e < 16; e += 2) {
-      const float p0 = __builtin_amdgcn_exp2f(fmaf(s_cur[e], sc, neg_ref));
-      const float p1 = __builtin_amdgcn_exp2f(fmaf(s_cur[e + 1], sc, neg_ref));
-      pw[e >> 1] = pack_bf16(p0, p1);
-      ps += p0 + p1;  // (the rounding of p to bf16 is unbiased: the sum takes the unrounded values)
+      pw[e >> 1] = pack_bf16(pe[e], pe[e + 1]);
+      ps += pe[e] + pe[e + 1];  // (the rounding of p to bf16 is unbiased: the sum takes the unrounded values)
     }
-    ps += __shfl_xor(ps, 32, WAVE);
+    {
+      const unsigned char *svp = st + T::REGION + vrow * ROWB + 8 * (lane % 4);
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const unsigned char *p = svp + ks * 16 * ROWB + (((db * 2 + hb) ^ vsw) * 32);
+          const shortx4 g0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(p));
+          const shortx4 g1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(p + 8 * ROWB));
+          const shortx8 av = __builtin_shufflevector(g0, g1, 0, 1, 2, 3, 4, 5, 6, 7);
+          vf[ks][db] = __builtin_bit_cast(bf16x8, av);
+        }
+    }
+    // instruction order
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // P V product
+      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // scale + shift of two scores
+      __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);  // an exponential
+      if (i == 3) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);  // the other four K reads
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // score product
+      __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);  // an exponential
+      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // rounding and sum
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);   // the V reads of tile t
+    ps = xhalf_sum(ps);
     l_run += ps;
-    bf16x8 pf[2];
     {
       const uint4 v0{pw[0], pw[1], pw[2], pw[3]}, v1{pw[4], pw[5], pw[6], pw[7]};
       pf[0] = __builtin_bit_cast(bf16x8, v0);
       pf[1] = __builtin_bit_cast(bf16x8, v1);
     }
-
-    // instruction order: one score product, its next operand read, and a share of the exponentials
-#pragma unroll
-    for (int i = 0; i < KK; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // matrix product
-      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // scale + shift of two scores
-      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);  // their exponentials
-      __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);  // rounding and sum of an earlier pair
-    }
-
-    // O^T += V^T P^T over the wave's 32 keys of tile t
-    const unsigned char *svp = st + T::REGION + vrow * ROWB + 8 * (lane % 4);
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const unsigned char *p = svp + ks * 16 * ROWB + (((db * 2 + hb) ^ vsw) * 32);
-        typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
-        const shortx4 g0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(p));
-        const shortx4 g1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(p + 8 * ROWB));
-        typedef short shortx8 __attribute__((ext_vector_type(8)));
-        const shortx8 av = __builtin_shufflevector(g0, g1, 0, 1, 2, 3, 4, 5, 6, 7);
-        const bf16x8 vf = __builtin_bit_cast(bf16x8, av);
-        acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ks], acc_o[db], 0, 0, 0);
-      }
     s_cur = s_next;
+  };
+  {
+    int t = 0;
+    const int n_steady = n_tiles - NS;  // tiles with a further fetch of a tile that is not the last (so: a full one)
+    for (; t < n_steady; ++t) body(t, std::true_type{});
+    for (; t < n_tiles; ++t) body(t, std::false_type{});
   }
+  pv();  // the last tile's
   }
   __syncthreads();  // every wave is done with the last tile: the stages become merge scratch
 

@@ -107,6 +107,14 @@ __device__ __forceinline__ void dma16(const void *g, uint32_t lds_base) {
                : "memory", "m0");
 }
 
+// The same copy with a wave-uniform base address (held in scalar registers) and a 32-bit byte
+// offset per lane: no 64-bit vector address arithmetic per copy.
+__device__ __forceinline__ void dma16_s(const void *sbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_base), "v"(voff), "s"(sbase)
+               : "memory", "m0");
+}
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
