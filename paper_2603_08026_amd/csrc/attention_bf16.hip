@@ -545,8 +545,12 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
   // fragments of tile t at the end, into registers the products have released.  No product waits
   // for an LDS read issued right before it, and the vector ALU works while the matrix pipe does.
   // STEADY: the tile fetched in this iteration is a full one and no key of tile t lies past the end.
-  auto body = [&](int t, auto steady_c) {
+  // STAGE: the LDS stage of tile t when the caller knows it at compile time (the loop is unrolled over
+  // the stages, so that the operand reads are a loop-invariant lane address plus an immediate), else -1.
+  auto body = [&](int t, auto steady_c, auto stage_c) {
     constexpr bool STEADY = decltype(steady_c)::value;
+    constexpr int STAGE = decltype(stage_c)::value;
+    const int sidx = STAGE >= 0 ? STAGE : t % NS;
     if (STEADY) {
       wait_vmcnt<(NS - 3) * LPW>();
     } else {
@@ -556,8 +560,8 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
     __syncthreads();  // tile t+1 is in LDS (all waves' parts); everyone is done with tile t-1's stage
     if (STEADY) issue_full(t + NS - 1);
     else if (t + NS - 1 < n_tiles) issue(t + NS - 1);
-    const unsigned char *st = smem_raw + (size_t)(t % NS) * T::STAGE_BYTES;
-    const unsigned char *st_next = smem_raw + (size_t)((t + 1) % NS) * T::STAGE_BYTES;
+    const unsigned char *st = smem_raw + (size_t)sidx * T::STAGE_BYTES;
+    const unsigned char *st_next = smem_raw + (size_t)((sidx + 1) % NS) * T::STAGE_BYTES;
     const int k0 = k_lo + t * TK;
 
     bf16x8 kf[KK];
@@ -628,13 +632,19 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
       s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s_next, 0, 0, 0);
 #pragma unroll
     for (int e = 8; e < 16; ++e) pe[e] = __builtin_amdgcn_exp2f(arg[e]);
-    float ps = 0.f;
+    // the row sum is taken over the rounded probabilities, the values the P V product uses
+    // (one two-element dot product with (1, 1) per register instead of two additions)
+    float ps0 = 0.f, ps1 = 0.f;
     uint32_t pw[8];
+    const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3f803f80u);
 #pragma unroll
-    for (int e = 0; e < 16; e += 2) {
+    for (int e = 0; e < 16; e += 4) {
       pw[e >> 1] = pack_bf16(pe[e], pe[e + 1]);
-      ps += pe[e] + pe[e + 1];  // (the rounding of p to bf16 is unbiased: the sum takes the unrounded values)
+      pw[(e >> 1) + 1] = pack_bf16(pe[e + 2], pe[e + 3]);
+      ps0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pw[e >> 1]), ones, ps0, false);
+      ps1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pw[(e >> 1) + 1]), ones, ps1, false);
     }
+    float ps = ps0 + ps1;
     {
       const unsigned char *svp = st + T::REGION + vrow * ROWB + 8 * (lane % 4);
 #pragma unroll
@@ -660,7 +670,7 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
     for (int i = 0; i < 8; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // score product
       __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);  // an exponential
-      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // rounding and sum
+      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // rounding and sum
     }
     __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);   // the V reads of tile t
     ps = xhalf_sum(ps);
@@ -675,8 +685,16 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
   {
     int t = 0;
     const int n_steady = n_tiles - NS;  // tiles with a further fetch of a tile that is not the last (so: a full one)
-    for (; t < n_steady; ++t) body(t, std::true_type{});
-    for (; t < n_tiles; ++t) body(t, std::false_type{});
+    using dyn = std::integral_constant<int, -1>;
+    static_assert(NS == 4, "the unrolled loop names the four stages");
+    for (; t + NS <= n_steady; t += NS) {  // t % NS == 0 here
+      body(t, std::true_type{}, std::integral_constant<int, 0>{});
+      body(t + 1, std::true_type{}, std::integral_constant<int, 1>{});
+      body(t + 2, std::true_type{}, std::integral_constant<int, 2>{});
+      body(t + 3, std::true_type{}, std::integral_constant<int, 3>{});
+    }
+    for (; t < n_steady; ++t) body(t, std::true_type{}, dyn{});
+    for (; t < n_tiles; ++t) body(t, std::false_type{}, dyn{});
   }
   pv();  // the last tile's
   }
