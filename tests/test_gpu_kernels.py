@@ -210,6 +210,31 @@ def test_partial_attention(dtype, gqa, dh, B, L, counts):
     lay.close()
 
 
+@pytest.mark.parametrize("B,L,counts", [(1, 1100, [150]), (2, 300, [130, 40])])
+def test_partial_attention_with_a_moving_softmax_reference(B, L, counts):
+    """Keys grow along the sequence, so the largest score of a key tile keeps exceeding the running
+    reference of the online softmax by more than the kernel's lazy threshold: the accumulator and
+    the pending product of the previous tile are rescaled in the middle of the key sweep, over
+    full tiles, a ragged last tile, query tiles with idle waves and several key splits."""
+    _say("partial_attention, growing keys", B, L, counts)
+    dtype, dh = "bf16", 128
+    s = small_shape(dtype, False, dh)
+    lay = Layer.from_shape(s, B, L)
+    idx, off = rand_rows(31, B, L, counts)
+    M = idx.size
+    q = _vals(32, (M, s.n_heads, dh), dtype, 1.5)
+    ramp = (1.0 + 5.0 * np.arange(L, dtype=np.float32) / L).reshape(1, L, 1, 1)
+    k = W.round_bf16(_vals(33, (B, L, s.n_kv_heads, dh), "f32", 1.5) * ramp)
+    v = _vals(34, (B, L, s.n_kv_heads, dh), dtype)
+    ref = O.partial_attention(q, k, v, idx, B, L)
+    rows = lay.make_list(idx, off, cap=M)
+    out = torch.zeros(M, s.dq, dtype=lay.k.dtype, device="cuda")
+    lay.ctx.partial_attention(to_device(q, dtype), to_device(k, dtype), to_device(v, dtype), rows, B, L, out)
+    torch.cuda.synchronize()
+    assert_close(to_host(out), ref, TOL[dtype], "context rows")
+    lay.close()
+
+
 def test_partial_attention_special_cases():
     _say("partial_attention special cases")
     s = small_shape("f32")
