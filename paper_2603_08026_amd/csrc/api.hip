@@ -217,7 +217,8 @@ AttnArgs attn_args(dyllm_ctx *ctx, const void *q, const void *k, const void *v, 
   a.key_offsets = nullptr; a.lse_out = nullptr; a.c_commit = nullptr; a.cos_part = nullptr;
   a.B = B; a.L = L; a.H = c.n_heads; a.Hkv = c.n_kv_heads; a.dh = c.head_dim;
   const int rows_per_seq = offsets ? (rows.cap + B - 1) / B : L;
-  attention_plan(dt(ctx), B, L, c.n_heads, c.head_dim, rows.cap, rows_per_seq, ctx->part_elems, &a);
+  attention_plan(dt(ctx), B, L, c.n_heads, c.head_dim, rows.cap, rows_per_seq, ctx->part_elems, &a,
+                 c.n_heads / c.n_kv_heads);
   a.partial = partial;
   a.part_o = ctx->part_o; a.part_ml = ctx->part_ml; a.out = out;
   return a;
@@ -405,7 +406,7 @@ int enqueue_approx_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
     AttnArgs a = attn_args(ctx, ctx->qs, ctx->ksal, ctx->dc, all, win.offsets, B, L, nullptr, 1);
     // key splits over the longest possible candidate run; the query side still walks sequences of L
     attention_plan(dt(ctx), B, lk_max, c.n_heads, c.head_dim, all.cap, win.offsets ? (all.cap + B - 1) / B : L,
-                   ctx->part_elems, &a);
+                   ctx->part_elems, &a, c.n_heads / c.n_kv_heads);
     a.q_by_token = by_token;
     a.key_offsets = idx_in->offsets;
     launch_attention(dt(ctx), a, s);

@@ -162,7 +162,7 @@ void launch_attn_finalize(DType t, const AttnArgs &a, void *c_cache, float tau, 
 // (sequence, head, query tile) triples; the splits' partials cost HBM traffic and a merge, so no more
 // than that.  Bounded by the partial buffer and by one key tile per split.
 void attention_plan(DType t, int B, int L, int H, int dh, int cap, int rows_per_seq, size_t part_elems,
-                    AttnArgs *a) {
+                    AttnArgs *a, int grouped_heads) {
   const int BK = (t == F32) ? 64 : 128;
   const int n_opt = (t == F32) ? 1 : 2;
   const int bq_opt[2] = {(t == F32) ? 16 : 128, 64};
@@ -173,11 +173,17 @@ void attention_plan(DType t, int B, int L, int H, int dh, int cap, int rows_per_
   // Once 128-row tiles alone fill the chip (two workgroups per CU) they are taken at any row count:
   // waves without a query skip the products, and the 64-row kernel holds one workgroup per CU only
   // (measured at about 66 rows in each of 16 sequences, 32 heads: 72 us against 116 us).
+  // The head_dim-128 bf16 kernel folds the query heads of a KV group into the rows of a tile: its
+  // tiles are counted over rows x group per KV head.
   const long target = 128;
-  const long tiles128 = (long)((rows_per_seq + 127) / 128) * B * H;
+  const int Hkv = H / (grouped_heads > 0 ? grouped_heads : 1);
+  const bool grouped = (t != F32) && dh == 128 && grouped_heads > 1;
+  const long rows_t = grouped ? (long)rows_per_seq * grouped_heads : rows_per_seq;  // packed rows per sequence
+  const long heads_t = grouped ? Hkv : H;
+  const long tiles128 = ((rows_t + 127) / 128) * B * heads_t;
   const int best_bq = (n_opt == 1) ? bq_opt[0]
-                                   : ((rows_per_seq > 80 && tiles128 >= target) || tiles128 >= 2 * 256 ? 128 : 64);
-  long tiles = (long)((rows_per_seq + best_bq - 1) / best_bq) * B * H;
+                                   : ((rows_t > 80 && tiles128 >= target) || tiles128 >= 2 * 256 ? 128 : 64);
+  long tiles = ((rows_t + best_bq - 1) / best_bq) * B * heads_t;
   if (tiles < 1) tiles = 1;  // empty list
   const int best_s = (int)((target + tiles - 1) / tiles);
   int s = best_s;

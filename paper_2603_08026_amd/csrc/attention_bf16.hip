@@ -389,20 +389,30 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
   constexpr int DH = T::DH, NW = T::NW, WK = T::WK, BQ = T::BQ, TK = T::TK, ROWB = T::ROWB, NS = T::NS,
                 DB = T::DB, KK = T::KK, LPW = T::LPW;
   extern __shared__ __align__(1024) unsigned char smem_raw[];
-  __shared__ int tile_info[3];
+  __shared__ int tile_info[4];
 
   const int tid = threadIdx.x, lane = tid % WAVE;
   const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
   const int l32 = lane % 32, lhi = lane / 32;
   const int wq = wave / WK, wk = wave % WK;
-  int tile, h, split;
-  if (!attn_work_item(a, q_tiles, &tile, &h, &split)) return;  // uniform
-  if (tid == 0) find_tile(a, BQ, tile, tile_info);
+  int tile, kvh, split;
+  if (!attn_work_item_grouped(a, q_tiles, &tile, &kvh, &split)) return;  // uniform
+  if (tid == 0) find_tile_grouped(a, BQ, tile, tile_info);
   __syncthreads();
   const int b = tile_info[0];
   if (b < 0) return;  // uniform: no such tile
-  const int j0 = tile_info[1], nq = tile_info[2];
-  const int kvh = h / (a.H / a.Hkv);
+  const int nq = tile_info[3];  // (row, head of the group) pairs in this tile
+  // this lane's query: packed row p = row * g + head of the group (rows past the end are clamped to
+  // the last one; their results are never stored)
+  const int grp = a.H / a.Hkv;
+  int jq, hq;
+  {
+    int r = wq * 32 + l32;
+    r = r < nq ? r : nq - 1;
+    const int p = tile_info[2] + r;
+    jq = tile_info[1] + p / grp;
+    hq = kvh * grp + p % grp;
+  }
   const int kbase = a.key_offsets ? a.key_offsets[b] : b * a.L;
   const int Lk = a.key_offsets ? a.key_offsets[b + 1] - kbase : a.L;
   const int k_lo = split * a.chunk, k_hi = min(Lk, k_lo + a.chunk);
@@ -415,10 +425,8 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
   // query operand: the wave's 32 queries, in registers for the whole key sweep
   bf16x8 qf[KK];
   {
-    int r = wq * 32 + l32;
-    r = r < nq ? r : nq - 1;  // rows past the end are clamped; their results are never stored
-    const size_t qrow = a.q_by_token ? (size_t)a.rows.idx[j0 + r] : (size_t)(j0 + r);
-    const bf16_t *qp = (const bf16_t *)a.q + (qrow * a.H + h) * DH + lhi * 8;
+    const size_t qrow = a.q_by_token ? (size_t)a.rows.idx[jq] : (size_t)jq;
+    const bf16_t *qp = (const bf16_t *)a.q + (qrow * a.H + hq) * DH + lhi * 8;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8 *>(qp + kk * 16);
   }
@@ -747,7 +755,7 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
     // stored values, overwrites the cached columns, and the two lanes of a query leave the head's sums.
     float dot = 0.f, na = 0.f, nb = 0.f;
     const bool live = r < nq;  // (lanes past the tile's last row take part in the shuffle only)
-    const int j = j0 + (live ? r : 0);
+    const int j = jq, h = hq;
     if (live) {
       const size_t tok = a.rows.idx ? (size_t)a.rows.idx[j] : (size_t)j;
       bf16_t *crow = (bf16_t *)a.c_commit + (tok * a.H + h) * DH + 4 * lhi;
@@ -785,7 +793,7 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
     return;
   }
   if (r >= nq) return;
-  const int j = j0 + r;
+  const int j = jq, h = hq;
   if (a.splits == 1 && !a.partial) {
     bf16_t *out = (bf16_t *)a.out + ((size_t)j * a.H + h) * DH + 4 * lhi;
     const float inv = 1.0f / l_run;
@@ -823,8 +831,8 @@ template <int WQ, int WK> void launch_dma(const AttnArgs &a, hipStream_t s) {
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::LDS_BYTES);
     done = true;
   }
-  const int q_tiles = max_q_tiles(a, T::BQ);
-  k_attn_bf16_dma<WQ, WK><<<attn_grid(a, q_tiles), T::NT, T::LDS_BYTES, s>>>(a, q_tiles);
+  const int q_tiles = max_q_tiles_grouped(a, T::BQ);
+  k_attn_bf16_dma<WQ, WK><<<attn_grid_grouped(a, q_tiles), T::NT, T::LDS_BYTES, s>>>(a, q_tiles);
 }
 
 template <int DH, int WQ, int NW, int QB> void launch_cfg(const AttnArgs &a, hipStream_t s) {

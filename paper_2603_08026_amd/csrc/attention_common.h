@@ -78,6 +78,70 @@ __device__ __forceinline__ bool attn_work_item(const AttnArgs &a, int q_tiles, i
   return true;
 }
 
+// ---- grouped form (head_dim 128 kernel): the g = H / Hkv query heads that share a KV head are
+// folded into the query rows of a tile.  Per sequence and KV head the "packed rows" are the pairs
+// (row of the list, head of the group), numbered p = row * g + head: a tile is BQ consecutive
+// packed rows, so a workgroup streams the keys and values of its KV head once for up to BQ
+// (row, head) pairs instead of once per head, and ragged row counts leave g times fewer idle waves.
+// With g = 1 this is the plain form above.
+inline int max_q_tiles_grouped(const AttnArgs &a, int BQ) {
+  const int g = a.H / a.Hkv;
+  if (!a.offsets) return a.B * ((a.L * g + BQ - 1) / BQ);
+  const long t = ((long)a.rows.cap * g + BQ - 1) / BQ + a.B;
+  return t < 1 ? 1 : (int)t;
+}
+inline int attn_grid_grouped(const AttnArgs &a, int q_tiles) {
+  const long items = (long)q_tiles * a.Hkv * a.splits;
+  return (int)((items + ATTN_XCD - 1) / ATTN_XCD) * ATTN_XCD;
+}
+// Tile number -> info[0] = sequence (or -1), info[1] = index of the sequence's first row in the row
+// list, info[2] = first packed row of the tile, info[3] = packed rows in the tile.  One thread.
+__device__ inline void find_tile_grouped(const AttnArgs &a, int BQ, int tile, int *info) {
+  const int g = a.H / a.Hkv;
+  info[0] = -1;
+  info[1] = info[2] = info[3] = 0;
+  if (!a.offsets) {
+    const int per = (a.L * g + BQ - 1) / BQ;
+    const int b = tile / per, t = tile % per;
+    if (b < a.B) {
+      info[0] = b;
+      info[1] = b * a.L;
+      info[2] = t * BQ;
+      info[3] = min(BQ, a.L * g - t * BQ);
+    }
+    return;
+  }
+  const int total = min(a.offsets[a.B], a.rows.cap);
+  int t = tile;
+  for (int b = 0; b < a.B; ++b) {
+    const int lo = min(a.offsets[b], total), hi = min(a.offsets[b + 1], total);
+    const int np = (hi - lo) * g;
+    const int nt = (np + BQ - 1) / BQ;
+    if (t < nt) {
+      info[0] = b;
+      info[1] = lo;
+      info[2] = t * BQ;
+      info[3] = min(BQ, np - t * BQ);
+      return;
+    }
+    t -= nt;
+  }
+}
+// Work item of a 1-D launch over (key split, KV head, tile of packed rows), XCD-aware as above.
+__device__ __forceinline__ bool attn_work_item_grouped(const AttnArgs &a, int q_tiles, int *tile, int *kvh,
+                                                       int *split) {
+  const int items = q_tiles * a.Hkv * a.splits;
+  const int per_xcd = (items + ATTN_XCD - 1) / ATTN_XCD;
+  const int p = blockIdx.x;
+  const int w = (p % ATTN_XCD) * per_xcd + p / ATTN_XCD;
+  if (p / ATTN_XCD >= per_xcd || w >= items) return false;
+  *tile = w % q_tiles;
+  const int rest = w / q_tiles;
+  *kvh = rest % a.Hkv;
+  *split = rest / a.Hkv;
+  return true;
+}
+
 void launch_attention_f32(DType t, const AttnArgs &a, hipStream_t s);
 void launch_attention_bf16(const AttnArgs &a, hipStream_t s);
 void launch_attn_combine(DType t, const AttnArgs &a, hipStream_t s);

@@ -99,9 +99,10 @@ void launch_attn_finalize(DType t, const AttnArgs &a, void *c_cache, float tau, 
                           uint8_t *flag_out, int32_t *out_idx, int32_t *out_offsets, int out_cap,
                           int32_t *status, int32_t *counter, hipStream_t s);
 // Chooses the query tile, the number of key splits and the keys per split for a call (host);
-// rows_per_seq = expected query rows per sequence (capacity / B for a row list, L for a dense step).
+// rows_per_seq = expected query rows per sequence (capacity / B for a row list, L for a dense step);
+// grouped_heads = query heads per KV head.
 void attention_plan(DType t, int B, int L, int H, int dh, int cap, int rows_per_seq, size_t part_elems,
-                    AttnArgs *a);
+                    AttnArgs *a, int grouped_heads);
 
 // ---- GEMMs  C[m,n] = sum_k A[m,k] * W[n,k]  (W [N,K]: row-major for fp32, 32-row panels for bf16) --
 struct GemmA {
