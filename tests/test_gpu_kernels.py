@@ -187,6 +187,8 @@ def test_qkv_refresh(dtype, gqa, dh, bias, counts):
     ("bf16", True, 64, 2, 333, [65, 129]),
     ("bf16", False, 128, 1, 1024, [106]),
     ("bf16", True, 128, 1, 77, [77]),
+    ("bf16", True, 128, 3, 200, [100, 0, 37]),   # grouped heads folded into ragged tiles, an empty sequence
+    ("bf16", True, 128, 2, 1100, [19, 150]),     # the same over several key splits of many tiles
 ])
 def test_partial_attention(dtype, gqa, dh, B, L, counts):
     _say("partial_attention", dtype, gqa, dh, B, L, counts)
