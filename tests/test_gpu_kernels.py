@@ -146,7 +146,9 @@ def test_compact_capacity_overflow_is_reported():
     ("f32", False, 64, False, [70, 0, 5]), ("f32", True, 128, True, [70, 0, 5]),
     ("bf16", False, 128, False, [70, 0, 5]), ("bf16", True, 64, True, [70, 0, 5]),
     # few rows: the weight-streaming GEMM leaves out the activation copies of absent row blocks
-    ("bf16", False, 128, True, [20, 0, 25]), ("bf16", True, 64, False, [3, 0, 9])])
+    ("bf16", False, 128, True, [20, 0, 25]), ("bf16", True, 64, False, [3, 0, 9]),
+    # 129 .. 320 rows: the 256-row weight-streaming tile, alone and with a short second row tile
+    ("bf16", False, 128, True, [90, 0, 80]), ("bf16", True, 64, False, [90, 88, 90])])
 def test_qkv_refresh(dtype, gqa, dh, bias, counts):
     _say("qkv_refresh", dtype, gqa, dh, bias, counts)
     s = small_shape(dtype, gqa, dh)
@@ -359,14 +361,17 @@ def test_error_paths_do_not_launch():
     lay.close()
 
 
-@pytest.mark.parametrize("ffn,rows", [(640, [70, 40]), (384, [101, 9]), (1024, [5, 0]), (384, [30, 20]), (640, [33, 31])])
+@pytest.mark.parametrize("ffn,rows", [(640, [70, 40]), (384, [101, 9]), (1024, [5, 0]), (384, [30, 20]), (640, [33, 31]),
+                                      # 129 .. 320 rows: one 256-row tile, and a short second one
+                                      (640, [150, 100]), (384, [129, 0]), (1024, [200, 119]), (384, [256, 1])])
 def test_salient_ffn_weight_streaming_tiles(ffn, rows):
-    """bf16, at most 128 rows: gate|up tiles hold 48 + 48 (F a multiple of 48) or 64 + 64 columns and
-    SwiGLU is applied inside the GEMM; the widths here reach both forms and several column tiles."""
+    """bf16, at most 320 rows: gate|up tiles hold 48 + 48 (F a multiple of 48) or 64 + 64 columns and
+    SwiGLU is applied inside the GEMM; the widths here reach both forms and several column tiles, the
+    row counts the 128-row and the 256-row tile."""
     _say("salient_ffn streaming tiles", ffn, rows)
     s = W.LayerShape(hidden=256, n_heads=4, n_kv_heads=4, head_dim=64, ffn=ffn, dtype="bf16", rope_theta=10000.0)
     cfg = oracle_cfg(s)
-    B, L = 2, 150
+    B, L = 2, max(150, max(rows) + 4)
     lay = Layer.from_shape(s, B, L)
     w = rand_weights(s, 61)
     lay.set_weights(w)
