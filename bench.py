@@ -325,16 +325,21 @@ def sweep_entry(wl, torch, np, K, Wu, dense_iters):
     """One line of the sweep: sparse step, both dense steps, dominant stage and its roofline fraction."""
     s = wl.shape
     esz = 4 if s.dtype == "f32" else 2
-    b = Bench(wl, "sparse", torch, np, host_inputs=False, n_sparse=Wu + K)
+    # One layer: the stage-timing pass repeats the timed steps from a snapshot of the caches.  A stack
+    # (whose snapshot would be tens of GB) times its stages on the NEXT K steps instead: repeating
+    # steps on caches that have already seen them would select fewer rows in the deeper layers.
+    stack = wl.n_layers > 1
+    b = Bench(wl, "sparse", torch, np, host_inputs=False, n_sparse=Wu + (2 * K if stack else K))
     b.warm_caches()
     b.run(range(Wu))
-    snap = b.snapshot() if wl.n_layers == 1 else None
+    snap = None if stack else b.snapshot()
     t_step = b.time_sparse(Wu, K)
     if snap is not None:
         b.restore(snap)
-    _, stage_ms, _ = b.time_stages(Wu, K)
+    s0 = Wu + K if stack else Wu
+    _, stage_ms, _ = b.time_stages(s0, K)
     t_dense = b.time_dense(dense_iters)
-    m_in = float(np.mean([m for _, _, m in b.steps[Wu:Wu + K]]))
+    m_in = float(np.mean([m for _, _, m in b.steps[s0:s0 + K]]))
     b.close()
     del b, snap
     torch.cuda.empty_cache()
