@@ -13,13 +13,14 @@
 //                    8*ks+i, i.e. key 16*ks + 8*(i/4) + 4*(l/32) + i%4 -- the V^T operand is read
 //                    with the same key order (two 8-byte LDS reads), and a matrix product does not
 //                    care in which order k is summed as long as both operands agree.
-// A workgroup of NW waves owns BQ = 32*QB*WQ query rows of one (sequence, head): WQ wave rows of QB
-// blocks of 32 queries each; the keys of a tile are split over the WK = NW/WQ wave columns (32 keys
-// each), whose partial (max, sum, output) are merged through LDS at the end.  For head_dim 128 a wave
-// holds one query block (QB = 1) and a workgroup has 8 waves: about 150 registers per lane, so two
-// waves share a SIMD and the softmax arithmetic of one overlaps the matrix products of the other
-// (two blocks per wave need more than 256 registers, one wave per SIMD, everything serialised).
-// K/V tiles are double-buffered in LDS with a register-staged prefetch.
+// Two kernels.  k_attn_bf16 (head_dim 64): a workgroup of NW waves owns BQ = 32*QB*WQ query rows of
+// one (sequence, head): WQ wave rows of QB blocks of 32 queries each; the keys of a tile are split
+// over the WK = NW/WQ wave columns (32 keys each), whose partial (max, sum, output) are merged
+// through LDS at the end; K/V tiles are double-buffered in LDS with a register-staged prefetch and V
+// is transposed while it is written.  k_attn_bf16_dma (head_dim 128, further down): K/V tiles arrive
+// by asynchronous global -> LDS copies into four stages, V^T comes from the LDS transpose read, a
+// wave holds one block of 32 queries (two waves per SIMD), the loop runs three tiles deep, and the
+// query heads of a KV group are folded into the rows of a tile.
 // The key range of a sequence can additionally be split over workgroups (few query rows): then
 // un-normalised partials go to global memory and k_attn_combine merges them.
 #include "attention_common.h"
