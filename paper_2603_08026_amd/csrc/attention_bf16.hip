@@ -351,7 +351,11 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a, int q_tiles) 
 //     names the 8 bytes of row key0 + j/4 at columns dh0 + 4*(j%4) .. +3 and lane i receives column
 //     dh0 + i of the rows key0 .. key0+3 -- four consecutive keys of one dh, which is exactly one half
 //     of the operand in the key order the P^T registers have.  The 32-byte pair p of row r sits at
-//     pair position p ^ (r % 8): the 4 rows x 64 bytes that 32 lanes read hit every bank once.
+//     pair position p ^ 2*(r % 4).  32 lanes read at a time: two groups of 16 (column pairs 2*db and
+//     2*db + 1), each 4 consecutive rows x 32 bytes; a pair position is one octet of the 64 banks, so
+//     the even pair lands on the four even-or-odd octets 2*db ^ {0, 2, 4, 6} and the odd pair on the
+//     other four -- every bank once (SQ_LDS_BANK_CONFLICT = 0; with p ^ (r % 8) both groups fell on
+//     the same four octets and every read took twice its cycles).
 
 // value of the lane 32 away combined with this lane's (v_permlane32_swap: no LDS round trip)
 __device__ __forceinline__ float xhalf_max(float x) {
@@ -453,7 +457,7 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
       int key = kbase + row;
       key = key < k_hi ? key : k_hi - 1;
       const int ck = cpos ^ (row & 15);
-      const int cv = (((cpos >> 1) ^ (row & 7)) << 1) | (cpos & 1);
+      const int cv = (((cpos >> 1) ^ ((row & 3) << 1)) << 1) | (cpos & 1);
       dma16(kc + (size_t)key * kv_stride + ck * 8, sb + (uint32_t)ii * 1024u);
       dma16(vc + (size_t)key * kv_stride + cv * 8, sb + (uint32_t)T::REGION + (uint32_t)ii * 1024u);
     }
@@ -465,7 +469,7 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
   for (int i = 0; i < LPW / 2; ++i) {
     const int ii = i * NW + wave, row = ii * 4 + r4;
     off_k[i] = (uint32_t)(((size_t)row * kv_stride + (cpos ^ (row & 15)) * 8) * 2);
-    off_v[i] = (uint32_t)(((size_t)row * kv_stride + (((((cpos >> 1) ^ (row & 7)) << 1) | (cpos & 1)) * 8)) * 2);
+    off_v[i] = (uint32_t)(((size_t)row * kv_stride + (((((cpos >> 1) ^ ((row & 3) << 1)) << 1) | (cpos & 1)) * 8)) * 2);
   }
   auto uniform_ptr = [](const void *p) {
     const uint64_t u = (uint64_t)p;
@@ -487,7 +491,7 @@ __global__ __launch_bounds__(64 * WQ * WK_, 2) void k_attn_bf16_dma(AttnArgs a, 
   // per-lane constants of the operand reads
   const int krow = wk * 32 + l32, ksw = l32 & 15;
   const int vq = (lane % 16) / 4;                       // row of this lane inside a 4-key group
-  const int vrow = wk * 32 + 4 * lhi + vq, vsw = (4 * lhi + vq) & 7, hb = (lane / 16) & 1;
+  const int vrow = wk * 32 + 4 * lhi + vq, vsw = 2 * vq, hb = (lane / 16) & 1;  // (row % 4 = vq)
   const int key_lane = wk * 32 + 4 * lhi;
 
 #pragma unroll
