@@ -236,9 +236,9 @@ int enqueue_attention(dyllm_ctx *ctx, const void *q, const void *k, const void *
 // out-projection + residual, norm, SwiGLU FFN + residual, scatter into the output cache
 // [Alg. 3: out_proj / FFN / cache lines]
 int enqueue_ffn(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x, const void *c_all,
-                Rows rows, void *out_cache, hipStream_t s) {
+                Rows rows, void *out_cache, size_t n_tokens, hipStream_t s) {
   const dyllm_layer_cfg &c = ctx->cfg;
-  const int splits = launch_gemm_raw(dt(ctx), GemmA{c_all, rows.idx, ctx->dq}, rows, ctx->dq,
+  const int splits = launch_gemm_raw(dt(ctx), GemmA{c_all, rows.idx, ctx->dq, n_tokens}, rows, ctx->dq,
                                      wseg_one(w->wo, c.hidden), ctx->part_o, ctx->part_elems, s);
   prof_mark(ctx, ST_GEMM_OPROJ, s);
   launch_oproj_finalize(dt(ctx), ctx->part_o, splits, (size_t)rows.cap * c.hidden, x, w->g_ffn, rows,
@@ -324,7 +324,7 @@ int enqueue_sparse_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
   // idx_out is a subset of idx_in: its count never exceeds idx_in's capacity, which sizes the grids
   Rows rout = rows_of(idx_out, B);
   if (rout.cap > idx_in->cap) rout.cap = idx_in->cap;
-  rc = enqueue_ffn(ctx, w, x, cache->c, rout, cache->out, s);
+  rc = enqueue_ffn(ctx, w, x, cache->c, rout, cache->out, (size_t)B * L, s);
   ctx->prof_cur = nullptr;
   return rc;
 }
@@ -416,7 +416,7 @@ int enqueue_approx_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
   }
   launch_compact(ctx->flag, all, B, L, idx_out->idx, idx_out->offsets, idx_out->cap, ctx->status, ctx->scan, s);
   if ((rc = check_launch(ctx, "approx: saliency / compact"))) return rc;
-  return enqueue_ffn(ctx, w, x, cache->c, rows_of(idx_out, B), cache->out, s);
+  return enqueue_ffn(ctx, w, x, cache->c, rows_of(idx_out, B), cache->out, (size_t)B * L, s);
 }
 
 // out = ascending unique union of a and b (either may be null), kept to positions >= pos_lo
@@ -450,7 +450,7 @@ int enqueue_dense_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_laye
   }
   prof_mark(ctx, ST_SALIENCY, s);
   prof_mark(ctx, ST_COMPACT, s);
-  rc = enqueue_ffn(ctx, w, x, cache->c, all, cache->out, s);
+  rc = enqueue_ffn(ctx, w, x, cache->c, all, cache->out, (size_t)B * L, s);
   ctx->prof_cur = nullptr;
   return rc;
 }
@@ -699,7 +699,7 @@ int dyllm_salient_ffn(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *
   if (x == out_cache) return fail(ctx, DYLLM_ERR_INVALID_ARG, "x aliases out_cache");
   if ((rc = check_bl(ctx, B, L))) return rc;
   if ((rc = check_list(ctx, rows_out, "rows_out"))) return rc;
-  return enqueue_ffn(ctx, w, x, c, rows_of(rows_out, B), out_cache, (hipStream_t)stream);
+  return enqueue_ffn(ctx, w, x, c, rows_of(rows_out, B), out_cache, (size_t)B * L, (hipStream_t)stream);
 }
 
 int dyllm_layer_step(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_layer_cache *cache,

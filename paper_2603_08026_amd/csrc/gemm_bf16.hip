@@ -9,16 +9,20 @@ using namespace mm;
 namespace {
 
 // Tile shapes per regime (rows = capacity of the row list):
-//  xlarge  256 x 256 tile (256 x (128+128) when gate and up are fused), 8 waves of 128 x 64, 2 LDS
-//          stages: a third fewer bytes per flop through the CU's L1 -> LDS path (measured at about
-//          54 bytes per clock and CU, which a 256 x 128 tile nearly saturates) and a quarter fewer
-//          LDS operand reads; taken when its coarser tiles still fill the rounds of the chip
+//  xlarge  256 x 256 tile (256 x (128+128) when gate and up are fused): a third fewer bytes per flop
+//          through the CU's L1 -> LDS path (measured at about 54 bytes per clock and CU, which a
+//          256 x 128 tile nearly saturates) and a quarter fewer LDS operand reads; taken when its
+//          coarser tiles still fill the rounds of the chip.  Four waves of 128 x 128 over a ring of
+//          five LDS slots when every operand can be addressed with 32-bit offsets, else 8 waves of
+//          128 x 64 over 2 LDS stages
 //  large   256 x 128 tile (256 x (64+64) when gate and up are fused), 8 waves, 2 LDS stages
 //  mid     128 x 128 tile, 4 waves, 2 stages (two workgroups per CU) for a few hundred rows
 //  skinny  all rows in one 128-row tile, 64-column tiles, 4 stages in flight and a K split so that
 //          about one workgroup per CU streams weights (weight-streaming-bound regime)
 typedef Shape<256, 256, 2, 4, false, 2> XLargeS;
 typedef Shape<256, 128, 2, 4, true, 2> XLargeD;
+typedef Shape<256, 256, 2, 2, false, 2> XLargeRingS;
+typedef Shape<256, 128, 2, 2, true, 2> XLargeRingD;
 typedef Shape<256, 128, 4, 2, false, 2> LargeS;
 typedef Shape<256, 64, 4, 2, true, 2> LargeD;
 typedef Shape<128, 128, 2, 2, false, 2> MidS;
@@ -65,6 +69,18 @@ double tile_rounds(int cap, long ncol, int sk) {
 // about 1.63 times as long as a large one (measured at many rounds).
 bool prefer_xlarge(int cap, int n_l, int n_x) {
   return 1.63 * tile_rounds(cap, n_x, 1) < tile_rounds(cap, n_l, 1);
+}
+
+// The ring loop addresses its operands with a scalar base and 32-bit byte offsets per lane: the rows
+// the activation operand can name, and each weight matrix, must span less than 4 GiB; a copy's 8
+// weight rows must lie in one matrix; at least three K slices per split.
+bool ring_ok(const GemmA &A, const Rows &rows, int K, const WSeg &seg, int n_rows_w, int splitk) {
+  const size_t a_rows = A.gather ? A.a_rows : (size_t)rows.cap;
+  const size_t lim = ((size_t)1 << 32) - ((size_t)1 << 20);
+  if (a_rows == 0 || a_rows * (size_t)A.lda * 2 >= lim) return false;
+  if ((size_t)n_rows_w * (size_t)K * 2 >= lim) return false;
+  if (seg.n_end[0] % 8 || seg.n_end[1] % 8) return false;
+  return K / BK / splitk >= RING_MIN_SLICES;
 }
 
 template <typename SH, typename Epi>
@@ -153,7 +169,8 @@ int gemm_bf16_raw(GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_
     return sk;
   }
   const LargePlan pl = plan_large(rows.cap, N, K, part_elems, N % XLargeS::BN == 0);
-  if (pl.xlarge) run_tiles<XLargeS>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s);
+  if (pl.xlarge && ring_ok(A, rows, K, seg, N, pl.splitk)) run_tiles<XLargeRingS>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s);
+  else if (pl.xlarge) run_tiles<XLargeS>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s);
   else run_tiles<LargeS>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s);
   return pl.splitk;
 }
@@ -173,8 +190,10 @@ void gemm_bf16_swiglu(GemmA A, Rows rows, int K, int N, const void *wg, const vo
     else
       run_tiles<SkinnyH128>(A, rows, K, 2 * N, seg, nullptr, EpiSwiGLUHalves<bf16_t, 64>{(bf16_t *)act, N}, 1, nullptr, s);
   } else if (rows.cap <= MID_MAX_ROWS) run_tiles<MidD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
-  else if (N % XLargeD::BN == 0 && prefer_xlarge(rows.cap, N / LargeD::BN, N / XLargeD::BN))
-    run_tiles<XLargeD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
+  else if (N % XLargeD::BN == 0 && prefer_xlarge(rows.cap, N / LargeD::BN, N / XLargeD::BN)) {
+    if (ring_ok(A, rows, K, wseg_one(wg, N), N, 1)) run_tiles<XLargeRingD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
+    else run_tiles<XLargeD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
+  }
   else run_tiles<LargeD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
 }
 
@@ -197,7 +216,9 @@ void gemm_bf16_down(GemmA A, Rows rows, int K, int N, const void *wd, const floa
   } else {
     const LargePlan pl = plan_large(rows.cap, N, K, part_elems, N % XLargeS::BN == 0);
     float *pp = pl.splitk > 1 ? part : nullptr;
-    if (pl.xlarge) run_tiles<XLargeS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, pl.splitk, pp, s);
+    if (pl.xlarge && ring_ok(A, rows, K, wseg_one(wd, N), N, pl.splitk))
+      run_tiles<XLargeRingS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, pl.splitk, pp, s);
+    else if (pl.xlarge) run_tiles<XLargeS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, pl.splitk, pp, s);
     else run_tiles<LargeS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, pl.splitk, pp, s);
     if (pl.splitk > 1) launch_down_finalize(BF16, part, pl.splitk, (size_t)rows.cap * N, h, rows, N, out, s);
   }

@@ -48,6 +48,12 @@ constexpr int ROWB = 128; // bytes per tile row and slice
 constexpr int N_XCD = 8;
 constexpr int WPANEL = 32;  // output rows per weight panel
 
+}  // namespace mm
+}  // namespace dy
+#include "gemm_bf16_ring.h"
+namespace dy {
+namespace mm {
+
 // Tile shape: BM x BN output tile, WAVES_M x WAVES_N waves, DUAL = two weight matrices per tile (fused
 // gate/up), NS LDS stages of one K slice each.
 template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, bool DUAL_, int NS_> struct Shape {
@@ -62,7 +68,9 @@ template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, bool DUAL_, int NS_> str
   static constexpr int B_LD = BN / (8 * NW);
   static constexpr int LPS = A_LD + NMAT * B_LD;  // copies per wave and slice
   static constexpr int A_BYTES = BM * ROWB, W_BYTES = NMAT * BN * ROWB;
-  static constexpr size_t LDS_BYTES = (size_t)NS * (A_BYTES + W_BYTES);
+  // four waves on a 256-row tile with 256 weight rows: full tiles run the five-slot ring loop
+  static constexpr bool RING = NW == 4 && BM == 256 && NMAT * BN == 256 && NS == 2;
+  static constexpr size_t LDS_BYTES = RING ? (size_t)RING_SLOTS * RING_SLOT : (size_t)NS * (A_BYTES + W_BYTES);
   // shapes with three or more stages (weight streaming) run the loop pipelined over slices
   static constexpr bool PIPE = NS >= 3;
   static_assert(NW == 4 || NW == 8, "four or eight waves per workgroup");
@@ -150,6 +158,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
     }
     // a column tile may span two of the stacked weight matrices: the matrix is looked up per row
     const bf16_t *wp[NMAT][SH::B_LD];
+    const bf16_t *wmat[SH::B_LD];  // start of the weight matrix row i's copy reads from
 #pragma unroll
     for (int i = 0; i < SH::B_LD; ++i) {
       const int nrow = (i * NW + wave) * 8 + r8;
@@ -171,6 +180,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
       // panel layout: slice kt of this row sits kt * (WPANEL * BK) elements further on
       const size_t woff = ((size_t)(nl / WPANEL) * (ldw / BK) + kbeg / BK) * (WPANEL * BK) + (nl % WPANEL) * BK + csrc * 8;
       wp[0][i] = wbase + woff;
+      wmat[i] = wbase;
       if (SH::DUAL)
         wp[NMAT - 1][i] = W2 + ((size_t)(n / WPANEL) * (ldw / BK) + kbeg / BK) * (WPANEL * BK) + (n % WPANEL) * BK + csrc * 8;
     }
@@ -280,6 +290,36 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
       if (SH::A_LD >= 4 && a_need <= 1) pipe_loop(std::integral_constant<int, 1>{});
       else if (SH::A_LD >= 2 && a_need <= SH::A_LD / 2) pipe_loop(std::integral_constant<int, (SH::A_LD >= 2 ? SH::A_LD / 2 : 1)>{});
       else pipe_loop(std::integral_constant<int, SH::A_LD>{});
+    } else if constexpr (SH::RING) {
+      // descriptors and 32-bit lane offsets of the wave's copies; a copy's 8 weight rows lie in one
+      // matrix (segment ends are multiples of 8), so its descriptor is wave-uniform
+      const __amdgpu_buffer_rsrc_t srd_a = make_srd(A, 0xfffffff0u);
+      __amdgpu_buffer_rsrc_t srd_w[8];
+      uint32_t va[8], vw[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) va[i] = (uint32_t)((const unsigned char *)ap[i] - (const unsigned char *)A);
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        const int t = c / SH::B_LD, i = c % SH::B_LD;
+        const bf16_t *base = t == 0 ? wmat[i] : W2;
+        const uint64_t b = (uint64_t)(uintptr_t)base;
+        const uint64_t bu = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
+                            (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+        srd_w[c] = make_srd((const void *)(uintptr_t)bu, 0xfffffff0u);
+        vw[c] = (uint32_t)((const unsigned char *)wp[t][i] - (const unsigned char *)base);
+      }
+      auto run_ring = [&](auto mbv_c) {
+        ring_tile<NMAT, NB, BN, decltype(mbv_c)::value>(acc, smem_raw, lds0, wave, srd_a, va, srd_w, vw,
+                                                       smem_raw + (wm0 + l32) * ROWB,
+                                                       smem_raw + (wn0 + l32) * ROWB, rd_off, KT);
+      };
+      // 32-row blocks of this wave that hold rows (wave-uniform); rows past the end are copied from
+      // row M-1 and their results are never stored
+      const int mbv = (M - (m0 + wm0) + 31) / 32;
+      if (mbv >= 3) run_ring(std::integral_constant<int, 4>{});
+      else if (mbv == 2) run_ring(std::integral_constant<int, 2>{});
+      else if (mbv == 1) run_ring(std::integral_constant<int, 1>{});
+      else run_ring(std::integral_constant<int, 0>{});
     } else if (NS == 2 && m0 + BM > M) {
       // A row tile that holds fewer than BM rows: copies of 8-row blocks past the end are left out,
       // and a wave multiplies only its 32-row blocks that hold rows (none at all for many waves), so
@@ -426,6 +466,44 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
             epi.store(j, tn * 64 + 32 + l32, acc[0][i][1][e], acc[0][i][3][e]);
           }
         }
+    } else if constexpr (Epi::PRELOAD) {
+      if (!split.part) {
+      // a 32-row block at a time: what the epilogue reads, then what it writes (two blocks in
+      // flight cost more registers than the four-wave shapes have left: measured slower)
+#pragma unroll
+      for (int i = 0; i < MB; ++i) {
+        float pre[16][NB];
+        int rowv[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
+          rowv[e] = (j < M && rows.idx) ? rows.idx[j] : j;
+#pragma unroll
+          for (int jn = 0; jn < NB; ++jn) pre[e][jn] = j < M ? epi.load(j, n0 + wn0 + jn * 32 + l32) : 0.f;
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
+          if (j < M) {
+#pragma unroll
+            for (int jn = 0; jn < NB; ++jn) epi.store(rowv[e], n0 + wn0 + jn * 32 + l32, acc[0][i][jn][e], pre[e][jn]);
+          }
+        }
+      }
+      } else {
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
+            if (j < M) {
+#pragma unroll
+              for (int jn = 0; jn < NB; ++jn)
+                split.part[(size_t)z * split.split_stride + (size_t)j * split.N + n0 + wn0 + jn * 32 + l32] =
+                    acc[0][i][jn][e];
+            }
+          }
+      }
     } else
 #pragma unroll
     for (int i = 0; i < MB; ++i)

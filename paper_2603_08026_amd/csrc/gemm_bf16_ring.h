@@ -1,0 +1,174 @@
+// Slice loop of the 256 x 256 bf16 GEMM tile with four waves (one per SIMD, 128 x 128 each, the
+// accumulators in the second register file) and a ring of five 32 KB LDS slots.
+//
+// Why a ring.  A K slice of the tile is 64 KB (A tile 32 KB + weight tile 32 KB), and two whole
+// slices are all that fit beside nothing else in the 160 KB of LDS.  With two stages, the copies of
+// slice kt+2 can only be issued once slice kt has been read out, and must have landed before slice
+// kt+1 is read out: the copy path runs empty before every barrier and is asked for a whole slice in a
+// burst after it (measured: 64 KB take about 3000 cycles to land that way, with or without matrix
+// work, against 2048 cycles of matrix instructions per slice).  Here the halves of a slice take
+// slots of their own, in the order A(0) W(0) A(1) W(1) A(2) ..., slot = position % 5.  There is one
+// barrier per slice, in its middle: by then a wave has the operands of the whole slice in registers
+// (128 of them), so the two slots of slice kt are free; W(kt+2) is copied into one during the second
+// half of slice kt and A(kt+3) into the other during the first half of slice kt+1 -- one copy after
+// every fourth matrix instruction, all the time -- and the eight newest copies stay in flight across
+// the barrier (s_waitcnt vmcnt(8) and a raw s_barrier: __syncthreads would wait for all of them).
+//
+// The copies are buffer loads with LDS destination: a scalar descriptor per source matrix, a 32-bit
+// byte offset per lane that is fixed for the tile, and the K walk as a scalar offset, so a copy costs
+// no vector address arithmetic between the matrix instructions (measured against per-lane 64-bit
+// addresses: 2150 against 2340 cycles per slice).  Lane offsets are 32 bits: the launcher takes this
+// kernel only when every operand spans less than 4 GiB.
+#pragma once
+#include <type_traits>
+#include "common.h"
+
+namespace dy {
+namespace mm {
+
+typedef __attribute__((address_space(3))) void lds_void_t;
+
+// lane i's 16 bytes at (descriptor base + voff + soff) -> LDS[lds_addr + 16 i]; lds_addr and soff
+// are wave-uniform.  Completion is tracked by vmcnt, in issue order.
+__device__ __forceinline__ void dma16_buf(__amdgpu_buffer_rsrc_t srd, uint32_t voff, uint32_t soff, uint32_t lds_addr) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(srd, (lds_void_t *)(uintptr_t)lds_addr, 16, voff, soff, 0, 0);
+}
+
+// descriptor of a raw byte buffer (no stride, no swizzle, 32-bit data format) that covers `bytes`
+// from p; reads past the end return zero instead of faulting
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_srd(const void *p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc((void *)p, 0, (int)bytes, 0x00020000);
+}
+
+constexpr uint32_t RING_SLOT = 32768;
+constexpr int RING_SLOTS = 5;
+constexpr int RING_MIN_SLICES = 3;
+
+// One tile: acc += A tile x W tile over KT >= 3 slices.
+//   srd_a / va[i]   descriptor and lane offsets of the wave's 8 A copies (8 tile rows each)
+//   srd_w[c] / vw[c] the same for its 8 weight copies (a copy's 8 rows lie in one weight matrix)
+//   rd_a / rd_w     this lane's operand-read addresses inside a slot (slot 0), without the chunk swizzle
+//   rd_off[s]       swizzled chunk offset of K step s
+// NMAT x NB column blocks of 32: block c = t * NB + j reads weight-tile rows (t * BN + wn0 + 32 j ...).
+// MBV = 32-row blocks of this wave that hold rows (4 in a full tile).  In a row tile with fewer than
+// 256 rows a wave multiplies only those, down to none: copies, waits and barriers are the same for
+// every wave, so such a tile costs about what its copies cost.
+template <int NMAT, int NB, int BN, int MBV, typename Acc>
+__device__ __forceinline__ void ring_tile(Acc &acc, const unsigned char *smem, uint32_t lds0, int wave,
+                                          __amdgpu_buffer_rsrc_t srd_a, const uint32_t (&va)[8],
+                                          const __amdgpu_buffer_rsrc_t (&srd_w)[8], const uint32_t (&vw)[8],
+                                          const unsigned char *rd_a, const unsigned char *rd_w,
+                                          const int (&rd_off)[4], int KT) {
+  static_assert(NMAT * NB == 4, "four column blocks per wave");
+  constexpr int ROW = 128, A_STEP = 128, W_STEP = 4096;  // bytes per tile row; K walk per slice
+  const uint32_t lds_w = lds0 + (uint32_t)wave * 1024u;
+  auto copy_a = [&](int i, int kt, int slot) {
+    dma16_buf(srd_a, va[i], (uint32_t)kt * A_STEP, lds_w + (uint32_t)slot * RING_SLOT + i * 4096u);
+  };
+  auto copy_w = [&](int c, int kt, int slot) {
+    dma16_buf(srd_w[c], vw[c], (uint32_t)kt * W_STEP, lds_w + (uint32_t)slot * RING_SLOT + c * 4096u);
+  };
+  auto w_row = [](int c) { return ((c / NB) * BN + (c % NB) * 32) * ROW; };
+  auto nxt = [](int s, int d) { const int t = s + d; return t >= RING_SLOTS ? t - RING_SLOTS : t; };
+
+  // fill the ring: A(0) W(0) A(1) W(1) A(2) into slots 0..4
+#pragma unroll
+  for (int i = 0; i < 8; ++i) copy_a(i, 0, 0);
+#pragma unroll
+  for (int c = 0; c < 8; ++c) copy_w(c, 0, 1);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) copy_a(i, 1, 2);
+#pragma unroll
+  for (int c = 0; c < 8; ++c) copy_w(c, 1, 3);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) copy_a(i, 2, 4);
+  wait_vmcnt<24>();  // slice 0 has landed (this wave's part)
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+
+  bf16x8 af[4][4], bfr[4][4];  // [K step][32-row block], [K step][column block]
+  // read x of a K step: A block x (x < 4) or column block x - 4; product q of a half slice: row
+  // block (q % 16) / 4, column block q % 4
+  auto has_read = [](int x) { return x < 4 ? x < MBV : MBV > 0; };
+  auto has_prod = [](int q) { return (q % 16) / 4 < MBV; };
+#pragma unroll
+  for (int i = 0; i < MBV; ++i) af[0][i] = *reinterpret_cast<const bf16x8 *>(rd_a + i * 32 * ROW + rd_off[0]);
+  if (MBV > 0) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) bfr[0][c] = *reinterpret_cast<const bf16x8 *>(rd_w + RING_SLOT + w_row(c) + rd_off[0]);
+  }
+
+  int slot_a = 0;  // slot of A(kt); W(kt) is in the next one
+  auto slice = [&](int kt, auto first_c, auto m1_c, auto m2_c) {
+    // FIRST: slice 0 (A(2) is already on its way); M1 / M2: slices kt+1 / kt+2 exist
+    constexpr bool FIRST = decltype(first_c)::value, M1 = decltype(m1_c)::value, M2 = decltype(m2_c)::value;
+    constexpr bool CA = !FIRST && M2;
+    const int slot_w = nxt(slot_a, 1), slot_a1 = nxt(slot_a, 2), slot_w1 = nxt(slot_a, 3), slot_a2 = nxt(slot_a, 4);
+    const unsigned char *sa = rd_a + (uint32_t)slot_a * RING_SLOT, *sb = rd_w + (uint32_t)slot_w * RING_SLOT;
+    // First half: products of K steps 0 and 1; operand reads of steps 1..3, one per product; the
+    // copies of A(kt+2) into the slot W(kt-1) left.
+#pragma unroll
+    for (int q = 0; q < 32; ++q) {
+      if (q < 24 && has_read(q % 8)) {
+        const int st = 1 + q / 8, x = q % 8;
+        if (x < 4) af[st][x] = *reinterpret_cast<const bf16x8 *>(sa + x * 32 * ROW + rd_off[st]);
+        else bfr[st][x - 4] = *reinterpret_cast<const bf16x8 *>(sb + w_row(x - 4) + rd_off[st]);
+      }
+      if (CA && q % 4 == 3) copy_a(q / 4, kt + 2, slot_a2);
+      if (has_prod(q)) {
+        const int i = (q % 16) / 4, c = q % 4;
+        acc[c / NB][i][c % NB] =
+            __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[q / 16][i], bfr[q / 16][c], acc[c / NB][i][c % NB], 0, 0, 0);
+      }
+    }
+    // instruction order: product, read, (copy) -- the scheduler left alone fetches each operand
+    // right before its use and bunches the copies
+#pragma unroll
+    for (int q = 0; q < 32; ++q) {
+      if (has_prod(q)) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (q < 24 && has_read(q % 8)) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      if (CA && q % 4 == 3) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+    }
+    // Middle: slice kt+1 has landed (the copies of A(kt+2) behind it may still be in flight), and
+    // with the barrier everyone's part of it; everyone has read slice kt out of its slots.
+    if (M1) {
+      if (M2) wait_vmcnt<8>();
+      else wait_vmcnt<0>();
+      wait_lgkmcnt0();
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+    }
+    // Second half: products of K steps 2 and 3, the copies of W(kt+2) into the slot A(kt) left, the
+    // operands of step 0 of slice kt+1.
+    const unsigned char *sa1 = rd_a + (uint32_t)slot_a1 * RING_SLOT, *sb1 = rd_w + (uint32_t)slot_w1 * RING_SLOT;
+#pragma unroll
+    for (int q = 0; q < 32; ++q) {
+      if (M1 && q >= 16 && q < 24 && has_read(q - 16)) {
+        const int x = q - 16;
+        if (x < 4) af[0][x] = *reinterpret_cast<const bf16x8 *>(sa1 + x * 32 * ROW + rd_off[0]);
+        else bfr[0][x - 4] = *reinterpret_cast<const bf16x8 *>(sb1 + w_row(x - 4) + rd_off[0]);
+      }
+      if (M2 && q % 4 == 3) copy_w(q / 4, kt + 2, slot_a);
+      if (has_prod(q)) {
+        const int i = (q % 16) / 4, c = q % 4;
+        acc[c / NB][i][c % NB] =
+            __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[2 + q / 16][i], bfr[2 + q / 16][c], acc[c / NB][i][c % NB], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < 32; ++q) {
+      if (has_prod(q)) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (M1 && q >= 16 && q < 24 && has_read(q - 16)) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      if (M2 && q % 4 == 3) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+    }
+    slot_a = slot_a1;
+  };
+  slice(0, std::true_type{}, std::true_type{}, std::true_type{});
+  int kt = 1;
+  for (; kt + 2 < KT; ++kt) slice(kt, std::false_type{}, std::true_type{}, std::true_type{});
+  slice(kt, std::false_type{}, std::true_type{}, std::false_type{});
+  slice(kt + 1, std::false_type{}, std::false_type{}, std::false_type{});
+}
+
+}  // namespace mm
+}  // namespace dy

@@ -17,6 +17,7 @@ namespace dy {
 struct EpiStoreF32 {
   static constexpr bool DUAL = false;
   static constexpr int INTERLEAVE = 0;
+  static constexpr bool PRELOAD = false;
   float *out;
   int ldo;
   __device__ __forceinline__ void operator()(int j, int row, int n, float acc, float) const {
@@ -28,6 +29,7 @@ struct EpiStoreF32 {
 template <typename T> struct EpiSwiGLU {
   static constexpr bool DUAL = true;
   static constexpr int INTERLEAVE = 0;
+  static constexpr bool PRELOAD = false;
   T *act;  // [cap, N]
   int N;
   __device__ __forceinline__ void operator()(int j, int row, int n, float gate, float up) const {
@@ -40,17 +42,26 @@ template <typename T> struct EpiSwiGLU {
 template <typename T> struct EpiDown {
   static constexpr bool DUAL = false;
   static constexpr int INTERLEAVE = 0;
+  // The residual is read before the result is written.  h and out may alias as far as the compiler
+  // knows, so element by element every load would wait for the store before it; the kernel instead
+  // loads a block's residuals (load) and then stores the block (store).
+  static constexpr bool PRELOAD = true;
   const float *h;  // [cap, N]
   T *out;          // [T, N]
   int N;
+  __device__ __forceinline__ float load(int j, int n) const { return h[(size_t)j * N + n]; }
+  __device__ __forceinline__ void store(int row, int n, float acc, float hv) const {
+    out[(size_t)row * N + n] = from_f<T>(hv + acc);
+  }
   __device__ __forceinline__ void operator()(int j, int row, int n, float acc, float) const {
-    out[(size_t)row * N + n] = from_f<T>(h[(size_t)j * N + n] + acc);
+    store(row, n, acc, load(j, n));
   }
 };
 
 template <typename T, int HALF> struct EpiSwiGLUHalves {
   static constexpr bool DUAL = false;
   static constexpr int INTERLEAVE = HALF;  // 48 (96-column tiles) or 64 (128-column tiles)
+  static constexpr bool PRELOAD = false;
   T *act;  // [cap, F]
   int F;
   // f = output column of the FFN's hidden layer

@@ -109,6 +109,9 @@ struct GemmA {
   const void *a;        // T-typed, row stride lda
   const int32_t *gather;  // nullptr, or row j of the GEMM reads a[gather[j], :]
   int lda;
+  // rows of the buffer `a` points to when `gather` is set (without it the row list's capacity bounds
+  // the rows read); 0 = unknown.  Kernels that address the operand with 32-bit offsets need it.
+  size_t a_rows = 0;
 };
 // Up to three weight matrices stacked along N (q | k | v); the bf16 kernels look the matrix up per
 // tile row, so a column tile may span two of them.
