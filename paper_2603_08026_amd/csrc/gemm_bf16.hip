@@ -66,9 +66,11 @@ double tile_rounds(int cap, long ncol, int sk) {
 }
 
 // 256-row tiles with n_l (large) or n_x (xlarge, twice as wide) column tiles: an xlarge tile takes
-// about 1.63 times as long as a large one (measured at many rounds).
-bool prefer_xlarge(int cap, int n_l, int n_x) {
-  return 1.63 * tile_rounds(cap, n_x, 1) < tile_rounds(cap, n_l, 1);
+// about 1.63 times as long as a large one with the eight-wave loop and about 1.45 times with the
+// four-wave ring loop (measured at many rounds).
+constexpr double XLARGE_COST = 1.63, XLARGE_RING_COST = 1.45;
+bool prefer_xlarge(int cap, int n_l, int n_x, bool ring) {
+  return (ring ? XLARGE_RING_COST : XLARGE_COST) * tile_rounds(cap, n_x, 1) < tile_rounds(cap, n_l, 1);
 }
 
 // The ring loop addresses its operands with a scalar base and 32-bit byte offsets per lane: the rows
@@ -95,6 +97,8 @@ void run_tiles(GemmA A, Rows rows, int K, int N, WSeg seg, const void *w2, Epi e
   int gx = ((n_full + N_XCD - 1) / N_XCD + (n_part + N_XCD - 1) / N_XCD) * N_XCD;
   if (gx < N_XCD) gx = N_XCD;
   if (gx > 2048) gx = 2048;
+  // ring shapes: one workgroup per CU walks its tiles and prefetches the next one's first slices
+  if (SH::RING && gx > cu_count() / N_XCD * N_XCD) gx = std::max(N_XCD, cu_count() / N_XCD * N_XCD);
   SplitStore sp{part, (size_t)rows.cap * N, N};
   dim3 grid(gx, splitk);
   k_gemm_bf16<SH, Epi><<<grid, SH::NT, SH::LDS_BYTES, s>>>(
@@ -126,12 +130,12 @@ template <typename SH> inline long tiles_of(int cap, int N) { return (long)((cap
 // of one 256x128 tile over the whole K: rounds of the chip x tile cost / split, plus the cost of
 // writing and re-reading the fp32 partials of a split (dear when N is wide and K short).
 struct LargePlan { bool xlarge; int splitk; };
-inline LargePlan plan_large(int cap, int N, int K, size_t part_elems, bool x_ok) {
+inline LargePlan plan_large(int cap, int N, int K, size_t part_elems, bool x_ok, bool ring) {
   LargePlan best{false, 1};
   double best_cost = 1e30;
   for (int x = 0; x <= (x_ok ? 1 : 0); ++x) {
     const long ncol = N / (x ? XLargeS::BN : LargeS::BN);
-    const double tile_cost = x ? 1.63 : 1.0;
+    const double tile_cost = x ? (ring ? XLARGE_RING_COST : XLARGE_COST) : 1.0;
     for (int sk = 1; sk <= 8; ++sk) {
       if ((K / BK) % sk != 0 || K / BK / sk < 8) continue;
       if (sk > 1 && (size_t)sk * cap * N > part_elems) continue;
@@ -168,7 +172,7 @@ int gemm_bf16_raw(GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_
     run_tiles<MidS>(A, rows, K, N, seg, nullptr, e, sk, part, s);
     return sk;
   }
-  const LargePlan pl = plan_large(rows.cap, N, K, part_elems, N % XLargeS::BN == 0);
+  const LargePlan pl = plan_large(rows.cap, N, K, part_elems, N % XLargeS::BN == 0, ring_ok(A, rows, K, seg, N, 1));
   if (pl.xlarge && ring_ok(A, rows, K, seg, N, pl.splitk)) run_tiles<XLargeRingS>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s);
   else if (pl.xlarge) run_tiles<XLargeS>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s);
   else run_tiles<LargeS>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s);
@@ -190,7 +194,8 @@ void gemm_bf16_swiglu(GemmA A, Rows rows, int K, int N, const void *wg, const vo
     else
       run_tiles<SkinnyH128>(A, rows, K, 2 * N, seg, nullptr, EpiSwiGLUHalves<bf16_t, 64>{(bf16_t *)act, N}, 1, nullptr, s);
   } else if (rows.cap <= MID_MAX_ROWS) run_tiles<MidD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
-  else if (N % XLargeD::BN == 0 && prefer_xlarge(rows.cap, N / LargeD::BN, N / XLargeD::BN)) {
+  else if (N % XLargeD::BN == 0 &&
+           prefer_xlarge(rows.cap, N / LargeD::BN, N / XLargeD::BN, ring_ok(A, rows, K, wseg_one(wg, N), N, 1))) {
     if (ring_ok(A, rows, K, wseg_one(wg, N), N, 1)) run_tiles<XLargeRingD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
     else run_tiles<XLargeD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
   }
@@ -214,7 +219,7 @@ void gemm_bf16_down(GemmA A, Rows rows, int K, int N, const void *wd, const floa
     run_tiles<MidS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, sk, sk > 1 ? part : nullptr, s);
     if (sk > 1) launch_down_finalize(BF16, part, sk, (size_t)rows.cap * N, h, rows, N, out, s);
   } else {
-    const LargePlan pl = plan_large(rows.cap, N, K, part_elems, N % XLargeS::BN == 0);
+    const LargePlan pl = plan_large(rows.cap, N, K, part_elems, N % XLargeS::BN == 0, ring_ok(A, rows, K, wseg_one(wd, N), N, 1));
     float *pp = pl.splitk > 1 ? part : nullptr;
     if (pl.xlarge && ring_ok(A, rows, K, wseg_one(wd, N), N, pl.splitk))
       run_tiles<XLargeRingS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, pl.splitk, pp, s);

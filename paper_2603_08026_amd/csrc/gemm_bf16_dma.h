@@ -128,12 +128,13 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
   const int fx = (n_full + N_XCD - 1) / N_XCD, px = (n_part + N_XCD - 1) / N_XCD;
   const int total_pad = (fx + px) * N_XCD;
 
-  for (int p = blockIdx.x; p < total_pad; p += gridDim.x) {
+  // tile (tm, tn) of position p in that order; false for the padding positions (uniform for the
+  // workgroup)
+  auto tile_at = [&](int p, int &tm, int &tn) -> bool {
     const int xcd = p % N_XCD, q = p / N_XCD;
-    int tm, tn;
     if (q < fx) {
       const int logical = xcd * fx + q;
-      if (logical >= n_full) continue;  // uniform for the workgroup
+      if (logical >= n_full) return false;
       const int gsz = group_m * tiles_n;
       const int g = logical / gsz, r = logical % gsz;
       const int gm = min(group_m, rows_full - g * group_m);
@@ -141,10 +142,182 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
       tn = r / gm;
     } else {
       const int lp = xcd * px + (q - fx);
-      if (lp >= n_part) continue;
+      if (lp >= n_part) return false;
       tm = tiles_m - 1;
       tn = lp;
     }
+    return true;
+  };
+
+  // Epilogue of one tile: the accumulators of this wave go through the fused epilogue (or, for a K
+  // split, into the raw partial result).
+  auto epilogue = [&](floatx16 (&acc)[NMAT][MB][NB], int m0, int n0, int tn) {
+    if constexpr (Epi::INTERLEAVE == 48) {
+      // 32 x 96 wave tile = columns [0,48) of matrix 0 (gate) and [48,96) of matrix 1 (up): gate
+      // column c pairs with tile column c + 48, which lane (c%32) ^ 16 holds one or two blocks on
+      static_assert(NB == 3 && SH::WAVES_N == 1 && NMAT == 1, "half-interleaved tiles are 96 columns of one wave");
+      const bool hi16 = (l32 & 16) != 0;
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
+          const float a0 = acc[0][i][0][e], a1 = acc[0][i][1][e], a2 = acc[0][i][2][e];
+          const float up0 = __shfl_xor(hi16 ? a1 : a2, 16, WAVE);  // up value of gate column l32
+          const float up1 = __shfl_xor(a2, 16, WAVE);              // lanes 0..15: up value of gate column 32 + l32
+          if (j < M) {
+            epi.store(j, tn * 48 + l32, a0, up0);
+            if (!hi16) epi.store(j, tn * 48 + 32 + l32, a1, up1);
+          }
+        }
+    } else if constexpr (Epi::INTERLEAVE == 64) {
+      // 32 x 128 wave tile = 64 gate + 64 up columns: the partner of a gate column is two blocks on
+      // in the same lane
+      static_assert(NB == 4 && SH::WAVES_N == 1 && NMAT == 1, "half-interleaved tiles are 128 columns of one wave");
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
+          if (j < M) {
+            epi.store(j, tn * 64 + l32, acc[0][i][0][e], acc[0][i][2][e]);
+            epi.store(j, tn * 64 + 32 + l32, acc[0][i][1][e], acc[0][i][3][e]);
+          }
+        }
+    } else if constexpr (Epi::PRELOAD) {
+      if (!split.part) {
+      // a 32-row block at a time: what the epilogue reads, then what it writes (two blocks in
+      // flight cost more registers than the four-wave shapes have left: measured slower)
+#pragma unroll
+      for (int i = 0; i < MB; ++i) {
+        float pre[16][NB];
+        int rowv[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
+          rowv[e] = (j < M && rows.idx) ? rows.idx[j] : j;
+#pragma unroll
+          for (int jn = 0; jn < NB; ++jn) pre[e][jn] = j < M ? epi.load(j, n0 + wn0 + jn * 32 + l32) : 0.f;
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
+          if (j < M) {
+#pragma unroll
+            for (int jn = 0; jn < NB; ++jn) epi.store(rowv[e], n0 + wn0 + jn * 32 + l32, acc[0][i][jn][e], pre[e][jn]);
+          }
+        }
+      }
+      } else {
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
+            if (j < M) {
+#pragma unroll
+              for (int jn = 0; jn < NB; ++jn)
+                split.part[(size_t)z * split.split_stride + (size_t)j * split.N + n0 + wn0 + jn * 32 + l32] =
+                    acc[0][i][jn][e];
+            }
+          }
+      }
+    } else
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
+        if (j < M) {
+          if (split.part) {
+#pragma unroll
+            for (int jn = 0; jn < NB; ++jn)
+              split.part[(size_t)z * split.split_stride + (size_t)j * split.N + n0 + wn0 + jn * 32 + l32] =
+                  acc[0][i][jn][e];
+          } else {
+            const int row = rows.idx ? rows.idx[j] : j;
+#pragma unroll
+            for (int jn = 0; jn < NB; ++jn)
+              epi(j, row, n0 + wn0 + jn * 32 + l32, acc[0][i][jn][e], acc[NMAT - 1][i][jn][e]);
+          }
+        }
+      }
+  };
+
+  if constexpr (SH::RING) {
+    // Four-wave ring shapes.  The workgroup walks its tiles itself (the launcher starts one per CU),
+    // and the ring is refilled for the next tile before the epilogue of the current one, so that
+    // the first slices of a tile land while the previous tile's results are written.
+    static_assert(Epi::INTERLEAVE == 0 && SH::A_LD == 8 && NMAT * SH::B_LD == 8, "ring shapes");
+    auto ring_sources = [&](int tm, int tn, RingSrc &src) {
+      const int m0 = tm * BM, n0 = tn * BN;
+      src.srd_a = make_srd(A, 0xfffffff0u);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        int j = m0 + (i * NW + wave) * 8 + r8;
+        j = j < M ? j : M - 1;  // rows past the end are clamped; their results are never stored
+        const int srow = gather ? gather[j] : j;
+        src.va[i] = (uint32_t)(((size_t)srow * lda + kbeg + csrc * 8) * 2);
+      }
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        const int t = c / SH::B_LD, i = c % SH::B_LD;
+        const int nrow0 = (i * NW + wave) * 8;  // first of the copy's 8 tile rows (wave-uniform)
+        const int nu = n0 + nrow0;
+        // a copy's rows lie in one matrix: segment ends are multiples of 8
+        const bool in1 = nu >= seg.n_end[0], in2 = nu >= seg.n_end[1];
+        const void *base = t == 1 ? (const void *)W2 : in2 ? seg.w[2] : in1 ? seg.w[1] : seg.w[0];
+        const int nl = nu + r8 - (t == 1 ? 0 : in2 ? seg.n_end[1] : in1 ? seg.n_end[0] : 0);
+        src.srd_w[c] = make_srd(base, 0xfffffff0u);
+        src.vw[c] = (uint32_t)((((size_t)(nl / WPANEL) * (ldw / BK) + kbeg / BK) * (WPANEL * BK) + (nl % WPANEL) * BK + csrc * 8) * 2);
+      }
+    };
+    int tm = 0, tn = 0, p = blockIdx.x;
+    while (p < total_pad && !tile_at(p, tm, tn)) p += gridDim.x;
+    if (p >= total_pad) return;
+    RingSrc src;
+    ring_sources(tm, tn, src);
+    ring_fill(src, lds0, wave);
+    bool all_landed = false;
+    const unsigned char *rd_a = smem_raw + (wm0 + l32) * ROWB, *rd_w = smem_raw + (wn0 + l32) * ROWB;
+    for (;;) {
+      const int m0 = tm * BM, n0 = tn * BN;
+      floatx16 acc[NMAT][MB][NB];
+#pragma unroll
+      for (int t = 0; t < NMAT; ++t)
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+          for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[t][i][j][e] = 0.f;
+      auto run_ring = [&](auto mbv_c) {
+        ring_tile<NMAT, NB, BN, decltype(mbv_c)::value>(acc, lds0, wave, src, rd_a, rd_w, rd_off, KT, all_landed);
+      };
+      // 32-row blocks of this wave that hold rows (wave-uniform)
+      const int mbv = (M - (m0 + wm0) + 31) / 32;
+      if (mbv >= 3) run_ring(std::integral_constant<int, 4>{});
+      else if (mbv == 2) run_ring(std::integral_constant<int, 2>{});
+      else if (mbv == 1) run_ring(std::integral_constant<int, 1>{});
+      else run_ring(std::integral_constant<int, 0>{});
+      int pn = p + gridDim.x, tmn = 0, tnn = 0;
+      while (pn < total_pad && !tile_at(pn, tmn, tnn)) pn += gridDim.x;
+      const bool more = pn < total_pad;
+      if (more) {
+        ring_sources(tmn, tnn, src);
+        ring_fill(src, lds0, wave);
+      }
+      epilogue(acc, m0, n0, tn);
+      if (!more) break;
+      p = pn; tm = tmn; tn = tnn;
+      all_landed = true;
+    }
+    return;
+  }
+
+  for (int p = blockIdx.x; p < total_pad; p += gridDim.x) {
+    int tm, tn;
+    if (!tile_at(p, tm, tn)) continue;
     const int m0 = tm * BM, n0 = tn * BN;
 
     // per-lane global sources of the copies it issues every slice
@@ -158,7 +331,6 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
     }
     // a column tile may span two of the stacked weight matrices: the matrix is looked up per row
     const bf16_t *wp[NMAT][SH::B_LD];
-    const bf16_t *wmat[SH::B_LD];  // start of the weight matrix row i's copy reads from
 #pragma unroll
     for (int i = 0; i < SH::B_LD; ++i) {
       const int nrow = (i * NW + wave) * 8 + r8;
@@ -180,7 +352,6 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
       // panel layout: slice kt of this row sits kt * (WPANEL * BK) elements further on
       const size_t woff = ((size_t)(nl / WPANEL) * (ldw / BK) + kbeg / BK) * (WPANEL * BK) + (nl % WPANEL) * BK + csrc * 8;
       wp[0][i] = wbase + woff;
-      wmat[i] = wbase;
       if (SH::DUAL)
         wp[NMAT - 1][i] = W2 + ((size_t)(n / WPANEL) * (ldw / BK) + kbeg / BK) * (WPANEL * BK) + (n % WPANEL) * BK + csrc * 8;
     }
@@ -290,36 +461,6 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
       if (SH::A_LD >= 4 && a_need <= 1) pipe_loop(std::integral_constant<int, 1>{});
       else if (SH::A_LD >= 2 && a_need <= SH::A_LD / 2) pipe_loop(std::integral_constant<int, (SH::A_LD >= 2 ? SH::A_LD / 2 : 1)>{});
       else pipe_loop(std::integral_constant<int, SH::A_LD>{});
-    } else if constexpr (SH::RING) {
-      // descriptors and 32-bit lane offsets of the wave's copies; a copy's 8 weight rows lie in one
-      // matrix (segment ends are multiples of 8), so its descriptor is wave-uniform
-      const __amdgpu_buffer_rsrc_t srd_a = make_srd(A, 0xfffffff0u);
-      __amdgpu_buffer_rsrc_t srd_w[8];
-      uint32_t va[8], vw[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) va[i] = (uint32_t)((const unsigned char *)ap[i] - (const unsigned char *)A);
-#pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        const int t = c / SH::B_LD, i = c % SH::B_LD;
-        const bf16_t *base = t == 0 ? wmat[i] : W2;
-        const uint64_t b = (uint64_t)(uintptr_t)base;
-        const uint64_t bu = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
-                            (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
-        srd_w[c] = make_srd((const void *)(uintptr_t)bu, 0xfffffff0u);
-        vw[c] = (uint32_t)((const unsigned char *)wp[t][i] - (const unsigned char *)base);
-      }
-      auto run_ring = [&](auto mbv_c) {
-        ring_tile<NMAT, NB, BN, decltype(mbv_c)::value>(acc, smem_raw, lds0, wave, srd_a, va, srd_w, vw,
-                                                       smem_raw + (wm0 + l32) * ROWB,
-                                                       smem_raw + (wn0 + l32) * ROWB, rd_off, KT);
-      };
-      // 32-row blocks of this wave that hold rows (wave-uniform); rows past the end are copied from
-      // row M-1 and their results are never stored
-      const int mbv = (M - (m0 + wm0) + 31) / 32;
-      if (mbv >= 3) run_ring(std::integral_constant<int, 4>{});
-      else if (mbv == 2) run_ring(std::integral_constant<int, 2>{});
-      else if (mbv == 1) run_ring(std::integral_constant<int, 1>{});
-      else run_ring(std::integral_constant<int, 0>{});
     } else if (NS == 2 && m0 + BM > M) {
       // A row tile that holds fewer than BM rows: copies of 8-row blocks past the end are left out,
       // and a wave multiplies only its 32-row blocks that hold rows (none at all for many waves), so
@@ -433,97 +574,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
     }
     }
 
-    // epilogue
-    if constexpr (Epi::INTERLEAVE == 48) {
-      // 32 x 96 wave tile = columns [0,48) of matrix 0 (gate) and [48,96) of matrix 1 (up): gate
-      // column c pairs with tile column c + 48, which lane (c%32) ^ 16 holds one or two blocks on
-      static_assert(NB == 3 && SH::WAVES_N == 1 && NMAT == 1, "half-interleaved tiles are 96 columns of one wave");
-      const bool hi16 = (l32 & 16) != 0;
-#pragma unroll
-      for (int i = 0; i < MB; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
-          const float a0 = acc[0][i][0][e], a1 = acc[0][i][1][e], a2 = acc[0][i][2][e];
-          const float up0 = __shfl_xor(hi16 ? a1 : a2, 16, WAVE);  // up value of gate column l32
-          const float up1 = __shfl_xor(a2, 16, WAVE);              // lanes 0..15: up value of gate column 32 + l32
-          if (j < M) {
-            epi.store(j, tn * 48 + l32, a0, up0);
-            if (!hi16) epi.store(j, tn * 48 + 32 + l32, a1, up1);
-          }
-        }
-    } else if constexpr (Epi::INTERLEAVE == 64) {
-      // 32 x 128 wave tile = 64 gate + 64 up columns: the partner of a gate column is two blocks on
-      // in the same lane
-      static_assert(NB == 4 && SH::WAVES_N == 1 && NMAT == 1, "half-interleaved tiles are 128 columns of one wave");
-#pragma unroll
-      for (int i = 0; i < MB; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
-          if (j < M) {
-            epi.store(j, tn * 64 + l32, acc[0][i][0][e], acc[0][i][2][e]);
-            epi.store(j, tn * 64 + 32 + l32, acc[0][i][1][e], acc[0][i][3][e]);
-          }
-        }
-    } else if constexpr (Epi::PRELOAD) {
-      if (!split.part) {
-      // a 32-row block at a time: what the epilogue reads, then what it writes (two blocks in
-      // flight cost more registers than the four-wave shapes have left: measured slower)
-#pragma unroll
-      for (int i = 0; i < MB; ++i) {
-        float pre[16][NB];
-        int rowv[16];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
-          rowv[e] = (j < M && rows.idx) ? rows.idx[j] : j;
-#pragma unroll
-          for (int jn = 0; jn < NB; ++jn) pre[e][jn] = j < M ? epi.load(j, n0 + wn0 + jn * 32 + l32) : 0.f;
-        }
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
-          if (j < M) {
-#pragma unroll
-            for (int jn = 0; jn < NB; ++jn) epi.store(rowv[e], n0 + wn0 + jn * 32 + l32, acc[0][i][jn][e], pre[e][jn]);
-          }
-        }
-      }
-      } else {
-#pragma unroll
-        for (int i = 0; i < MB; ++i)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
-            if (j < M) {
-#pragma unroll
-              for (int jn = 0; jn < NB; ++jn)
-                split.part[(size_t)z * split.split_stride + (size_t)j * split.N + n0 + wn0 + jn * 32 + l32] =
-                    acc[0][i][jn][e];
-            }
-          }
-      }
-    } else
-#pragma unroll
-    for (int i = 0; i < MB; ++i)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
-        if (j < M) {
-          if (split.part) {
-#pragma unroll
-            for (int jn = 0; jn < NB; ++jn)
-              split.part[(size_t)z * split.split_stride + (size_t)j * split.N + n0 + wn0 + jn * 32 + l32] =
-                  acc[0][i][jn][e];
-          } else {
-            const int row = rows.idx ? rows.idx[j] : j;
-#pragma unroll
-            for (int jn = 0; jn < NB; ++jn)
-              epi(j, row, n0 + wn0 + jn * 32 + l32, acc[0][i][jn][e], acc[NMAT - 1][i][jn][e]);
-          }
-        }
-      }
+    epilogue(acc, m0, n0, tn);
   }
 }
 

@@ -44,45 +44,58 @@ constexpr uint32_t RING_SLOT = 32768;
 constexpr int RING_SLOTS = 5;
 constexpr int RING_MIN_SLICES = 3;
 
-// One tile: acc += A tile x W tile over KT >= 3 slices.
-//   srd_a / va[i]   descriptor and lane offsets of the wave's 8 A copies (8 tile rows each)
+// Sources of a wave's copies for one tile:
+//   srd_a / va[i]   descriptor and lane offsets of its 8 A copies (8 tile rows each)
 //   srd_w[c] / vw[c] the same for its 8 weight copies (a copy's 8 rows lie in one weight matrix)
+struct RingSrc {
+  __amdgpu_buffer_rsrc_t srd_a, srd_w[8];
+  uint32_t va[8], vw[8];
+};
+
+// Fills the ring for a tile: A(0) W(0) A(1) W(1) A(2) into slots 0..4.  The slots must be free (every
+// wave past the middle barrier of the previous tile's last slice).
+__device__ __forceinline__ void ring_fill(const RingSrc &src, uint32_t lds0, int wave) {
+  const uint32_t lds_w = lds0 + (uint32_t)wave * 1024u;
+#pragma unroll
+  for (int h = 0; h < RING_SLOTS; ++h) {
+    const int kt = h / 2;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (h % 2 == 0) dma16_buf(src.srd_a, src.va[i], (uint32_t)kt * 128u, lds_w + h * RING_SLOT + i * 4096u);
+      else dma16_buf(src.srd_w[i], src.vw[i], (uint32_t)kt * 4096u, lds_w + h * RING_SLOT + i * 4096u);
+    }
+  }
+}
+
+// One tile: acc += A tile x W tile over KT >= 3 slices; the ring has been filled (ring_fill).
+//   all_landed      wait for everything this wave has in flight (a fill issued before the previous
+//                   tile's epilogue, whose own loads and stores are counted with it) instead of for
+//                   the first slice alone; wave-uniform
 //   rd_a / rd_w     this lane's operand-read addresses inside a slot (slot 0), without the chunk swizzle
 //   rd_off[s]       swizzled chunk offset of K step s
 // NMAT x NB column blocks of 32: block c = t * NB + j reads weight-tile rows (t * BN + wn0 + 32 j ...).
 // MBV = 32-row blocks of this wave that hold rows (4 in a full tile).  In a row tile with fewer than
 // 256 rows a wave multiplies only those, down to none: copies, waits and barriers are the same for
-// every wave, so such a tile costs about what its copies cost.
+// every wave, so such a tile costs about what its copies cost (leaving out the A copies of the empty
+// row groups as well was measured: no faster).
 template <int NMAT, int NB, int BN, int MBV, typename Acc>
-__device__ __forceinline__ void ring_tile(Acc &acc, const unsigned char *smem, uint32_t lds0, int wave,
-                                          __amdgpu_buffer_rsrc_t srd_a, const uint32_t (&va)[8],
-                                          const __amdgpu_buffer_rsrc_t (&srd_w)[8], const uint32_t (&vw)[8],
+__device__ __forceinline__ void ring_tile(Acc &acc, uint32_t lds0, int wave, const RingSrc &src,
                                           const unsigned char *rd_a, const unsigned char *rd_w,
-                                          const int (&rd_off)[4], int KT) {
+                                          const int (&rd_off)[4], int KT, bool all_landed) {
   static_assert(NMAT * NB == 4, "four column blocks per wave");
   constexpr int ROW = 128, A_STEP = 128, W_STEP = 4096;  // bytes per tile row; K walk per slice
   const uint32_t lds_w = lds0 + (uint32_t)wave * 1024u;
   auto copy_a = [&](int i, int kt, int slot) {
-    dma16_buf(srd_a, va[i], (uint32_t)kt * A_STEP, lds_w + (uint32_t)slot * RING_SLOT + i * 4096u);
+    dma16_buf(src.srd_a, src.va[i], (uint32_t)kt * A_STEP, lds_w + (uint32_t)slot * RING_SLOT + i * 4096u);
   };
   auto copy_w = [&](int c, int kt, int slot) {
-    dma16_buf(srd_w[c], vw[c], (uint32_t)kt * W_STEP, lds_w + (uint32_t)slot * RING_SLOT + c * 4096u);
+    dma16_buf(src.srd_w[c], src.vw[c], (uint32_t)kt * W_STEP, lds_w + (uint32_t)slot * RING_SLOT + c * 4096u);
   };
   auto w_row = [](int c) { return ((c / NB) * BN + (c % NB) * 32) * ROW; };
   auto nxt = [](int s, int d) { const int t = s + d; return t >= RING_SLOTS ? t - RING_SLOTS : t; };
 
-  // fill the ring: A(0) W(0) A(1) W(1) A(2) into slots 0..4
-#pragma unroll
-  for (int i = 0; i < 8; ++i) copy_a(i, 0, 0);
-#pragma unroll
-  for (int c = 0; c < 8; ++c) copy_w(c, 0, 1);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) copy_a(i, 1, 2);
-#pragma unroll
-  for (int c = 0; c < 8; ++c) copy_w(c, 1, 3);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) copy_a(i, 2, 4);
-  wait_vmcnt<24>();  // slice 0 has landed (this wave's part)
+  if (all_landed) wait_vmcnt<0>();
+  else wait_vmcnt<24>();  // slice 0 has landed (this wave's part); 24 copies of the fill are behind it
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 
@@ -100,7 +113,9 @@ __device__ __forceinline__ void ring_tile(Acc &acc, const unsigned char *smem, u
 
   int slot_a = 0;  // slot of A(kt); W(kt) is in the next one
   auto slice = [&](int kt, auto first_c, auto m1_c, auto m2_c) {
-    // FIRST: slice 0 (A(2) is already on its way); M1 / M2: slices kt+1 / kt+2 exist
+    // FIRST: slice 0 (A(2) is already on its way); M1 / M2: slices kt+1 / kt+2 exist.  The last slice
+    // keeps its barrier: past it every wave has read the tile's last operands out of the ring, which
+    // the caller may then refill for its next tile.
     constexpr bool FIRST = decltype(first_c)::value, M1 = decltype(m1_c)::value, M2 = decltype(m2_c)::value;
     constexpr bool CA = !FIRST && M2;
     const int slot_w = nxt(slot_a, 1), slot_a1 = nxt(slot_a, 2), slot_w1 = nxt(slot_a, 3), slot_a2 = nxt(slot_a, 4);
@@ -134,10 +149,10 @@ __device__ __forceinline__ void ring_tile(Acc &acc, const unsigned char *smem, u
     if (M1) {
       if (M2) wait_vmcnt<8>();
       else wait_vmcnt<0>();
-      wait_lgkmcnt0();
-      __builtin_amdgcn_s_barrier();
-      asm volatile("" ::: "memory");
     }
+    wait_lgkmcnt0();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
     // Second half: products of K steps 2 and 3, the copies of W(kt+2) into the slot A(kt) left, the
     // operands of step 0 of slice kt+1.
     const unsigned char *sa1 = rd_a + (uint32_t)slot_a1 * RING_SLOT, *sb1 = rd_w + (uint32_t)slot_w1 * RING_SLOT;
