@@ -184,6 +184,63 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
             epi.store(j, tn * 64 + 32 + l32, acc[0][i][1][e], acc[0][i][3][e]);
           }
         }
+    } else if (m0 + BM <= M) {
+      // Full tile: no row checks, and every address is a wave-uniform base (scalar registers) plus a
+      // byte offset per lane that is fixed for the tile.
+      const int rbase = m0 + wm0, cbase = n0 + wn0;  // wave-uniform
+      if (split.part) {
+        float *pz = split.part + (size_t)z * split.split_stride;
+        const uint32_t lb = ((uint32_t)(4 * lhi) * split.N + l32) * 4u;
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            float *r = pz + (size_t)(rbase + i * 32 + 8 * (e / 4) + (e % 4)) * split.N + cbase;
+#pragma unroll
+            for (int jn = 0; jn < NB; ++jn)
+              *reinterpret_cast<float *>(reinterpret_cast<char *>(r + jn * 32) + lb) = acc[0][i][jn][e];
+          }
+      } else if constexpr (Epi::PRELOAD) {
+        // a 32-row block at a time: what the epilogue reads, then what it writes
+        const uint32_t lbh = epi.lane_bytes_h(lhi, l32), lbo = epi.lane_bytes(lhi, l32);
+        const int ld = epi.ld();
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+          float pre[16][NB];
+          int rowv[16];
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int rr = rbase + i * 32 + 8 * (e / 4) + (e % 4);
+            if (rows.idx)
+              rowv[e] = *reinterpret_cast<const int *>(reinterpret_cast<const char *>(rows.idx + rr) + 16 * lhi);
+#pragma unroll
+            for (int jn = 0; jn < NB; ++jn) pre[e][jn] = epi.get((size_t)rr * ld + cbase + jn * 32, lbh);
+          }
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int rr = rbase + i * 32 + 8 * (e / 4) + (e % 4);
+            if (rows.idx) {
+              auto *o = epi.row_ptr(rowv[e], cbase + l32);
+#pragma unroll
+              for (int jn = 0; jn < NB; ++jn) o[jn * 32] = from_f<std::remove_reference_t<decltype(o[0])>>(pre[e][jn] + acc[0][i][jn][e]);
+            } else {
+#pragma unroll
+              for (int jn = 0; jn < NB; ++jn) epi.put((size_t)rr * ld + cbase + jn * 32, lbo, acc[0][i][jn][e], pre[e][jn]);
+            }
+          }
+        }
+      } else {
+        const uint32_t lbo = epi.lane_bytes(lhi, l32);
+        const int ld = epi.ld();
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const size_t u = (size_t)(rbase + i * 32 + 8 * (e / 4) + (e % 4)) * ld + cbase;
+#pragma unroll
+            for (int jn = 0; jn < NB; ++jn) epi.put(u + jn * 32, lbo, acc[0][i][jn][e], acc[NMAT - 1][i][jn][e]);
+          }
+      }
     } else if constexpr (Epi::PRELOAD) {
       if (!split.part) {
       // a 32-row block at a time: what the epilogue reads, then what it writes (two blocks in

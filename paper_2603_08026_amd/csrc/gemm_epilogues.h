@@ -8,6 +8,11 @@
 //                   weight rows up that way), so one matrix serves per tile and the product never
 //                   leaves the registers
 // INTERLEAVE = that HALF (0: the tile's columns are consecutive rows of the stacked matrices).
+//
+// Full tiles address their results as a wave-uniform element offset u = row * ld + col (held in
+// scalar registers) plus one byte offset per lane that is fixed for the whole tile (lane_bytes: the
+// lane's 4 * (lane / 32) rows and lane % 32 columns), so a store costs no vector address arithmetic:
+// put(u, lane_bytes, ...).
 #pragma once
 #include "common.h"
 #include "kernels.h"
@@ -24,6 +29,11 @@ struct EpiStoreF32 {
     (void)row;
     out[(size_t)j * ldo + n] = acc;
   }
+  __device__ __forceinline__ int ld() const { return ldo; }
+  __device__ __forceinline__ uint32_t lane_bytes(int lhi, int l32) const { return ((uint32_t)(4 * lhi) * ldo + l32) * 4u; }
+  __device__ __forceinline__ void put(size_t u, uint32_t lb, float acc, float) const {
+    *reinterpret_cast<float *>(reinterpret_cast<char *>(out + u) + lb) = acc;
+  }
 };
 
 template <typename T> struct EpiSwiGLU {
@@ -36,6 +46,14 @@ template <typename T> struct EpiSwiGLU {
     (void)row;
     const float s = gate / (1.0f + __expf(-gate));
     act[(size_t)j * N + n] = from_f<T>(s * up);
+  }
+  __device__ __forceinline__ int ld() const { return N; }
+  __device__ __forceinline__ uint32_t lane_bytes(int lhi, int l32) const {
+    return ((uint32_t)(4 * lhi) * N + l32) * (uint32_t)sizeof(T);
+  }
+  __device__ __forceinline__ void put(size_t u, uint32_t lb, float gate, float up) const {
+    const float s = gate / (1.0f + __expf(-gate));
+    *reinterpret_cast<T *>(reinterpret_cast<char *>(act + u) + lb) = from_f<T>(s * up);
   }
 };
 
@@ -56,6 +74,20 @@ template <typename T> struct EpiDown {
   __device__ __forceinline__ void operator()(int j, int row, int n, float acc, float) const {
     store(row, n, acc, load(j, n));
   }
+  __device__ __forceinline__ int ld() const { return N; }
+  __device__ __forceinline__ uint32_t lane_bytes(int lhi, int l32) const {
+    return ((uint32_t)(4 * lhi) * N + l32) * (uint32_t)sizeof(T);
+  }
+  __device__ __forceinline__ uint32_t lane_bytes_h(int lhi, int l32) const { return ((uint32_t)(4 * lhi) * N + l32) * 4u; }
+  __device__ __forceinline__ float get(size_t u, uint32_t lbh) const {
+    return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(h + u) + lbh);
+  }
+  // row j of the list is written where it is (no scatter)
+  __device__ __forceinline__ void put(size_t u, uint32_t lb, float acc, float hv) const {
+    *reinterpret_cast<T *>(reinterpret_cast<char *>(out + u) + lb) = from_f<T>(hv + acc);
+  }
+  // scatter: start of the lane's run in row `row` (column n), then blocks of 32 columns
+  __device__ __forceinline__ T *row_ptr(int row, int n) const { return out + (size_t)row * N + n; }
 };
 
 template <typename T, int HALF> struct EpiSwiGLUHalves {
