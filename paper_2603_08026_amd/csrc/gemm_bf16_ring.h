@@ -17,8 +17,8 @@
 // The copies are buffer loads with LDS destination: a scalar descriptor per source matrix, a 32-bit
 // byte offset per lane that is fixed for the tile, and the K walk as a scalar offset, so a copy costs
 // no vector address arithmetic between the matrix instructions (measured against per-lane 64-bit
-// addresses: 2150 against 2340 cycles per slice).  Lane offsets are 32 bits: the launcher takes this
-// kernel only when every operand spans less than 4 GiB.
+// addresses: 2150 against 2340 cycles per slice).  Lane offsets are 32 bits: the launcher takes these
+// shapes only when every operand spans less than 4 GiB.
 #pragma once
 #include <type_traits>
 #include "common.h"
