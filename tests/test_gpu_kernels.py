@@ -338,6 +338,51 @@ def test_large_tile_regime_with_ragged_row_counts(M, cap):
     lay.close()
 
 
+@pytest.mark.parametrize("hidden,heads,kv_heads,ffn", [(512, 6, 1, 512), (256, 4, 4, 512), (384, 6, 6, 256)])
+def test_four_wave_256x256_tiles_with_short_k_and_stacked_weights(hidden, heads, kv_heads, ffn):
+    """Enough rows that the planner takes the 256 x 256 tiles at small widths (more than 256 tiles, so
+    every workgroup walks several of them and refills its LDS ring for the next): K of 8, 4 and 6
+    slices (4 is the shortest a bf16 configuration can have), a column tile that spans the q, k and v matrices (q|k|v is 384 + 64 + 64 columns in the
+    first case), and a last row tile of 156 rows (one wave pair multiplies four 32-row blocks, the
+    other one)."""
+    _say("256x256 tiles, short K", hidden, heads, kv_heads, ffn)
+    dtype = "bf16"
+    s = W.LayerShape(hidden=hidden, n_heads=heads, n_kv_heads=kv_heads, head_dim=64, ffn=ffn, dtype=dtype,
+                     rope_theta=10000.0)
+    cfg = oracle_cfg(s)
+    B, L = 20, 2048
+    T = B * L
+    M = T - 100
+    lay = Layer.from_shape(s, B, L)
+    w = rand_weights(s, 151, bias=True)
+    lay.set_weights(w)
+    per = [M // B + (1 if b < M % B else 0) for b in range(B)]
+    idx, off = rand_rows(152, B, L, per)
+    rows = lay.make_list(idx, off, cap=T)
+    tol = TOL[dtype]
+    x = _vals(153, (B, L, s.hidden), dtype)
+    q_out = torch.zeros(T, s.dq, dtype=lay.k.dtype, device="cuda")
+    lay.ctx.qkv_refresh(lay.w, lay.upload(x), rows, B, L, lay.cache, q_out)
+    torch.cuda.synchronize()
+    n = O.rmsnorm(x.reshape(T, -1)[idx], w["g_attn"], cfg.rms_eps)
+    q, k, v = O.project_qkv(n, idx % L, w, cfg)
+    assert_close(to_host(q_out)[:M], q.reshape(M, -1), tol, "q")
+    assert_close(to_host(lay.k).reshape(T, -1)[idx], k.reshape(M, -1), tol, "k rows")
+    assert_close(to_host(lay.v).reshape(T, -1)[idx], v.reshape(M, -1), tol, "v rows")
+    c = _vals(154, (T, s.dq), dtype)
+    out0 = _vals(155, (T, s.hidden), dtype)
+    ref = out0.astype(np.float64)
+    O.salient_ffn(x.reshape(T, -1), c, idx, w, cfg, ref)
+    d_out = to_device(out0, dtype)
+    lay.ctx.salient_ffn(lay.w, lay.upload(x), to_device(c, dtype), rows, B, L, d_out)
+    torch.cuda.synchronize()
+    got = to_host(d_out)
+    assert_close(got[idx], ref[idx], tol, "ffn rows")
+    others = np.setdiff1d(np.arange(T), idx)
+    assert np.array_equal(got[others], out0[others].astype(np.float64))
+    lay.close()
+
+
 def test_error_paths_do_not_launch():
     _say("error paths")
     s = small_shape("f32")
