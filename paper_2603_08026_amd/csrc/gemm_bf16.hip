@@ -13,14 +13,18 @@ namespace {
 //          a ring of five LDS slots: a third fewer bytes per flop through the CU's L1 -> LDS path
 //          than a 256 x 128 tile and half the LDS operand reads; taken when its coarser tiles still
 //          fill the rounds of the chip and every operand can be addressed with 32-bit offsets
-//  large   256 x 128 tile (256 x (64+64) when gate and up are fused), 8 waves, 2 LDS stages
+//  large   256 x 128 tile (256 x (64+64) when gate and up are fused), the same ring loop with two
+//          column blocks per wave; eight waves over two LDS stages when the operand cannot be
+//          addressed that way
 //  mid     128 x 128 tile, 4 waves, 2 stages (two workgroups per CU) for a few hundred rows
 //  skinny  all rows in one 128-row tile, 64-column tiles, 4 stages in flight and a K split so that
 //          about one workgroup per CU streams weights (weight-streaming-bound regime)
 typedef Shape<256, 256, 2, 2, false, 2> XLargeS;
 typedef Shape<256, 128, 2, 2, true, 2> XLargeD;
-typedef Shape<256, 128, 4, 2, false, 2> LargeS;
-typedef Shape<256, 64, 4, 2, true, 2> LargeD;
+typedef Shape<256, 128, 2, 2, false, 2> LargeS;
+typedef Shape<256, 64, 2, 2, true, 2> LargeD;
+typedef Shape<256, 128, 4, 2, false, 2> LargeS8;  // eight waves, two LDS stages
+typedef Shape<256, 64, 4, 2, true, 2> LargeD8;
 typedef Shape<128, 128, 2, 2, false, 2> MidS;
 typedef Shape<128, 64, 2, 2, true, 2> MidD;
 typedef Shape<128, 64, 4, 2, false, 4> SkinnyS;
@@ -62,20 +66,22 @@ double tile_rounds(int cap, long ncol, int sk) {
 }
 
 // 256-row tiles with n_l (large) or n_x (xlarge, twice as wide) column tiles: an xlarge tile takes
-// about 1.45 times as long as a large one (measured at many rounds).
-constexpr double XLARGE_COST = 1.45;
+// about 1.65 times as long as a large one (measured at many rounds).
+constexpr double XLARGE_COST = 1.65;
 bool prefer_xlarge(int cap, int n_l, int n_x) {
   return XLARGE_COST * tile_rounds(cap, n_x, 1) < tile_rounds(cap, n_l, 1);
 }
 
-// The ring loop of the xlarge shapes addresses its operands with a scalar base and 32-bit byte
-// offsets per lane: the rows the activation operand can name, and each weight matrix, must span less
-// than 4 GiB, and a copy's 8 weight rows must lie in one matrix; otherwise the 256 x 128 shapes run.
-// (Every K split of the plans keeps at least 8 slices; the loop needs 3.)
+// The ring loop addresses its operands with a scalar base and 32-bit byte offsets per lane.  The base
+// of the activation operand moves with the tile unless rows are gathered: a gathered operand, and
+// each weight matrix, must span less than 4 GiB, and a copy's 8 weight rows must lie in one matrix;
+// otherwise the eight-wave 256 x 128 shapes run.  (Every K split of the plans keeps at least 8
+// slices; the loop needs 3.)
 bool ring_ok(const GemmA &A, const Rows &rows, int K, const WSeg &seg, int n_rows_w) {
-  const size_t a_rows = A.gather ? A.a_rows : (size_t)rows.cap;
+  (void)rows;
   const size_t lim = ((size_t)1 << 32) - ((size_t)1 << 20);
-  if (a_rows == 0 || a_rows * (size_t)A.lda * 2 >= lim) return false;
+  if (A.gather && (A.a_rows == 0 || A.a_rows * (size_t)A.lda * 2 >= lim)) return false;
+  if ((size_t)A.lda * 2 * 256 >= lim) return false;
   if ((size_t)n_rows_w * (size_t)K * 2 >= lim) return false;
   if (seg.n_end[0] % 8 || seg.n_end[1] % 8) return false;
   return K / BK >= RING_MIN_SLICES;
@@ -168,9 +174,11 @@ int gemm_bf16_raw(GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_
     run_tiles<MidS>(A, rows, K, N, seg, nullptr, e, sk, part, s);
     return sk;
   }
-  const LargePlan pl = plan_large(rows.cap, N, K, part_elems, N % XLargeS::BN == 0 && ring_ok(A, rows, K, seg, N));
+  const bool ring = ring_ok(A, rows, K, seg, N);
+  const LargePlan pl = plan_large(rows.cap, N, K, part_elems, N % XLargeS::BN == 0 && ring);
   if (pl.xlarge) run_tiles<XLargeS>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s);
-  else run_tiles<LargeS>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s);
+  else if (ring) run_tiles<LargeS>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s);
+  else run_tiles<LargeS8>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s);
   return pl.splitk;
 }
 
@@ -189,8 +197,8 @@ void gemm_bf16_swiglu(GemmA A, Rows rows, int K, int N, const void *wg, const vo
     else
       run_tiles<SkinnyH128>(A, rows, K, 2 * N, seg, nullptr, EpiSwiGLUHalves<bf16_t, 64>{(bf16_t *)act, N}, 1, nullptr, s);
   } else if (rows.cap <= MID_MAX_ROWS) run_tiles<MidD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
-  else if (N % XLargeD::BN == 0 && ring_ok(A, rows, K, wseg_one(wg, N), N) &&
-           prefer_xlarge(rows.cap, N / LargeD::BN, N / XLargeD::BN))
+  else if (!ring_ok(A, rows, K, wseg_one(wg, N), N)) run_tiles<LargeD8>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
+  else if (N % XLargeD::BN == 0 && prefer_xlarge(rows.cap, N / LargeD::BN, N / XLargeD::BN))
     run_tiles<XLargeD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
   else run_tiles<LargeD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
 }
@@ -212,10 +220,12 @@ void gemm_bf16_down(GemmA A, Rows rows, int K, int N, const void *wd, const floa
     run_tiles<MidS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, sk, sk > 1 ? part : nullptr, s);
     if (sk > 1) launch_down_finalize(BF16, part, sk, (size_t)rows.cap * N, h, rows, N, out, s);
   } else {
-    const LargePlan pl = plan_large(rows.cap, N, K, part_elems, N % XLargeS::BN == 0 && ring_ok(A, rows, K, wseg_one(wd, N), N));
+    const bool ring = ring_ok(A, rows, K, wseg_one(wd, N), N);
+    const LargePlan pl = plan_large(rows.cap, N, K, part_elems, N % XLargeS::BN == 0 && ring);
     float *pp = pl.splitk > 1 ? part : nullptr;
     if (pl.xlarge) run_tiles<XLargeS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, pl.splitk, pp, s);
-    else run_tiles<LargeS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, pl.splitk, pp, s);
+    else if (ring) run_tiles<LargeS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, pl.splitk, pp, s);
+    else run_tiles<LargeS8>(A, rows, K, N, wseg_one(wd, N), nullptr, e, pl.splitk, pp, s);
     if (pl.splitk > 1) launch_down_finalize(BF16, part, pl.splitk, (size_t)rows.cap * N, h, rows, N, out, s);
   }
 }

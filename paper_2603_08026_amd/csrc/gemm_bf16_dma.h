@@ -68,8 +68,8 @@ template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, bool DUAL_, int NS_> str
   static constexpr int B_LD = BN / (8 * NW);
   static constexpr int LPS = A_LD + NMAT * B_LD;  // copies per wave and slice
   static constexpr int A_BYTES = BM * ROWB, W_BYTES = NMAT * BN * ROWB;
-  // four waves on a 256-row tile with 256 weight rows: full tiles run the five-slot ring loop
-  static constexpr bool RING = NW == 4 && BM == 256 && NMAT * BN == 256 && NS == 2;
+  // four waves on a 256-row tile with 256 or 128 weight rows: the five-slot ring loop
+  static constexpr bool RING = NW == 4 && BM == 256 && (NMAT * BN == 256 || NMAT * BN == 128) && NS == 2;
   static constexpr size_t LDS_BYTES = RING ? (size_t)RING_SLOTS * RING_SLOT : (size_t)NS * (A_BYTES + W_BYTES);
   // shapes with three or more stages (weight streaming) run the loop pipelined over slices
   static constexpr bool PIPE = NS >= 3;
@@ -305,19 +305,24 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
     // Four-wave ring shapes.  The workgroup walks its tiles itself (the launcher starts one per CU),
     // and the ring is refilled for the next tile before the epilogue of the current one, so that
     // the first slices of a tile land while the previous tile's results are written.
-    static_assert(Epi::INTERLEAVE == 0 && SH::A_LD == 8 && NMAT * SH::B_LD == 8, "ring shapes");
+    using RingFull = Ring<NMAT, NB, BN, 4>;
+    constexpr int NWC = RingFull::NWC;
+    static_assert(Epi::INTERLEAVE == 0 && SH::A_LD == 8 && NMAT * SH::B_LD == NWC, "ring shapes");
     auto ring_sources = [&](int tm, int tn, RingSrc &src) {
       const int m0 = tm * BM, n0 = tn * BN;
-      src.srd_a = make_srd(A, 0xfffffff0u);
+      // Lane offsets are 32 bits.  Without a gather list the descriptor starts at the tile's first
+      // row, so the offsets stay below 256 rows; with one they are taken from the start of the
+      // operand (the launcher checks that it spans less than 4 GiB).
+      src.srd_a = make_srd(gather ? A : A + (size_t)m0 * lda, 0xfffffff0u);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         int j = m0 + (i * NW + wave) * 8 + r8;
         j = j < M ? j : M - 1;  // rows past the end are clamped; their results are never stored
-        const int srow = gather ? gather[j] : j;
+        const int srow = gather ? gather[j] : j - m0;
         src.va[i] = (uint32_t)(((size_t)srow * lda + kbeg + csrc * 8) * 2);
       }
 #pragma unroll
-      for (int c = 0; c < 8; ++c) {
+      for (int c = 0; c < NWC; ++c) {
         const int t = c / SH::B_LD, i = c % SH::B_LD;
         const int nrow0 = (i * NW + wave) * 8;  // first of the copy's 8 tile rows (wave-uniform)
         const int nu = n0 + nrow0;
@@ -334,7 +339,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
     if (p >= total_pad) return;
     RingSrc src;
     ring_sources(tm, tn, src);
-    ring_fill(src, lds0, wave);
+    RingFull::fill(src, lds0, wave);
     bool all_landed = false;
     const unsigned char *rd_a = smem_raw + (wm0 + l32) * ROWB, *rd_w = smem_raw + (wn0 + l32) * ROWB;
     for (;;) {
@@ -349,7 +354,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[t][i][j][e] = 0.f;
       auto run_ring = [&](auto mbv_c) {
-        ring_tile<NMAT, NB, BN, decltype(mbv_c)::value>(acc, lds0, wave, src, rd_a, rd_w, rd_off, KT, all_landed);
+        Ring<NMAT, NB, BN, decltype(mbv_c)::value>::tile(acc, lds0, wave, src, rd_a, rd_w, rd_off, KT, all_landed);
       };
       // 32-row blocks of this wave that hold rows (wave-uniform)
       const int mbv = (M - (m0 + wm0) + 31) / 32;
@@ -362,7 +367,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
       const bool more = pn < total_pad;
       if (more) {
         ring_sources(tmn, tnn, src);
-        ring_fill(src, lds0, wave);
+        RingFull::fill(src, lds0, wave);
       }
       epilogue(acc, m0, n0, tn);
       if (!more) break;
