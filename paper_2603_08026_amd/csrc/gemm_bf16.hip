@@ -1,5 +1,6 @@
 // bf16 salient-row GEMMs: tile-shape choice per regime and the four fused launchers.
 #include <algorithm>
+#include <cstdlib>
 #include "gemm_bf16_dma.h"
 
 namespace dy {
@@ -77,8 +78,11 @@ bool prefer_xlarge(int cap, int n_l, int n_x) {
 // each weight matrix, must span less than 4 GiB, and a copy's 8 weight rows must lie in one matrix;
 // otherwise the eight-wave 256 x 128 shapes run.  (Every K split of the plans keeps at least 8
 // slices; the loop needs 3.)
+// DYLLM_GEMM_NO_RING=1 in the environment takes the fallback for every call (diagnostics and tests).
 bool ring_ok(const GemmA &A, const Rows &rows, int K, const WSeg &seg, int n_rows_w) {
   (void)rows;
+  if (const char *e = getenv("DYLLM_GEMM_NO_RING"))
+    if (e[0] == '1') return false;
   const size_t lim = ((size_t)1 << 32) - ((size_t)1 << 20);
   if (A.gather && (A.a_rows == 0 || A.a_rows * (size_t)A.lda * 2 >= lim)) return false;
   if ((size_t)A.lda * 2 * 256 >= lim) return false;

@@ -383,6 +383,19 @@ def test_four_wave_256x256_tiles_with_short_k_and_stacked_weights(hidden, heads,
     lay.close()
 
 
+def test_eight_wave_fallback_of_the_large_tile_regime():
+    """Gathered operands of 4 GiB or more cannot be addressed by the four-wave loop's 32-bit lane
+    offsets and take the eight-wave 256 x 128 kernels; the library's diagnostic switch sends every
+    call there, and the ragged large-tile cases must still agree with the oracle."""
+    import os
+    os.environ["DYLLM_GEMM_NO_RING"] = "1"
+    try:
+        test_large_tile_regime_with_ragged_row_counts(700, 701)
+        test_large_tile_regime_with_ragged_row_counts(769, 1600)
+    finally:
+        del os.environ["DYLLM_GEMM_NO_RING"]
+
+
 def test_error_paths_do_not_launch():
     _say("error paths")
     s = small_shape("f32")
