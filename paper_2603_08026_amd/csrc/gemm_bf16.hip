@@ -17,7 +17,6 @@ namespace {
 //  large   256 x 128 tile (256 x (64+64) when gate and up are fused), the same ring loop with two
 //          column blocks per wave; eight waves over two LDS stages when the operand cannot be
 //          addressed that way
-//  mid     128 x 128 tile, 4 waves, 2 stages (two workgroups per CU) for a few hundred rows
 //  skinny  all rows in one 128-row tile, 64-column tiles, 4 stages in flight and a K split so that
 //          about one workgroup per CU streams weights (weight-streaming-bound regime)
 typedef Shape<256, 256, 2, 2, false, 2> XLargeS;
@@ -26,15 +25,12 @@ typedef Shape<256, 128, 2, 2, false, 2> LargeS;
 typedef Shape<256, 64, 2, 2, true, 2> LargeD;
 typedef Shape<256, 128, 4, 2, false, 2> LargeS8;  // eight waves, two LDS stages
 typedef Shape<256, 64, 4, 2, true, 2> LargeD8;
-typedef Shape<128, 128, 2, 2, false, 2> MidS;
-typedef Shape<128, 64, 2, 2, true, 2> MidD;
 typedef Shape<128, 64, 4, 2, false, 4> SkinnyS;
 // skinny regime, wide column tiles (fewer re-reads of the activation tile): q|k|v raw result, and
 // gate|up with half-interleaved tiles (48 + 48 or 64 + 64 columns) and SwiGLU in registers
 typedef Shape<128, 96, 4, 1, false, 4> SkinnyW96;
 typedef Shape<128, 128, 4, 1, false, 4> SkinnyH128;
 
-constexpr int MID_MAX_ROWS = 320;  // above, 256-row tiles with a cheap partial second row tile do better
 constexpr int SKINNY_MAX_ROWS = 128;
 
 int cu_count() {
@@ -121,17 +117,6 @@ inline int pick_splitk(int N, int K, int bn, size_t part_elems, int cap) {
   return s;
 }
 
-// K split for the mid / large regimes when the tiles alone leave most of the chip idle (few rows and a
-// narrow N): `slots` workgroups run at a time; each split keeps at least 8 slices.
-inline int pick_split_tiles(long tiles, int slots, int K, int cap, int N, size_t part_elems) {
-  if (tiles <= 0 || tiles * 10 >= (long)slots * 7) return 1;
-  int s = (int)(slots / tiles);
-  if (s > 8) s = 8;
-  while (s > 1 && ((K / BK) % s != 0 || K / BK / s < 8 || (size_t)s * cap * N > part_elems)) --s;
-  return s;
-}
-template <typename SH> inline long tiles_of(int cap, int N) { return (long)((cap + SH::BM - 1) / SH::BM) * (N / SH::BN); }
-
 // Large regime: tile shape (256x128 or 256x256) and K split with the least estimated time, in units
 // of one 256x128 tile over the whole K: rounds of the chip x tile cost / split, plus the cost of
 // writing and re-reading the fp32 partials of a split (dear when N is wide and K short).
@@ -173,11 +158,6 @@ int gemm_bf16_raw(GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_
     run_tiles<SkinnyS>(A, rows, K, N, seg, nullptr, e, sk, part, s);
     return sk;
   }
-  if (rows.cap <= MID_MAX_ROWS) {
-    const int sk = pick_split_tiles(tiles_of<MidS>(rows.cap, N), 2 * cu_count(), K, rows.cap, N, part_elems);
-    run_tiles<MidS>(A, rows, K, N, seg, nullptr, e, sk, part, s);
-    return sk;
-  }
   const bool ring = ring_ok(A, rows, K, seg, N);
   const LargePlan pl = plan_large(rows.cap, N, K, part_elems, N % XLargeS::BN == 0 && ring);
   if (pl.xlarge) run_tiles<XLargeS>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s);
@@ -200,8 +180,7 @@ void gemm_bf16_swiglu(GemmA A, Rows rows, int K, int N, const void *wg, const vo
       run_tiles<SkinnyW96>(A, rows, K, 2 * N, seg, nullptr, EpiSwiGLUHalves<bf16_t, 48>{(bf16_t *)act, N}, 1, nullptr, s);
     else
       run_tiles<SkinnyH128>(A, rows, K, 2 * N, seg, nullptr, EpiSwiGLUHalves<bf16_t, 64>{(bf16_t *)act, N}, 1, nullptr, s);
-  } else if (rows.cap <= MID_MAX_ROWS) run_tiles<MidD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
-  else if (!ring_ok(A, rows, K, wseg_one(wg, N), N)) run_tiles<LargeD8>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
+  } else if (!ring_ok(A, rows, K, wseg_one(wg, N), N)) run_tiles<LargeD8>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
   else if (N % XLargeD::BN == 0 && prefer_xlarge(rows.cap, N / LargeD::BN, N / XLargeD::BN))
     run_tiles<XLargeD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
   else run_tiles<LargeD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
@@ -219,10 +198,6 @@ void gemm_bf16_down(GemmA A, Rows rows, int K, int N, const void *wd, const floa
     } else {
       run_tiles<SkinnyS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, 1, nullptr, s);
     }
-  } else if (rows.cap <= MID_MAX_ROWS) {
-    const int sk = pick_split_tiles(tiles_of<MidS>(rows.cap, N), 2 * cu_count(), K, rows.cap, N, part_elems);
-    run_tiles<MidS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, sk, sk > 1 ? part : nullptr, s);
-    if (sk > 1) launch_down_finalize(BF16, part, sk, (size_t)rows.cap * N, h, rows, N, out, s);
   } else {
     const bool ring = ring_ok(A, rows, K, wseg_one(wd, N), N);
     const LargePlan pl = plan_large(rows.cap, N, K, part_elems, N % XLargeS::BN == 0 && ring);
