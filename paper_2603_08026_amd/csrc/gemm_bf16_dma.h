@@ -15,7 +15,9 @@
 // every lane names its own 16-byte global source, the hardware writes lane i's data to
 // LDS[M0 + 16*i].  One such instruction therefore fills 8 tile rows x 128 bytes.  No register is
 // used for staging, so NS-1 slices can be in flight per workgroup while the MFMAs of the current
-// slice run; the only synchronisation is one s_waitcnt vmcnt + one barrier per slice.
+// slice run; the only synchronisation is one s_waitcnt vmcnt + one barrier per slice.  The 256-row
+// tiles of the large regime use the same copies through buffer descriptors and keep five half
+// slices in flight in a ring of LDS slots (gemm_bf16_ring.h).
 //
 // LDS layout.  Rows are 128 bytes, unpadded (the copy engine writes lanes back to back), with an
 // XOR swizzle instead: the 16-byte chunk c of tile row r lives at chunk position c ^ ((r/2) % 8).

@@ -1,5 +1,6 @@
-// Slice loop of the 256 x 256 bf16 GEMM tile with four waves (one per SIMD, 128 x 128 each, the
-// accumulators in the second register file) and a ring of five 32 KB LDS slots.
+// Slice loop of the 256-row bf16 GEMM tiles with four waves (one per SIMD; 128 x 128 outputs each
+// for the 256 x 256 tile, 128 x 64 for the 256 x 128 tile; the accumulators in the second register
+// file) and a ring of five 32 KB LDS slots.
 //
 // Why a ring.  A K slice of the tile is 64 KB (A tile 32 KB + weight tile 32 KB), and two whole
 // slices are all that fit beside nothing else in the 160 KB of LDS.  With two stages, the copies of
@@ -17,8 +18,9 @@
 // The copies are buffer loads with LDS destination: a scalar descriptor per source matrix, a 32-bit
 // byte offset per lane that is fixed for the tile, and the K walk as a scalar offset, so a copy costs
 // no vector address arithmetic between the matrix instructions (measured against per-lane 64-bit
-// addresses: 2150 against 2340 cycles per slice).  Lane offsets are 32 bits: the launcher takes these
-// shapes only when every operand spans less than 4 GiB.
+// addresses: 2150 against 2340 cycles per slice).  Lane offsets are 32 bits: the activation
+// descriptor starts at the tile's first row, and the launcher takes these shapes only when a gathered
+// activation operand and every weight matrix span less than 4 GiB.
 #pragma once
 #include <type_traits>
 #include "common.h"
