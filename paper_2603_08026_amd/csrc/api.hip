@@ -199,7 +199,7 @@ int enqueue_qkv(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x, Row
   WSeg seg;
   seg.w[0] = w->wq; seg.w[1] = w->wk; seg.w[2] = w->wv;
   seg.n_end[0] = ctx->dq; seg.n_end[1] = ctx->dq + ctx->dkv; seg.n_end[2] = ctx->dq + 2 * ctx->dkv;
-  const int splits = launch_gemm_raw(dt(ctx), GemmA{ctx->ns, nullptr, c.hidden}, rows, c.hidden, seg,
+  const Splits splits = launch_gemm_raw(dt(ctx), GemmA{ctx->ns, nullptr, c.hidden}, rows, c.hidden, seg,
                                      ctx->part_o, ctx->part_elems, s);
   prof_mark(ctx, ST_GEMM_QKV, s);
   launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)rows.cap * seg.n_end[2], ctx->rope, rows, L,
@@ -238,7 +238,7 @@ int enqueue_attention(dyllm_ctx *ctx, const void *q, const void *k, const void *
 int enqueue_ffn(dyllm_ctx *ctx, const dyllm_layer_weights *w, const void *x, const void *c_all,
                 Rows rows, void *out_cache, size_t n_tokens, hipStream_t s) {
   const dyllm_layer_cfg &c = ctx->cfg;
-  const int splits = launch_gemm_raw(dt(ctx), GemmA{c_all, rows.idx, ctx->dq, n_tokens}, rows, ctx->dq,
+  const Splits splits = launch_gemm_raw(dt(ctx), GemmA{c_all, rows.idx, ctx->dq, n_tokens}, rows, ctx->dq,
                                      wseg_one(w->wo, c.hidden), ctx->part_o, ctx->part_elems, s);
   prof_mark(ctx, ST_GEMM_OPROJ, s);
   launch_oproj_finalize(dt(ctx), ctx->part_o, splits, (size_t)rows.cap * c.hidden, x, w->g_ffn, rows,
@@ -353,7 +353,7 @@ int enqueue_approx_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
   // norm and q projection (+ rotation) of EVERY token of the step  [Alg. 3: Q <- q_proj(x)]
   launch_gather_rmsnorm(dt(ctx), x, w->g_attn, all, c.hidden, c.rms_eps, ctx->ns, s);
   {
-    const int splits = launch_gemm_raw(dt(ctx), GemmA{ctx->ns, nullptr, c.hidden}, all, c.hidden,
+    const Splits splits = launch_gemm_raw(dt(ctx), GemmA{ctx->ns, nullptr, c.hidden}, all, c.hidden,
                                        wseg_one(w->wq, ctx->dq), ctx->part_o, ctx->part_elems, s);
     launch_qkv_finalize(dt(ctx), ctx->part_o, splits, (size_t)all.cap * ctx->dq, ctx->rope, all, L, c.n_heads,
                         0, c.head_dim, w->bq, nullptr, nullptr, ctx->qs, nullptr, nullptr, nullptr, by_token,
@@ -365,7 +365,7 @@ int enqueue_approx_layer(dyllm_ctx *ctx, const dyllm_layer_weights *w, dyllm_lay
     WSeg seg;
     seg.w[0] = w->wk; seg.w[1] = w->wv; seg.w[2] = w->wv;
     seg.n_end[0] = ctx->dkv; seg.n_end[1] = 2 * ctx->dkv; seg.n_end[2] = 2 * ctx->dkv;
-    const int splits = launch_gemm_raw(dt(ctx), GemmA{ctx->fs, nullptr, c.hidden}, rin, c.hidden, seg,
+    const Splits splits = launch_gemm_raw(dt(ctx), GemmA{ctx->fs, nullptr, c.hidden}, rin, c.hidden, seg,
                                        ctx->part_o, ctx->part_elems, s);
     // value residual: by token into the zero-padded [T, dkv] buffer (Alg. 4 as printed), or by list
     // entry next to a compact copy of the new keys (reused normalisers: only candidates are scored)

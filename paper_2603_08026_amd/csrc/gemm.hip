@@ -7,15 +7,15 @@ void gemm_f32_raw(DType, GemmA, Rows, int, WSeg, float *, hipStream_t);
 void gemm_f32_swiglu(DType, GemmA, Rows, int, int, const void *, const void *, void *, hipStream_t);
 void gemm_f32_down(DType, GemmA, Rows, int, int, const void *, const float *, void *, hipStream_t);
 
-int gemm_bf16_raw(GemmA, Rows, int, WSeg, float *, size_t, hipStream_t);
+Splits gemm_bf16_raw(GemmA, Rows, int, WSeg, float *, size_t, hipStream_t);
 void gemm_bf16_swiglu(GemmA, Rows, int, int, const void *, const void *, void *, float *, size_t, hipStream_t);
 void gemm_bf16_down(GemmA, Rows, int, int, const void *, const float *, void *, float *, size_t, hipStream_t);
 
-int launch_gemm_raw(DType t, GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_elems,
-                    hipStream_t s) {
+Splits launch_gemm_raw(DType t, GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_elems,
+                       hipStream_t s) {
   if (t == F32) {
     gemm_f32_raw(t, A, rows, K, seg, part, s);
-    return 1;
+    return Splits{};
   }
   return gemm_bf16_raw(A, rows, K, seg, part, part_elems, s);
 }

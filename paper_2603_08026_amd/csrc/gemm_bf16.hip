@@ -1,5 +1,6 @@
 // bf16 salient-row GEMMs: tile-shape choice per regime and the four fused launchers.
 #include <algorithm>
+#include <climits>
 #include <cstdlib>
 #include "gemm_bf16_dma.h"
 
@@ -89,13 +90,14 @@ bool ring_ok(const GemmA &A, const Rows &rows, int K, const WSeg &seg, int n_row
 
 template <typename SH, typename Epi>
 void run_tiles(GemmA A, Rows rows, int K, int N, WSeg seg, const void *w2, Epi epi, int splitk,
-               float *part, hipStream_t s) {
+               float *part, hipStream_t s, int row_lo = 0, int row_hi = INT_MAX) {
   set_lds_once<SH, Epi>();
   // one workgroup per tile up to 2048, as the kernel numbers them when the list is full: per XCD its
   // share of the full row tiles' tiles and its share of a partial last row tile's, each rounded up
   // (a shorter list leaves workgroups without a tile, or in rare splits gives a few a second one)
-  const int ncol = N / SH::BN;
-  const int n_full = (rows.cap / SH::BM) * ncol, n_part = (rows.cap % SH::BM) ? ncol : 0;
+  // (the launch covers rows [row_lo, min(count, row_hi)) of the list)
+  const int ncol = N / SH::BN, m_rel = std::max(std::min(rows.cap, row_hi) - row_lo, 0);
+  const int n_full = (m_rel / SH::BM) * ncol, n_part = (m_rel % SH::BM) ? ncol : 0;
   int gx = ((n_full + N_XCD - 1) / N_XCD + (n_part + N_XCD - 1) / N_XCD) * N_XCD;
   if (gx < N_XCD) gx = N_XCD;
   if (gx > 2048) gx = 2048;
@@ -105,7 +107,7 @@ void run_tiles(GemmA A, Rows rows, int K, int N, WSeg seg, const void *w2, Epi e
   dim3 grid(gx, splitk);
   k_gemm_bf16<SH, Epi><<<grid, SH::NT, SH::LDS_BYTES, s>>>(
       (const bf16_t *)A.a, A.gather, A.lda, rows, N, seg, (const bf16_t *)w2, K, K / splitk,
-      /*group_m=*/4, epi, sp);
+      /*group_m=*/4, epi, sp, row_lo, row_hi);
 }
 
 // K split for the skinny regime when the column tiles alone cannot fill the chip.
@@ -141,49 +143,93 @@ inline LargePlan plan_large(int cap, int N, int K, size_t part_elems, bool x_ok)
   return best;
 }
 
+// Rows of a short last row tile that go to the weight-streaming shapes in a launch of their own
+// (0: none).  The column tiles of such a row tile each stream their weight columns alone, on as many
+// CUs as there are column tiles, and open a round of their own when the full tiles fill theirs;
+// the streaming shapes spread the same bytes over the whole chip.  Estimated times: a partial tile
+// 0.55 of a full one (tile flops at ~5 TFLOP/s per CU), the stream all w_elems weight elements once
+// at ~5 TB/s plus a launch.  ncol column tiles of tile_cols columns, sk K splits.
+int streamed_tail(int cap, double w_elems, int K, int ncol, int tile_cols, int sk) {
+  const int tail = cap % 256;
+  if (cap < 256 || tail == 0 || tail > SKINNY_MAX_ROWS) return 0;
+  const double extra_rounds = tile_rounds(cap, ncol, sk) - tile_rounds(cap - tail, ncol, sk);
+  const double t_partial = extra_rounds * (2.0 * 256 * tile_cols * (double)K / sk / 5e12);
+  const double t_stream = w_elems * 2 / 5e12 + 5e-6;
+  return t_stream < 0.9 * t_partial ? tail : 0;
+}
+
 }  // namespace
 
-// raw result part[z][j][n]; returns the number of K splits
-int gemm_bf16_raw(GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_elems, hipStream_t s) {
-  if (rows.cap <= 0) return 1;
+// raw result part[z][j][n]; returns the numbers of K splits
+Splits gemm_bf16_raw(GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_elems, hipStream_t s) {
+  Splits out;
+  if (rows.cap <= 0) return out;
   const int N = seg.n_end[2];
   EpiStoreF32 e{part, N};
-  if (rows.cap <= SKINNY_MAX_ROWS) {
-    if (N % SkinnyW96::BN == 0) {  // wider column tiles: fewer re-reads of the activation tile
-      const int sk = pick_splitk(N, K, SkinnyW96::BN, part_elems, rows.cap);
-      run_tiles<SkinnyW96>(A, rows, K, N, seg, nullptr, e, sk, part, s);
-      return sk;
-    }
-    const int sk = pick_splitk(N, K, SkinnyS::BN, part_elems, rows.cap);
-    run_tiles<SkinnyS>(A, rows, K, N, seg, nullptr, e, sk, part, s);
+  // weight streaming for rows [row_lo, ...): wider column tiles where N allows (fewer re-reads of the
+  // activation tile)
+  auto stream_rows = [&](int row_lo) -> int {
+    const bool w96 = N % SkinnyW96::BN == 0;
+    const int sk = pick_splitk(N, K, w96 ? SkinnyW96::BN : SkinnyS::BN, part_elems, rows.cap);
+    if (w96) run_tiles<SkinnyW96>(A, rows, K, N, seg, nullptr, e, sk, part, s, row_lo);
+    else run_tiles<SkinnyS>(A, rows, K, N, seg, nullptr, e, sk, part, s, row_lo);
     return sk;
+  };
+  if (rows.cap <= SKINNY_MAX_ROWS) {
+    out.n = stream_rows(0);
+    return out;
   }
   const bool ring = ring_ok(A, rows, K, seg, N);
-  const LargePlan pl = plan_large(rows.cap, N, K, part_elems, N % XLargeS::BN == 0 && ring);
-  if (pl.xlarge) run_tiles<XLargeS>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s);
-  else if (ring) run_tiles<LargeS>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s);
+  const bool x_ok = N % XLargeS::BN == 0 && ring;
+  LargePlan pl = plan_large(rows.cap, N, K, part_elems, x_ok);
+  int cap_tiles = rows.cap, row_hi = INT_MAX;
+  if (ring) {
+    const int bn = pl.xlarge ? XLargeS::BN : LargeS::BN;
+    if (const int tail = streamed_tail(rows.cap, (double)N * K, K, N / bn, bn, pl.splitk)) {
+      cap_tiles = row_hi = rows.cap - tail;  // the 256-row tiles end where the stream begins
+      pl = plan_large(cap_tiles, N, K, part_elems, x_ok);
+    }
+  }
+  if (pl.xlarge) run_tiles<XLargeS>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s, 0, row_hi);
+  else if (ring) run_tiles<LargeS>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s, 0, row_hi);
   else run_tiles<LargeS8>(A, rows, K, N, seg, nullptr, e, pl.splitk, part, s);
-  return pl.splitk;
+  out.n = pl.splitk;
+  if (cap_tiles < rows.cap) {
+    out.tail_from = cap_tiles;
+    out.n_tail = stream_rows(cap_tiles);
+  }
+  return out;
 }
 
 void gemm_bf16_swiglu(GemmA A, Rows rows, int K, int N, const void *wg, const void *wu, void *act,
                       float *, size_t, hipStream_t s) {
   if (rows.cap <= 0) return;
   EpiSwiGLU<bf16_t> e{(bf16_t *)act, N};
-  if (rows.cap <= SKINNY_MAX_ROWS && (N % 48 == 0 || N % 64 == 0)) {
-    // weight streaming: tiles of HALF gate + HALF up columns, SwiGLU in registers, no raw result
-    // (N is a multiple of 64 for every bf16 configuration the library accepts)
+  // weight streaming: tiles of HALF gate + HALF up columns, SwiGLU in registers, no raw result
+  // (N is a multiple of 64 for every bf16 configuration the library accepts)
+  auto stream_rows = [&](int row_lo) {
     WSeg seg;
     seg.w[0] = wg; seg.w[1] = wu; seg.w[2] = wu;
     seg.n_end[0] = N; seg.n_end[1] = 2 * N; seg.n_end[2] = 2 * N;
     if (N % 48 == 0)
-      run_tiles<SkinnyW96>(A, rows, K, 2 * N, seg, nullptr, EpiSwiGLUHalves<bf16_t, 48>{(bf16_t *)act, N}, 1, nullptr, s);
+      run_tiles<SkinnyW96>(A, rows, K, 2 * N, seg, nullptr, EpiSwiGLUHalves<bf16_t, 48>{(bf16_t *)act, N}, 1, nullptr, s, row_lo);
     else
-      run_tiles<SkinnyH128>(A, rows, K, 2 * N, seg, nullptr, EpiSwiGLUHalves<bf16_t, 64>{(bf16_t *)act, N}, 1, nullptr, s);
-  } else if (!ring_ok(A, rows, K, wseg_one(wg, N), N)) run_tiles<LargeD8>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
-  else if (N % XLargeD::BN == 0 && prefer_xlarge(rows.cap, N / LargeD::BN, N / XLargeD::BN))
-    run_tiles<XLargeD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
-  else run_tiles<LargeD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
+      run_tiles<SkinnyH128>(A, rows, K, 2 * N, seg, nullptr, EpiSwiGLUHalves<bf16_t, 64>{(bf16_t *)act, N}, 1, nullptr, s, row_lo);
+  };
+  if (rows.cap <= SKINNY_MAX_ROWS && (N % 48 == 0 || N % 64 == 0)) {
+    stream_rows(0);
+  } else if (!ring_ok(A, rows, K, wseg_one(wg, N), N)) {
+    run_tiles<LargeD8>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s);
+  } else {
+    bool xl = N % XLargeD::BN == 0 && prefer_xlarge(rows.cap, N / LargeD::BN, N / XLargeD::BN);
+    const int bn = xl ? XLargeD::BN : LargeD::BN;
+    const int tail = (N % 48 && N % 64) ? 0 : streamed_tail(rows.cap, 2.0 * N * K, K, N / bn, 2 * bn, 1);
+    const int row_hi = tail ? rows.cap - tail : INT_MAX;  // the 256-row tiles end where the stream begins
+    if (tail) xl = N % XLargeD::BN == 0 && prefer_xlarge(rows.cap - tail, N / LargeD::BN, N / XLargeD::BN);
+    if (xl) run_tiles<XLargeD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s, 0, row_hi);
+    else run_tiles<LargeD>(A, rows, K, N, wseg_one(wg, N), wu, e, 1, nullptr, s, 0, row_hi);
+    if (tail) stream_rows(rows.cap - tail);
+  }
 }
 
 void gemm_bf16_down(GemmA A, Rows rows, int K, int N, const void *wd, const float *h, void *out,

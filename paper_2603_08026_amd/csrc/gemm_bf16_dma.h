@@ -95,12 +95,16 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
                                                    const int32_t *__restrict__ gather, int lda,
                                                    Rows rows, int N, WSeg seg,
                                                    const bf16_t *__restrict__ W2, int ldw, int kchunk,
-                                                   int group_m, Epi epi, SplitStore split) {
+                                                   int group_m, Epi epi, SplitStore split,
+                                                   int row_lo, int row_hi) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
   constexpr int BM = SH::BM, BN = SH::BN, MB = SH::MB, NB = SH::NB, NMAT = SH::NMAT, NS = SH::NS, NW = SH::NW;
 
-  const int M = rows.count ? min(*rows.count, rows.cap) : rows.cap;
-  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+  // rows [row_lo, min(count, row_hi)) of the list are this launch's; row_lo is a multiple of BM
+  const int M = min(rows.count ? min(*rows.count, rows.cap) : rows.cap, row_hi);
+  const int tm_lo = row_lo / BM;
+  const int m_rel = max(M - tm_lo * BM, 0);
+  const int tiles_m = (m_rel + BM - 1) / BM, tiles_n = N / BN;
   const int tid = threadIdx.x, lane = tid % WAVE;
   const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);  // wave-uniform, kept scalar
   const int wm0 = (wave / SH::WAVES_N) * SH::WM, wn0 = (wave % SH::WAVES_N) * SH::WN;
@@ -124,7 +128,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
   // so that the tiles it runs at one time share operands in its L2) and, after those, its share of
   // the tiles of a last row tile that holds fewer than BM rows: those cost a fraction of a full tile
   // (see the partial loop below) and fill the end of every XCD's schedule instead of one XCD's.
-  const int has_tail = (tiles_m > 0 && M % BM != 0) ? 1 : 0;
+  const int has_tail = (m_rel % BM != 0) ? 1 : 0;
   const int rows_full = tiles_m - has_tail;
   const int n_full = rows_full * tiles_n, n_part = has_tail * tiles_n;
   const int fx = (n_full + N_XCD - 1) / N_XCD, px = (n_part + N_XCD - 1) / N_XCD;
@@ -311,7 +315,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
     constexpr int NWC = RingFull::NWC;
     static_assert(Epi::INTERLEAVE == 0 && SH::A_LD == 8 && NMAT * SH::B_LD == NWC, "ring shapes");
     auto ring_sources = [&](int tm, int tn, RingSrc &src) {
-      const int m0 = tm * BM, n0 = tn * BN;
+      const int m0 = (tm_lo + tm) * BM, n0 = tn * BN;
       // Lane offsets are 32 bits.  Without a gather list the descriptor starts at the tile's first
       // row, so the offsets stay below 256 rows; with one they are taken from the start of the
       // operand (the launcher checks that it spans less than 4 GiB).
@@ -345,7 +349,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
     bool all_landed = false;
     const unsigned char *rd_a = smem_raw + (wm0 + l32) * ROWB, *rd_w = smem_raw + (wn0 + l32) * ROWB;
     for (;;) {
-      const int m0 = tm * BM, n0 = tn * BN;
+      const int m0 = (tm_lo + tm) * BM, n0 = tn * BN;
       floatx16 acc[NMAT][MB][NB];
 #pragma unroll
       for (int t = 0; t < NMAT; ++t)
@@ -382,7 +386,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
   for (int p = blockIdx.x; p < total_pad; p += gridDim.x) {
     int tm, tn;
     if (!tile_at(p, tm, tn)) continue;
-    const int m0 = tm * BM, n0 = tn * BN;
+    const int m0 = (tm_lo + tm) * BM, n0 = tn * BN;
 
     // per-lane global sources of the copies it issues every slice
     const bf16_t *ap[SH::A_LD];

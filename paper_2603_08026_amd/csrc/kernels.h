@@ -15,6 +15,13 @@ struct Rows {
   int32_t cap;
 };
 
+// K splits of a raw GEMM result: the rows below tail_from hold n partial sums each, the rows from
+// tail_from on (a short last row tile that a launch of its own computed) n_tail.
+struct Splits {
+  int n = 1, tail_from = 0x7fffffff, n_tail = 1;
+  __host__ __device__ int of(int j) const { return j < tail_from ? n : n_tail; }
+};
+
 // ---- row kernels (HBM-bound) ------------------------------------------------------------------
 // out[j,:] = RMSNorm(x[row_j,:]) * gain            x: [T,d] T-typed, out: [cap,d] T-typed
 void launch_gather_rmsnorm(DType t, const void *x, const void *gain, Rows rows, int d, float eps,
@@ -30,13 +37,13 @@ void launch_gather_rmsnorm(DType t, const void *x, const void *gain, Rows rows, 
 // dv_out (optional, [T, Hkv*dh] T-typed): value residual new - cached of the rows, taken before the merge
 // entry_of (optional, [T] int32): entry_of[row_j] = j + 1, the map from a token to its list entry, written
 // for the rows at positions >= entry_lo of their sequence only
-void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_stride,
+void launch_qkv_finalize(DType t, const float *part, Splits splits, size_t split_stride,
                          const float *rope_tab, Rows rows, int L, int H, int Hkv, int dh,
                          const void *bq, const void *bk, const void *bv, void *q_out, void *k_cache,
                          void *v_cache, void *dv_out, int q_by_token, void *ksal_out, int dv_by_entry,
                          int32_t *entry_of, int entry_lo, hipStream_t s);
 // out-projection: h[j] = x[row_j] + sum of splits (fp32 [cap,d]); f[j] = RMSNorm(h[j]) * gain (T-typed)
-void launch_oproj_finalize(DType t, const float *part, int splits, size_t split_stride, const void *x,
+void launch_oproj_finalize(DType t, const float *part, Splits splits, size_t split_stride, const void *x,
                            const void *gain, Rows rows, int d, float eps, float *h, void *f,
                            hipStream_t s);
 // down projection after a K split: out_cache[row_j] = h[j] + sum of splits
@@ -126,8 +133,8 @@ inline WSeg wseg_one(const void *w, int N) {
   return s;
 }
 // raw GEMM: part[z][j][n] = sum over K split z of A[j,:] * W[n,:] (fp32, split stride cap*N);
-// returns the number of splits used (>= 1), chosen from the capacity, N and K.
-int launch_gemm_raw(DType t, GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_elems,
+// returns the numbers of splits used (>= 1), chosen from the capacity, N and K.
+Splits launch_gemm_raw(DType t, GemmA A, Rows rows, int K, WSeg seg, float *part, size_t part_elems,
                     hipStream_t s);
 // up: act[j,:] = silu(A w_gate^T) * (A w_up^T), T-typed out [cap, N]
 // `scratch` holds the raw gate|up result in the weight-streaming regime (then a row kernel applies

@@ -59,7 +59,7 @@ __global__ __launch_bounds__(NT) void k_gather_rmsnorm(const T *__restrict__ x,
 // ---- out-projection tail  [Alg. 3: x <- layernorm(out_proj(C)), with the residual] ---------------
 // h[j] = x[row_j] + sum_z part[z][j] (kept in fp32 for the second residual), f[j] = RMSNorm(h[j]) * gain
 template <typename T>
-__global__ __launch_bounds__(RB) void k_oproj_finalize(const float *__restrict__ part, int splits,
+__global__ __launch_bounds__(RB) void k_oproj_finalize(const float *__restrict__ part, Splits splits_of,
                                                         size_t split_stride, const T *__restrict__ x,
                                                         const T *__restrict__ gain, Rows rows, int d,
                                                         float eps, float *__restrict__ h,
@@ -68,6 +68,7 @@ __global__ __launch_bounds__(RB) void k_oproj_finalize(const float *__restrict__
   const int n = row_count(rows), nv = d / 4;
   for (int j = blockIdx.x; j < n; j += gridDim.x) {
     const int r = rows.idx ? rows.idx[j] : j;
+    const int splits = splits_of.of(j);
     const T *xr = x + (size_t)r * d;
     float *hr = h + (size_t)j * d;
     float ss = 0.f;
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(RB) void k_down_finalize(const float *__restrict__ 
 // pos * theta^(-2p/dh); the table holds (cos, sin) per (pos, p).  A thread handles 4 neighbouring
 // pairs of one head (two float4 of the raw result, two float4 of the table).
 template <typename T>
-__global__ __launch_bounds__(RB) void k_qkv_finalize(const float *__restrict__ part, int splits,
+__global__ __launch_bounds__(RB) void k_qkv_finalize(const float *__restrict__ part, Splits splits_of,
                                                       size_t split_stride, const float *__restrict__ tab,
                                                       Rows rows, int L, int H, int Hkv, int dh,
                                                       const T *__restrict__ bq, const T *__restrict__ bk,
@@ -147,6 +148,7 @@ __global__ __launch_bounds__(RB) void k_qkv_finalize(const float *__restrict__ p
   const int qk_items = (H + Hkv) * per_head, v_items = dkv / 4;
   for (int j = blockIdx.x; j < n; j += gridDim.x) {
     const int r = rows.idx ? rows.idx[j] : j;
+    const int splits = splits_of.of(j);
     const int pos = r % L;
     // token -> its list entry (0 = not in the list), for the tokens at positions >= entry_lo only
     if (entry_of && threadIdx.x == 0 && pos >= entry_lo) entry_of[r] = j + 1;
@@ -372,7 +374,7 @@ void launch_gather_rmsnorm(DType t, const void *x, const void *gain, Rows rows, 
   }
 }
 
-void launch_oproj_finalize(DType t, const float *part, int splits, size_t split_stride, const void *x,
+void launch_oproj_finalize(DType t, const float *part, Splits splits, size_t split_stride, const void *x,
                            const void *gain, Rows rows, int d, float eps, float *h, void *f,
                            hipStream_t s) {
   if (rows.cap <= 0) return;
@@ -396,7 +398,7 @@ void launch_down_finalize(DType t, const float *part, int splits, size_t split_s
                                                               (bf16_t *)out_cache);
 }
 
-void launch_qkv_finalize(DType t, const float *part, int splits, size_t split_stride,
+void launch_qkv_finalize(DType t, const float *part, Splits splits, size_t split_stride,
                          const float *rope_tab, Rows rows, int L, int H, int Hkv, int dh,
                          const void *bq, const void *bk, const void *bv, void *q_out, void *k_cache,
                          void *v_cache, void *dv_out, int q_by_token, void *ksal_out, int dv_by_entry,

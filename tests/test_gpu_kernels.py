@@ -383,6 +383,50 @@ def test_four_wave_256x256_tiles_with_short_k_and_stacked_weights(hidden, heads,
     lay.close()
 
 
+@pytest.mark.parametrize("M,cap", [(2075, 2075), (2060, 2075), (1990, 2075)])
+def test_short_last_row_tile_streamed_in_a_launch_of_its_own(M, cap):
+    """Widths at which eight full 256-row tiles fill the chip's 256 CUs exactly (q|k|v 8192, out-projection
+    and gate|up 4096 columns over K = 4096), so that the 27 rows of a ninth row tile would open a round of their own:
+    the launchers hand rows 2048.. to the weight-streaming tiles in a second launch, whose K split
+    differs from the first one's.  With fewer rows than the capacity that launch has fewer rows than
+    planned (2060) or none, and the first one a partial tile of its own (1990)."""
+    _say("streamed last row tile", M, cap)
+    dtype = "bf16"
+    s = W.LayerShape(hidden=4096, n_heads=32, n_kv_heads=16, head_dim=128, ffn=4096, dtype=dtype, rope_theta=10000.0)
+    cfg = oracle_cfg(s)
+    B, L = 2, 1100
+    T = B * L
+    lay = Layer.from_shape(s, B, L)
+    w = rand_weights(s, 171, bias=True)
+    lay.set_weights(w)
+    per = [M // B + (1 if b < M % B else 0) for b in range(B)]
+    idx, off = rand_rows(172, B, L, per)
+    rows = lay.make_list(idx, off, cap=cap)
+    tol = TOL[dtype]
+    x = _vals(173, (B, L, s.hidden), dtype)
+    q_out = torch.zeros(cap, s.dq, dtype=lay.k.dtype, device="cuda")
+    lay.ctx.qkv_refresh(lay.w, lay.upload(x), rows, B, L, lay.cache, q_out)
+    torch.cuda.synchronize()
+    n = O.rmsnorm(x.reshape(T, -1)[idx], w["g_attn"], cfg.rms_eps)
+    q, k, v = O.project_qkv(n, idx % L, w, cfg)
+    assert_close(to_host(q_out)[:M], q.reshape(M, -1), tol, "q")
+    assert_close(to_host(lay.k).reshape(T, -1)[idx], k.reshape(M, -1), tol, "k rows")
+    assert_close(to_host(lay.v).reshape(T, -1)[idx], v.reshape(M, -1), tol, "v rows")
+    assert np.all(to_host(q_out)[M:] == 0)
+    c = _vals(174, (T, s.dq), dtype)
+    out0 = _vals(175, (T, s.hidden), dtype)
+    ref = out0.astype(np.float64)
+    O.salient_ffn(x.reshape(T, -1), c, idx, w, cfg, ref)
+    d_out = to_device(out0, dtype)
+    lay.ctx.salient_ffn(lay.w, lay.upload(x), to_device(c, dtype), rows, B, L, d_out)
+    torch.cuda.synchronize()
+    got = to_host(d_out)
+    assert_close(got[idx], ref[idx], tol, "ffn rows")
+    others = np.setdiff1d(np.arange(T), idx)
+    assert np.array_equal(got[others], out0[others].astype(np.float64))
+    lay.close()
+
+
 def test_eight_wave_fallback_of_the_large_tile_regime():
     """Gathered operands of 4 GiB or more cannot be addressed by the four-wave loop's 32-bit lane
     offsets and take the eight-wave 256 x 128 kernels; the library's diagnostic switch sends every
