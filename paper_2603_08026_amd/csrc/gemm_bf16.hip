@@ -88,10 +88,24 @@ bool ring_ok(const GemmA &A, const Rows &rows, int K, const WSeg &seg, int n_row
   return K / BK >= RING_MIN_SLICES;
 }
 
+// Which forms of the kernel an epilogue is launched in: the raw fp32 store (SPLIT), the fused
+// epilogue, or either (the down projection, with and without a K split).
+template <typename Epi> struct SplitForms { static constexpr bool raw = false, fused = true; };
+template <> struct SplitForms<EpiStoreF32> { static constexpr bool raw = true, fused = false; };
+template <typename T> struct SplitForms<EpiDown<T>> { static constexpr bool raw = true, fused = true; };
+
+template <typename SH, typename Epi, bool SPLIT>
+void launch_tiles(dim3 grid, GemmA A, Rows rows, int K, int N, WSeg seg, const void *w2, Epi epi, int splitk,
+                  SplitStore sp, hipStream_t s, int row_lo, int row_hi) {
+  set_lds_once<SH, Epi, SPLIT>();
+  k_gemm_bf16<SH, Epi, SPLIT><<<grid, SH::NT, SH::LDS_BYTES, s>>>(
+      (const bf16_t *)A.a, A.gather, A.lda, rows, N, seg, (const bf16_t *)w2, K, K / splitk,
+      /*group_m=*/4, epi, sp, row_lo, row_hi);
+}
+
 template <typename SH, typename Epi>
 void run_tiles(GemmA A, Rows rows, int K, int N, WSeg seg, const void *w2, Epi epi, int splitk,
                float *part, hipStream_t s, int row_lo = 0, int row_hi = INT_MAX) {
-  set_lds_once<SH, Epi>();
   // one workgroup per tile up to 2048, as the kernel numbers them when the list is full: per XCD its
   // share of the full row tiles' tiles and its share of a partial last row tile's, each rounded up
   // (a shorter list leaves workgroups without a tile, or in rare splits gives a few a second one)
@@ -105,9 +119,13 @@ void run_tiles(GemmA A, Rows rows, int K, int N, WSeg seg, const void *w2, Epi e
   if (SH::RING && gx > cu_count() / N_XCD * N_XCD) gx = std::max(N_XCD, cu_count() / N_XCD * N_XCD);
   SplitStore sp{part, (size_t)rows.cap * N, N};
   dim3 grid(gx, splitk);
-  k_gemm_bf16<SH, Epi><<<grid, SH::NT, SH::LDS_BYTES, s>>>(
-      (const bf16_t *)A.a, A.gather, A.lda, rows, N, seg, (const bf16_t *)w2, K, K / splitk,
-      /*group_m=*/4, epi, sp, row_lo, row_hi);
+  using F = SplitForms<Epi>;
+  if constexpr (F::raw && F::fused) {
+    if (part) launch_tiles<SH, Epi, true>(grid, A, rows, K, N, seg, w2, epi, splitk, sp, s, row_lo, row_hi);
+    else launch_tiles<SH, Epi, false>(grid, A, rows, K, N, seg, w2, epi, splitk, sp, s, row_lo, row_hi);
+  } else {
+    launch_tiles<SH, Epi, F::raw>(grid, A, rows, K, N, seg, w2, epi, splitk, sp, s, row_lo, row_hi);
+  }
 }
 
 // K split for the skinny regime when the column tiles alone cannot fill the chip.

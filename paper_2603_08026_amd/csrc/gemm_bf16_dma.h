@@ -90,7 +90,11 @@ struct SplitStore {  // part != nullptr: raw fp32 tile part[z][j][n] instead of 
   int N;
 };
 
-template <typename SH, typename Epi>
+// SPLIT: the tile goes to the raw fp32 result part[z][j][n] (split.part) instead of through the
+// fused epilogue.  A compile-time switch: with both forms behind a run-time branch the compiler
+// moves the accumulators out of the accumulation registers ahead of the branch, where they do not
+// fit, and the epilogue's stores each wait for a reload from scratch memory.
+template <typename SH, typename Epi, bool SPLIT>
 __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__ A,
                                                    const int32_t *__restrict__ gather, int lda,
                                                    Rows rows, int N, WSeg seg,
@@ -194,7 +198,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
       // Full tile: no row checks, and every address is a wave-uniform base (scalar registers) plus a
       // byte offset per lane that is fixed for the tile.
       const int rbase = m0 + wm0, cbase = n0 + wn0;  // wave-uniform
-      if (split.part) {
+      if constexpr (SPLIT) {
         float *pz = split.part + (size_t)z * split.split_stride;
         const uint32_t lb = ((uint32_t)(4 * lhi) * split.N + l32) * 4u;
 #pragma unroll
@@ -248,7 +252,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
           }
       }
     } else if constexpr (Epi::PRELOAD) {
-      if (!split.part) {
+      if constexpr (!SPLIT) {
       // a 32-row block at a time: what the epilogue reads, then what it writes (two blocks in
       // flight cost more registers than the four-wave shapes have left: measured slower)
 #pragma unroll
@@ -292,7 +296,7 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
       for (int e = 0; e < 16; ++e) {
         const int j = m0 + wm0 + i * 32 + 8 * (e / 4) + 4 * lhi + (e % 4);
         if (j < M) {
-          if (split.part) {
+          if constexpr (SPLIT) {
 #pragma unroll
             for (int jn = 0; jn < NB; ++jn)
               split.part[(size_t)z * split.split_stride + (size_t)j * split.N + n0 + wn0 + jn * 32 + l32] =
@@ -646,10 +650,10 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
   }
 }
 
-template <typename SH, typename Epi> void set_lds_once() {
+template <typename SH, typename Epi, bool SPLIT> void set_lds_once() {
   static bool done = false;
   if (!done) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<SH, Epi>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<SH, Epi, SPLIT>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)SH::LDS_BYTES);
     done = true;
   }

@@ -427,6 +427,44 @@ def test_short_last_row_tile_streamed_in_a_launch_of_its_own(M, cap):
     lay.close()
 
 
+@pytest.mark.parametrize("B,L,M,cap,bias", [(16, 2048, 32668, 32768, True), (16, 1100, 16411, 16411, True),
+                                              (16, 1100, 16400, 16411, False), (16, 1100, 9000, 16411, True)])
+def test_qkv_refresh_with_128_wide_heads_at_many_rows(B, L, M, cap, bias):
+    """bf16 with 128-wide heads and enough rows for 256 x 256 tiles (grouped-query shape: 4 query
+    heads, 2 key/value heads, so a column tile holds q heads, or a k and a v head pair), with and without
+    biases.  Cases: a last row tile of 156 rows inside the same launch; 16384 + 27 rows, where the 27 go
+    to the weight-streaming tiles with a K split of their own; fewer rows than the capacity, so that
+    the second launch has 16 rows, or none and the first one a partial tile.  Rows outside the list
+    keep their cached keys and values bit for bit."""
+    _say("q/k/v refresh, 128-wide heads, many rows", B, L, M, cap)
+    dtype = "bf16"
+    s = W.LayerShape(hidden=1024, n_heads=4, n_kv_heads=2, head_dim=128, ffn=512, dtype=dtype, rope_theta=10000.0)
+    cfg = oracle_cfg(s)
+    T = B * L
+    lay = Layer.from_shape(s, B, L)
+    w = rand_weights(s, 181, bias=bias)
+    lay.set_weights(w)
+    per = [M // B + (1 if b < M % B else 0) for b in range(B)]
+    idx, off = rand_rows(182, B, L, per)
+    rows = lay.make_list(idx, off, cap=cap)
+    tol = TOL[dtype]
+    x = _vals(183, (B, L, s.hidden), dtype)
+    k0, v0 = to_host(lay.k).reshape(T, -1).copy(), to_host(lay.v).reshape(T, -1).copy()
+    q_out = torch.zeros(cap, s.dq, dtype=lay.k.dtype, device="cuda")
+    lay.ctx.qkv_refresh(lay.w, lay.upload(x), rows, B, L, lay.cache, q_out)
+    torch.cuda.synchronize()
+    n = O.rmsnorm(x.reshape(T, -1)[idx], w["g_attn"], cfg.rms_eps)
+    q, k, v = O.project_qkv(n, idx % L, w, cfg)
+    assert_close(to_host(q_out)[:M], q.reshape(M, -1), tol, "q")
+    k1, v1 = to_host(lay.k).reshape(T, -1), to_host(lay.v).reshape(T, -1)
+    assert_close(k1[idx], k.reshape(M, -1), tol, "k rows")
+    assert_close(v1[idx], v.reshape(M, -1), tol, "v rows")
+    assert np.all(to_host(q_out)[M:] == 0)
+    others = np.setdiff1d(np.arange(T), idx)
+    assert np.array_equal(k1[others], k0[others]) and np.array_equal(v1[others], v0[others])
+    lay.close()
+
+
 def test_eight_wave_fallback_of_the_large_tile_regime():
     """Gathered operands of 4 GiB or more cannot be addressed by the four-wave loop's 32-bit lane
     offsets and take the eight-wave 256 x 128 kernels; the library's diagnostic switch sends every
