@@ -324,13 +324,22 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
       // row, so the offsets stay below 256 rows; with one they are taken from the start of the
       // operand (the launcher checks that it spans less than 4 GiB).
       src.srd_a = make_srd(gather ? A : A + (size_t)m0 * lda, 0xfffffff0u);
+      // (the eight list entries of a gathered operand are loaded back to back, then used)
+      int srow[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        int j = m0 + (i * NW + wave) * 8 + r8;
-        j = j < M ? j : M - 1;  // rows past the end are clamped; their results are never stored
-        const int srow = gather ? gather[j] : j - m0;
-        src.va[i] = (uint32_t)(((size_t)srow * lda + kbeg + csrc * 8) * 2);
+        const int j = m0 + (i * NW + wave) * 8 + r8;
+        srow[i] = j < M ? j : M - 1;  // rows past the end are clamped; their results are never stored
       }
+      if (gather) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) srow[i] = gather[srow[i]];
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) srow[i] -= m0;
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) src.va[i] = (uint32_t)(((size_t)srow[i] * lda + kbeg + csrc * 8) * 2);
 #pragma unroll
       for (int c = 0; c < NWC; ++c) {
         const int t = c / SH::B_LD, i = c % SH::B_LD;
