@@ -211,33 +211,45 @@ __global__ __launch_bounds__(SH::NT) void k_gemm_bf16(const bf16_t *__restrict__
               *reinterpret_cast<float *>(reinterpret_cast<char *>(r + jn * 32) + lb) = acc[0][i][jn][e];
           }
       } else if constexpr (Epi::PRELOAD) {
-        // a 32-row block at a time: what the epilogue reads, then what it writes
+        // A step of RS rows at a time: what the epilogue reads, then what it writes.  The reads of
+        // step u + 1 are issued before the stores of step u: a wave's memory operations complete
+        // in order, so a load behind stores would wait for all of them.
+        constexpr int RS = NB >= 4 ? 8 : 16, STEPS = MB * 16 / RS;
+        struct Pre {
+          float v[RS][NB];
+          int row[RS];
+        };
         const uint32_t lbh = epi.lane_bytes_h(lhi, l32), lbo = epi.lane_bytes(lhi, l32);
         const int ld = epi.ld();
+        auto row_of = [&](int u, int x) { return rbase + ((u * RS + x) / 16) * 32 + 8 * (((u * RS + x) % 16) / 4) + (x % 4); };
+        auto load = [&](int u, Pre &p) {
 #pragma unroll
-        for (int i = 0; i < MB; ++i) {
-          float pre[16][NB];
-          int rowv[16];
+          for (int x = 0; x < RS; ++x) {
+            const int rr = row_of(u, x);
+            p.row[x] = rows.idx ? *reinterpret_cast<const int *>(reinterpret_cast<const char *>(rows.idx + rr) + 16 * lhi) : 0;
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int rr = rbase + i * 32 + 8 * (e / 4) + (e % 4);
-            if (rows.idx)
-              rowv[e] = *reinterpret_cast<const int *>(reinterpret_cast<const char *>(rows.idx + rr) + 16 * lhi);
-#pragma unroll
-            for (int jn = 0; jn < NB; ++jn) pre[e][jn] = epi.get((size_t)rr * ld + cbase + jn * 32, lbh);
+            for (int jn = 0; jn < NB; ++jn) p.v[x][jn] = epi.get((size_t)rr * ld + cbase + jn * 32, lbh);
           }
+        };
+        Pre cur;
+        load(0, cur);
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int rr = rbase + i * 32 + 8 * (e / 4) + (e % 4);
+        for (int u = 0; u < STEPS; ++u) {
+          Pre nxt;
+          if (u + 1 < STEPS) load(u + 1, nxt);
+#pragma unroll
+          for (int x = 0; x < RS; ++x) {
+            const int i = (u * RS + x) / 16, e = (u * RS + x) % 16;
             if (rows.idx) {
-              auto *o = epi.row_ptr(rowv[e], cbase + l32);
+              auto *o = epi.row_ptr(cur.row[x], cbase + l32);
 #pragma unroll
-              for (int jn = 0; jn < NB; ++jn) o[jn * 32] = from_f<std::remove_reference_t<decltype(o[0])>>(pre[e][jn] + acc[0][i][jn][e]);
+              for (int jn = 0; jn < NB; ++jn) o[jn * 32] = from_f<std::remove_reference_t<decltype(o[0])>>(cur.v[x][jn] + acc[0][i][jn][e]);
             } else {
 #pragma unroll
-              for (int jn = 0; jn < NB; ++jn) epi.put((size_t)rr * ld + cbase + jn * 32, lbo, acc[0][i][jn][e], pre[e][jn]);
+              for (int jn = 0; jn < NB; ++jn) epi.put((size_t)row_of(u, x) * ld + cbase + jn * 32, lbo, acc[0][i][jn][e], cur.v[x][jn]);
             }
           }
+          if (u + 1 < STEPS) cur = nxt;
         }
       } else {
         const uint32_t lbo = epi.lane_bytes(lhi, l32);
