@@ -33,7 +33,15 @@
 //
 // Tile walk.  The row count lives on the device; the grid is sized from the list capacity and each
 // workgroup walks the existing tiles in a grouped order, remapped so that neighbouring tiles run on
-// one XCD (workgroup i is dispatched to XCD i % 8) and share A / weight tiles in its L2.
+// one XCD (workgroup i is dispatched to XCD i % 8) and share A / weight tiles in its L2.  A launch
+// covers a window of list rows [row_lo, row_hi), so that a launcher can give a short last row tile
+// to another tile shape in a launch of its own.
+//
+// Epilogues.  A wave's loads and stores complete in order, and a wave of the 256-row shapes is alone
+// on its SIMD: a load issued behind stores (a residual, a register reloaded from scratch memory)
+// returns only after all of them.  The epilogues therefore issue what they read ahead of the stores
+// it could wait for, and the raw fp32 store of a K split is a compile-time form of the kernel (SPLIT)
+// rather than a run-time branch beside the fused epilogue.
 #pragma once
 #include <type_traits>
 #include "gemm_epilogues.h"
