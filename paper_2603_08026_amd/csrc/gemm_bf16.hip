@@ -140,9 +140,9 @@ inline int pick_splitk(int N, int K, int bn, size_t part_elems, int cap) {
 // Large regime: tile shape (256x128 or 256x256) and K split with the least estimated time, in units
 // of one 256x128 tile over the whole K: rounds of the chip x tile cost / split, plus the cost of
 // writing and re-reading the fp32 partials of a split (dear when N is wide and K short).
-struct LargePlan { bool xlarge; int splitk; };
+struct LargePlan { bool xlarge; int splitk; double cost; };
 inline LargePlan plan_large(int cap, int N, int K, size_t part_elems, bool x_ok) {
-  LargePlan best{false, 1};
+  LargePlan best{false, 1, 1e30};
   double best_cost = 1e30;
   for (int x = 0; x <= (x_ok ? 1 : 0); ++x) {
     const long ncol = N / (x ? XLargeS::BN : LargeS::BN);
@@ -155,7 +155,7 @@ inline LargePlan plan_large(int cap, int N, int K, size_t part_elems, bool x_ok)
       // (256 tiles x 2*256*128*K flop at ~1 PFLOP/s)
       const double partials = sk > 1 ? 1.2e-4 * sk * (double)cap * N / K + 0.02 : 0.0;
       const double cost = rounds * tile_cost / sk + partials;
-      if (cost < best_cost - 1e-9) { best_cost = cost; best = LargePlan{x == 1, sk}; }
+      if (cost < best_cost - 1e-9) { best_cost = cost; best = LargePlan{x == 1, sk, cost}; }
     }
   }
   return best;
@@ -258,18 +258,51 @@ void gemm_bf16_down(GemmA A, Rows rows, int K, int N, const void *wd, const floa
     const int sk = pick_splitk(N, K, SkinnyS::BN, part_elems, rows.cap);
     if (sk > 1) {
       run_tiles<SkinnyS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, sk, part, s);
-      launch_down_finalize(BF16, part, sk, (size_t)rows.cap * N, h, rows, N, out, s);
+      Splits sp;
+      sp.n = sk;
+      launch_down_finalize(BF16, part, sp, (size_t)rows.cap * N, h, rows, N, out, s);
     } else {
       run_tiles<SkinnyS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, 1, nullptr, s);
     }
   } else {
-    const bool ring = ring_ok(A, rows, K, wseg_one(wd, N), N);
-    const LargePlan pl = plan_large(rows.cap, N, K, part_elems, N % XLargeS::BN == 0 && ring);
+    const bool ring = ring_ok(A, rows, K, wseg_one(wd, N), N), x_ok = N % XLargeS::BN == 0 && ring;
+    LargePlan pl = plan_large(rows.cap, N, K, part_elems, x_ok);
+    // A last row tile of at most 128 rows goes to the weight-streaming tiles in a launch of its own
+    // when the plan for the full row tiles alone plus that stream is estimated well below the plan
+    // for all rows (a unit of the plans' cost = one 256 x 128 tile over all of K at ~5 TFLOP/s per
+    // CU; the stream: the weights once at ~5 TB/s, a launch, and its rows' share of a sum kernel).
+    const int tail = rows.cap % 256;
+    int row_hi = INT_MAX, cap_tiles = rows.cap;
+    if (ring && rows.cap >= 256 && tail > 0 && tail <= SKINNY_MAX_ROWS) {
+      const LargePlan pf = plan_large(rows.cap - tail, N, K, part_elems, x_ok);
+      const double unit = 2.0 * 256 * 128 * (double)K / 5e12, t_stream = (double)N * K * 2 / 5e12 + 8e-6;
+      if (pf.cost * unit + t_stream < 0.9 * pl.cost * unit) {
+        pl = pf;
+        row_hi = cap_tiles = rows.cap - tail;
+      }
+    }
     float *pp = pl.splitk > 1 ? part : nullptr;
-    if (pl.xlarge) run_tiles<XLargeS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, pl.splitk, pp, s);
-    else if (ring) run_tiles<LargeS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, pl.splitk, pp, s);
+    if (pl.xlarge) run_tiles<XLargeS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, pl.splitk, pp, s, 0, row_hi);
+    else if (ring) run_tiles<LargeS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, pl.splitk, pp, s, 0, row_hi);
     else run_tiles<LargeS8>(A, rows, K, N, wseg_one(wd, N), nullptr, e, pl.splitk, pp, s);
-    if (pl.splitk > 1) launch_down_finalize(BF16, part, pl.splitk, (size_t)rows.cap * N, h, rows, N, out, s);
+    Splits sp;
+    sp.n = pl.splitk;
+    sp.done_to = pl.splitk > 1 ? 0 : cap_tiles;  // rows the fused epilogue has finished
+    if (cap_tiles < rows.cap) {
+      const int sk = pick_splitk(N, K, SkinnyS::BN, part_elems, rows.cap);
+      sp.tail_from = cap_tiles;
+      sp.n_tail = sk;
+      if (sk > 1) {
+        run_tiles<SkinnyS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, sk, part, s, cap_tiles);
+      } else {
+        run_tiles<SkinnyS>(A, rows, K, N, wseg_one(wd, N), nullptr, e, 1, nullptr, s, cap_tiles);
+        if (pl.splitk == 1) sp.done_to = rows.cap;  // nothing left to sum
+        // (with a split of the full tiles only, the sum kernel must skip the tail rows: n_tail = 0)
+        else sp.n_tail = 0;
+      }
+    }
+    if (sp.done_to < rows.cap && (pl.splitk > 1 || sp.n_tail > 1))
+      launch_down_finalize(BF16, part, sp, (size_t)rows.cap * N, h, rows, N, out, s);
   }
 }
 

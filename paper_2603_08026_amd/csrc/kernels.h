@@ -19,6 +19,7 @@ struct Rows {
 // tail_from on (a short last row tile that a launch of its own computed) n_tail.
 struct Splits {
   int n = 1, tail_from = 0x7fffffff, n_tail = 1;
+  int done_to = 0;  // down projection: rows below it need no sum kernel (the GEMM's own epilogue wrote them)
   __host__ __device__ int of(int j) const { return j < tail_from ? n : n_tail; }
 };
 
@@ -46,8 +47,9 @@ void launch_qkv_finalize(DType t, const float *part, Splits splits, size_t split
 void launch_oproj_finalize(DType t, const float *part, Splits splits, size_t split_stride, const void *x,
                            const void *gain, Rows rows, int d, float eps, float *h, void *f,
                            hipStream_t s);
-// down projection after a K split: out_cache[row_j] = h[j] + sum of splits
-void launch_down_finalize(DType t, const float *part, int splits, size_t split_stride, const float *h,
+// down projection after a K split: out_cache[row_j] = h[j] + sum of splits, for the rows from
+// splits.done_to on (the rows below it were written by the GEMM's own epilogue)
+void launch_down_finalize(DType t, const float *part, Splits splits, size_t split_stride, const float *h,
                           Rows rows, int d, void *out_cache, hipStream_t s);
 // cosine of c_new[j] vs c_cache[row_j], flag = cos < tau, optional commit of the new row.
 void launch_saliency(DType t, const void *c_new, void *c_cache, Rows rows, int D, float tau,

@@ -109,12 +109,14 @@ __global__ __launch_bounds__(RB) void k_oproj_finalize(const float *__restrict__
 
 // ---- down-projection tail after a K split  [Alg. 3: FFN second half + cache commit] ---------------
 template <typename T>
-__global__ __launch_bounds__(RB) void k_down_finalize(const float *__restrict__ part, int splits,
+__global__ __launch_bounds__(RB) void k_down_finalize(const float *__restrict__ part, Splits splits_of,
                                                        size_t split_stride, const float *__restrict__ h,
                                                        Rows rows, int d, T *__restrict__ out) {
   const int n = row_count(rows), nv = d / 4;
-  for (int j = blockIdx.x; j < n; j += gridDim.x) {
+  for (int j = splits_of.done_to + blockIdx.x; j < n; j += gridDim.x) {
     const int r = rows.idx ? rows.idx[j] : j;
+    const int splits = splits_of.of(j);
+    if (splits == 0) continue;  // the row's result is in place already (its GEMM had no K split)
     T *orow = out + (size_t)r * d;
     for (int v = threadIdx.x; v < nv; v += RB) {
       float4 a = *reinterpret_cast<const float4 *>(h + (size_t)j * d + v * 4);
@@ -387,15 +389,14 @@ void launch_oproj_finalize(DType t, const float *part, Splits splits, size_t spl
                                                                (bf16_t *)f);
 }
 
-void launch_down_finalize(DType t, const float *part, int splits, size_t split_stride, const float *h,
+void launch_down_finalize(DType t, const float *part, Splits splits, size_t split_stride, const float *h,
                           Rows rows, int d, void *out_cache, hipStream_t s) {
-  if (rows.cap <= 0) return;
+  if (rows.cap <= 0 || splits.done_to >= rows.cap) return;
+  const int g = row_grid(rows.cap - splits.done_to);
   if (t == F32)
-    k_down_finalize<float><<<row_grid(rows.cap), RB, 0, s>>>(part, splits, split_stride, h, rows, d,
-                                                             (float *)out_cache);
+    k_down_finalize<float><<<g, RB, 0, s>>>(part, splits, split_stride, h, rows, d, (float *)out_cache);
   else
-    k_down_finalize<bf16_t><<<row_grid(rows.cap), RB, 0, s>>>(part, splits, split_stride, h, rows, d,
-                                                              (bf16_t *)out_cache);
+    k_down_finalize<bf16_t><<<g, RB, 0, s>>>(part, splits, split_stride, h, rows, d, (bf16_t *)out_cache);
 }
 
 void launch_qkv_finalize(DType t, const float *part, Splits splits, size_t split_stride,

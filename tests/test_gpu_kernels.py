@@ -383,16 +383,20 @@ def test_four_wave_256x256_tiles_with_short_k_and_stacked_weights(hidden, heads,
     lay.close()
 
 
-@pytest.mark.parametrize("M,cap", [(2075, 2075), (2060, 2075), (1990, 2075)])
-def test_short_last_row_tile_streamed_in_a_launch_of_its_own(M, cap):
+@pytest.mark.parametrize("M,cap,ffn", [(2075, 2075, 4096), (2060, 2075, 4096), (1990, 2075, 4096), (1819, 1819, 12288),
+                                       (1800, 1819, 12288)])
+def test_short_last_row_tile_streamed_in_a_launch_of_its_own(M, cap, ffn):
     """Widths at which eight full 256-row tiles fill the chip's 256 CUs exactly (q|k|v 8192, out-projection
     and gate|up 4096 columns over K = 4096), so that the 27 rows of a ninth row tile would open a round of their own:
     the launchers hand rows 2048.. to the weight-streaming tiles in a second launch, whose K split
     differs from the first one's.  With fewer rows than the capacity that launch has fewer rows than
-    planned (2060) or none, and the first one a partial tile of its own (1990)."""
+    planned (2060) or none, and the first one a partial tile of its own (1990).  The down projection
+    does the same: with 4096 FFN columns its full tiles go through the fused epilogue and only the streamed
+    rows have partial sums; with 12288 (7 row tiles + 27 rows) the full tiles have a K split of their own,
+    and the sum kernel takes a different number of partial results on either side of row 1792."""
     _say("streamed last row tile", M, cap)
     dtype = "bf16"
-    s = W.LayerShape(hidden=4096, n_heads=32, n_kv_heads=16, head_dim=128, ffn=4096, dtype=dtype, rope_theta=10000.0)
+    s = W.LayerShape(hidden=4096, n_heads=32, n_kv_heads=16, head_dim=128, ffn=ffn, dtype=dtype, rope_theta=10000.0)
     cfg = oracle_cfg(s)
     B, L = 2, 1100
     T = B * L
